@@ -1,0 +1,205 @@
+"""ctypes loader for the CPU oracle (``sentry_oracle.c``): TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  The GPU library and its Python binding
+never do.  The wrappers below only marshal numpy arrays into the C functions;
+every piece of arithmetic is in the C file.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sentry_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+LANES = 1024
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain C99, -O2, no threads)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    tmp = _LIB + ".tmp.%d" % os.getpid()
+    subprocess.run(["gcc", "-std=gnu99", "-O2", "-fPIC", "-shared", "-o", tmp, _SRC],
+                   check=True)
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        vp, sz, u32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32
+        L.oracle_sha256.argtypes = [vp, sz, vp]
+        L.oracle_sha256.restype = None
+        L.oracle_sha256_constants.argtypes = [vp, vp]
+        L.oracle_sha256_constants.restype = None
+        L.oracle_merkle_reduce.argtypes = [vp, sz, vp]
+        L.oracle_merkle_reduce.restype = None
+        L.oracle_merkle_leaves.argtypes = [vp, sz, sz, vp]
+        L.oracle_merkle_leaves.restype = sz
+        L.oracle_merkle_root.argtypes = [vp, sz, sz, vp]
+        L.oracle_merkle_root.restype = ctypes.c_int
+        L.oracle_merkle_segments.argtypes = [vp, vp, sz, sz, vp, vp]
+        L.oracle_merkle_segments.restype = ctypes.c_int
+        L.oracle_verify.argtypes = [vp, vp]
+        L.oracle_verify.restype = ctypes.c_int
+        L.oracle_blake2b_constants.argtypes = [vp, vp]
+        L.oracle_blake2b_constants.restype = None
+        L.oracle_blake2b_param.argtypes = [vp, vp, sz, vp, sz]
+        L.oracle_blake2b_param.restype = None
+        L.oracle_blake2xb_root.argtypes = [vp, sz, u32, vp]
+        L.oracle_blake2xb_root.restype = None
+        L.oracle_blake2xb.argtypes = [vp, sz, vp, u32]
+        L.oracle_blake2xb.restype = None
+        L.oracle_lthash_one.argtypes = [vp, sz, vp]
+        L.oracle_lthash_one.restype = None
+        L.oracle_lthash.argtypes = [vp, vp, sz, vp]
+        L.oracle_lthash.restype = None
+        L.oracle_lthash_combine.argtypes = [vp, vp]
+        L.oracle_lthash_combine.restype = None
+        L.oracle_lthash_remove.argtypes = [vp, vp]
+        L.oracle_lthash_remove.restype = None
+        _lib = L
+    return _lib
+
+
+def _u8(data):
+    """Contiguous uint8 view of bytes / bytearray / ndarray (no arithmetic)."""
+    if isinstance(data, np.ndarray):
+        a = np.ascontiguousarray(data)
+        return a.view(np.uint8).reshape(-1)
+    return np.frombuffer(bytes(data), dtype=np.uint8)
+
+
+def _ptr(a):
+    return a.ctypes.data if a.size else None
+
+
+def sha256(data):
+    a = _u8(data)
+    out = np.empty(32, np.uint8)
+    lib().oracle_sha256(_ptr(a), a.size, out.ctypes.data)
+    return out.tobytes()
+
+
+def sha256_constants():
+    k = np.empty(64, np.uint32)
+    h0 = np.empty(8, np.uint32)
+    lib().oracle_sha256_constants(k.ctypes.data, h0.ctypes.data)
+    return k, h0
+
+
+def merkle_leaves(data, leaf_bytes):
+    a = _u8(data)
+    n = max(1, -(-a.size // leaf_bytes))
+    out = np.empty((n, 32), np.uint8)
+    got = lib().oracle_merkle_leaves(_ptr(a), a.size, leaf_bytes, out.ctypes.data)
+    assert got == n
+    return out
+
+
+def merkle_reduce(nodes):
+    a = np.array(nodes, dtype=np.uint8, copy=True).reshape(-1, 32)   # reduced in place
+    out = np.empty(32, np.uint8)
+    lib().oracle_merkle_reduce(a.ctypes.data, a.shape[0], out.ctypes.data)
+    return out.tobytes()
+
+
+def merkle_root(data, leaf_bytes):
+    a = _u8(data)
+    out = np.empty(32, np.uint8)
+    rc = lib().oracle_merkle_root(_ptr(a), a.size, leaf_bytes, out.ctypes.data)
+    if rc:
+        raise ValueError("oracle_merkle_root rc=%d" % rc)
+    return out.tobytes()
+
+
+def merkle_segments(segments, leaf_bytes):
+    """segments: list of byte-like; returns (list of per-segment roots, global root)."""
+    arrs = [_u8(s) for s in segments]
+    n = len(arrs)
+    ptrs = (ctypes.c_void_p * n)(*[_ptr(a) for a in arrs])
+    lens = (ctypes.c_size_t * n)(*[a.size for a in arrs])
+    seg = np.empty((max(n, 1), 32), np.uint8)
+    out = np.empty(32, np.uint8)
+    rc = lib().oracle_merkle_segments(ptrs, lens, n, leaf_bytes, seg.ctypes.data, out.ctypes.data)
+    if rc:
+        raise ValueError("oracle_merkle_segments rc=%d" % rc)
+    return [seg[i].tobytes() for i in range(n)], out.tobytes()
+
+
+def verify(a, b):
+    x, y = _u8(a), _u8(b)
+    assert x.size == 32 and y.size == 32
+    return lib().oracle_verify(x.ctypes.data, y.ctypes.data)
+
+
+def blake2b_constants():
+    iv = np.empty(8, np.uint64)
+    sigma = np.empty(160, np.uint8)
+    lib().oracle_blake2b_constants(iv.ctypes.data, sigma.ctypes.data)
+    return iv, sigma.reshape(10, 16)
+
+
+def blake2b_param(param, data, out_len=64):
+    p = _u8(param)
+    assert p.size == 64
+    a = _u8(data)
+    out = np.empty(out_len, np.uint8)
+    lib().oracle_blake2b_param(p.ctypes.data, _ptr(a), a.size, out.ctypes.data, out_len)
+    return out.tobytes()
+
+
+def blake2xb_root(data, xof_len=2048):
+    a = _u8(data)
+    out = np.empty(64, np.uint8)
+    lib().oracle_blake2xb_root(_ptr(a), a.size, xof_len, out.ctypes.data)
+    return out.tobytes()
+
+
+def blake2xb(data, xof_len=2048):
+    a = _u8(data)
+    out = np.empty(xof_len, np.uint8)
+    lib().oracle_blake2xb(_ptr(a), a.size, out.ctypes.data, xof_len)
+    return out.tobytes()
+
+
+def lthash_one(data):
+    a = _u8(data)
+    out = np.empty(LANES, np.uint16)
+    lib().oracle_lthash_one(_ptr(a), a.size, out.ctypes.data)
+    return out
+
+
+def lthash(records, offsets):
+    """records: byte-like; offsets: n+1 uint64 byte offsets into records."""
+    a = _u8(records)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    n = max(off.size - 1, 0)
+    out = np.full(LANES, 0xAAAA, np.uint16)      # the C function must overwrite every lane
+    if n:
+        assert int(off[-1]) <= a.size
+    lib().oracle_lthash(_ptr(a), _ptr(off), n, out.ctypes.data)
+    return out
+
+
+def lthash_combine(acc, x):
+    r = np.array(acc, dtype=np.uint16, copy=True)
+    xx = np.ascontiguousarray(x, dtype=np.uint16)
+    lib().oracle_lthash_combine(r.ctypes.data, xx.ctypes.data)
+    return r
+
+
+def lthash_remove(acc, x):
+    r = np.array(acc, dtype=np.uint16, copy=True)
+    xx = np.ascontiguousarray(x, dtype=np.uint16)
+    lib().oracle_lthash_remove(r.ctypes.data, xx.ctypes.data)
+    return r

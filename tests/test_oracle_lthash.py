@@ -1,0 +1,95 @@
+"""Pins for the oracle's lattice hash (section 2.2, Eq. (1); section 4.2.2): the
+set-homomorphism identities the paper states, closed forms, the modulus, and a
+brute-force sum in Python integers."""
+import hashlib
+import random
+
+import numpy as np
+
+import oracle
+
+
+def pack(records):
+    off = np.zeros(len(records) + 1, np.uint64)
+    off[1:] = np.cumsum([len(r) for r in records])
+    return b"".join(records), off
+
+
+def lanes_via_xof(rec):
+    return np.frombuffer(oracle.blake2xb(rec, 2048), dtype="<u2").astype(np.int64)
+
+
+def test_empty_set_is_zero():
+    assert not oracle.lthash(b"", np.zeros(1, np.uint64)).any()
+    assert not oracle.lthash(b"", np.zeros(0, np.uint64)).any()
+
+
+def test_single_record_is_its_xof_lanes():
+    rec = random.Random(21).randbytes(3072)
+    data, off = pack([rec])
+    got = oracle.lthash(data, off)
+    assert (got == lanes_via_xof(rec)).all()
+    assert (oracle.lthash_one(rec) == got).all()
+    # first lane = first two XOF bytes, little endian; the XOF's first block hangs off H0,
+    # and H0 is pinned by hashlib
+    x = oracle.blake2xb(rec, 2048)
+    assert int(got[0]) == x[0] | (x[1] << 8)
+    assert int(got[1023]) == x[2046] | (x[2047] << 8)
+    assert oracle.blake2xb_root(rec, 2048) == hashlib.blake2b(rec, node_offset=2048 << 32).digest()
+
+
+def test_brute_force_sum_small_sets():
+    rng = random.Random(22)
+    for n in (1, 2, 3, 16):
+        recs = [rng.randbytes(rng.randrange(0, 400)) for _ in range(n)]
+        data, off = pack(recs)
+        want = sum(lanes_via_xof(r) for r in recs) % 65536
+        assert (oracle.lthash(data, off).astype(np.int64) == want).all()
+
+
+def test_union_of_disjoint_sets_is_sum():
+    rng = random.Random(23)
+    recs = [rng.randbytes(rng.randrange(1, 300)) for _ in range(40)]
+    a, b = recs[:17], recs[17:]
+    ha, hb, hab = (oracle.lthash(*pack(x)) for x in (a, b, recs))
+    assert (oracle.lthash_combine(ha, hb) == hab).all()
+    assert (oracle.lthash_remove(hab, ha) == hb).all()       # LtHash(S1 u S2) - LtHash(S1) = LtHash(S2)
+    assert (oracle.lthash_remove(oracle.lthash_combine(ha, hb), hb) == ha).all()
+
+
+def test_order_invariance_and_multiset():
+    rng = random.Random(24)
+    recs = [rng.randbytes(rng.randrange(0, 200)) for _ in range(30)]
+    h = oracle.lthash(*pack(recs))
+    shuffled = recs[:]
+    rng.shuffle(shuffled)
+    assert (oracle.lthash(*pack(shuffled)) == h).all()
+    # a record present twice counts twice
+    twice = oracle.lthash(*pack(recs + [recs[3]]))
+    assert (twice == oracle.lthash_combine(h, oracle.lthash_one(recs[3]))).all()
+
+
+def test_offsets_need_not_start_at_zero_and_empty_records_count():
+    rng = random.Random(25)
+    blob = rng.randbytes(1000)
+    off = np.array([100, 100, 350, 900], np.uint64)          # first record is empty
+    want = sum(lanes_via_xof(blob[int(off[i]):int(off[i + 1])]) for i in range(3)) % 65536
+    assert (oracle.lthash(blob, off).astype(np.int64) == want).all()
+    assert lanes_via_xof(b"").any()                          # h(empty record) is not zero
+
+
+def test_modulus_is_2_to_16():
+    rec = b"wraparound"
+    one = oracle.lthash_one(rec)
+    # 65,536 copies of one record sum to zero in every lane
+    data, off = pack([rec] * 65536)
+    assert not oracle.lthash(data, off).any()
+    # per-lane carries are dropped, lanes do not leak into their neighbours
+    a = np.full(1024, 0xFFFF, np.uint16)
+    b = np.zeros(1024, np.uint16)
+    b[::2] = 1
+    s = oracle.lthash_combine(a, b)
+    assert (s[::2] == 0).all() and (s[1::2] == 0xFFFF).all()
+    d = oracle.lthash_remove(np.zeros(1024, np.uint16), b)
+    assert (d[::2] == 0xFFFF).all() and (d[1::2] == 0).all()
+    assert (oracle.lthash_combine(one, one).astype(np.int64) == (2 * one.astype(np.int64)) % 65536).all()
