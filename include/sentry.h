@@ -1,0 +1,203 @@
+/*
+ * sentry.h: C ABI of the MI355X (gfx950) artifact-hashing library.
+ *
+ * The library hashes ML artifacts that already sit in GPU memory, as in Sentry
+ * (CCS '25): a SHA-256 Merkle tree over model-weight bytes and a lattice
+ * (homomorphic, LtHash-style) hash over dataset samples.  Every step runs in
+ * hand-written HIP kernels; signing and signature checks stay with the caller.
+ *
+ * Conventions shared by all entry points
+ *   - Return value: SENTRY_OK (0) on success, SENTRY_MISMATCH (1) only from
+ *     sentry_verify, a negative SENTRY_ERR_* otherwise.  Nothing throws or
+ *     aborts.  sentry_last_error() returns a thread-local text for the last
+ *     failing call of the calling thread.
+ *   - "device" pointers are HIP device allocations of the current device;
+ *     "device-accessible" means device memory or pinned host memory (the result
+ *     is written by a kernel); "host" means ordinary process memory.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return; outputs are valid once the caller
+ *     has synchronised the stream.  Inputs must stay alive and unchanged until
+ *     then.  The library never writes to an input and never frees caller memory
+ *     (section 4.2.1, "In-place Hashing": the state dict must stay unchanged).
+ *   - The library owns its scratch memory (leaf digests, level buffers, lane
+ *     partials, tables), allocated lazily per stream and reused; concurrent
+ *     calls on one stream from several host threads are not supported.
+ *     sentry_release_scratch() frees it.
+ *   - Digests are the 32 bytes of FIPS 180-4 SHA-256 in their usual byte order.
+ *     Lattice digests are SENTRY_LANES uint16 values.
+ */
+#ifndef SENTRY_H
+#define SENTRY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* the library is built with hidden visibility; only these entry points are exported */
+#define SENTRY_API __attribute__((visibility("default")))
+
+enum {
+    SENTRY_OK = 0,
+    SENTRY_MISMATCH = 1,
+    SENTRY_ERR_INVALID_ARG = -1,
+    SENTRY_ERR_HIP = -2,
+    SENTRY_ERR_NOMEM = -3
+};
+
+#define SENTRY_DIGEST_BYTES 32
+#define SENTRY_LANES 1024
+
+/* ------------------------------------------------------------------------ */
+/* Merkle tree over weight bytes (section 2.2 "Merkle Tree"; section 4.2.1) */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Root of the binary SHA-256 Merkle tree over one contiguous device buffer
+ * (Algorithm 1 once the tensors are one buffer; block hashing kernel and
+ * reduction kernel of section 4.2.1).
+ *   leaf i   = bytes [i*leaf_bytes, min((i+1)*leaf_bytes, len)); the last leaf
+ *              may be short and is hashed at its true length; len == 0 is one
+ *              empty leaf.
+ *   node     = SHA-256(left || right); a level's lone last node moves up
+ *              unchanged.
+ * dev_buf     device, 16-byte aligned (may be NULL only if len == 0).
+ * leaf_bytes  > 0 and a multiple of 64.
+ * out_digest  device-accessible, 32 bytes.
+ * Errors: SENTRY_ERR_INVALID_ARG for NULL/misaligned pointers or a bad
+ * leaf_bytes; SENTRY_ERR_NOMEM / SENTRY_ERR_HIP if scratch or a launch fails.
+ */
+SENTRY_API int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes,
+                       uint8_t *out_digest, void *stream);
+
+/*
+ * Per-tensor trees and the model digest over them (Algorithm 2, per-layer
+ * hashing) in one table-driven launch over fragmented tensors (the lookup
+ * table of section 4.2.1, "In-place Hashing").
+ *   seg_root[t] = sentry_merkle_root of tensor t (same leaf rules);
+ *   out_root    = the pairwise reduction of [seg_root[0..n_seg)] taken as
+ *                 ready-made nodes (they are not hashed again as leaves).
+ * dev_ptrs       host array of n_seg device pointers, each 16-byte aligned.
+ * lens           host array of n_seg byte lengths.
+ * out_seg_roots  device-accessible, n_seg*32 bytes, or NULL if not wanted.
+ * out_root       device-accessible, 32 bytes.
+ * n_seg >= 1.  The two host arrays are read before the call returns.
+ */
+SENTRY_API int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                           size_t leaf_bytes, uint8_t *out_seg_roots, uint8_t *out_root,
+                           void *stream);
+
+/*
+ * The block hashing kernel alone: the max(1, ceil(len/leaf_bytes)) leaf digests
+ * of a buffer, 32 bytes each, in leaf order (section 4.2.1).
+ * out_leaf_digests  device, 16-byte aligned, 32 bytes per leaf.
+ */
+SENTRY_API int sentry_merkle_leaves(const void *dev_buf, size_t len, size_t leaf_bytes,
+                         uint8_t *out_leaf_digests, void *stream);
+
+/*
+ * The reduction kernel alone: n >= 1 ready-made 32-byte nodes to one root by
+ * the pairwise rule above (section 4.2.1; HashReduce in Algorithms 1-3).
+ * dev_nodes   device, 16-byte aligned, n*32 bytes, not modified.
+ */
+SENTRY_API int sentry_merkle_reduce(const uint8_t *dev_nodes, size_t n, uint8_t *out_digest, void *stream);
+
+/*
+ * One tree over a byte stream that arrives in chunks already on the device.
+ * begin   sizes the state for total_len bytes and leaf_bytes; *state is an
+ *         opaque handle owned by the library until final (or abort).
+ * update  hashes the leaves of the next chunk; every chunk but the last must be
+ *         a multiple of leaf_bytes; the chunk buffer may be reused once the
+ *         stream has passed the update.  dev_chunk: device, 16-byte aligned.
+ * final   reduces the leaf digests to the root (equal to sentry_merkle_root over
+ *         the concatenated chunks), writes it to out_digest (device-accessible)
+ *         and releases the state after the stream has drained it.
+ *         SENTRY_ERR_INVALID_ARG if fewer than total_len bytes were fed.
+ * abort   releases a state without a result.
+ */
+SENTRY_API int sentry_merkle_stream_begin(size_t total_len, size_t leaf_bytes, void **state);
+SENTRY_API int sentry_merkle_stream_update(void *state, const void *dev_chunk, size_t len, void *stream);
+SENTRY_API int sentry_merkle_stream_final(void *state, uint8_t *out_digest, void *stream);
+SENTRY_API int sentry_merkle_stream_abort(void *state);
+
+/*
+ * Hash while loading (section 4.4: authentication on the fly as the model is
+ * loaded; pinned hipMemcpyAsync stands in for the paper's GPUDirect loads):
+ * the root of the tree over a host buffer, copied in chunks on a side stream
+ * into two device staging buffers while the previous chunk is hashed on
+ * `stream`.  Equal to sentry_merkle_root over the same bytes.
+ * host_buf     host, pinned for the copies to overlap (pageable memory works
+ *              but serialises), 16-byte aligned.
+ * chunk_bytes  > 0 and a multiple of leaf_bytes; two device buffers of this
+ *              size are held in the library's scratch.
+ * The call returns after enqueuing everything; host_buf must stay unchanged
+ * until `stream` is synchronised.
+ */
+SENTRY_API int sentry_merkle_root_h2d(const void *host_buf, size_t len, size_t leaf_bytes,
+                           size_t chunk_bytes, uint8_t *out_digest, void *stream);
+
+/* Constant-time comparison of two host digests ("recompute model digests and
+ * verify", section 4.1.1).  SENTRY_OK if equal, SENTRY_MISMATCH if not,
+ * SENTRY_ERR_INVALID_ARG for NULL. */
+SENTRY_API int sentry_verify(const uint8_t *root, const uint8_t *expected);
+
+/* ------------------------------------------------------------------------ */
+/* Lattice hash over dataset samples (section 2.2 Eq. (1); 4.2.2; 4.3)      */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * out_lanes[l] = sum over records i of h(record_i)[l] mod 2^16, l < 1024
+ * (Eq. (1) with q = 2^16; one block per sample, section 4.3).  h(M) is
+ * BLAKE2Xb(M) with 2048 output bytes read as little-endian uint16 lanes: a
+ * BLAKE2b-512 root hash carrying the XOF length, expanded by 32 one-block
+ * BLAKE2b calls.  Records with equal bytes count once each (multiset).
+ * dev_records  device; record i = bytes [offsets[i], offsets[i+1]) of it; any
+ *              alignment; may be NULL if every record is empty.  The kernels
+ *              read whole aligned 4-byte words, so up to 3 bytes on either side
+ *              of a record may be read (never past the word that holds a byte
+ *              of the record).
+ * dev_offsets  device, n+1 non-decreasing uint64 byte offsets (8-byte aligned);
+ *              offsets[0] need not be 0.  Monotonicity is not checked: the
+ *              result is undefined, and reads may fault, if it is violated.
+ * n            number of records; 0 gives all-zero lanes (dev_offsets may be
+ *              NULL then).
+ * out_lanes    device-accessible, 1024 uint16 (2-byte aligned), overwritten.
+ */
+SENTRY_API int sentry_lthash(const void *dev_records, const uint64_t *dev_offsets, size_t n,
+                  uint16_t *out_lanes, void *stream);
+
+/* acc[l] = (acc[l] + x[l]) mod 2^16 and (acc[l] - x[l]) mod 2^16 (section 2.2:
+ * LtHash(S1)+LtHash(S2) = LtHash(S1 u S2), LtHash(S1 u S2)-LtHash(S1) =
+ * LtHash(S2); the lattice addition of section 4.2.2).  Both device-accessible,
+ * 1024 uint16, 2-byte aligned; x is not modified; acc == x is allowed. */
+SENTRY_API int sentry_lthash_combine(uint16_t *acc, const uint16_t *x, void *stream);
+SENTRY_API int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stream);
+
+/*
+ * Lattice hash of records that sit in host memory, loaded in batches on a side
+ * stream while the previous batch is hashed, the running sum carried across
+ * batches (section 4.3: per-batch digests added to a running sum).  Equal to
+ * sentry_lthash over the same records.
+ * host_records  host (pinned for overlap); host_offsets: host, n+1 offsets.
+ * batch_bytes   upper bound on the record bytes copied per batch (> 0); a
+ *               record longer than this is an error.  Batches are cut at record
+ *               boundaries.  Two device buffers of this size are held in scratch.
+ * out_lanes     device-accessible, overwritten with the sum over all n records.
+ */
+SENTRY_API int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, size_t n,
+                      size_t batch_bytes, uint16_t *out_lanes, void *stream);
+
+/* ------------------------------------------------------------------------ */
+
+/* Text for the calling thread's last failing call ("" if none). */
+SENTRY_API const char *sentry_last_error(void);
+
+/* Free all cached scratch memory of the current device (synchronises it). */
+SENTRY_API int sentry_release_scratch(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SENTRY_H */

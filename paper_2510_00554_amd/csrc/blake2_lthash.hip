@@ -1,0 +1,387 @@
+// Lattice hash over dataset samples on gfx950 (section 2.2 Eq. (1), section 4.2.2,
+// section 4.3): per-record digest h(M) = BLAKE2Xb(M) with 2048 output bytes read as
+// 1024 little-endian uint16 lanes, summed lane-wise mod 2^16.
+//
+// Three kernels:
+//   lthash_root_kernel    one record per lane: the sequential BLAKE2b-512 root hash H0
+//                         (the only serial part), 64 bytes per record to scratch;
+//   lthash_expand_kernel  one (record, output block) pair per lane: the 32 expansion
+//                         compressions of a record are independent, so they are spread
+//                         over all lanes of the chip; each lane keeps the 16 packed words
+//                         of "its" output block in registers and adds every record's
+//                         block to them (v_pk_add_u16), so the 2048-byte digests never
+//                         exist in memory; per-workgroup partial sums go to scratch;
+//   lthash_fold_kernel    adds the partial sums column-wise into the 1024 lanes.
+#include "sentry_internal.h"
+
+namespace {
+
+constexpr int ROOT_WG = 256;
+constexpr int EXP_WG = 256;
+constexpr int EXP_WAVES = EXP_WG / 64;
+constexpr int LANE_WORDS = SENTRY_LANES / 2;   // 512 packed 32-bit words = 2048 bytes
+constexpr int FOLD_WG = 256;
+constexpr int FOLD_COLS = 32;                  // packed words per fold workgroup
+constexpr uint32_t XOF_BYTES = 2 * SENTRY_LANES;
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------
+// BLAKE2b (RFC 7693) on 64-bit values held in register pairs
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ uint64_t pack64(uint32_t lo, uint32_t hi) { return ((uint64_t)hi << 32) | lo; }
+
+// rotations as two 32-bit funnel shifts on the halves; by 32 it is a swap of the halves
+__device__ __forceinline__ uint64_t rotr64_32(uint64_t x) { return pack64((uint32_t)(x >> 32), (uint32_t)x); }
+template <int N>   // 0 < N < 32
+__device__ __forceinline__ uint64_t rotr64_lt32(uint64_t x)
+{
+    const uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
+    return pack64(__builtin_amdgcn_alignbit(hi, lo, N), __builtin_amdgcn_alignbit(lo, hi, N));
+}
+__device__ __forceinline__ uint64_t rotr64_63(uint64_t x)   // = rotate left by one
+{
+    const uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
+    return pack64(__builtin_amdgcn_alignbit(lo, hi, 31), __builtin_amdgcn_alignbit(hi, lo, 31));
+}
+
+#define B2_G(a, b, c, d, x, y)                     \
+    do {                                           \
+        a = a + b + (x); d = rotr64_32(d ^ a);     \
+        c = c + d;       b = rotr64_lt32<24>(b ^ c); \
+        a = a + b + (y); d = rotr64_lt32<16>(d ^ a); \
+        c = c + d;       b = rotr64_63(b ^ c);     \
+    } while (0)
+
+constexpr uint64_t b2_iv(int i)
+{
+    constexpr uint64_t iv[8] = {0x6a09e667f3bcc908ull, 0xbb67ae8584caa73bull, 0x3c6ef372fe94f82bull,
+                                0xa54ff53a5f1d36f1ull, 0x510e527fade682d1ull, 0x9b05688c2b3e6c1full,
+                                0x1f83d9abfb41bd6bull, 0x5be0cd19137e2179ull};
+    return iv[i];
+}
+
+constexpr int b2_sigma(int r, int i)
+{
+    constexpr unsigned char S[10][16] = {
+        {0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15}, {14, 10, 4, 8, 9, 15, 13, 6, 1, 12, 0, 2, 11, 7, 5, 3},
+        {11, 8, 12, 0, 5, 2, 15, 13, 10, 14, 3, 6, 7, 1, 9, 4}, {7, 9, 3, 1, 13, 12, 11, 14, 2, 6, 5, 10, 4, 0, 15, 8},
+        {9, 0, 5, 7, 2, 4, 10, 15, 14, 1, 11, 12, 6, 8, 3, 13}, {2, 12, 6, 10, 0, 11, 8, 3, 4, 13, 7, 5, 15, 14, 1, 9},
+        {12, 5, 1, 15, 14, 13, 4, 10, 0, 7, 6, 3, 9, 2, 8, 11}, {13, 11, 7, 14, 12, 1, 3, 9, 5, 0, 15, 4, 8, 6, 2, 10},
+        {6, 15, 14, 9, 11, 3, 0, 8, 12, 2, 13, 7, 1, 4, 10, 5}, {10, 2, 8, 4, 7, 6, 1, 5, 15, 11, 9, 14, 3, 12, 13, 0}};
+    return S[r % 10][i];
+}
+
+// h <- F(h, m, t, last): twelve rounds, fully unrolled so that the message permutation
+// becomes static register indexing.  t = message bytes so far (below 2^64).
+__device__ __forceinline__ void blake2b_compress(uint64_t (&h)[8], const uint64_t (&m)[16], uint64_t t, bool last)
+{
+    uint64_t v[16];
+#pragma unroll
+    for (int i = 0; i < 8; i++) { v[i] = h[i]; v[8 + i] = b2_iv(i); }
+    v[12] ^= t;
+    if (last) v[14] = ~v[14];
+#pragma unroll
+    for (int r = 0; r < 12; r++) {
+        B2_G(v[0], v[4], v[8], v[12], m[b2_sigma(r, 0)], m[b2_sigma(r, 1)]);
+        B2_G(v[1], v[5], v[9], v[13], m[b2_sigma(r, 2)], m[b2_sigma(r, 3)]);
+        B2_G(v[2], v[6], v[10], v[14], m[b2_sigma(r, 4)], m[b2_sigma(r, 5)]);
+        B2_G(v[3], v[7], v[11], v[15], m[b2_sigma(r, 6)], m[b2_sigma(r, 7)]);
+        B2_G(v[0], v[5], v[10], v[15], m[b2_sigma(r, 8)], m[b2_sigma(r, 9)]);
+        B2_G(v[1], v[6], v[11], v[12], m[b2_sigma(r, 10)], m[b2_sigma(r, 11)]);
+        B2_G(v[2], v[7], v[8], v[13], m[b2_sigma(r, 12)], m[b2_sigma(r, 13)]);
+        B2_G(v[3], v[4], v[9], v[14], m[b2_sigma(r, 14)], m[b2_sigma(r, 15)]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) h[i] ^= v[i] ^ v[8 + i];
+}
+
+// BLAKE2Xb parameter blocks (byte 0 digest length, 1 key length, 2 fanout, 3 depth,
+// 4..7 leaf length, 8..11 node offset, 12..15 XOF length, 16 node depth, 17 inner length).
+// Root hash: digest 64, fanout 1, depth 1, XOF length 2048.
+constexpr uint64_t ROOT_P0 = 0x0000000001010040ull;
+constexpr uint64_t ROOT_P1 = (uint64_t)XOF_BYTES << 32;
+// Expansion node j: digest 64, fanout 0, depth 0, leaf length 64, node offset j, XOF
+// length 2048, inner length 64.
+constexpr uint64_t EXP_P0 = 0x0000004000000040ull;
+constexpr uint64_t EXP_P1_HI = (uint64_t)XOF_BYTES << 32;
+constexpr uint64_t EXP_P2 = 0x0000000000004000ull;
+
+// ---------------------------------------------------------------------------
+// root hash kernel
+// ---------------------------------------------------------------------------
+
+// 32-bit word k of a 128-byte block that starts `sh`/8 bytes into the aligned word d[0]
+#define M32(k) __builtin_amdgcn_alignbit(d[(k) + 1], d[k], sh)
+
+__global__ void __launch_bounds__(ROOT_WG)
+lthash_root_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
+                   uint64_t *h0_out)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * ROOT_WG + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t beg = offsets[i] - offset_base;
+    const uint64_t len = offsets[i + 1] - offsets[i];
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(records) + beg;
+    const uint32_t a = (uint32_t)(addr & 3);
+    const uint32_t sh = 8 * a;
+    const uint32_t *q = reinterpret_cast<const uint32_t *>(addr - a);
+
+    uint64_t h[8];
+#pragma unroll
+    for (int k = 0; k < 8; k++) h[k] = b2_iv(k);
+    h[0] ^= ROOT_P0;
+    h[1] ^= ROOT_P1;
+
+    uint32_t d[33];
+    uint64_t done = 0;
+    // every block but the last is full; a full block that is not the last is followed by at
+    // least one more byte of the record, so all 33 aligned words it touches hold record bytes
+    if (len > 128) {
+#pragma unroll
+        for (int k = 0; k < 33; k++) d[k] = q[k];
+    }
+    while (len - done > 128) {
+        uint64_t m[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) m[k] = pack64(M32(2 * k), M32(2 * k + 1));
+        done += 128;
+        q += 32;
+        if (len - done > 128) {   // fetch the next full block while this one is compressed
+            d[0] = d[32];
+#pragma unroll
+            for (int k = 1; k < 33; k++) d[k] = q[k];
+        }
+        blake2b_compress(h, m, done, false);
+    }
+    // last block: 1..128 bytes (0 only for the empty record), zero padded; words that hold
+    // no byte of the record are not read
+    {
+        const uint32_t rem = (uint32_t)(len - done);
+        const uint32_t span = rem ? a + rem : 0u;   // bytes from the aligned base to the record's end
+#pragma unroll
+        for (int k = 0; k < 33; k++) d[k] = ((uint32_t)(4 * k) < span) ? q[k] : 0u;
+        uint32_t w[32];
+#pragma unroll
+        for (int k = 0; k < 32; k++) {
+            const uint32_t lo = (uint32_t)(4 * k);
+            uint32_t x = M32(k);
+            if (rem < lo + 4) x = (rem <= lo) ? 0u : (x & ((1u << (8 * (rem - lo))) - 1u));
+            w[k] = x;
+        }
+        uint64_t m[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) m[k] = pack64(w[2 * k], w[2 * k + 1]);
+        blake2b_compress(h, m, len, true);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; k++) h0_out[8 * i + k] = h[k];
+}
+#undef M32
+
+// ---------------------------------------------------------------------------
+// expansion + lane accumulation kernel
+// ---------------------------------------------------------------------------
+
+// Lane l of every wave owns output block j = l & 31 and takes records 2*slot + (l >> 5),
+// slot = wave index, wave index + total waves, ...  part_out: one 2048-byte partial sum per
+// workgroup.
+__global__ void __launch_bounds__(EXP_WG)
+lthash_expand_kernel(const uint64_t *h0, uint64_t n, uint32_t *part_out)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t j = lane & 31;
+    const uint64_t total_waves = (uint64_t)gridDim.x * EXP_WAVES;
+    u16x2 acc[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) acc[k] = u16x2{0, 0};
+
+    for (uint64_t slot = (uint64_t)blockIdx.x * EXP_WAVES + wave;; slot += total_waves) {
+        if (2 * slot >= n) break;                      // wave-uniform
+        const uint64_t rec = 2 * slot + (lane >> 5);
+        if (rec < n) {
+            uint64_t m[16];
+#pragma unroll
+            for (int k = 0; k < 8; k++) { m[k] = h0[8 * rec + k]; m[8 + k] = 0; }
+            uint64_t h[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) h[k] = b2_iv(k);
+            h[0] ^= EXP_P0;
+            h[1] ^= EXP_P1_HI | (uint64_t)j;
+            h[2] ^= EXP_P2;
+            blake2b_compress(h, m, 64, true);
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const uint32_t lo = (uint32_t)h[k], hi = (uint32_t)(h[k] >> 32);
+                acc[2 * k] += u16x2{(unsigned short)lo, (unsigned short)(lo >> 16)};
+                acc[2 * k + 1] += u16x2{(unsigned short)hi, (unsigned short)(hi >> 16)};
+            }
+        }
+    }
+    // the two half-waves hold the same 32 blocks: add the upper half into the lower one
+    __shared__ uint32_t lds[EXP_WAVES][LANE_WORDS];
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+        uint32_t x = (uint32_t)acc[k].x | ((uint32_t)acc[k].y << 16);
+        uint32_t y = (uint32_t)__shfl_xor((int)x, 32, 64);
+        u16x2 s = acc[k] + u16x2{(unsigned short)y, (unsigned short)(y >> 16)};
+        if (lane < 32) lds[wave][16 * j + k] = (uint32_t)s.x | ((uint32_t)s.y << 16);
+    }
+    __syncthreads();
+    for (uint32_t c = tid; c < LANE_WORDS; c += EXP_WG) {
+        u16x2 s = u16x2{0, 0};
+#pragma unroll
+        for (int w = 0; w < EXP_WAVES; w++) {
+            const uint32_t x = lds[w][c];
+            s += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+        }
+        part_out[(uint64_t)blockIdx.x * LANE_WORDS + c] = (uint32_t)s.x | ((uint32_t)s.y << 16);
+    }
+}
+
+// out[c] = sum over partial sums p of part[p][c] (packed uint16 pairs), c < 512.
+// Each workgroup owns FOLD_COLS columns; its lanes split the rows eight ways.
+__global__ void __launch_bounds__(FOLD_WG)
+lthash_fold_kernel(const uint32_t *part, uint32_t n_part, uint16_t *out)
+{
+    constexpr int ROWS = FOLD_WG / FOLD_COLS;
+    const uint32_t col = blockIdx.x * FOLD_COLS + (threadIdx.x % FOLD_COLS);
+    const uint32_t row0 = threadIdx.x / FOLD_COLS;
+    u16x2 s = u16x2{0, 0};
+    for (uint32_t p = row0; p < n_part; p += ROWS) {
+        const uint32_t x = part[(uint64_t)p * LANE_WORDS + col];
+        s += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+    }
+    __shared__ uint32_t lds[ROWS][FOLD_COLS];
+    lds[row0][threadIdx.x % FOLD_COLS] = (uint32_t)s.x | ((uint32_t)s.y << 16);
+    __syncthreads();
+    if (row0 == 0) {
+        u16x2 t = u16x2{0, 0};
+#pragma unroll
+        for (int r = 0; r < ROWS; r++) {
+            const uint32_t x = lds[r][threadIdx.x];
+            t += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+        }
+        out[2 * col] = t.x;          // 16-bit stores: out needs no more than 2-byte alignment
+        out[2 * col + 1] = t.y;
+    }
+}
+
+// acc[l] = acc[l] +/- x[l] mod 2^16: the lattice addition of section 4.2.2, two lanes per
+// thread; the 16-bit lanes cannot carry into each other.
+template <bool SUB>
+__global__ void __launch_bounds__(LANE_WORDS)
+lthash_addsub_kernel(uint16_t *acc, const uint16_t *x)
+{
+    const uint32_t c = threadIdx.x;
+    u16x2 a = u16x2{acc[2 * c], acc[2 * c + 1]};
+    u16x2 b = u16x2{x[2 * c], x[2 * c + 1]};
+    u16x2 r = SUB ? (a - b) : (a + b);
+    acc[2 * c] = r.x;
+    acc[2 * c + 1] = r.y;
+}
+
+inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+int g_cu_count = 0;
+int cu_count()
+{
+    if (!g_cu_count) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            g_cu_count = n;
+        else
+            g_cu_count = 256;
+    }
+    return g_cu_count;
+}
+
+}  // namespace
+
+namespace sentry {
+
+// Grow the per-record scratch once for the largest batch of a pipelined run.
+int lthash_presize(uint64_t max_records, hipStream_t s)
+{
+    void *p;
+    return scratch_get(s, R_LT_H0, 64 * (max_records ? max_records : 1), &p);
+}
+
+// Lattice hash of n records at dev_records (offsets relative to offset_base); result either
+// overwrites out (accumulate == false) or is added to it lane-wise.
+int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
+                uint16_t *out, bool accumulate, hipStream_t s)
+{
+    void *h0, *part;
+    int rc = scratch_get(s, R_LT_H0, 64 * (n ? n : 1), &h0);
+    if (rc) return rc;
+    // expansion grid: enough workgroups to give every SIMD two waves, no more than the work
+    const uint64_t slots = ceil_div(n, 2);                        // one wave pass = two records
+    uint64_t grid = ceil_div(slots, EXP_WAVES);
+    const uint64_t cap = (uint64_t)cu_count() * 2;
+    if (grid > cap) grid = cap;
+    if (grid == 0) grid = 1;
+    const uint64_t n_part = grid + (accumulate ? 1 : 0);
+    rc = scratch_get(s, R_LT_PART, n_part * LANE_WORDS * 4, &part);
+    if (rc) return rc;
+    if (n) {
+        hipLaunchKernelGGL(lthash_root_kernel, dim3((uint32_t)ceil_div(n, ROOT_WG)), dim3(ROOT_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
+                           static_cast<uint64_t *>(h0));
+        SENTRY_HIP_CHECK(hipGetLastError());
+    }
+    hipLaunchKernelGGL(lthash_expand_kernel, dim3((uint32_t)grid), dim3(EXP_WG), 0, s,
+                       static_cast<const uint64_t *>(h0), n, static_cast<uint32_t *>(part));
+    SENTRY_HIP_CHECK(hipGetLastError());
+    if (accumulate)   // the running sum joins as one more partial row
+        SENTRY_HIP_CHECK(hipMemcpyAsync(static_cast<uint32_t *>(part) + grid * LANE_WORDS, out, XOF_BYTES,
+                                        hipMemcpyDefault, s));
+    hipLaunchKernelGGL(lthash_fold_kernel, dim3(LANE_WORDS / FOLD_COLS), dim3(FOLD_WG), 0, s,
+                       static_cast<const uint32_t *>(part), (uint32_t)n_part, out);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
+}  // namespace sentry
+
+extern "C" {
+
+int sentry_lthash(const void *dev_records, const uint64_t *dev_offsets, size_t n, uint16_t *out_lanes, void *stream)
+{
+    sentry::clear_error();
+    SENTRY_REQUIRE(out_lanes != nullptr && (reinterpret_cast<uintptr_t>(out_lanes) & 1) == 0,
+                   "sentry_lthash: out_lanes must be non-NULL and 2-byte aligned");
+    SENTRY_REQUIRE(n == 0 || (dev_offsets != nullptr && (reinterpret_cast<uintptr_t>(dev_offsets) & 7) == 0),
+                   "sentry_lthash: dev_offsets must be non-NULL and 8-byte aligned when n > 0");
+    SENTRY_REQUIRE(ceil_div(n, ROOT_WG) <= 0x7fffffffull, "sentry_lthash: too many records");
+    return sentry::lthash_into(dev_records, dev_offsets, 0, n, out_lanes, false, static_cast<hipStream_t>(stream));
+}
+
+static int addsub(const char *fn, uint16_t *acc, const uint16_t *x, void *stream, bool sub)
+{
+    sentry::clear_error();
+    SENTRY_REQUIRE(acc != nullptr && x != nullptr, "%s: NULL argument", fn);
+    SENTRY_REQUIRE(((reinterpret_cast<uintptr_t>(acc) | reinterpret_cast<uintptr_t>(x)) & 1) == 0,
+                   "%s: lanes must be 2-byte aligned", fn);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (sub)
+        hipLaunchKernelGGL(lthash_addsub_kernel<true>, dim3(1), dim3(LANE_WORDS), 0, s, acc, x);
+    else
+        hipLaunchKernelGGL(lthash_addsub_kernel<false>, dim3(1), dim3(LANE_WORDS), 0, s, acc, x);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
+int sentry_lthash_combine(uint16_t *acc, const uint16_t *x, void *stream)
+{
+    return addsub("sentry_lthash_combine", acc, x, stream, false);
+}
+
+int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stream)
+{
+    return addsub("sentry_lthash_remove", acc, x, stream, true);
+}
+
+}  // extern "C"

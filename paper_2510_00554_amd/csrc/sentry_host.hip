@@ -1,0 +1,222 @@
+// Host-only part of the library: error text, scratch arena, digest comparison.
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <utility>
+#include <vector>
+
+#include "sentry_internal.h"
+
+namespace sentry {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+struct StreamCtx {
+    void *region[R_COUNT] = {};
+    size_t cap[R_COUNT] = {};
+    void *tab_host = nullptr;      // pinned
+    size_t tab_cap = 0;
+    hipEvent_t tab_event = nullptr;
+    bool tab_pending = false;
+    CopyPipe pipe = {};
+    bool pipe_ready = false;
+};
+
+static std::mutex g_mu;
+static std::map<std::pair<int, hipStream_t>, StreamCtx> g_ctx;
+
+static int ctx_for(hipStream_t stream, StreamCtx **out)
+{
+    int dev = 0;
+    SENTRY_HIP_CHECK(hipGetDevice(&dev));
+    *out = &g_ctx[std::make_pair(dev, stream)];
+    return SENTRY_OK;
+}
+
+int scratch_get(hipStream_t stream, Region r, size_t bytes, void **out)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    StreamCtx *c;
+    int rc = ctx_for(stream, &c);
+    if (rc) return rc;
+    if (bytes == 0) bytes = 256;
+    if (c->cap[r] < bytes) {
+        if (c->region[r]) {
+            // work that still uses the old allocation may be in flight on the stream
+            SENTRY_HIP_CHECK(hipStreamSynchronize(stream));
+            SENTRY_HIP_CHECK(hipFree(c->region[r]));
+            c->region[r] = nullptr;
+            c->cap[r] = 0;
+        }
+        size_t want = (bytes + 4095) & ~(size_t)4095;
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, want);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("scratch allocation of %zu bytes failed: %s", want, hipGetErrorString(e));
+            return SENTRY_ERR_NOMEM;
+        }
+        c->region[r] = p;
+        c->cap[r] = want;
+    }
+    *out = c->region[r];
+    return SENTRY_OK;
+}
+
+int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    StreamCtx *c;
+    int rc = ctx_for(stream, &c);
+    if (rc) return rc;
+    if (c->tab_pending) {   // the previous upload must have left the pinned memory
+        SENTRY_HIP_CHECK(hipEventSynchronize(c->tab_event));
+        c->tab_pending = false;
+    }
+    if (c->tab_cap < bytes) {
+        if (c->tab_host) SENTRY_HIP_CHECK(hipHostFree(c->tab_host));
+        c->tab_host = nullptr;
+        c->tab_cap = 0;
+        size_t want = (bytes + 4095) & ~(size_t)4095;
+        void *p = nullptr;
+        hipError_t e = hipHostMalloc(&p, want, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("pinned table allocation of %zu bytes failed: %s", want, hipGetErrorString(e));
+            return SENTRY_ERR_NOMEM;
+        }
+        c->tab_host = p;
+        c->tab_cap = want;
+    }
+    if (!c->tab_event) SENTRY_HIP_CHECK(hipEventCreateWithFlags(&c->tab_event, hipEventDisableTiming));
+    *host_ptr = c->tab_host;
+    return SENTRY_OK;
+}
+
+int table_staging_mark(hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    StreamCtx *c;
+    int rc = ctx_for(stream, &c);
+    if (rc) return rc;
+    SENTRY_HIP_CHECK(hipEventRecord(c->tab_event, stream));
+    c->tab_pending = true;
+    return SENTRY_OK;
+}
+
+int copy_pipe_get(hipStream_t stream, CopyPipe **out)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    StreamCtx *c;
+    int rc = ctx_for(stream, &c);
+    if (rc) return rc;
+    if (!c->pipe_ready) {
+        // default priority on purpose: mixed stream priorities are not used anywhere
+        SENTRY_HIP_CHECK(hipStreamCreateWithFlags(&c->pipe.copy_stream, hipStreamNonBlocking));
+        for (int i = 0; i < 2; i++) {
+            SENTRY_HIP_CHECK(hipEventCreateWithFlags(&c->pipe.copied[i], hipEventDisableTiming));
+            SENTRY_HIP_CHECK(hipEventCreateWithFlags(&c->pipe.consumed[i], hipEventDisableTiming));
+        }
+        c->pipe_ready = true;
+    }
+    *out = &c->pipe;
+    return SENTRY_OK;
+}
+
+struct Retired {
+    void *ptr;
+    hipEvent_t done;
+};
+static std::vector<Retired> g_retired;
+
+int retire_device_memory(void *dev_ptr, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    Retired r = {dev_ptr, nullptr};
+    SENTRY_HIP_CHECK(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
+    SENTRY_HIP_CHECK(hipEventRecord(r.done, stream));
+    g_retired.push_back(r);
+    return SENTRY_OK;
+}
+
+static int sweep_retired_locked()
+{
+    for (size_t i = 0; i < g_retired.size();) {
+        hipError_t q = hipEventQuery(g_retired[i].done);
+        if (q == hipErrorNotReady) { i++; continue; }
+        SENTRY_HIP_CHECK(q);
+        SENTRY_HIP_CHECK(hipFree(g_retired[i].ptr));
+        SENTRY_HIP_CHECK(hipEventDestroy(g_retired[i].done));
+        g_retired[i] = g_retired.back();
+        g_retired.pop_back();
+    }
+    return SENTRY_OK;
+}
+
+int sweep_retired()
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    return sweep_retired_locked();
+}
+
+int release_all_scratch()
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    int dev = 0;
+    SENTRY_HIP_CHECK(hipGetDevice(&dev));
+    SENTRY_HIP_CHECK(hipDeviceSynchronize());
+    {
+        int rc = sweep_retired_locked();
+        if (rc) return rc;
+    }
+    for (auto it = g_ctx.begin(); it != g_ctx.end();) {
+        if (it->first.first != dev) { ++it; continue; }
+        StreamCtx &c = it->second;
+        for (int r = 0; r < R_COUNT; r++)
+            if (c.region[r]) SENTRY_HIP_CHECK(hipFree(c.region[r]));
+        if (c.tab_host) SENTRY_HIP_CHECK(hipHostFree(c.tab_host));
+        if (c.tab_event) SENTRY_HIP_CHECK(hipEventDestroy(c.tab_event));
+        if (c.pipe_ready) {
+            SENTRY_HIP_CHECK(hipStreamDestroy(c.pipe.copy_stream));
+            for (int i = 0; i < 2; i++) {
+                SENTRY_HIP_CHECK(hipEventDestroy(c.pipe.copied[i]));
+                SENTRY_HIP_CHECK(hipEventDestroy(c.pipe.consumed[i]));
+            }
+        }
+        it = g_ctx.erase(it);
+    }
+    return SENTRY_OK;
+}
+
+}  // namespace sentry
+
+extern "C" {
+
+const char *sentry_last_error(void) { return sentry::g_err; }
+
+int sentry_release_scratch(void)
+{
+    sentry::clear_error();
+    return sentry::release_all_scratch();
+}
+
+int sentry_verify(const uint8_t *root, const uint8_t *expected)
+{
+    sentry::clear_error();
+    SENTRY_REQUIRE(root && expected, "sentry_verify: NULL digest");
+    unsigned diff = 0;   // no early exit: the time does not depend on where they differ
+    for (int i = 0; i < SENTRY_DIGEST_BYTES; i++) diff |= (unsigned)(root[i] ^ expected[i]);
+    return diff ? SENTRY_MISMATCH : SENTRY_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,82 @@
+// Host-side plumbing shared by the HIP translation units of the library:
+// error reporting and the per-stream scratch arena.  No hashing arithmetic here.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstddef>
+#include <cstdint>
+#include <cstdio>
+
+#include "sentry.h"
+
+namespace sentry {
+
+// thread-local error text returned by sentry_last_error()
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+void clear_error();
+
+#define SENTRY_HIP_CHECK(expr)                                                        \
+    do {                                                                              \
+        hipError_t _e = (expr);                                                       \
+        if (_e != hipSuccess) {                                                       \
+            ::sentry::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), \
+                                __FILE__, __LINE__);                                  \
+            return SENTRY_ERR_HIP;                                                    \
+        }                                                                             \
+    } while (0)
+
+#define SENTRY_REQUIRE(cond, ...)              \
+    do {                                       \
+        if (!(cond)) {                         \
+            ::sentry::set_error(__VA_ARGS__);  \
+            return SENTRY_ERR_INVALID_ARG;     \
+        }                                      \
+    } while (0)
+
+// Named regions of the per-(device, stream) scratch arena.  Each region is its
+// own grow-only device allocation, so a region that grows does not move others.
+enum Region {
+    R_NODES_A = 0,   // Merkle stage output (leaf stage, even segment stages)
+    R_NODES_B,       // Merkle stage output (odd segment stages)
+    R_RED_0,         // ping-pong level buffers private to the node reduction
+    R_RED_1,
+    R_TABLES,        // segment / group tables on the device
+    R_SEG_ROOTS,     // per-segment roots when the caller does not want them
+    R_LT_H0,         // BLAKE2Xb root hashes, 64 B per record
+    R_LT_PART,       // per-workgroup lane partial sums
+    R_LT_SUM,        // running lane sum of the host-streaming entry point
+    R_STAGE0,        // device staging buffers of the host-streaming entry points
+    R_STAGE1,
+    R_STAGE_OFF0,    // staged record offsets
+    R_STAGE_OFF1,
+    R_COUNT
+};
+
+// Returns a device pointer of at least `bytes` bytes for (current device, stream, region).
+// Growing a region frees the old allocation, which synchronises the device.
+int scratch_get(hipStream_t stream, Region r, size_t bytes, void **out);
+
+// Pinned host staging for tables (per stream): returns a host pointer of >= bytes.  Before
+// the memory is reused the previous upload from it has completed (tracked by an event).
+int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr);
+// Record that an upload from the staging memory was enqueued on `stream`.
+int table_staging_mark(hipStream_t stream);
+
+// Side stream and events for the host-streaming entry points (per stream).
+struct CopyPipe {
+    hipStream_t copy_stream;
+    hipEvent_t copied[2];     // chunk k%2 has landed in its staging buffer
+    hipEvent_t consumed[2];   // the hash kernels have finished reading staging buffer k%2
+};
+int copy_pipe_get(hipStream_t stream, CopyPipe **out);
+
+// Device memory that kernels already enqueued on `stream` still read: freed by a later
+// sweep once the stream has passed the point of this call.
+int retire_device_memory(void *dev_ptr, hipStream_t stream);
+int sweep_retired();
+
+int release_all_scratch();
+
+}  // namespace sentry

@@ -1,0 +1,240 @@
+// Chunked and host-streaming entry points: a Merkle tree over a byte stream that arrives in
+// device chunks, and hashing while loading from pinned host memory (section 4.4: artifacts
+// are authenticated on the fly as they are loaded; two HIP streams and pinned
+// hipMemcpyAsync take the place of the paper's GPUDirect loads).
+//
+// Pipeline of the *_h2d calls: chunk k is copied on the side stream into staging buffer
+// k%2 while the kernels of chunk k-1 read buffer (k-1)%2 on the caller's stream.  Events
+// order "copy done -> hash" and "hash done -> buffer may be overwritten"; the host only
+// enqueues and never waits.
+#include <new>
+#include <vector>
+
+#include "sentry_internal.h"
+
+namespace sentry {
+int merkle_leaves_into(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *dst, hipStream_t s);
+int merkle_reduce_into(const uint8_t *dev_nodes, uint64_t n, uint8_t *out_digest, hipStream_t s);
+int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
+                uint16_t *out, bool accumulate, hipStream_t s);
+int lthash_presize(uint64_t max_records, hipStream_t s);
+}  // namespace sentry
+
+namespace {
+
+struct MerkleStream {
+    uint64_t magic;
+    size_t total_len, leaf_bytes, fed;
+    uint64_t n_leaves;
+    uint8_t *leaf_digests;   // device, 32 bytes per leaf of the whole stream
+};
+constexpr uint64_t STREAM_MAGIC = 0x53454e5452594d53ull;
+
+inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+extern "C" {
+
+int sentry_merkle_stream_begin(size_t total_len, size_t leaf_bytes, void **state)
+{
+    sentry::clear_error();
+    SENTRY_REQUIRE(state != nullptr, "sentry_merkle_stream_begin: NULL state");
+    SENTRY_REQUIRE(leaf_bytes > 0 && leaf_bytes % 64 == 0,
+                   "sentry_merkle_stream_begin: leaf_bytes must be a positive multiple of 64 (got %zu)", leaf_bytes);
+    MerkleStream *st = new (std::nothrow) MerkleStream();
+    if (!st) { sentry::set_error("sentry_merkle_stream_begin: out of host memory"); return SENTRY_ERR_NOMEM; }
+    st->magic = STREAM_MAGIC;
+    st->total_len = total_len;
+    st->leaf_bytes = leaf_bytes;
+    st->fed = 0;
+    st->n_leaves = ceil_div(total_len, leaf_bytes);
+    if (st->n_leaves == 0) st->n_leaves = 1;
+    (void)sentry::sweep_retired();
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, 32 * st->n_leaves);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        sentry::set_error("sentry_merkle_stream_begin: %zu bytes of leaf digests: %s", (size_t)(32 * st->n_leaves),
+                          hipGetErrorString(e));
+        delete st;
+        return SENTRY_ERR_NOMEM;
+    }
+    st->leaf_digests = static_cast<uint8_t *>(p);
+    *state = st;
+    return SENTRY_OK;
+}
+
+int sentry_merkle_stream_update(void *state, const void *dev_chunk, size_t len, void *stream)
+{
+    sentry::clear_error();
+    MerkleStream *st = static_cast<MerkleStream *>(state);
+    SENTRY_REQUIRE(st && st->magic == STREAM_MAGIC, "sentry_merkle_stream_update: bad state");
+    if (len == 0) return SENTRY_OK;
+    SENTRY_REQUIRE(dev_chunk != nullptr && (reinterpret_cast<uintptr_t>(dev_chunk) & 15) == 0,
+                   "sentry_merkle_stream_update: chunk must be non-NULL and 16-byte aligned");
+    SENTRY_REQUIRE(st->fed % st->leaf_bytes == 0,
+                   "sentry_merkle_stream_update: a chunk that is not a multiple of leaf_bytes must be the last");
+    SENTRY_REQUIRE(len <= st->total_len - st->fed, "sentry_merkle_stream_update: more than total_len bytes fed");
+    SENTRY_REQUIRE(len % st->leaf_bytes == 0 || st->fed + len == st->total_len,
+                   "sentry_merkle_stream_update: only the last chunk may end inside a leaf");
+    uint8_t *dst = st->leaf_digests + 32 * (st->fed / st->leaf_bytes);
+    int rc = sentry::merkle_leaves_into(dev_chunk, len, st->leaf_bytes, dst, static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+    st->fed += len;
+    return SENTRY_OK;
+}
+
+int sentry_merkle_stream_final(void *state, uint8_t *out_digest, void *stream)
+{
+    sentry::clear_error();
+    MerkleStream *st = static_cast<MerkleStream *>(state);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(st && st->magic == STREAM_MAGIC, "sentry_merkle_stream_final: bad state");
+    SENTRY_REQUIRE(out_digest != nullptr, "sentry_merkle_stream_final: NULL out_digest");
+    SENTRY_REQUIRE(st->fed == st->total_len, "sentry_merkle_stream_final: %zu of %zu bytes fed", st->fed, st->total_len);
+    if (st->total_len == 0) {   // one empty leaf
+        int rc = sentry::merkle_leaves_into(nullptr, 0, st->leaf_bytes, st->leaf_digests, s);
+        if (rc) return rc;
+    }
+    int rc = sentry::merkle_reduce_into(st->leaf_digests, st->n_leaves, out_digest, s);
+    if (rc) return rc;
+    // the leaf digests are still being read by the enqueued kernels: hand them to the
+    // retired list, which frees them once the stream has passed this point
+    rc = sentry::retire_device_memory(st->leaf_digests, s);
+    st->magic = 0;
+    delete st;
+    return rc;
+}
+
+int sentry_merkle_stream_abort(void *state)
+{
+    sentry::clear_error();
+    MerkleStream *st = static_cast<MerkleStream *>(state);
+    SENTRY_REQUIRE(st && st->magic == STREAM_MAGIC, "sentry_merkle_stream_abort: bad state");
+    SENTRY_HIP_CHECK(hipDeviceSynchronize());
+    SENTRY_HIP_CHECK(hipFree(st->leaf_digests));
+    st->magic = 0;
+    delete st;
+    return SENTRY_OK;
+}
+
+int sentry_merkle_root_h2d(const void *host_buf, size_t len, size_t leaf_bytes, size_t chunk_bytes,
+                           uint8_t *out_digest, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(leaf_bytes > 0 && leaf_bytes % 64 == 0,
+                   "sentry_merkle_root_h2d: leaf_bytes must be a positive multiple of 64 (got %zu)", leaf_bytes);
+    SENTRY_REQUIRE(chunk_bytes > 0 && chunk_bytes % leaf_bytes == 0,
+                   "sentry_merkle_root_h2d: chunk_bytes must be a positive multiple of leaf_bytes");
+    SENTRY_REQUIRE(host_buf != nullptr || len == 0, "sentry_merkle_root_h2d: NULL buffer");
+    SENTRY_REQUIRE((reinterpret_cast<uintptr_t>(host_buf) & 15) == 0, "sentry_merkle_root_h2d: buffer not 16-byte aligned");
+    SENTRY_REQUIRE(out_digest != nullptr, "sentry_merkle_root_h2d: NULL out_digest");
+    uint64_t n_leaves = ceil_div(len, leaf_bytes);
+    if (n_leaves == 0) n_leaves = 1;
+
+    void *stage[2], *digests;
+    const size_t stage_bytes = len < chunk_bytes ? (len ? len : 256) : chunk_bytes;
+    int rc = sentry::scratch_get(s, sentry::R_STAGE0, stage_bytes, &stage[0]);
+    if (rc) return rc;
+    rc = sentry::scratch_get(s, sentry::R_STAGE1, stage_bytes, &stage[1]);
+    if (rc) return rc;
+    rc = sentry::scratch_get(s, sentry::R_NODES_B, 32 * n_leaves, &digests);
+    if (rc) return rc;
+    sentry::CopyPipe *pipe;
+    rc = sentry::copy_pipe_get(s, &pipe);
+    if (rc) return rc;
+
+    // the side stream must not start overwriting the staging buffers before earlier work on
+    // the caller's stream (a previous call's kernels) has finished with them
+    SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[0], s));
+    SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[1], s));
+
+    const uint8_t *src = static_cast<const uint8_t *>(host_buf);
+    size_t off = 0;
+    uint64_t k = 0;
+    do {
+        const size_t sz = len - off < chunk_bytes ? len - off : chunk_bytes;
+        const int b = (int)(k & 1);
+        SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->consumed[b], 0));
+        if (sz) SENTRY_HIP_CHECK(hipMemcpyAsync(stage[b], src + off, sz, hipMemcpyHostToDevice, pipe->copy_stream));
+        SENTRY_HIP_CHECK(hipEventRecord(pipe->copied[b], pipe->copy_stream));
+        SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->copied[b], 0));
+        rc = sentry::merkle_leaves_into(stage[b], sz, leaf_bytes,
+                                        static_cast<uint8_t *>(digests) + 32 * (off / leaf_bytes), s);
+        if (rc) return rc;
+        SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], s));
+        off += sz;
+        k++;
+    } while (off < len);
+    return sentry::merkle_reduce_into(static_cast<const uint8_t *>(digests), n_leaves, out_digest, s);
+}
+
+int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, size_t n, size_t batch_bytes,
+                      uint16_t *out_lanes, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(out_lanes != nullptr && (reinterpret_cast<uintptr_t>(out_lanes) & 1) == 0,
+                   "sentry_lthash_h2d: out_lanes must be non-NULL and 2-byte aligned");
+    SENTRY_REQUIRE(batch_bytes > 0, "sentry_lthash_h2d: batch_bytes must be positive");
+    SENTRY_REQUIRE(n == 0 || host_offsets != nullptr, "sentry_lthash_h2d: NULL offsets");
+    if (n == 0) return sentry::lthash_into(nullptr, nullptr, 0, 0, out_lanes, false, s);
+    SENTRY_REQUIRE(host_records != nullptr || host_offsets[n] == host_offsets[0], "sentry_lthash_h2d: NULL records");
+
+    // cut the records into batches of at most batch_bytes at record boundaries (host side,
+    // offsets are host memory here); also the largest batch, to size the staging buffers
+    struct Batch { size_t first, count; };
+    std::vector<Batch> batches;
+    size_t max_bytes = 0, max_count = 0;
+    for (size_t i = 0; i < n;) {
+        size_t j = i;
+        while (j < n && host_offsets[j + 1] - host_offsets[i] <= batch_bytes) {
+            SENTRY_REQUIRE(host_offsets[j + 1] >= host_offsets[j], "sentry_lthash_h2d: offsets decrease at record %zu", j);
+            j++;
+        }
+        SENTRY_REQUIRE(j > i, "sentry_lthash_h2d: record %zu is longer than batch_bytes", i);
+        batches.push_back(Batch{i, j - i});
+        const size_t bytes = host_offsets[j] - host_offsets[i];
+        if (bytes > max_bytes) max_bytes = bytes;
+        if (j - i > max_count) max_count = j - i;
+        i = j;
+    }
+
+    void *stage[2], *stage_off[2];
+    int rc;
+    // spare bytes: the kernel reads the whole aligned word that holds a record's last byte
+    if ((rc = sentry::scratch_get(s, sentry::R_STAGE0, max_bytes + 8, &stage[0]))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_STAGE1, max_bytes + 8, &stage[1]))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_STAGE_OFF0, 8 * (max_count + 1), &stage_off[0]))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_STAGE_OFF1, 8 * (max_count + 1), &stage_off[1]))) return rc;
+    if ((rc = sentry::lthash_presize(max_count, s))) return rc;   // no regrowth inside the pipeline
+    sentry::CopyPipe *pipe;
+    if ((rc = sentry::copy_pipe_get(s, &pipe))) return rc;
+    SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[0], s));
+    SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[1], s));
+
+    const uint8_t *src = static_cast<const uint8_t *>(host_records);
+    for (size_t k = 0; k < batches.size(); k++) {
+        const Batch &bt = batches[k];
+        const int b = (int)(k & 1);
+        const uint64_t beg = host_offsets[bt.first], end = host_offsets[bt.first + bt.count];
+        SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->consumed[b], 0));
+        if (end > beg)
+            SENTRY_HIP_CHECK(hipMemcpyAsync(stage[b], src + beg, end - beg, hipMemcpyHostToDevice, pipe->copy_stream));
+        SENTRY_HIP_CHECK(hipMemcpyAsync(stage_off[b], host_offsets + bt.first, 8 * (bt.count + 1),
+                                        hipMemcpyHostToDevice, pipe->copy_stream));
+        SENTRY_HIP_CHECK(hipEventRecord(pipe->copied[b], pipe->copy_stream));
+        SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->copied[b], 0));
+        // record i of the batch sits at stage + (offset[i] - beg); the kernel copes with any
+        // byte alignment of a record
+        rc = sentry::lthash_into(stage[b], static_cast<const uint64_t *>(stage_off[b]), beg, bt.count, out_lanes,
+                                 k > 0, s);
+        if (rc) return rc;
+        SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], s));
+    }
+    return SENTRY_OK;
+}
+
+}  // extern "C"

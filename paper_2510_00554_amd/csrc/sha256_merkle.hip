@@ -1,0 +1,573 @@
+// SHA-256 Merkle tree on gfx950: block hashing kernel and reduction kernel of
+// section 4.2.1, the table-driven launch over fragmented tensors of section
+// 4.2.1 "In-place Hashing", and the per-tensor digests of Algorithm 2.
+//
+// Mapping: one leaf per lane (SHA-256 is serial inside a leaf), 256 leaves per
+// workgroup.  The workgroup folds its 256 leaf digests through eight tree
+// levels in LDS, so the leaf kernel emits one node per 256 leaves; later stages
+// fold 512 nodes per workgroup.  256- and 512-aligned groups reduce to the same
+// subtrees as the level-by-level rule, and only the last group of a buffer can
+// be partial, so the promoted odd node lands where the plain rule puts it.
+#include <cstring>
+#include <vector>
+
+#include "sentry_internal.h"
+
+namespace {
+
+constexpr int LEAF_WG = 256;          // lanes = leaves per workgroup of the leaf kernel
+constexpr int RED_WG = 256;           // lanes per workgroup of the reduce kernel
+constexpr int RED_IN = 2 * RED_WG;    // nodes folded by one reduce workgroup
+
+struct SegDesc {
+    const uint8_t *base;
+    uint64_t len;
+};
+
+// One workgroup's share of a stage: `count` consecutive items starting at `first`
+// (leaf index inside segment `seg` for the leaf kernel, node index in the input
+// array for the reduce kernel).
+struct Group {
+    uint64_t first;
+    uint32_t count;
+    uint32_t seg;
+};
+
+// ---------------------------------------------------------------------------
+// SHA-256 (FIPS 180-4) on 32-bit lanes
+// ---------------------------------------------------------------------------
+
+constexpr uint32_t k256(int t)
+{
+    constexpr uint32_t K[64] = {
+        0x428a2f98u, 0x71374491u, 0xb5c0fbcfu, 0xe9b5dba5u, 0x3956c25bu, 0x59f111f1u, 0x923f82a4u, 0xab1c5ed5u,
+        0xd807aa98u, 0x12835b01u, 0x243185beu, 0x550c7dc3u, 0x72be5d74u, 0x80deb1feu, 0x9bdc06a7u, 0xc19bf174u,
+        0xe49b69c1u, 0xefbe4786u, 0x0fc19dc6u, 0x240ca1ccu, 0x2de92c6fu, 0x4a7484aau, 0x5cb0a9dcu, 0x76f988dau,
+        0x983e5152u, 0xa831c66du, 0xb00327c8u, 0xbf597fc7u, 0xc6e00bf3u, 0xd5a79147u, 0x06ca6351u, 0x14292967u,
+        0x27b70a85u, 0x2e1b2138u, 0x4d2c6dfcu, 0x53380d13u, 0x650a7354u, 0x766a0abbu, 0x81c2c92eu, 0x92722c85u,
+        0xa2bfe8a1u, 0xa81a664bu, 0xc24b8b70u, 0xc76c51a3u, 0xd192e819u, 0xd6990624u, 0xf40e3585u, 0x106aa070u,
+        0x19a4c116u, 0x1e376c08u, 0x2748774cu, 0x34b0bcb5u, 0x391c0cb3u, 0x4ed8aa4au, 0x5b9cca4fu, 0x682e6ff3u,
+        0x748f82eeu, 0x78a5636fu, 0x84c87814u, 0x8cc70208u, 0x90befffau, 0xa4506cebu, 0xbef9a3f7u, 0xc67178f2u};
+    return K[t];
+}
+
+constexpr uint32_t crotr(uint32_t x, int n) { return (x >> n) | (x << (32 - n)); }
+
+// K[t] + W[t] of the second block of a 64-byte message: 0x80, zeros, bit length 512.
+// The block is the same for every inner node, so its message schedule is a constant.
+struct KW64 {
+    uint32_t v[64];
+};
+constexpr KW64 make_pad64()
+{
+    uint32_t w[64] = {};
+    w[0] = 0x80000000u;
+    w[15] = 512u;
+    for (int t = 16; t < 64; t++) {
+        uint32_t s0 = crotr(w[t - 15], 7) ^ crotr(w[t - 15], 18) ^ (w[t - 15] >> 3);
+        uint32_t s1 = crotr(w[t - 2], 17) ^ crotr(w[t - 2], 19) ^ (w[t - 2] >> 10);
+        w[t] = s1 + w[t - 7] + s0 + w[t - 16];
+    }
+    KW64 r = {};
+    for (int t = 0; t < 64; t++) r.v[t] = k256(t) + w[t];
+    return r;
+}
+
+// gfx950 has a three-input boolean instruction (v_bitop3_b32); the immediate is the truth
+// table of the function evaluated on a = 0xF0, b = 0xCC, c = 0xAA.
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) { return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96); }
+__device__ __forceinline__ uint32_t ch(uint32_t e, uint32_t f, uint32_t g) { return __builtin_amdgcn_bitop3_b32(e, f, g, 0xCA); }
+__device__ __forceinline__ uint32_t maj(uint32_t a, uint32_t b, uint32_t c) { return __builtin_amdgcn_bitop3_b32(a, b, c, 0xE8); }
+__device__ __forceinline__ uint32_t rotr(uint32_t x, uint32_t n) { return __builtin_amdgcn_alignbit(x, x, n); }
+__device__ __forceinline__ uint32_t bsig0(uint32_t x) { return xor3(rotr(x, 2), rotr(x, 13), rotr(x, 22)); }
+__device__ __forceinline__ uint32_t bsig1(uint32_t x) { return xor3(rotr(x, 6), rotr(x, 11), rotr(x, 25)); }
+__device__ __forceinline__ uint32_t ssig0(uint32_t x) { return xor3(rotr(x, 7), rotr(x, 18), x >> 3); }
+__device__ __forceinline__ uint32_t ssig1(uint32_t x) { return xor3(rotr(x, 17), rotr(x, 19), x >> 10); }
+
+#define SENTRY_H0 {0x6a09e667u, 0xbb67ae85u, 0x3c6ef372u, 0xa54ff53au, 0x510e527fu, 0x9b05688cu, 0x1f83d9abu, 0x5be0cd19u}
+
+// One compression: st <- st + rounds(st, block).  w holds the 16 big-endian words of
+// the block and is overwritten by the rolling message schedule.  The eight working
+// variables stay in fixed registers; the role of each register rotates with t.
+__device__ __forceinline__ void sha256_compress(uint32_t (&st)[8], uint32_t (&w)[16])
+{
+    uint32_t v[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = st[i];
+#pragma unroll
+    for (int t = 0; t < 64; t++) {
+        uint32_t wt;
+        if (t < 16) {
+            wt = w[t];
+        } else {
+            wt = w[t & 15] + ssig0(w[(t + 1) & 15]) + w[(t + 9) & 15] + ssig1(w[(t + 14) & 15]);
+            w[t & 15] = wt;
+        }
+#define V(i) v[((i) - t) & 7]
+        uint32_t t1 = V(7) + bsig1(V(4)) + ch(V(4), V(5), V(6)) + k256(t) + wt;
+        V(3) += t1;
+        V(7) = t1 + bsig0(V(0)) + maj(V(0), V(1), V(2));
+#undef V
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) st[i] += v[i];
+}
+
+// The compression of the constant padding block that ends every 64-byte message.
+__device__ __forceinline__ void sha256_compress_pad64(uint32_t (&st)[8])
+{
+    constexpr KW64 kw = make_pad64();
+    uint32_t v[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = st[i];
+#pragma unroll
+    for (int t = 0; t < 64; t++) {
+#define V(i) v[((i) - t) & 7]
+        uint32_t t1 = V(7) + bsig1(V(4)) + ch(V(4), V(5), V(6)) + kw.v[t];
+        V(3) += t1;
+        V(7) = t1 + bsig0(V(0)) + maj(V(0), V(1), V(2));
+#undef V
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) st[i] += v[i];
+}
+
+// node = SHA-256(left || right); words are the big-endian words of the digests
+__device__ __forceinline__ void node_hash(const uint32_t (&l)[8], const uint32_t (&r)[8], uint32_t (&out)[8])
+{
+    uint32_t st[8] = SENTRY_H0;
+    uint32_t w[16];
+#pragma unroll
+    for (int i = 0; i < 8; i++) { w[i] = l[i]; w[8 + i] = r[i]; }
+    sha256_compress(st, w);
+    sha256_compress_pad64(st);
+#pragma unroll
+    for (int i = 0; i < 8; i++) out[i] = st[i];
+}
+
+// Padding blocks of a leaf of llen bytes whose last r = llen % 64 bytes start at tail:
+// k = 0 is the block holding those bytes and 0x80, k = 1 the extra block needed when
+// r >= 56.  Only whole 4-byte words inside the leaf and single bytes are read.
+__device__ __forceinline__ void build_tail(uint32_t (&w)[16], const uint8_t *tail, uint32_t r,
+                                           uint64_t llen, uint32_t k)
+{
+#pragma unroll
+    for (int i = 0; i < 16; i++) w[i] = 0;
+    if (k == 0) {
+        const uint32_t *tw = reinterpret_cast<const uint32_t *>(tail);   // leaf starts are 16-byte aligned
+        const uint32_t rw = r >> 2, rb = r & 3;
+        uint32_t part = 0x80u << (24 - 8 * rb);
+        for (uint32_t j = 0; j < rb; j++) part |= (uint32_t)tail[4 * rw + j] << (24 - 8 * j);
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            if ((uint32_t)(4 * i + 4) <= r) w[i] = __builtin_bswap32(tw[i]);
+            if ((uint32_t)i == rw) w[i] = part;
+        }
+    }
+    if (k == 1 || r < 56) {
+        const uint64_t bits = llen * 8;
+        w[14] = (uint32_t)(bits >> 32);
+        w[15] = (uint32_t)bits;
+    }
+}
+
+// SHA-256 of llen bytes at p (16-byte aligned).  Full blocks come in as four 16-byte
+// loads, fetched one block ahead of the compression that uses them.
+__device__ __forceinline__ void hash_leaf(uint32_t (&st)[8], const uint8_t *p, uint64_t llen)
+{
+    const uint64_t nblk = llen >> 6;
+    const uint32_t r = (uint32_t)(llen & 63);
+    const uint64_t total = nblk + 1 + (r >= 56 ? 1 : 0);
+    const uint4 *q = reinterpret_cast<const uint4 *>(p);
+    uint4 c0 = {}, c1 = {}, c2 = {}, c3 = {};
+    if (nblk) { c0 = q[0]; c1 = q[1]; c2 = q[2]; c3 = q[3]; }
+    for (uint64_t b = 0; b < total; b++) {
+        uint32_t w[16];
+        if (b < nblk) {
+            w[0] = __builtin_bswap32(c0.x); w[1] = __builtin_bswap32(c0.y);
+            w[2] = __builtin_bswap32(c0.z); w[3] = __builtin_bswap32(c0.w);
+            w[4] = __builtin_bswap32(c1.x); w[5] = __builtin_bswap32(c1.y);
+            w[6] = __builtin_bswap32(c1.z); w[7] = __builtin_bswap32(c1.w);
+            w[8] = __builtin_bswap32(c2.x); w[9] = __builtin_bswap32(c2.y);
+            w[10] = __builtin_bswap32(c2.z); w[11] = __builtin_bswap32(c2.w);
+            w[12] = __builtin_bswap32(c3.x); w[13] = __builtin_bswap32(c3.y);
+            w[14] = __builtin_bswap32(c3.z); w[15] = __builtin_bswap32(c3.w);
+            q += 4;
+            if (b + 1 < nblk) { c0 = q[0]; c1 = q[1]; c2 = q[2]; c3 = q[3]; }
+        } else {
+            build_tail(w, p + (nblk << 6), r, llen, (uint32_t)(b - nblk));
+        }
+        sha256_compress(st, w);
+    }
+}
+
+// Store a digest (big-endian words) as its 32 canonical bytes.
+__device__ __forceinline__ void store_digest(uint8_t *out, const uint32_t (&d)[8])
+{
+    if ((reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+        uint4 *o = reinterpret_cast<uint4 *>(out);
+        o[0] = make_uint4(__builtin_bswap32(d[0]), __builtin_bswap32(d[1]), __builtin_bswap32(d[2]), __builtin_bswap32(d[3]));
+        o[1] = make_uint4(__builtin_bswap32(d[4]), __builtin_bswap32(d[5]), __builtin_bswap32(d[6]), __builtin_bswap32(d[7]));
+    } else {
+        for (int i = 0; i < 8; i++)
+            for (int j = 0; j < 4; j++) out[4 * i + j] = (uint8_t)(d[i] >> (24 - 8 * j));
+    }
+}
+
+__device__ __forceinline__ void load_digest(const uint8_t *in, uint32_t (&d)[8])   // 16-byte aligned
+{
+    const uint4 *p = reinterpret_cast<const uint4 *>(in);
+    uint4 a = p[0], b = p[1];
+    d[0] = __builtin_bswap32(a.x); d[1] = __builtin_bswap32(a.y);
+    d[2] = __builtin_bswap32(a.z); d[3] = __builtin_bswap32(a.w);
+    d[4] = __builtin_bswap32(b.x); d[5] = __builtin_bswap32(b.y);
+    d[6] = __builtin_bswap32(b.z); d[7] = __builtin_bswap32(b.w);
+}
+
+// Fold cnt (<= WG) nodes held in lds[0] (word-major: lds[buf][word][node]) to one node by
+// the pairwise rule; a lone last node moves up unchanged.  All lanes of the workgroup
+// call this; on return lane 0 holds the result in out.
+template <int WG>
+__device__ __forceinline__ void wg_tree_fold(uint32_t (&lds)[2][8][WG], uint32_t cnt, uint32_t tid,
+                                             uint32_t (&out)[8])
+{
+    int cur = 0;
+    while (cnt > 1) {
+        const uint32_t pairs = cnt >> 1;
+        if (tid < pairs) {
+            uint32_t l[8], r[8], d[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) { l[i] = lds[cur][i][2 * tid]; r[i] = lds[cur][i][2 * tid + 1]; }
+            node_hash(l, r, d);
+#pragma unroll
+            for (int i = 0; i < 8; i++) lds[cur ^ 1][i][tid] = d[i];
+        } else if (tid == pairs && (cnt & 1)) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) lds[cur ^ 1][i][pairs] = lds[cur][i][cnt - 1];
+        }
+        __syncthreads();
+        cnt = pairs + (cnt & 1);
+        cur ^= 1;
+    }
+    if (tid == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) out[i] = lds[cur][i][0];
+    }
+}
+
+// Block hashing kernel.  FUSE: fold the workgroup's leaves in LDS and store one node per
+// workgroup at out + 32*blockIdx; otherwise store every leaf digest at out + 32*leaf.
+template <bool FUSE, bool SEGMENTED>
+__global__ void __launch_bounds__(LEAF_WG)
+merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const SegDesc *segs,
+                   const Group *groups, uint64_t leaf_bytes, uint8_t *out)
+{
+    const uint32_t g = blockIdx.x, tid = threadIdx.x;
+    const uint8_t *base;
+    uint64_t seglen, first;
+    uint32_t count;
+    if (SEGMENTED) {
+        const Group gr = groups[g];
+        const SegDesc sd = segs[gr.seg];
+        base = sd.base; seglen = sd.len; first = gr.first; count = gr.count;
+    } else {
+        base = base0; seglen = len0; first = (uint64_t)g * LEAF_WG;
+        const uint64_t rem = nleaves0 - first;
+        count = rem < (uint64_t)LEAF_WG ? (uint32_t)rem : (uint32_t)LEAF_WG;
+    }
+    uint32_t st[8] = SENTRY_H0;
+    if (tid < count) {
+        const uint64_t start = (first + tid) * leaf_bytes;
+        const uint64_t left = seglen - start;            // 0 only for the empty buffer's single leaf
+        hash_leaf(st, base + start, left < leaf_bytes ? left : leaf_bytes);
+    }
+    if (!FUSE) {
+        if (tid < count) store_digest(out + 32 * (first + tid), st);
+        return;
+    }
+    __shared__ uint32_t lds[2][8][LEAF_WG];
+#pragma unroll
+    for (int i = 0; i < 8; i++) lds[0][i][tid] = st[i];
+    __syncthreads();
+    uint32_t root[8];
+    wg_tree_fold<LEAF_WG>(lds, count, tid, root);
+    if (tid == 0) store_digest(out + 32 * (uint64_t)g, root);
+}
+
+// Reduction kernel: each workgroup folds up to 512 consecutive nodes of one segment into one.
+template <bool SEGMENTED>
+__global__ void __launch_bounds__(RED_WG)
+merkle_reduce_kernel(const uint8_t *in, uint64_t n0, const Group *groups, uint8_t *out)
+{
+    const uint32_t g = blockIdx.x, tid = threadIdx.x;
+    uint64_t first;
+    uint32_t count;
+    if (SEGMENTED) {
+        const Group gr = groups[g];
+        first = gr.first; count = gr.count;
+    } else {
+        first = (uint64_t)g * RED_IN;
+        const uint64_t rem = n0 - first;
+        count = rem < (uint64_t)RED_IN ? (uint32_t)rem : (uint32_t)RED_IN;
+    }
+    __shared__ uint32_t lds[2][8][RED_WG];
+    const uint32_t pairs = count >> 1;
+    if (tid < pairs) {
+        uint32_t l[8], r[8], d[8];
+        load_digest(in + 32 * (first + 2 * tid), l);
+        load_digest(in + 32 * (first + 2 * tid + 1), r);
+        node_hash(l, r, d);
+#pragma unroll
+        for (int i = 0; i < 8; i++) lds[0][i][tid] = d[i];
+    } else if (tid == pairs && (count & 1)) {
+        uint32_t d[8];
+        load_digest(in + 32 * (first + count - 1), d);
+#pragma unroll
+        for (int i = 0; i < 8; i++) lds[0][i][tid] = d[i];
+    }
+    __syncthreads();
+    uint32_t root[8];
+    wg_tree_fold<RED_WG>(lds, pairs + (count & 1), tid, root);
+    if (tid == 0) store_digest(out + 32 * (uint64_t)g, root);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+inline uint64_t leaf_count(uint64_t len, uint64_t leaf_bytes)
+{
+    uint64_t n = ceil_div(len, leaf_bytes);
+    return n ? n : 1;
+}
+
+constexpr uint64_t MAX_GRID = 0x7fffffffull;
+
+int check_leaf_args(const char *fn, const void *buf, size_t len, size_t leaf_bytes)
+{
+    SENTRY_REQUIRE(leaf_bytes > 0 && leaf_bytes % 64 == 0,
+                   "%s: leaf_bytes must be a positive multiple of 64 (got %zu)", fn, leaf_bytes);
+    SENTRY_REQUIRE(buf != nullptr || len == 0, "%s: NULL buffer with len %zu", fn, len);
+    SENTRY_REQUIRE((reinterpret_cast<uintptr_t>(buf) & 15) == 0, "%s: buffer %p is not 16-byte aligned", fn, buf);
+    SENTRY_REQUIRE(ceil_div(leaf_count(len, leaf_bytes), LEAF_WG) <= MAX_GRID, "%s: too many leaves", fn);
+    return SENTRY_OK;
+}
+
+// Reduce n nodes at `in` (device, 16-byte aligned, not one of the R_RED regions) to one
+// digest at out_digest; intermediate levels ping-pong between the two R_RED regions.
+int reduce_nodes(const uint8_t *in, uint64_t n, uint8_t *out_digest, hipStream_t s)
+{
+    const uint8_t *src = in;
+    uint8_t *bufs[2] = {nullptr, nullptr};
+    uint64_t m = n;
+    int turn = 0;
+    do {   // at least one pass so that the result lands in out_digest
+        const uint64_t g = ceil_div(m, RED_IN);
+        uint8_t *dst;
+        if (g == 1) {
+            dst = out_digest;
+        } else {
+            if (!bufs[0]) {   // first pass is the largest
+                void *a, *b;
+                int rc = sentry::scratch_get(s, sentry::R_RED_0, 32 * g, &a);
+                if (rc) return rc;
+                rc = sentry::scratch_get(s, sentry::R_RED_1, 32 * g, &b);
+                if (rc) return rc;
+                bufs[0] = static_cast<uint8_t *>(a);
+                bufs[1] = static_cast<uint8_t *>(b);
+            }
+            dst = bufs[turn];
+        }
+        hipLaunchKernelGGL(merkle_reduce_kernel<false>, dim3((uint32_t)g), dim3(RED_WG), 0, s, src, m,
+                           (const Group *)nullptr, dst);
+        SENTRY_HIP_CHECK(hipGetLastError());
+        src = dst;
+        m = g;
+        turn ^= 1;
+    } while (m > 1);
+    return SENTRY_OK;
+}
+
+}  // namespace
+
+namespace sentry {
+
+// Leaf digests of a device chunk into dst (32 bytes per leaf), used by the streaming paths.
+int merkle_leaves_into(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *dst, hipStream_t s)
+{
+    const uint64_t n = leaf_count(len, leaf_bytes);
+    hipLaunchKernelGGL((merkle_leaf_kernel<false, false>), dim3((uint32_t)ceil_div(n, LEAF_WG)), dim3(LEAF_WG), 0, s,
+                       static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
+                       (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
+int merkle_reduce_into(const uint8_t *dev_nodes, uint64_t n, uint8_t *out_digest, hipStream_t s)
+{
+    return reduce_nodes(dev_nodes, n, out_digest, s);
+}
+
+}  // namespace sentry
+
+extern "C" {
+
+int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *out_digest, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = check_leaf_args("sentry_merkle_root", dev_buf, len, leaf_bytes);
+    if (rc) return rc;
+    SENTRY_REQUIRE(out_digest != nullptr, "sentry_merkle_root: NULL out_digest");
+    const uint64_t n = leaf_count(len, leaf_bytes);
+    const uint64_t g = ceil_div(n, LEAF_WG);
+    uint8_t *dst = out_digest;
+    if (g > 1) {
+        void *a;
+        rc = sentry::scratch_get(s, sentry::R_NODES_A, 32 * g, &a);
+        if (rc) return rc;
+        dst = static_cast<uint8_t *>(a);
+    }
+    hipLaunchKernelGGL((merkle_leaf_kernel<true, false>), dim3((uint32_t)g), dim3(LEAF_WG), 0, s,
+                       static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
+                       (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    if (g > 1) return reduce_nodes(dst, g, out_digest, s);
+    return SENTRY_OK;
+}
+
+int sentry_merkle_leaves(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *out_leaf_digests, void *stream)
+{
+    sentry::clear_error();
+    int rc = check_leaf_args("sentry_merkle_leaves", dev_buf, len, leaf_bytes);
+    if (rc) return rc;
+    SENTRY_REQUIRE(out_leaf_digests != nullptr && (reinterpret_cast<uintptr_t>(out_leaf_digests) & 15) == 0,
+                   "sentry_merkle_leaves: out_leaf_digests must be non-NULL and 16-byte aligned");
+    return sentry::merkle_leaves_into(dev_buf, len, leaf_bytes, out_leaf_digests, static_cast<hipStream_t>(stream));
+}
+
+int sentry_merkle_reduce(const uint8_t *dev_nodes, size_t n, uint8_t *out_digest, void *stream)
+{
+    sentry::clear_error();
+    SENTRY_REQUIRE(n >= 1, "sentry_merkle_reduce: n must be at least 1");
+    SENTRY_REQUIRE(dev_nodes != nullptr && (reinterpret_cast<uintptr_t>(dev_nodes) & 15) == 0,
+                   "sentry_merkle_reduce: dev_nodes must be non-NULL and 16-byte aligned");
+    SENTRY_REQUIRE(out_digest != nullptr, "sentry_merkle_reduce: NULL out_digest");
+    SENTRY_REQUIRE(ceil_div(n, RED_IN) <= MAX_GRID, "sentry_merkle_reduce: too many nodes");
+    return reduce_nodes(dev_nodes, n, out_digest, static_cast<hipStream_t>(stream));
+}
+
+int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes,
+                           uint8_t *out_seg_roots, uint8_t *out_root, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(n_seg >= 1, "sentry_merkle_segments: n_seg must be at least 1");
+    SENTRY_REQUIRE(dev_ptrs && lens && out_root, "sentry_merkle_segments: NULL argument");
+    SENTRY_REQUIRE(leaf_bytes > 0 && leaf_bytes % 64 == 0,
+                   "sentry_merkle_segments: leaf_bytes must be a positive multiple of 64 (got %zu)", leaf_bytes);
+    for (size_t t = 0; t < n_seg; t++) {
+        SENTRY_REQUIRE(dev_ptrs[t] != nullptr || lens[t] == 0, "sentry_merkle_segments: segment %zu is NULL", t);
+        SENTRY_REQUIRE((reinterpret_cast<uintptr_t>(dev_ptrs[t]) & 15) == 0,
+                       "sentry_merkle_segments: segment %zu is not 16-byte aligned", t);
+    }
+    SENTRY_REQUIRE(n_seg <= 0xffffffffull, "sentry_merkle_segments: too many segments");
+
+    // Stage tables, built on the host: stage 0 splits every segment's leaves into groups of
+    // 256; each later stage splits every segment's nodes into groups of 512, until every
+    // segment is down to one node.
+    std::vector<std::vector<Group>> stages;
+    std::vector<uint64_t> m(n_seg);   // nodes per segment after the current stage
+    {
+        std::vector<Group> g0;
+        for (size_t t = 0; t < n_seg; t++) {
+            const uint64_t nl = leaf_count(lens[t], leaf_bytes);
+            for (uint64_t f = 0; f < nl; f += LEAF_WG)
+                g0.push_back(Group{f, (uint32_t)(nl - f < LEAF_WG ? nl - f : LEAF_WG), (uint32_t)t});
+            m[t] = ceil_div(nl, LEAF_WG);
+        }
+        stages.push_back(std::move(g0));
+    }
+    for (;;) {
+        bool more = false;
+        for (size_t t = 0; t < n_seg; t++) more |= m[t] > 1;
+        if (!more) break;
+        std::vector<Group> gs;
+        uint64_t node0 = 0;
+        for (size_t t = 0; t < n_seg; t++) {
+            for (uint64_t f = 0; f < m[t]; f += RED_IN)
+                gs.push_back(Group{node0 + f, (uint32_t)(m[t] - f < RED_IN ? m[t] - f : RED_IN), (uint32_t)t});
+            node0 += m[t];
+            m[t] = ceil_div(m[t], RED_IN);
+        }
+        stages.push_back(std::move(gs));
+    }
+    size_t table_bytes = n_seg * sizeof(SegDesc);
+    for (auto &st : stages) {
+        SENTRY_REQUIRE(st.size() <= MAX_GRID, "sentry_merkle_segments: too many leaves");
+        table_bytes += st.size() * sizeof(Group);
+    }
+
+    void *host_tab, *dev_tab;
+    int rc = sentry::table_staging_get(s, table_bytes, &host_tab);
+    if (rc) return rc;
+    rc = sentry::scratch_get(s, sentry::R_TABLES, table_bytes, &dev_tab);
+    if (rc) return rc;
+    SegDesc *hseg = static_cast<SegDesc *>(host_tab);
+    for (size_t t = 0; t < n_seg; t++) hseg[t] = SegDesc{static_cast<const uint8_t *>(dev_ptrs[t]), lens[t]};
+    std::vector<const Group *> dev_groups;
+    {
+        char *hp = static_cast<char *>(host_tab) + n_seg * sizeof(SegDesc);
+        char *dp = static_cast<char *>(dev_tab) + n_seg * sizeof(SegDesc);
+        for (auto &st : stages) {
+            std::memcpy(hp, st.data(), st.size() * sizeof(Group));
+            dev_groups.push_back(reinterpret_cast<const Group *>(dp));
+            hp += st.size() * sizeof(Group);
+            dp += st.size() * sizeof(Group);
+        }
+    }
+    SENTRY_HIP_CHECK(hipMemcpyAsync(dev_tab, host_tab, table_bytes, hipMemcpyHostToDevice, s));
+    rc = sentry::table_staging_mark(s);
+    if (rc) return rc;
+
+    // where the per-segment roots end up
+    uint8_t *roots = out_seg_roots;
+    if (!roots || (reinterpret_cast<uintptr_t>(roots) & 15)) {
+        void *p;
+        rc = sentry::scratch_get(s, sentry::R_SEG_ROOTS, 32 * n_seg, &p);
+        if (rc) return rc;
+        roots = static_cast<uint8_t *>(p);
+    }
+    uint8_t *bufs[2] = {nullptr, nullptr};
+    if (stages.size() > 1) {
+        void *a, *b;
+        rc = sentry::scratch_get(s, sentry::R_NODES_A, 32 * stages[0].size(), &a);
+        if (rc) return rc;
+        rc = sentry::scratch_get(s, sentry::R_NODES_B, 32 * stages[1].size(), &b);
+        if (rc) return rc;
+        bufs[0] = static_cast<uint8_t *>(a);
+        bufs[1] = static_cast<uint8_t *>(b);
+    }
+    const SegDesc *dseg = static_cast<const SegDesc *>(dev_tab);
+    const uint8_t *src = nullptr;
+    for (size_t k = 0; k < stages.size(); k++) {
+        uint8_t *dst = (k + 1 == stages.size()) ? roots : bufs[k & 1];
+        const uint32_t grid = (uint32_t)stages[k].size();
+        if (k == 0) {
+            hipLaunchKernelGGL((merkle_leaf_kernel<true, true>), dim3(grid), dim3(LEAF_WG), 0, s,
+                               (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dev_groups[0],
+                               (uint64_t)leaf_bytes, dst);
+        } else {
+            hipLaunchKernelGGL(merkle_reduce_kernel<true>, dim3(grid), dim3(RED_WG), 0, s, src, (uint64_t)0,
+                               dev_groups[k], dst);
+        }
+        SENTRY_HIP_CHECK(hipGetLastError());
+        src = dst;
+    }
+    if (out_seg_roots && roots != out_seg_roots)
+        SENTRY_HIP_CHECK(hipMemcpyAsync(out_seg_roots, roots, 32 * n_seg, hipMemcpyDefault, s));
+    return reduce_nodes(roots, n_seg, out_root, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,235 @@
+"""Seeded synthetic inputs with the shapes of the paper's workloads.
+
+This module holds no hashing arithmetic.  It serves the GPU tests, ``bench.py`` and the
+scripts that write golden values, so every generator exists twice with bit-identical
+results: a numpy version (host, used with the CPU oracle) and a torch version (fills a
+tensor on the GPU without a host copy).  Both are the same counter-based construction
+in exact integer arithmetic, so a 138 GB checkpoint never has to exist in host memory to
+be reproducible:
+
+  word(seed, i)  = mix64(mix64(seed) + (i + 1) * GAMMA)        (the SplitMix64 sequence)
+  uniform bytes  = the little-endian bytes of word(seed, 0), word(seed, 1), ...
+  bf16 "normal"  = the sum of the four 16-bit fields of word(seed, i), centred, scaled to
+                   standard deviation 0.02 in float32 (one exact multiply) and rounded to
+                   bfloat16 (round to nearest even on the bit pattern).  The sum of four
+                   uniforms is close to a Gaussian (bounded at 3.46 sigma); hashing cost
+                   does not depend on the values.
+
+Shapes stand in for the paper's artifacts: 32x32x3 uint8 images (section 5, "Datasets
+and Models"), Llama-style checkpoints laid out tensor by tensor (a ``state_dict``,
+section 4.2), variable-length records.
+"""
+import math
+
+import numpy as np
+
+GAMMA = 0x9E3779B97F4A7C15
+M1 = 0xBF58476D1CE4E5B9
+M2 = 0x94D049BB133111EB
+MASK64 = (1 << 64) - 1
+BASE_SEED = 20251000
+
+# float32 scale that maps the centred four-field sum to standard deviation 0.02
+_SUM_STD = math.sqrt(4 * (65536.0 ** 2 - 1.0) / 12.0)
+SCALE32 = float(np.float32(0.02 / _SUM_STD))
+
+
+def _mix_int(z):
+    z &= MASK64
+    z = ((z ^ (z >> 30)) * M1) & MASK64
+    z = ((z ^ (z >> 27)) * M2) & MASK64
+    return z ^ (z >> 31)
+
+
+def _signed(x):
+    x &= MASK64
+    return x - (1 << 64) if x >= (1 << 63) else x
+
+
+# ---------------------------------------------------------------------------
+# numpy backend
+# ---------------------------------------------------------------------------
+
+def _words_np(seed, w0, w1):
+    key = np.uint64(_mix_int(seed))
+    with np.errstate(over="ignore"):
+        z = (np.arange(w0 + 1, w1 + 1, dtype=np.uint64) * np.uint64(GAMMA)) + key
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(M1)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(M2)
+        z = z ^ (z >> np.uint64(31))
+    return z
+
+
+def _bf16_bits_np(words):
+    s = ((words & np.uint64(0xFFFF)) + ((words >> np.uint64(16)) & np.uint64(0xFFFF))
+         + ((words >> np.uint64(32)) & np.uint64(0xFFFF)) + (words >> np.uint64(48)))
+    c = s.astype(np.int64) - 131070
+    x = c.astype(np.float32) * np.float32(SCALE32)
+    b = x.view(np.uint32).astype(np.uint64)
+    r = (b + np.uint64(0x7FFF) + ((b >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)
+    return r.astype(np.uint16)
+
+
+# ---------------------------------------------------------------------------
+# torch backend (any device)
+# ---------------------------------------------------------------------------
+
+def _lsr_t(z, k):
+    import torch
+    return torch.bitwise_and(torch.bitwise_right_shift(z, k), (1 << (64 - k)) - 1)
+
+
+def _words_t(seed, w0, w1, device):
+    import torch
+    key = _signed(_mix_int(seed))
+    z = torch.arange(w0 + 1, w1 + 1, dtype=torch.int64, device=device) * _signed(GAMMA) + key
+    z = (z ^ _lsr_t(z, 30)) * _signed(M1)
+    z = (z ^ _lsr_t(z, 27)) * _signed(M2)
+    return z ^ _lsr_t(z, 31)
+
+
+def _bf16_bits_t(words):
+    import torch
+    s = ((words & 0xFFFF) + (_lsr_t(words, 16) & 0xFFFF) + (_lsr_t(words, 32) & 0xFFFF) + _lsr_t(words, 48))
+    x = (s - 131070).to(torch.float32) * SCALE32
+    b = x.view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+    r = ((b + 0x7FFF + ((b >> 16) & 1)) >> 16) & 0xFFFF
+    return (((r + 0x8000) & 0xFFFF) - 0x8000).to(torch.int16)
+
+
+# ---------------------------------------------------------------------------
+# public generators
+# ---------------------------------------------------------------------------
+
+def uniform_bytes(seed, start, nbytes, device=None, out=None, chunk=1 << 27):
+    """Bytes [start, start+nbytes) of the uniform stream `seed`.
+
+    device None -> numpy uint8 array; otherwise a torch uint8 tensor on `device`
+    (written into `out` if given, a 1-D uint8 tensor of nbytes elements)."""
+    if device is None:
+        w0, w1 = start // 8, -(-(start + nbytes) // 8)
+        b = _words_np(seed, w0, w1).view(np.uint8)
+        return b[start - 8 * w0: start - 8 * w0 + nbytes].copy()
+    import torch
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    pos = 0
+    while pos < nbytes:
+        n = min(chunk, nbytes - pos)
+        s = start + pos
+        w0, w1 = s // 8, -(-(s + n) // 8)
+        b = _words_t(seed, w0, w1, device).view(torch.uint8)
+        out[pos:pos + n] = b[s - 8 * w0: s - 8 * w0 + n]
+        pos += n
+    return out
+
+
+def normal_bf16_bits(seed, start_elem, n, device=None, out=None, chunk=1 << 26):
+    """bf16 bit patterns of elements [start_elem, start_elem+n) of the weight stream `seed`.
+
+    device None -> numpy uint16 array; otherwise a torch int16 tensor (same bits)."""
+    if device is None:
+        return _bf16_bits_np(_words_np(seed, start_elem, start_elem + n))
+    import torch
+    if out is None:
+        out = torch.empty(n, dtype=torch.int16, device=device)
+    pos = 0
+    while pos < n:
+        m = min(chunk, n - pos)
+        out[pos:pos + m] = _bf16_bits_t(_words_t(seed, start_elem + pos, start_elem + pos + m, device))
+        pos += m
+    return out
+
+
+# ---------------------------------------------------------------------------
+# workload shapes
+# ---------------------------------------------------------------------------
+
+def llama_layout(layers, d, ffn, vocab, kv_dim=None):
+    """(name, numel) of every tensor of a Llama-style checkpoint in state-dict order."""
+    kv = d if kv_dim is None else kv_dim
+    out = [("embed", vocab * d)]
+    for i in range(layers):
+        out += [("l%d.q" % i, d * d), ("l%d.k" % i, kv * d), ("l%d.v" % i, kv * d), ("l%d.o" % i, d * d),
+                ("l%d.gate" % i, ffn * d), ("l%d.up" % i, ffn * d), ("l%d.down" % i, d * ffn),
+                ("l%d.input_norm" % i, d), ("l%d.post_attn_norm" % i, d)]
+    out += [("final_norm", d), ("lm_head", vocab * d)]
+    return out
+
+
+def layout_7b():
+    """32 layers, d=4096, ffn=11008, vocab 32000: 291 tensors, 13,476,831,232 bytes in bf16."""
+    return llama_layout(32, 4096, 11008, 32000)
+
+
+def layout_70b():
+    """80 layers, d=8192, ffn=28672, vocab 32000, 8 KV heads of 128: 723 tensors, 137,953,296,384 bytes."""
+    return llama_layout(80, 8192, 28672, 32000, kv_dim=1024)
+
+
+def layout_tiny():
+    """A small model of the same structure for tests: 2 layers, d=256, ffn=704, vocab 1000."""
+    return llama_layout(2, 256, 704, 1000, kv_dim=64)
+
+
+def tensor_seed(base_seed, index):
+    return base_seed + 1000 * (index + 1)
+
+
+def checkpoint_tensor(layout, index, base_seed=BASE_SEED, device=None):
+    """Tensor `index` of a checkpoint as bf16 bit patterns (numpy uint16 / torch int16)."""
+    return normal_bf16_bits(tensor_seed(base_seed, index), 0, layout[index][1], device=device)
+
+
+def checkpoint_bytes_np(layout, base_seed=BASE_SEED):
+    """All tensors as a list of numpy uint8 arrays (small layouts only)."""
+    return [checkpoint_tensor(layout, i, base_seed).view(np.uint8) for i in range(len(layout))]
+
+
+def checkpoint_flat_torch(layout, device, base_seed=BASE_SEED):
+    """The whole checkpoint as one uint8 tensor on `device`, tensors back to back, plus the
+    byte offset of every tensor."""
+    import torch
+    offs = [0]
+    for _, numel in layout:
+        offs.append(offs[-1] + 2 * numel)
+    buf = torch.empty(offs[-1], dtype=torch.uint8, device=device)
+    as16 = buf.view(torch.int16)
+    for i, (_, numel) in enumerate(layout):
+        normal_bf16_bits(tensor_seed(base_seed, i), 0, numel, device=device,
+                         out=as16[offs[i] // 2: offs[i] // 2 + numel])
+    return buf, offs
+
+
+def image_records(n, seed=BASE_SEED + 2, device=None):
+    """n samples of 32x32x3 uint8 (3072 bytes each), packed; returns (bytes, offsets)."""
+    data = uniform_bytes(seed, 0, 3072 * n, device=device)
+    off = np.arange(n + 1, dtype=np.uint64) * np.uint64(3072)
+    return data, off
+
+
+def lognormal_record_lengths(n, seed=BASE_SEED + 4, median=110_000, sigma=0.5, lo=8_000, hi=1_000_000):
+    """Record lengths in bytes: round(median * exp(sigma * z)) clipped to [lo, hi], z a
+    12-uniform-sum standard normal drawn from the counter generator (host, float64)."""
+    w = _words_np(seed, 0, 3 * n).reshape(n, 3)
+    fields = np.stack([(w >> np.uint64(16 * k)) & np.uint64(0xFFFF) for k in range(4)], axis=-1)
+    z = (fields.reshape(n, 12).astype(np.float64).sum(axis=1) - 6 * 65535.0) / math.sqrt(65536.0 ** 2 - 1.0)
+    ln = np.rint(median * np.exp(sigma * z))
+    return np.clip(ln, lo, hi).astype(np.uint64)
+
+
+def offsets_from_lengths(lengths):
+    off = np.zeros(len(lengths) + 1, np.uint64)
+    np.cumsum(lengths, out=off[1:])
+    return off
+
+
+def cut_batches(offsets, batch_bytes):
+    """Record index ranges [(first, last_exclusive), ...] whose bytes fit batch_bytes each."""
+    out, i, n = [], 0, len(offsets) - 1
+    while i < n:
+        j = int(np.searchsorted(offsets, offsets[i] + np.uint64(batch_bytes), side="right")) - 1
+        j = min(max(j, i + 1), n)
+        out.append((i, j))
+        i = j
+    return out

@@ -16,3 +16,15 @@ def golden_lines(name):
     """Non-comment lines of a text fixture under tests/golden/."""
     with open(os.path.join(GOLDEN, name)) as f:
         return [ln.rstrip("\n") for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def to_dev(a):
+    """numpy array -> torch tensor on cuda:0 (same bytes)."""
+    import numpy as np
+    import torch
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint64:
+        return torch.from_numpy(a.view(np.int64)).cuda()
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda()
+    return torch.from_numpy(a).cuda()

@@ -1,0 +1,73 @@
+"""The C-ABI library loads without a GPU, exports every entry point the header declares,
+and rejects bad arguments on the host before any GPU work (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2510_00554_amd as sentry
+from paper_2510_00554_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sentry.h")).read()
+    return sorted(set(re.findall(r"SENTRY_API[^;(]*?\b(sentry_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    lib = ctypes.CDLL(sentry.lib_path())
+    names = declared_symbols()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.PROTOTYPES) == names
+    for n in names:
+        assert callable(getattr(sentry, n)), n
+
+
+def test_verify_is_host_only():
+    a = bytes(range(32))
+    assert sentry.sentry_verify(a, a) == 0
+    b = bytearray(a)
+    b[31] ^= 0x80
+    assert sentry.sentry_verify(a, bytes(b)) == 1
+    with pytest.raises(sentry.SentryError) as e:
+        sentry.sentry_verify(None, a)
+    assert e.value.code == binding.ERR_INVALID_ARG and "NULL" in str(e.value)
+
+
+@pytest.mark.parametrize("call", [
+    lambda: sentry.sentry_merkle_root(0x1000, 4096, 0, 0x2000),          # leaf_bytes == 0
+    lambda: sentry.sentry_merkle_root(0x1000, 4096, 100, 0x2000),        # not a multiple of 64
+    lambda: sentry.sentry_merkle_root(0x1004, 4096, 64, 0x2000),         # misaligned buffer
+    lambda: sentry.sentry_merkle_root(0, 4096, 64, 0x2000),              # NULL with len > 0
+    lambda: sentry.sentry_merkle_root(0x1000, 4096, 64, 0),              # NULL output
+    lambda: sentry.sentry_merkle_leaves(0x1000, 4096, 64, 0x2008),       # misaligned output
+    lambda: sentry.sentry_merkle_reduce(0x1000, 0, 0x2000),              # n == 0
+    lambda: sentry.sentry_merkle_reduce(0x1008, 4, 0x2000),              # misaligned nodes
+    lambda: sentry.sentry_merkle_segments([], [], 64, 0, 0x2000),        # no segments
+    lambda: sentry.sentry_merkle_segments([0x1000, 0x3008], [64, 64], 64, 0, 0x2000),
+    lambda: sentry.sentry_merkle_segments([0x1000], [64], 96, 0, 0x2000),
+    lambda: sentry.sentry_merkle_root_h2d(0x1000, 4096, 64, 100, 0x2000),  # chunk not a leaf multiple
+    lambda: sentry.sentry_lthash(0x1000, 0, 5, 0x2000),                  # NULL offsets with n > 0
+    lambda: sentry.sentry_lthash(0x1000, 0x3004, 5, 0x2000),             # misaligned offsets
+    lambda: sentry.sentry_lthash(0x1000, 0x3000, 5, 0),                  # NULL lanes
+    lambda: sentry.sentry_lthash_combine(0, 0x2000),
+    lambda: sentry.sentry_lthash_remove(0x2001, 0x2000),
+    lambda: sentry.sentry_lthash_h2d(0x1000, 0x3000, 5, 0, 0x2000),      # batch_bytes == 0
+])
+def test_bad_arguments_are_rejected_on_the_host(call):
+    with pytest.raises(sentry.SentryError) as e:
+        call()
+    assert e.value.code == binding.ERR_INVALID_ARG
+    assert sentry.sentry_last_error() != ""
+
+
+def test_stream_state_checks():
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_merkle_stream_begin(1000, 65)
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_merkle_stream_update(None, 0x1000, 64)
