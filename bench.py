@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Benchmark of the artifact-hashing hot path on one MI355X.
+
+One step = one pass of the whole path over inputs already resident in HBM:
+  * Merkle root of the 70B-parameter bf16 checkpoint laid out as one byte stream
+    (137.95 GB, 64 KiB leaves)                         -> sentry_merkle_root, sentry_verify
+  * per-tensor roots + model root of the 7B checkpoint (291 tensors, 13.48 GB,
+    1 MiB leaves)                                      -> sentry_merkle_segments
+  * lattice hash of one 8 GB batch of variable-length records (log-normal lengths),
+    folded into the running sum                        -> sentry_lthash, sentry_lthash_combine
+`value` = bytes hashed per step / step time (GB = 1e9 bytes).  The host-to-device streaming
+legs are PCIe-bound and are reported beside it (`streaming`), never inside `value`.
+
+Prints one JSON line.  --quick shrinks every input (for smoke runs; the workload name says so).
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+ALU_PEAK_OPS = 256 * 4 * 16 * 2.4e9          # CUs x SIMDs x lanes x clock: 32-bit VALU lane-ops/s
+HBM_PEAK = 8.0e12
+
+# algorithmic 32-bit VALU operations of SHA-256 on gfx950 (rotate, 3-input boolean and
+# 3-input add are one instruction each): 64 rounds x 14 + 48 schedule steps x 10 + 16 byte
+# swaps + 8 feed-forward adds; a block whose message schedule is a constant (the padding
+# block of a fixed-size leaf, the second block of an inner node) needs rounds and adds only
+SHA_BLOCK_OPS = 64 * 14 + 48 * 10 + 16 + 8
+SHA_CONST_BLOCK_OPS = 64 * 14 + 8
+
+
+def merkle_ops(n_leaves, leaf_bytes, n_nodes):
+    per_leaf = (leaf_bytes // 64) * SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS
+    return n_leaves * per_leaf + n_nodes * (SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--quick", action="store_true", help="1/64-size inputs (not the reported workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip per-config and streaming side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (got --gpus %d); no multi-GPU figure exists" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    import paper_2510_00554_amd as sentry
+    from paper_2510_00554_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    sentry.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    t_setup = time.time()
+
+    def log(msg):
+        print("[bench %6.1fs] %s" % (time.time() - t_setup, msg), file=sys.stderr, flush=True)
+
+    # ---------------- inputs, resident in HBM ----------------
+    if args.quick:
+        lay70, lay7 = wl.llama_layout(4, 4096, 14336, 32000, kv_dim=512), wl.llama_layout(2, 2048, 5504, 32000)
+        batch_bytes, n_records_total = 128_000_000, 20_000
+    else:
+        lay70, lay7 = wl.layout_70b(), wl.layout_7b()
+        batch_bytes, n_records_total = 8_000_000_000, 1_281_167
+    need = 2 * sum(n for _, n in lay70) + 2 * sum(n for _, n in lay7) + batch_bytes + (2 << 30)
+    free, _ = torch.cuda.mem_get_info()
+    if free < need:
+        sys.exit("bench.py: needs %.1f GB of free HBM, %.1f GB available" % (need / 1e9, free / 1e9))
+
+    log("generating the 70B-shaped checkpoint (%d tensors)" % len(lay70))
+    ckpt70, _ = wl.checkpoint_flat_torch(lay70, dev)
+    log("generating the 7B-shaped checkpoint (%d tensors, one allocation each)" % len(lay7))
+    t7 = [wl.checkpoint_tensor(lay7, i, base_seed=wl.BASE_SEED + 3, device=dev) for i in range(len(lay7))]
+    t7_ptrs = [t.data_ptr() for t in t7]
+    t7_lens = [t.numel() * 2 for t in t7]
+    log("generating one batch of variable-length records")
+    lengths = wl.lognormal_record_lengths(n_records_total)
+    offsets = wl.offsets_from_lengths(lengths)
+    b0, b1 = wl.cut_batches(offsets, batch_bytes)[0]
+    rec_off = offsets[b0:b1 + 1]
+    rec_bytes = int(rec_off[-1] - rec_off[0])
+    n_rec = b1 - b0
+    records = wl.uniform_bytes(wl.BASE_SEED + 4, int(rec_off[0]), rec_bytes, device=dev)
+    d_off = torch.from_numpy(rec_off.view(np.int64).copy()).to(dev)
+    torch.cuda.synchronize()
+
+    LEAF70, LEAF7 = 64 << 10, 1 << 20
+    root70 = torch.zeros(32, dtype=torch.uint8, device=dev)
+    root7 = torch.zeros(32, dtype=torch.uint8, device=dev)
+    seg_roots = torch.zeros(32 * len(t7), dtype=torch.uint8, device=dev)
+    lanes = torch.zeros(1024, dtype=torch.int16, device=dev)
+    running = torch.zeros(1024, dtype=torch.int16, device=dev)
+    host_root = torch.zeros(32, dtype=torch.uint8).pin_memory()
+
+    bytes70, bytes7 = ckpt70.numel(), sum(t7_lens)
+    step_bytes = bytes70 + bytes7 + rec_bytes
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+
+    def step(expected=None, timed=None):
+        if timed is not None:
+            ev[0].record()
+        sentry.sentry_merkle_root(ckpt70.data_ptr(), bytes70, LEAF70, root70.data_ptr(), stream)
+        if timed is not None:
+            ev[1].record()
+        sentry.sentry_merkle_segments(t7_ptrs, t7_lens, LEAF7, seg_roots.data_ptr(), root7.data_ptr(), stream)
+        if timed is not None:
+            ev[2].record()
+        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), stream)
+        sentry.sentry_lthash_combine(running.data_ptr(), lanes.data_ptr(), stream)
+        if timed is not None:
+            ev[3].record()
+        host_root.copy_(root70, non_blocking=True)
+        torch.cuda.synchronize()
+        got = bytes(host_root.numpy())
+        if expected is not None and sentry.sentry_verify(got, expected) != 0:
+            sys.exit("bench.py: root changed between steps")
+        if timed is not None:
+            timed.append((ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])))
+        return got
+
+    log("warm-up")
+    expected = step()
+    for _ in range(max(args.warmup - 1, 0)):
+        step(expected)
+    log("timing %d steps" % args.steps)
+    parts = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(expected, parts)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    value = step_bytes / (dt / args.steps) / 1e9
+    ms70 = statistics.mean(p[0] for p in parts)
+    ms7 = statistics.mean(p[1] for p in parts)
+    mslt = statistics.mean(p[2] for p in parts)
+
+    # ---------------- roofline of the dominant kernel (SHA-256 leaf kernel, 70B stream) ----------------
+    n_leaves70 = -(-bytes70 // LEAF70)
+    full_leaves = bytes70 // LEAF70
+    # the leaf kernel hashes every leaf and folds each group of 256 leaf digests in LDS
+    groups = -(-n_leaves70 // 256)
+    ops_leaf_kernel = merkle_ops(full_leaves, LEAF70, n_leaves70 - groups)
+    if n_leaves70 != full_leaves:
+        ops_leaf_kernel += ((bytes70 - full_leaves * LEAF70) // 64) * SHA_BLOCK_OPS + SHA_BLOCK_OPS
+    achieved = ops_leaf_kernel / (ms70 * 1e-3)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath) and not args.quick:
+        traffic = json.load(open(tpath)).get("merkle_leaf_kernel_c5_bytes_per_launch")
+    roofline = {"kernel": "merkle_leaf_kernel (SHA-256 leaves + 8 in-LDS tree levels), 70B stream, 64 KiB leaves",
+                "bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_OPS / 1e12, "unit": "TOP/s",
+                "frac": achieved / ALU_PEAK_OPS, "traffic": traffic,
+                "ms_per_launch": ms70, "algorithmic_ops_per_launch": ops_leaf_kernel,
+                "algorithmic_bytes_per_launch": bytes70 + 32 * groups,
+                "hbm_frac": (bytes70 + 32 * groups) / (ms70 * 1e-3) / HBM_PEAK}
+
+    per_config = {
+        "C5_merkle_70b_64KiB_resident": {"GB/s": bytes70 / ms70 / 1e6, "ms": ms70, "bytes": bytes70},
+        "C3_merkle_7b_segments_1MiB": {"GB/s": bytes7 / ms7 / 1e6, "ms": ms7, "bytes": bytes7,
+                                       "leaves": sum(max(1, -(-l // LEAF7)) for l in t7_lens)},
+        "C4_lthash_one_8GB_batch_resident": {"GB/s": rec_bytes / mslt / 1e6, "ms": mslt, "bytes": rec_bytes,
+                                             "samples/s": n_rec / (mslt * 1e-3), "records": n_rec,
+                                             "longest_record": int(lengths[b0:b1].max())},
+    }
+
+    def timed_call(fn, reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a.record()
+            fn()
+            b.record()
+            b.synchronize()
+            ts.append(a.elapsed_time(b))
+        return statistics.median(ts)
+
+    streaming = None
+    if not args.no_extras:
+        log("side measurements: configs 1 and 2, streaming legs")
+        c1 = wl.uniform_bytes(wl.BASE_SEED + 1, 0, 16 << 20, device=dev)
+        ms = timed_call(lambda: sentry.sentry_merkle_root(c1.data_ptr(), c1.numel(), 4096, root7.data_ptr(), stream), 50)
+        per_config["C1_merkle_16MiB_4KiB"] = {"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()}
+        img, ioff = wl.image_records(50_000, device=dev)
+        d_ioff = torch.from_numpy(ioff.view(np.int64).copy()).to(dev)
+        ms = timed_call(lambda: sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream), 50)
+        per_config["C2_lthash_50k_images"] = {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(),
+                                              "samples/s": 50_000 / (ms * 1e-3)}
+        # host-to-device streaming: pinned host buffers, copy-only rate vs hash-while-loading rate
+        hbytes = (1 << 28) if args.quick else (4 << 30)
+        host = torch.empty(hbytes, dtype=torch.uint8).pin_memory()
+        host.copy_(ckpt70[:hbytes])
+        stage = torch.empty(hbytes, dtype=torch.uint8, device=dev)
+        ms_copy = timed_call(lambda: stage.copy_(host, non_blocking=True), 3)
+        chunk = min(hbytes, 256 << 20)
+        ms_m = timed_call(lambda: sentry.sentry_merkle_root_h2d(host.data_ptr(), hbytes, LEAF70, chunk,
+                                                                root7.data_ptr(), stream), 3)
+        nb = int(np.searchsorted(rec_off - rec_off[0], np.uint64(hbytes), side="right")) - 1
+        lt_bytes = int(rec_off[nb] - rec_off[0])
+        host[:lt_bytes].copy_(records[:lt_bytes])
+        h_off = torch.from_numpy((rec_off[:nb + 1] - rec_off[0]).view(np.int64).copy()).pin_memory()
+        ms_l = timed_call(lambda: sentry.sentry_lthash_h2d(host.data_ptr(), h_off.data_ptr(), nb, chunk,
+                                                           lanes.data_ptr(), stream), 3)
+        streaming = {"pinned_bytes": hbytes, "copy_only_GB/s": hbytes / ms_copy / 1e6,
+                     "merkle_h2d_GB/s": hbytes / ms_m / 1e6, "merkle_overlap_efficiency": ms_copy / ms_m,
+                     "lthash_h2d_GB/s": lt_bytes / ms_l / 1e6,
+                     "lthash_overlap_efficiency": (lt_bytes / hbytes) * ms_copy / ms_l, "chunk_bytes": chunk}
+        del host, stage
+
+    # ---------------- CPU baseline: the oracle, one thread, on a bounded sample ----------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        log("CPU baseline (oracle, 1 thread)")
+        m_bytes = (64 << 20) if args.quick else (2 << 30)
+        l_bytes = (32 << 20) if args.quick else (1 << 30)
+        sample_m = ckpt70[:m_bytes].cpu().numpy()
+        nb = int(np.searchsorted(rec_off - rec_off[0], np.uint64(l_bytes), side="right")) - 1
+        lt_b = int(rec_off[nb] - rec_off[0])
+        sample_l = records[:lt_b].cpu().numpy()
+        sample_off = (rec_off[:nb + 1] - rec_off[0]).copy()
+        t = time.perf_counter()
+        r_cpu = oracle.merkle_root(sample_m, LEAF70)
+        t_m = time.perf_counter() - t
+        t = time.perf_counter()
+        l_cpu = oracle.lthash(sample_l, sample_off)
+        t_l = time.perf_counter() - t
+        # the same sample on the GPU must agree
+        sentry.sentry_merkle_root(ckpt70.data_ptr(), m_bytes, LEAF70, root7.data_ptr(), stream)
+        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), nb, lanes.data_ptr(), stream)
+        torch.cuda.synchronize()
+        if bytes(root7.cpu().numpy()) != r_cpu or (lanes.cpu().numpy().view(np.uint16) != l_cpu).any():
+            sys.exit("bench.py: GPU result differs from the oracle on the CPU-baseline sample")
+        cpu = {"value": (m_bytes + lt_b) / (t_m + t_l) / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "Merkle over the first %d bytes of the 70B stream (64 KiB leaves) + lattice hash of the "
+                         "first %d records (%d bytes) of the batch; GPU results on the same sample match"
+                         % (m_bytes, nb, lt_b),
+               "merkle_GB/s": m_bytes / t_m / 1e9, "lthash_GB/s": lt_b / t_l / 1e9,
+               "host_cpus": os.cpu_count()}
+
+    out = {
+        "metric": "GB/s hashed on 1 MI355X (Merkle and lattice hash); fraction of ALU/HBM roofline",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": ("QUICK (1/64-size smoke inputs): " if args.quick else "") +
+                   "Merkle root of the 70B bf16 checkpoint stream resident in HBM (config 5 shape, 64 KiB leaves) + "
+                   "per-tensor roots and model root of the 7B checkpoint (config 3, 1 MiB leaves) + lattice hash of "
+                   "one 8 GB batch of log-normal records folded into the running sum (config 4 shape)",
+                   "bytes_per_step": step_bytes, "records_per_step": n_rec},
+        "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config, "streaming": streaming,
+        "root_70b": expected.hex(),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
