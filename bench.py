@@ -48,6 +48,10 @@ def main():
     ap.add_argument("--quick", action="store_true", help="1/64-size inputs (not the reported workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip per-config and streaming side measurements")
+    ap.add_argument("--merkle-prefix-gib", type=int, default=0,
+                    help="hash only the first N GiB of the 70B stream (for counter runs; the workload name says so)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 4 GiB device copy kernel (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (got --gpus %d); no multi-GPU figure exists" % args.gpus)
@@ -76,15 +80,24 @@ def main():
     else:
         lay70, lay7 = wl.layout_70b(), wl.layout_7b()
         batch_bytes, n_records_total = 8_000_000_000, 1_281_167
+    if args.merkle_prefix_gib:
+        # cut the layout after the tensors that cover the prefix, so that no more is generated
+        acc, cut = 0, []
+        for name, numel in lay70:
+            cut.append((name, numel))
+            acc += 2 * numel
+            if acc >= args.merkle_prefix_gib << 30:
+                break
+        lay70 = cut
     need = 2 * sum(n for _, n in lay70) + 2 * sum(n for _, n in lay7) + batch_bytes + (2 << 30)
     free, _ = torch.cuda.mem_get_info()
     if free < need:
         sys.exit("bench.py: needs %.1f GB of free HBM, %.1f GB available" % (need / 1e9, free / 1e9))
 
     log("generating the 70B-shaped checkpoint (%d tensors)" % len(lay70))
-    ckpt70, _ = wl.checkpoint_flat_torch(lay70, dev)
+    ckpt70, _ = wl.checkpoint_flat_torch(lay70, dev, base_seed=wl.SEED_C5)
     log("generating the 7B-shaped checkpoint (%d tensors, one allocation each)" % len(lay7))
-    t7 = [wl.checkpoint_tensor(lay7, i, base_seed=wl.BASE_SEED + 3, device=dev) for i in range(len(lay7))]
+    t7 = [wl.checkpoint_tensor(lay7, i, base_seed=wl.SEED_C3, device=dev) for i in range(len(lay7))]
     t7_ptrs = [t.data_ptr() for t in t7]
     t7_lens = [t.numel() * 2 for t in t7]
     log("generating one batch of variable-length records")
@@ -94,7 +107,7 @@ def main():
     rec_off = offsets[b0:b1 + 1]
     rec_bytes = int(rec_off[-1] - rec_off[0])
     n_rec = b1 - b0
-    records = wl.uniform_bytes(wl.BASE_SEED + 4, int(rec_off[0]), rec_bytes, device=dev)
+    records = wl.uniform_bytes(wl.SEED_C4_BYTES, int(rec_off[0]), rec_bytes, device=dev)
     d_off = torch.from_numpy(rec_off.view(np.int64).copy()).to(dev)
     torch.cuda.synchronize()
 
@@ -107,6 +120,8 @@ def main():
     host_root = torch.zeros(32, dtype=torch.uint8).pin_memory()
 
     bytes70, bytes7 = ckpt70.numel(), sum(t7_lens)
+    if args.merkle_prefix_gib:
+        bytes70 = min(bytes70, args.merkle_prefix_gib << 30)
     step_bytes = bytes70 + bytes7 + rec_bytes
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
 
@@ -131,6 +146,14 @@ def main():
         if timed is not None:
             timed.append((ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])))
         return got
+
+    if args.copy_probe:
+        # a plain copy of known size: 2^30 int32 elements read and written once by one kernel
+        src = torch.ones(1 << 30, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     log("warm-up")
     expected = step()
@@ -196,7 +219,7 @@ def main():
     streaming = None
     if not args.no_extras:
         log("side measurements: configs 1 and 2, streaming legs")
-        c1 = wl.uniform_bytes(wl.BASE_SEED + 1, 0, 16 << 20, device=dev)
+        c1 = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20, device=dev)
         ms = timed_call(lambda: sentry.sentry_merkle_root(c1.data_ptr(), c1.numel(), 4096, root7.data_ptr(), stream), 50)
         per_config["C1_merkle_16MiB_4KiB"] = {"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()}
         img, ioff = wl.image_records(50_000, device=dev)
@@ -262,6 +285,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
         "config": {"workload": ("QUICK (1/64-size smoke inputs): " if args.quick else "") +
+                   ("PREFIX RUN (first %d GiB of the 70B stream only): " % args.merkle_prefix_gib
+                    if args.merkle_prefix_gib else "") +
                    "Merkle root of the 70B bf16 checkpoint stream resident in HBM (config 5 shape, 64 KiB leaves) + "
                    "per-tensor roots and model root of the 7B checkpoint (config 3, 1 MiB leaves) + lattice hash of "
                    "one 8 GB batch of log-normal records folded into the running sum (config 4 shape)",

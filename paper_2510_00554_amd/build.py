@@ -8,6 +8,9 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsentry_hip.so")
 SOURCES = ["sentry_host.hip", "sha256_merkle.hip", "blake2_lthash.hip", "sentry_stream.hip"]
+# synthetic-input fill kernels for tests and bench.py: a library of its own, not part of the product
+WORKLOADS_LIB = os.path.join(HERE, "libsentry_workloads.so")
+WORKLOADS_SOURCE = "workloads_fill.hip"
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
@@ -47,6 +50,13 @@ def build(verbose=False):
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
     subprocess.run(cmd, check=True)
     os.replace(tmp, LIB)
+    tmp = WORKLOADS_LIB + ".tmp.%d" % os.getpid()
+    cmd = [hipcc()] + FLAGS + ["-shared", os.path.join(CSRC, WORKLOADS_SOURCE), "-o", tmp]
+    p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if p.returncode != 0:
+        sys.stderr.write(p.stdout)
+        raise RuntimeError("hipcc failed on " + WORKLOADS_SOURCE)
+    os.replace(tmp, WORKLOADS_LIB)
     return LIB
 
 

@@ -355,7 +355,8 @@ int sentry_lthash(const void *dev_records, const uint64_t *dev_offsets, size_t n
                    "sentry_lthash: out_lanes must be non-NULL and 2-byte aligned");
     SENTRY_REQUIRE(n == 0 || (dev_offsets != nullptr && (reinterpret_cast<uintptr_t>(dev_offsets) & 7) == 0),
                    "sentry_lthash: dev_offsets must be non-NULL and 8-byte aligned when n > 0");
-    SENTRY_REQUIRE(ceil_div(n, ROOT_WG) <= 0x7fffffffull, "sentry_lthash: too many records");
+    // a launch holds fewer than 2^32 work-items in all
+    SENTRY_REQUIRE(n <= 0xffffffffull - ROOT_WG, "sentry_lthash: too many records");
     return sentry::lthash_into(dev_records, dev_offsets, 0, n, out_lanes, false, static_cast<hipStream_t>(stream));
 }
 

@@ -342,7 +342,8 @@ inline uint64_t leaf_count(uint64_t len, uint64_t leaf_bytes)
     return n ? n : 1;
 }
 
-constexpr uint64_t MAX_GRID = 0x7fffffffull;
+// a launch holds fewer than 2^32 work-items in all (grid x workgroup size)
+constexpr uint64_t MAX_GRID = 0xffffffffull / 256;
 
 int check_leaf_args(const char *fn, const void *buf, size_t len, size_t leaf_bytes)
 {

@@ -29,6 +29,18 @@ M2 = 0x94D049BB133111EB
 MASK64 = (1 << 64) - 1
 BASE_SEED = 20251000
 
+_NP_BLOCK = 1 << 16   # words per numpy pass
+
+# seeds of the five target configurations
+SEED_C1 = BASE_SEED + 1          # 16 MiB of uniform bytes
+SEED_C2 = BASE_SEED + 2          # 50,000 image-shaped samples
+SEED_C3 = BASE_SEED + 3          # 7B checkpoint (per-tensor seeds derive from it)
+SEED_C4_LEN = BASE_SEED + 4      # record lengths
+SEED_C4_BYTES = BASE_SEED + 5    # record bytes: one uniform stream cut at record boundaries
+SEED_C5 = BASE_SEED + 6          # 70B checkpoint
+C4_RECORDS = 1_281_167
+C4_BATCH_BYTES = 8_000_000_000
+
 # float32 scale that maps the centred four-field sum to standard deviation 0.02
 _SUM_STD = math.sqrt(4 * (65536.0 ** 2 - 1.0) / 12.0)
 SCALE32 = float(np.float32(0.02 / _SUM_STD))
@@ -98,21 +110,62 @@ def _bf16_bits_t(words):
 
 
 # ---------------------------------------------------------------------------
+# HIP backend: the same two generators as fill kernels (libsentry_workloads.so), used for
+# CUDA tensors when the library is built; one launch per call instead of dozens of torch ops
+# ---------------------------------------------------------------------------
+
+_fill_lib = None
+
+
+def _hip_fill():
+    global _fill_lib
+    if _fill_lib is None:
+        import ctypes
+        import os
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsentry_workloads.so")
+        if not os.path.exists(path):
+            _fill_lib = False
+        else:
+            L = ctypes.CDLL(path)
+            u64, vp = ctypes.c_uint64, ctypes.c_void_p
+            L.workloads_fill_uniform.argtypes = [vp, u64, u64, u64, vp]
+            L.workloads_fill_uniform.restype = ctypes.c_int
+            L.workloads_fill_normal_bf16.argtypes = [vp, u64, u64, u64, ctypes.c_float, vp]
+            L.workloads_fill_normal_bf16.restype = ctypes.c_int
+            _fill_lib = L
+    return _fill_lib or None
+
+
+def _is_cuda(device):
+    return device is not None and str(device).startswith("cuda")
+
+
+# ---------------------------------------------------------------------------
 # public generators
 # ---------------------------------------------------------------------------
 
-def uniform_bytes(seed, start, nbytes, device=None, out=None, chunk=1 << 27):
+def uniform_bytes(seed, start, nbytes, device=None, out=None, chunk=1 << 27, backend=None):
     """Bytes [start, start+nbytes) of the uniform stream `seed`.
 
     device None -> numpy uint8 array; otherwise a torch uint8 tensor on `device`
     (written into `out` if given, a 1-D uint8 tensor of nbytes elements)."""
     if device is None:
+        # small blocks: the temporaries stay in cache and in the allocator's free lists
         w0, w1 = start // 8, -(-(start + nbytes) // 8)
-        b = _words_np(seed, w0, w1).view(np.uint8)
+        words = np.empty(w1 - w0, np.uint64)
+        for p in range(w0, w1, _NP_BLOCK):
+            q = min(p + _NP_BLOCK, w1)
+            words[p - w0:q - w0] = _words_np(seed, p, q)
+        b = words.view(np.uint8)
         return b[start - 8 * w0: start - 8 * w0 + nbytes].copy()
     import torch
     if out is None:
         out = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    if _is_cuda(device) and backend != "torch" and _hip_fill() is not None:
+        rc = _hip_fill().workloads_fill_uniform(out.data_ptr(), _mix_int(seed), start, nbytes,
+                                                torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+        return out
     pos = 0
     while pos < nbytes:
         n = min(chunk, nbytes - pos)
@@ -124,15 +177,24 @@ def uniform_bytes(seed, start, nbytes, device=None, out=None, chunk=1 << 27):
     return out
 
 
-def normal_bf16_bits(seed, start_elem, n, device=None, out=None, chunk=1 << 26):
+def normal_bf16_bits(seed, start_elem, n, device=None, out=None, chunk=1 << 26, backend=None):
     """bf16 bit patterns of elements [start_elem, start_elem+n) of the weight stream `seed`.
 
     device None -> numpy uint16 array; otherwise a torch int16 tensor (same bits)."""
     if device is None:
-        return _bf16_bits_np(_words_np(seed, start_elem, start_elem + n))
+        res = np.empty(n, np.uint16)
+        for p in range(0, n, _NP_BLOCK):
+            q = min(p + _NP_BLOCK, n)
+            res[p:q] = _bf16_bits_np(_words_np(seed, start_elem + p, start_elem + q))
+        return res
     import torch
     if out is None:
         out = torch.empty(n, dtype=torch.int16, device=device)
+    if _is_cuda(device) and backend != "torch" and _hip_fill() is not None:
+        rc = _hip_fill().workloads_fill_normal_bf16(out.data_ptr(), _mix_int(seed), start_elem, n, SCALE32,
+                                                    torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+        return out
     pos = 0
     while pos < n:
         m = min(chunk, n - pos)
@@ -201,14 +263,40 @@ def checkpoint_flat_torch(layout, device, base_seed=BASE_SEED):
     return buf, offs
 
 
-def image_records(n, seed=BASE_SEED + 2, device=None):
+def checkpoint_offsets(layout):
+    offs = [0]
+    for _, numel in layout:
+        offs.append(offs[-1] + 2 * numel)
+    return offs
+
+
+def checkpoint_stream_np(layout, start, nbytes, base_seed=BASE_SEED, offs=None):
+    """Bytes [start, start+nbytes) of the checkpoint laid out tensor by tensor (numpy uint8)."""
+    import bisect
+    offs = checkpoint_offsets(layout) if offs is None else offs
+    out = np.empty(nbytes, np.uint8)
+    pos = start
+    end = start + nbytes
+    i = bisect.bisect_right(offs, pos) - 1
+    while pos < end:
+        t_end = min(end, offs[i + 1])
+        e0, e1 = (pos - offs[i]) // 2, -(-(t_end - offs[i]) // 2)
+        piece = normal_bf16_bits(tensor_seed(base_seed, i), e0, e1 - e0).view(np.uint8)
+        lo = (pos - offs[i]) - 2 * e0
+        out[pos - start:t_end - start] = piece[lo:lo + (t_end - pos)]
+        pos = t_end
+        i += 1
+    return out
+
+
+def image_records(n, seed=SEED_C2, device=None):
     """n samples of 32x32x3 uint8 (3072 bytes each), packed; returns (bytes, offsets)."""
     data = uniform_bytes(seed, 0, 3072 * n, device=device)
     off = np.arange(n + 1, dtype=np.uint64) * np.uint64(3072)
     return data, off
 
 
-def lognormal_record_lengths(n, seed=BASE_SEED + 4, median=110_000, sigma=0.5, lo=8_000, hi=1_000_000):
+def lognormal_record_lengths(n, seed=SEED_C4_LEN, median=110_000, sigma=0.5, lo=8_000, hi=1_000_000):
     """Record lengths in bytes: round(median * exp(sigma * z)) clipped to [lo, hi], z a
     12-uniform-sum standard normal drawn from the counter generator (host, float64)."""
     w = _words_np(seed, 0, 3 * n).reshape(n, 3)

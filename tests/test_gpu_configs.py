@@ -1,0 +1,153 @@
+"""The five target configurations at full size on the GPU, against expected values that
+tests/golden/make_golden.py computed with the CPU oracle on the same synthetic inputs."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_00554_amd as sentry
+from paper_2510_00554_amd import workloads as wl
+from conftest import golden_lines, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def lanes_from_hex(text):
+    return np.array([int(x, 16) for x in text.split()], dtype=np.uint16)
+
+
+def free_gpu():
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def test_config1_root():
+    want = bytes.fromhex(golden_lines("config1_root.txt")[0])
+    buf = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20, device="cuda")
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_root(buf.data_ptr(), buf.numel(), 4096, out.data_ptr())
+    torch.cuda.synchronize()
+    assert sentry.sentry_verify(bytes(out.cpu().numpy()), want) == 0
+
+
+def test_config2_lanes_and_halves():
+    full, a, b = (lanes_from_hex(x) for x in golden_lines("config2_lanes.txt"))
+    data, off = wl.image_records(50_000, device="cuda")
+    d_off = to_dev(off)
+    out = [torch.zeros(1024, dtype=torch.int16, device="cuda") for _ in range(3)]
+    sentry.sentry_lthash(data.data_ptr(), d_off.data_ptr(), 50_000, out[0].data_ptr())
+    sentry.sentry_lthash(data.data_ptr(), d_off.data_ptr(), 25_000, out[1].data_ptr())
+    sentry.sentry_lthash(data.data_ptr(), d_off.data_ptr() + 8 * 25_000, 25_000, out[2].data_ptr())
+    torch.cuda.synchronize()
+    got = [o.cpu().numpy().view(np.uint16) for o in out]
+    assert (got[0] == full).all() and (got[1] == a).all() and (got[2] == b).all()
+    sentry.sentry_lthash_combine(out[1].data_ptr(), out[2].data_ptr())
+    torch.cuda.synchronize()
+    assert (out[1].cpu().numpy().view(np.uint16) == full).all()
+
+
+def test_config3_7b_checkpoint_per_tensor_roots():
+    lines = golden_lines("config3_roots.txt")
+    want_top = bytes.fromhex(lines[0])
+    want_roots = [bytes.fromhex(ln.split()[1]) for ln in lines[1:]]
+    lay = wl.layout_7b()
+    assert len(want_roots) == len(lay) == 291
+    tensors = [wl.checkpoint_tensor(lay, i, base_seed=wl.SEED_C3, device="cuda") for i in range(len(lay))]
+    roots = torch.zeros(32 * len(lay), dtype=torch.uint8, device="cuda")
+    top = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_segments([t.data_ptr() for t in tensors], [2 * t.numel() for t in tensors], 1 << 20,
+                                  roots.data_ptr(), top.data_ptr())
+    torch.cuda.synchronize()
+    got = roots.cpu().numpy().reshape(len(lay), 32)
+    bad = [lay[i][0] for i in range(len(lay)) if bytes(got[i]) != want_roots[i]]
+    assert not bad, bad[:5]
+    assert bytes(top.cpu().numpy()) == want_top
+    del tensors
+    free_gpu()
+
+
+def test_config4_streamed_lattice_hash_with_running_sum():
+    lines = golden_lines("config4_lanes.txt")
+    want_total = lanes_from_hex(lines[0])
+    want_batches = {}
+    for ln in lines[1:]:
+        _, k, a, b, lanes = ln.split(" ", 4)
+        want_batches[int(k)] = (int(a), int(b), lanes_from_hex(lanes))
+    off = wl.offsets_from_lengths(wl.lognormal_record_lengths(wl.C4_RECORDS))
+    batches = wl.cut_batches(off, wl.C4_BATCH_BYTES)
+    assert len(batches) == len(want_batches)
+    host = [torch.empty(wl.C4_BATCH_BYTES, dtype=torch.uint8).pin_memory() for _ in range(2)]
+    running = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    part = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    for k, (a, b) in enumerate(batches):
+        assert (a, b) == want_batches[k][:2]
+        nbytes = int(off[b] - off[a])
+        dev = wl.uniform_bytes(wl.SEED_C4_BYTES, int(off[a]), nbytes, device="cuda")
+        h = host[k & 1]
+        h[:nbytes].copy_(dev)                      # the batch now sits in pinned host memory
+        del dev
+        h_off = torch.from_numpy((off[a:b + 1] - off[a]).view(np.int64).copy())
+        # loaded in 1 GB pieces on the side stream while the previous piece is hashed
+        sentry.sentry_lthash_h2d(h.data_ptr(), h_off.data_ptr(), b - a, 1_000_000_000, part.data_ptr())
+        sentry.sentry_lthash_combine(running.data_ptr(), part.data_ptr())
+        torch.cuda.synchronize()
+        assert (part.cpu().numpy().view(np.uint16) == want_batches[k][2]).all(), "batch %d" % k
+        print("config 4: batch %d/%d ok" % (k + 1, len(batches)), flush=True)
+    assert (running.cpu().numpy().view(np.uint16) == want_total).all()
+    del host
+    free_gpu()
+
+
+def test_config5_70b_checkpoint_resident_and_streamed():
+    lines = golden_lines("config5_root.txt")
+    want = bytes.fromhex(lines[0])
+    want_leaves = {int(ln.split()[1]): bytes.fromhex(ln.split()[2]) for ln in lines[1:]}
+    lay = wl.layout_70b()
+    leaf = 64 << 10
+    buf, offs = wl.checkpoint_flat_torch(lay, "cuda", base_seed=wl.SEED_C5)
+    total = buf.numel()
+    assert total == 137_953_296_384
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    # resident, in the launch configuration bench.py times
+    sentry.sentry_merkle_root(buf.data_ptr(), total, leaf, out.data_ptr())
+    torch.cuda.synchronize()
+    assert sentry.sentry_verify(bytes(out.cpu().numpy()), want) == 0
+    # sampled leaf digests
+    d = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    for i, dig in want_leaves.items():
+        n = min(leaf, total - i * leaf)
+        sentry.sentry_merkle_leaves(buf.data_ptr() + i * leaf, n, leaf, d.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(d.cpu().numpy()) == dig, i
+    print("config 5: resident root ok", flush=True)
+    # streamed: pinned host chunks copied on a side stream into two device buffers, each hashed
+    # on the main stream while the next one loads; compared with the stored root
+    chunk = 1 << 30
+    host = [torch.empty(chunk, dtype=torch.uint8).pin_memory() for _ in range(2)]
+    stage = [torch.empty(chunk, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    copy_stream = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+    copied = [torch.cuda.Event() for _ in range(2)]
+    hashed = [torch.cuda.Event() for _ in range(2)]
+    st = sentry.sentry_merkle_stream_begin(total, leaf)
+    pos, k = 0, 0
+    while pos < total:
+        n = min(chunk, total - pos)
+        b = k & 1
+        hashed[b].synchronize()                        # host buffer b and stage b are free again
+        host[b][:n].copy_(buf[pos:pos + n])            # stands in for reading the file into pinned memory
+        torch.cuda.synchronize()
+        with torch.cuda.stream(copy_stream):
+            stage[b][:n].copy_(host[b][:n], non_blocking=True)
+            copied[b].record(copy_stream)
+        main.wait_event(copied[b])
+        sentry.sentry_merkle_stream_update(st, stage[b].data_ptr(), n, main.cuda_stream)
+        hashed[b].record(main)
+        pos += n
+        k += 1
+    sentry.sentry_merkle_stream_final(st, out.data_ptr(), main.cuda_stream)
+    torch.cuda.synchronize()
+    assert sentry.sentry_verify(bytes(out.cpu().numpy()), want) == 0
+    del buf, host, stage
+    free_gpu()

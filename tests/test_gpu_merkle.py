@@ -38,7 +38,7 @@ def test_leaf_counts_across_group_boundaries(n_leaves):
 
 
 def test_config1_16mib_4k_leaves():
-    buf = wl.uniform_bytes(wl.BASE_SEED + 1, 0, 16 << 20)
+    buf = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20)
     want = oracle.merkle_root(buf, 4096)
     got = gpu_root(buf, 4096)
     assert got == want

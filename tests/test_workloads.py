@@ -61,3 +61,10 @@ def test_checkpoint_flat_equals_per_tensor():
     assert offs[-1] == sum(p.size for p in per)
     for i, p in enumerate(per):
         assert (buf[offs[i]:offs[i + 1]].numpy() == p).all()
+
+
+def test_checkpoint_stream_ranges():
+    lay = wl.layout_tiny()
+    flat = np.concatenate(wl.checkpoint_bytes_np(lay))
+    for start, n in ((0, 1000), (511, 4097), (flat.size - 777, 777), (2 * lay[0][1] - 3, 10)):
+        assert (wl.checkpoint_stream_np(lay, start, n) == flat[start:start + n]).all(), (start, n)
