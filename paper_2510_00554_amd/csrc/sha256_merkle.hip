@@ -3,11 +3,12 @@
 // 4.2.1 "In-place Hashing", and the per-tensor digests of Algorithm 2.
 //
 // Mapping: one leaf per lane (SHA-256 is serial inside a leaf), 256 leaves per
-// workgroup.  The workgroup folds its 256 leaf digests through eight tree
-// levels in LDS, so the leaf kernel emits one node per 256 leaves; later stages
-// fold 512 nodes per workgroup.  256- and 512-aligned groups reduce to the same
-// subtrees as the level-by-level rule, and only the last group of a buffer can
-// be partial, so the promoted odd node lands where the plain rule puts it.
+// workgroup (64 when a launch has few leaves).  The workgroup folds its leaf
+// digests through eight (six) tree levels in LDS, so the leaf kernel emits one
+// node per 256 (64) leaves; later stages fold 512 nodes per workgroup.
+// Power-of-two-aligned groups reduce to the same subtrees as the level-by-level
+// rule, and only the last group of a buffer can be partial, so the promoted odd
+// node lands where the plain rule puts it.
 #include <cstring>
 #include <vector>
 
@@ -15,7 +16,15 @@
 
 namespace {
 
-constexpr int LEAF_WG = 256;          // lanes = leaves per workgroup of the leaf kernel
+#ifdef SENTRY_LEAF_WAVES
+#define SENTRY_LEAF_OCCUPANCY __attribute__((amdgpu_waves_per_eu(SENTRY_LEAF_WAVES, 8)))
+#else
+#define SENTRY_LEAF_OCCUPANCY
+#endif
+
+constexpr int LEAF_WG = 256;          // lanes = leaves per workgroup of the leaf kernel ...
+constexpr int LEAF_WG_SMALL = 64;     // ... and when there are too few leaves to fill the chip
+constexpr uint64_t SMALL_LAUNCH_WAVES = 2048;   // two waves per SIMD on 256 CUs x 4 SIMDs
 constexpr int RED_WG = 256;           // lanes per workgroup of the reduce kernel
 constexpr int RED_IN = 2 * RED_WG;    // nodes folded by one reduce workgroup
 
@@ -171,29 +180,39 @@ __device__ __forceinline__ void build_tail(uint32_t (&w)[16], const uint8_t *tai
     }
 }
 
-// SHA-256 of llen bytes at p (16-byte aligned).  Full blocks come in as four 16-byte
-// loads, fetched one block ahead of the compression that uses them.
+__device__ __forceinline__ void bswap_block(uint32_t (&w)[16], const uint4 &a, const uint4 &b, const uint4 &c,
+                                            const uint4 &d)
+{
+    w[0] = __builtin_bswap32(a.x); w[1] = __builtin_bswap32(a.y); w[2] = __builtin_bswap32(a.z); w[3] = __builtin_bswap32(a.w);
+    w[4] = __builtin_bswap32(b.x); w[5] = __builtin_bswap32(b.y); w[6] = __builtin_bswap32(b.z); w[7] = __builtin_bswap32(b.w);
+    w[8] = __builtin_bswap32(c.x); w[9] = __builtin_bswap32(c.y); w[10] = __builtin_bswap32(c.z); w[11] = __builtin_bswap32(c.w);
+    w[12] = __builtin_bswap32(d.x); w[13] = __builtin_bswap32(d.y); w[14] = __builtin_bswap32(d.z); w[15] = __builtin_bswap32(d.w);
+}
+
+// SHA-256 of llen bytes at p (16-byte aligned).  A lane walks its leaf in pairs of blocks:
+// the eight 16-byte loads of a pair cover one whole 128-byte cache line, so every line is
+// fetched by one burst of one lane and never has to survive in L2 between two visits.  The
+// loads of the next pair are issued before the second compression of the current pair.
 __device__ __forceinline__ void hash_leaf(uint32_t (&st)[8], const uint8_t *p, uint64_t llen)
 {
     const uint64_t nblk = llen >> 6;
     const uint32_t r = (uint32_t)(llen & 63);
     const uint64_t total = nblk + 1 + (r >= 56 ? 1 : 0);
     const uint4 *q = reinterpret_cast<const uint4 *>(p);
-    uint4 c0 = {}, c1 = {}, c2 = {}, c3 = {};
-    if (nblk) { c0 = q[0]; c1 = q[1]; c2 = q[2]; c3 = q[3]; }
+    uint4 c[8] = {};
+    if (nblk >= 1) { c[0] = q[0]; c[1] = q[1]; c[2] = q[2]; c[3] = q[3]; }
+    if (nblk >= 2) { c[4] = q[4]; c[5] = q[5]; c[6] = q[6]; c[7] = q[7]; }
     for (uint64_t b = 0; b < total; b++) {
         uint32_t w[16];
         if (b < nblk) {
-            w[0] = __builtin_bswap32(c0.x); w[1] = __builtin_bswap32(c0.y);
-            w[2] = __builtin_bswap32(c0.z); w[3] = __builtin_bswap32(c0.w);
-            w[4] = __builtin_bswap32(c1.x); w[5] = __builtin_bswap32(c1.y);
-            w[6] = __builtin_bswap32(c1.z); w[7] = __builtin_bswap32(c1.w);
-            w[8] = __builtin_bswap32(c2.x); w[9] = __builtin_bswap32(c2.y);
-            w[10] = __builtin_bswap32(c2.z); w[11] = __builtin_bswap32(c2.w);
-            w[12] = __builtin_bswap32(c3.x); w[13] = __builtin_bswap32(c3.y);
-            w[14] = __builtin_bswap32(c3.z); w[15] = __builtin_bswap32(c3.w);
-            q += 4;
-            if (b + 1 < nblk) { c0 = q[0]; c1 = q[1]; c2 = q[2]; c3 = q[3]; }
+            if ((b & 1) == 0) {
+                bswap_block(w, c[0], c[1], c[2], c[3]);
+            } else {
+                bswap_block(w, c[4], c[5], c[6], c[7]);
+                q += 8;                                  // blocks b+1 and b+2
+                if (b + 1 < nblk) { c[0] = q[0]; c[1] = q[1]; c[2] = q[2]; c[3] = q[3]; }
+                if (b + 2 < nblk) { c[4] = q[4]; c[5] = q[5]; c[6] = q[6]; c[7] = q[7]; }
+            }
         } else {
             build_tail(w, p + (nblk << 6), r, llen, (uint32_t)(b - nblk));
         }
@@ -257,8 +276,12 @@ __device__ __forceinline__ void wg_tree_fold(uint32_t (&lds)[2][8][WG], uint32_t
 
 // Block hashing kernel.  FUSE: fold the workgroup's leaves in LDS and store one node per
 // workgroup at out + 32*blockIdx; otherwise store every leaf digest at out + 32*leaf.
-template <bool FUSE, bool SEGMENTED>
-__global__ void __launch_bounds__(LEAF_WG)
+// WG = leaves per workgroup: 256, or 64 (one wave per workgroup) for launches with few leaves.
+// A lone wave on a SIMD issues faster than two that share it, so a launch that cannot give
+// every SIMD two waves is cut into single-wave workgroups, which the dispatcher spreads over
+// all SIMDs of the chip.
+template <int WG, bool FUSE, bool SEGMENTED>
+__global__ void __launch_bounds__(WG) SENTRY_LEAF_OCCUPANCY
 merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const SegDesc *segs,
                    const Group *groups, uint64_t leaf_bytes, uint8_t *out)
 {
@@ -271,9 +294,9 @@ merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const
         const SegDesc sd = segs[gr.seg];
         base = sd.base; seglen = sd.len; first = gr.first; count = gr.count;
     } else {
-        base = base0; seglen = len0; first = (uint64_t)g * LEAF_WG;
+        base = base0; seglen = len0; first = (uint64_t)g * WG;
         const uint64_t rem = nleaves0 - first;
-        count = rem < (uint64_t)LEAF_WG ? (uint32_t)rem : (uint32_t)LEAF_WG;
+        count = rem < (uint64_t)WG ? (uint32_t)rem : (uint32_t)WG;
     }
     uint32_t st[8] = SENTRY_H0;
     if (tid < count) {
@@ -285,12 +308,12 @@ merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const
         if (tid < count) store_digest(out + 32 * (first + tid), st);
         return;
     }
-    __shared__ uint32_t lds[2][8][LEAF_WG];
+    __shared__ uint32_t lds[2][8][WG];
 #pragma unroll
     for (int i = 0; i < 8; i++) lds[0][i][tid] = st[i];
     __syncthreads();
     uint32_t root[8];
-    wg_tree_fold<LEAF_WG>(lds, count, tid, root);
+    wg_tree_fold<WG>(lds, count, tid, root);
     if (tid == 0) store_digest(out + 32 * (uint64_t)g, root);
 }
 
@@ -398,9 +421,14 @@ namespace sentry {
 int merkle_leaves_into(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *dst, hipStream_t s)
 {
     const uint64_t n = leaf_count(len, leaf_bytes);
-    hipLaunchKernelGGL((merkle_leaf_kernel<false, false>), dim3((uint32_t)ceil_div(n, LEAF_WG)), dim3(LEAF_WG), 0, s,
-                       static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
-                       (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+    if (ceil_div(n, 64) <= SMALL_LAUNCH_WAVES)
+        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, false, false>), dim3((uint32_t)ceil_div(n, LEAF_WG_SMALL)),
+                           dim3(LEAF_WG_SMALL), 0, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n,
+                           (const SegDesc *)nullptr, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+    else
+        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, false, false>), dim3((uint32_t)ceil_div(n, LEAF_WG)),
+                           dim3(LEAF_WG), 0, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n,
+                           (const SegDesc *)nullptr, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
     SENTRY_HIP_CHECK(hipGetLastError());
     return SENTRY_OK;
 }
@@ -422,7 +450,8 @@ int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
     if (rc) return rc;
     SENTRY_REQUIRE(out_digest != nullptr, "sentry_merkle_root: NULL out_digest");
     const uint64_t n = leaf_count(len, leaf_bytes);
-    const uint64_t g = ceil_div(n, LEAF_WG);
+    const bool small = ceil_div(n, 64) <= SMALL_LAUNCH_WAVES;
+    const uint64_t g = ceil_div(n, small ? LEAF_WG_SMALL : LEAF_WG);
     uint8_t *dst = out_digest;
     if (g > 1) {
         void *a;
@@ -430,9 +459,14 @@ int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
         if (rc) return rc;
         dst = static_cast<uint8_t *>(a);
     }
-    hipLaunchKernelGGL((merkle_leaf_kernel<true, false>), dim3((uint32_t)g), dim3(LEAF_WG), 0, s,
-                       static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
-                       (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+    if (small)
+        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, false>), dim3((uint32_t)g), dim3(LEAF_WG_SMALL), 0, s,
+                           static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
+                           (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+    else
+        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, true, false>), dim3((uint32_t)g), dim3(LEAF_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
+                           (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
     SENTRY_HIP_CHECK(hipGetLastError());
     if (g > 1) return reduce_nodes(dst, g, out_digest, s);
     return SENTRY_OK;
@@ -480,13 +514,17 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
     // segment is down to one node.
     std::vector<std::vector<Group>> stages;
     std::vector<uint64_t> m(n_seg);   // nodes per segment after the current stage
+    uint64_t waves = 0;
+    for (size_t t = 0; t < n_seg; t++) waves += ceil_div(leaf_count(lens[t], leaf_bytes), 64);
+    const bool small = waves <= SMALL_LAUNCH_WAVES;
+    const uint64_t wg0 = small ? LEAF_WG_SMALL : LEAF_WG;
     {
         std::vector<Group> g0;
         for (size_t t = 0; t < n_seg; t++) {
             const uint64_t nl = leaf_count(lens[t], leaf_bytes);
-            for (uint64_t f = 0; f < nl; f += LEAF_WG)
-                g0.push_back(Group{f, (uint32_t)(nl - f < LEAF_WG ? nl - f : LEAF_WG), (uint32_t)t});
-            m[t] = ceil_div(nl, LEAF_WG);
+            for (uint64_t f = 0; f < nl; f += wg0)
+                g0.push_back(Group{f, (uint32_t)(nl - f < wg0 ? nl - f : wg0), (uint32_t)t});
+            m[t] = ceil_div(nl, wg0);
         }
         stages.push_back(std::move(g0));
     }
@@ -556,9 +594,14 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
         uint8_t *dst = (k + 1 == stages.size()) ? roots : bufs[k & 1];
         const uint32_t grid = (uint32_t)stages[k].size();
         if (k == 0) {
-            hipLaunchKernelGGL((merkle_leaf_kernel<true, true>), dim3(grid), dim3(LEAF_WG), 0, s,
-                               (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dev_groups[0],
-                               (uint64_t)leaf_bytes, dst);
+            if (small)
+                hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, true>), dim3(grid), dim3(LEAF_WG_SMALL), 0, s,
+                                   (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dev_groups[0],
+                                   (uint64_t)leaf_bytes, dst);
+            else
+                hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, true, true>), dim3(grid), dim3(LEAF_WG), 0, s,
+                                   (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dev_groups[0],
+                                   (uint64_t)leaf_bytes, dst);
         } else {
             hipLaunchKernelGGL(merkle_reduce_kernel<true>, dim3(grid), dim3(RED_WG), 0, s, src, (uint64_t)0,
                                dev_groups[k], dst);
