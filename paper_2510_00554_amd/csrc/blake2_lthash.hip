@@ -3,8 +3,9 @@
 // 1024 little-endian uint16 lanes, summed lane-wise mod 2^16.
 //
 // Three kernels:
-//   lthash_root_kernel    one record per lane: the sequential BLAKE2b-512 root hash H0
-//                         (the only serial part), 64 bytes per record to scratch;
+//   lthash_root_kernel    the sequential BLAKE2b-512 root hash H0 of every record (the only
+//                         serial part), one lane per record or four lanes per record,
+//                         64 bytes per record to scratch;
 //   lthash_expand_kernel  one (record, output block) pair per lane: the 32 expansion
 //                         compressions of a record are independent, so they are spread
 //                         over all lanes of the chip; each lane keeps the 16 packed words
@@ -16,7 +17,6 @@
 
 namespace {
 
-constexpr int ROOT_WG = 256;
 constexpr int EXP_WG = 256;
 constexpr int EXP_WAVES = EXP_WG / 64;
 constexpr int LANE_WORDS = SENTRY_LANES / 2;   // 512 packed 32-bit words = 2048 bytes
@@ -115,18 +115,16 @@ constexpr uint64_t EXP_P2 = 0x0000000000004000ull;
 // 32-bit word k of a 128-byte block that starts `sh`/8 bytes into the aligned word d[0]
 #define M32(k) __builtin_amdgcn_alignbit(d[(k) + 1], d[k], sh)
 
-__global__ void __launch_bounds__(ROOT_WG)
-lthash_root_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
-                   uint64_t *h0_out)
+// One record per lane: record i of n.
+__device__ __forceinline__ void root_one_lane(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base,
+                                              uint64_t n, uint64_t *h0_out, uint64_t i)
 {
-    const uint64_t i = (uint64_t)blockIdx.x * ROOT_WG + threadIdx.x;
     if (i >= n) return;
     const uint64_t beg = offsets[i] - offset_base;
     const uint64_t len = offsets[i + 1] - offsets[i];
-    const uintptr_t addr = reinterpret_cast<uintptr_t>(records) + beg;
-    const uint32_t a = (uint32_t)(addr & 3);
+    const uint32_t a = (uint32_t)((reinterpret_cast<uintptr_t>(records) + beg) & 3);
     const uint32_t sh = 8 * a;
-    const uint32_t *q = reinterpret_cast<const uint32_t *>(addr - a);
+    const uint32_t *q = reinterpret_cast<const uint32_t *>(records + beg - a);
 
     uint64_t h[8];
 #pragma unroll
@@ -179,6 +177,185 @@ lthash_root_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t off
     for (int k = 0; k < 8; k++) h0_out[8 * i + k] = h[k];
 }
 #undef M32
+
+// ---------------------------------------------------------------------------
+// root hash kernel, four lanes per record
+// ---------------------------------------------------------------------------
+//
+// BLAKE2b's state is a 4x4 matrix of 64-bit words; a round applies G to the four columns,
+// then to the four diagonals, and the four G calls of a step are independent.  Here lane j
+// of a quad holds column j (a = v[j], b = v[4+j], c = v[8+j], d = v[12+j]); the column step
+// runs in all four lanes at once, the diagonal step after rotating b, c, d by one, two and
+// three lanes inside the quad (DPP quad_perm).  This cuts the serial chain of a long record
+// to about a third, which is what bounds a launch with fewer records than lanes.
+//
+// Each lane needs different message words in every step (the sigma permutation), which
+// static register indexing cannot give; the quad therefore stages the 128-byte block in LDS
+// (lane j loads bytes [32j, 32j+32) from global memory) and every lane reads its four words
+// per round from per-lane addresses that are computed once per kernel (16-bit addresses,
+// two per register, ten rounds of sigma; rounds 10 and 11 reuse rows 0 and 1).
+
+constexpr int ROOT4_WG = 64;               // one wave per workgroup, 16 records per wave
+constexpr int ROOT4_RECORDS = ROOT4_WG / 4;
+
+__device__ const unsigned char B2_SIGMA_TABLE[10][16] = {
+    {0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15}, {14, 10, 4, 8, 9, 15, 13, 6, 1, 12, 0, 2, 11, 7, 5, 3},
+    {11, 8, 12, 0, 5, 2, 15, 13, 10, 14, 3, 6, 7, 1, 9, 4}, {7, 9, 3, 1, 13, 12, 11, 14, 2, 6, 5, 10, 4, 0, 15, 8},
+    {9, 0, 5, 7, 2, 4, 10, 15, 14, 1, 11, 12, 6, 8, 3, 13}, {2, 12, 6, 10, 0, 11, 8, 3, 4, 13, 7, 5, 15, 14, 1, 9},
+    {12, 5, 1, 15, 14, 13, 4, 10, 0, 7, 6, 3, 9, 2, 8, 11}, {13, 11, 7, 14, 12, 1, 3, 9, 5, 0, 15, 4, 8, 6, 2, 10},
+    {6, 15, 14, 9, 11, 3, 0, 8, 12, 2, 13, 7, 1, 4, 10, 5}, {10, 2, 8, 4, 7, 6, 1, 5, 15, 11, 9, 14, 3, 12, 13, 0}};
+
+// value of x in the lane of the same quad selected by the quad_perm control word
+template <int CTRL>
+__device__ __forceinline__ uint64_t quad_rotate(uint64_t x)
+{
+    // all rows and banks enabled and every source lane inside the quad: each lane is written
+    const int lo = __builtin_amdgcn_mov_dpp((int)(uint32_t)x, CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_mov_dpp((int)(uint32_t)(x >> 32), CTRL, 0xf, 0xf, true);
+    return pack64((uint32_t)lo, (uint32_t)hi);
+}
+constexpr int QP_FROM_NEXT1 = 1 | (2 << 2) | (3 << 4) | (0 << 6);   // lane j reads lane (j+1)&3
+constexpr int QP_FROM_NEXT2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);   // lane j reads lane (j+2)&3
+constexpr int QP_FROM_NEXT3 = 3 | (0 << 2) | (1 << 4) | (2 << 6);   // lane j reads lane (j+3)&3
+
+// Sixteen records per wave, four lanes each: the wave's records are first_rec .. first_rec + 15.
+__device__ __forceinline__ void root_four_lanes(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base,
+                                                uint64_t n, uint64_t *h0_out, uint64_t first_rec, unsigned char *stage)
+{
+    const uint32_t lane = threadIdx.x, quad = lane >> 2, j = lane & 3;
+    const uint64_t rec = first_rec + quad;
+    const bool active = rec < n;
+    uint64_t beg = 0, len = 0;
+    if (active) {
+        beg = offsets[rec] - offset_base;
+        len = offsets[rec + 1] - offsets[rec];
+    }
+    // the longest record of the wave sets the wave's issue priority: in a launch with few
+    // long records, their chains decide the run time and should not wait for short ones
+    {
+        uint32_t nb = (uint32_t)((len + 127) >> 7 > 0xffffffffull ? 0xffffffffull : (len + 127) >> 7);
+#pragma unroll
+        for (int sft = 32; sft >= 4; sft >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)nb, sft, 64);
+            nb = o > nb ? o : nb;
+        }
+        nb = __builtin_amdgcn_readfirstlane(nb);
+        if (nb >= 2048) __builtin_amdgcn_s_setprio(3);
+        else if (nb >= 512) __builtin_amdgcn_s_setprio(2);
+        else if (nb >= 128) __builtin_amdgcn_s_setprio(1);
+    }
+    if (!active) return;   // whole quads leave together, so quad_perm never reads a dead lane
+
+    const uint32_t al = (uint32_t)((reinterpret_cast<uintptr_t>(records) + beg) & 3);
+    const uint32_t sh = 8 * al;
+    // aligned words of this lane's 32-byte slice of the first block
+    const uint32_t *q = reinterpret_cast<const uint32_t *>(records + beg - al) + 8 * j;
+
+    // per-lane LDS addresses of the message words of every round
+    const uint32_t qbase = quad * 128;
+    uint32_t maddr[10][2];
+#pragma unroll
+    for (int r = 0; r < 10; r++) {
+#pragma unroll
+        for (int st = 0; st < 2; st++) {
+            const uint32_t x = qbase + 8u * B2_SIGMA_TABLE[r][8 * st + 2 * j];
+            const uint32_t y = qbase + 8u * B2_SIGMA_TABLE[r][8 * st + 2 * j + 1];
+            maddr[r][st] = x | (y << 16);
+        }
+    }
+    unsigned char *my_slice = stage + qbase + 32 * j;
+
+    // column j of the chaining value and of the IV
+    const uint64_t iv_lo = j == 0 ? b2_iv(0) : j == 1 ? b2_iv(1) : j == 2 ? b2_iv(2) : b2_iv(3);
+    const uint64_t iv_hi = j == 0 ? b2_iv(4) : j == 1 ? b2_iv(5) : j == 2 ? b2_iv(6) : b2_iv(7);
+    uint64_t h_lo = iv_lo ^ (j == 0 ? ROOT_P0 : j == 1 ? ROOT_P1 : 0ull);
+    uint64_t h_hi = iv_hi;
+
+    uint32_t d[9];
+    uint64_t done = 0;
+    if (len > 128) {
+#pragma unroll
+        for (int k = 0; k < 9; k++) d[k] = q[k];
+    }
+    for (;;) {
+        const bool last = len - done <= 128;
+        uint32_t w[8];
+        uint64_t t;
+        if (!last) {
+#pragma unroll
+            for (int k = 0; k < 8; k++) w[k] = __builtin_amdgcn_alignbit(d[k + 1], d[k], sh);
+            done += 128;
+            q += 32;
+            t = done;
+            if (len - done > 128) {   // the next block is full too: fetch it during this compression
+#pragma unroll
+                for (int k = 0; k < 9; k++) d[k] = q[k];
+            }
+        } else {
+            // 1..128 bytes (0 for the empty record), zero padded; words without a record byte are not read
+            const uint32_t rem = (uint32_t)(len - done);
+            const uint32_t span = rem ? al + rem : 0u;
+#pragma unroll
+            for (int k = 0; k < 9; k++) d[k] = ((uint32_t)(4 * (8 * j + k)) < span) ? q[k] : 0u;
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const uint32_t lo = 4u * (8u * j + (uint32_t)k);
+                uint32_t x = __builtin_amdgcn_alignbit(d[k + 1], d[k], sh);
+                if (rem < lo + 4) x = (rem <= lo) ? 0u : (x & ((1u << (8 * (rem - lo))) - 1u));
+                w[k] = x;
+            }
+            t = len;
+        }
+        // stage the block: this lane's four message words
+        *reinterpret_cast<uint4 *>(my_slice) = make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4 *>(my_slice + 16) = make_uint4(w[4], w[5], w[6], w[7]);
+
+        uint64_t a = h_lo, b = h_hi, c = iv_lo, dd = iv_hi;
+        if (j == 0) dd ^= t;
+        if (last && j == 2) dd = ~dd;
+#pragma unroll
+        for (int r = 0; r < 12; r++) {
+            const uint32_t pc = maddr[r % 10][0], pd = maddr[r % 10][1];
+            const uint64_t mc0 = *reinterpret_cast<const uint64_t *>(stage + (pc & 0xffffu));
+            const uint64_t mc1 = *reinterpret_cast<const uint64_t *>(stage + (pc >> 16));
+            const uint64_t md0 = *reinterpret_cast<const uint64_t *>(stage + (pd & 0xffffu));
+            const uint64_t md1 = *reinterpret_cast<const uint64_t *>(stage + (pd >> 16));
+            B2_G(a, b, c, dd, mc0, mc1);
+            b = quad_rotate<QP_FROM_NEXT1>(b);
+            c = quad_rotate<QP_FROM_NEXT2>(c);
+            dd = quad_rotate<QP_FROM_NEXT3>(dd);
+            B2_G(a, b, c, dd, md0, md1);
+            b = quad_rotate<QP_FROM_NEXT3>(b);
+            c = quad_rotate<QP_FROM_NEXT2>(c);
+            dd = quad_rotate<QP_FROM_NEXT1>(dd);
+        }
+        h_lo ^= a ^ c;
+        h_hi ^= b ^ dd;
+        if (last) break;
+    }
+    h0_out[8 * rec + j] = h_lo;
+    h0_out[8 * rec + 4 + j] = h_hi;
+}
+
+// Root hashes of n records.  mode 1: one lane per record; mode 4: four lanes per record;
+// mode 0: chosen here from the mean record length, which the kernel can read from the
+// offsets while the host cannot (the offsets are device memory and the call does not
+// wait): records of 16 KiB and more on average make a launch chain-bound, so they get four
+// lanes; short records get one lane, whose start-up is cheaper.  Workgroups are single waves;
+// the grid is sized for mode 4 and the surplus workgroups of mode 1 leave at once.
+constexpr uint64_t FOUR_LANE_MEAN_BYTES = 16384;
+
+__global__ void __launch_bounds__(ROOT4_WG)
+lthash_root_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
+                   uint64_t *h0_out, int mode)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char stage[ROOT4_RECORDS * 128];
+    if (mode == 0) mode = (offsets[n] - offsets[0]) >= FOUR_LANE_MEAN_BYTES * n ? 4 : 1;
+    if (mode == 4)
+        root_four_lanes(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT4_RECORDS, stage);
+    else
+        root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT4_WG + threadIdx.x);
+}
 
 // ---------------------------------------------------------------------------
 // expansion + lane accumulation kernel
@@ -327,9 +504,17 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
     rc = scratch_get(s, R_LT_PART, n_part * LANE_WORDS * 4, &part);
     if (rc) return rc;
     if (n) {
-        hipLaunchKernelGGL(lthash_root_kernel, dim3((uint32_t)ceil_div(n, ROOT_WG)), dim3(ROOT_WG), 0, s,
+        // With fewer records than four times the lanes of the chip the launch is bound by its
+        // longest chain, not by throughput: spend four lanes per record.  Otherwise one lane
+        // per record does the least total work.
+        // With at least four records per lane of the chip the launch is throughput-bound whatever
+        // the lengths are, and one lane per record does the least total work; below that the
+        // kernel decides from the mean record length.
+        const bool full = n >= (uint64_t)cu_count() * 256 * 4;
+        const uint64_t grid_r = full ? ceil_div(n, ROOT4_WG) : ceil_div(n, ROOT4_RECORDS);
+        hipLaunchKernelGGL(lthash_root_kernel, dim3((uint32_t)grid_r), dim3(ROOT4_WG), 0, s,
                            static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
-                           static_cast<uint64_t *>(h0));
+                           static_cast<uint64_t *>(h0), full ? 1 : 0);
         SENTRY_HIP_CHECK(hipGetLastError());
     }
     hipLaunchKernelGGL(lthash_expand_kernel, dim3((uint32_t)grid), dim3(EXP_WG), 0, s,
@@ -356,7 +541,7 @@ int sentry_lthash(const void *dev_records, const uint64_t *dev_offsets, size_t n
     SENTRY_REQUIRE(n == 0 || (dev_offsets != nullptr && (reinterpret_cast<uintptr_t>(dev_offsets) & 7) == 0),
                    "sentry_lthash: dev_offsets must be non-NULL and 8-byte aligned when n > 0");
     // a launch holds fewer than 2^32 work-items in all
-    SENTRY_REQUIRE(n <= 0xffffffffull - ROOT_WG, "sentry_lthash: too many records");
+    SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash: too many records");
     return sentry::lthash_into(dev_records, dev_offsets, 0, n, out_lanes, false, static_cast<hipStream_t>(stream));
 }
 

@@ -134,3 +134,31 @@ def test_same_record_65536_times_is_zero():
     data = np.tile(rec, 65536)
     off = np.arange(65537, dtype=np.uint64) * np.uint64(40)
     assert not gpu_lthash(data, off).any()
+
+
+def test_four_lane_path_edge_lengths_and_alignments():
+    # a mean record length of 16 KiB or more selects four lanes per record: short records of
+    # every edge length ride along with one long record
+    lens = [0, 1, 2, 3, 4, 5, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 130, 131, 132,
+            159, 160, 161, 255, 256, 257, 383, 384, 385, 4095, 4096, 4097, 1_500_003]
+    off = wl.offsets_from_lengths(np.array(lens, np.uint64))
+    assert int(off[-1]) >= 16384 * len(lens)
+    data = wl.uniform_bytes(1500, 0, int(off[-1]))
+    want = oracle.lthash(data, off)
+    for shift in (0, 1, 2, 3):
+        assert (gpu_lthash(data, off, shift) == want).all(), shift
+    # the long record first, and a record count that is not a multiple of 16
+    lens2 = [1_000_001] + lens[:20]
+    off2 = wl.offsets_from_lengths(np.array(lens2, np.uint64))
+    data2 = wl.uniform_bytes(1501, 0, int(off2[-1]))
+    assert (gpu_lthash(data2, off2, 1) == oracle.lthash(data2, off2)).all()
+
+
+def test_many_records_take_the_one_lane_path():
+    # at least four records per lane of the chip: one lane per record regardless of lengths
+    n = 262_144 + 37
+    rng = np.random.default_rng(61)
+    lens = rng.integers(0, 48, n).astype(np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(1600, 0, int(off[-1]))
+    assert (gpu_lthash(data, off) == oracle.lthash(data, off)).all()
