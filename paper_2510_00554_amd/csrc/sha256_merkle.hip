@@ -25,6 +25,8 @@ namespace {
 constexpr int LEAF_WG = 256;          // lanes = leaves per workgroup of the leaf kernel ...
 constexpr int LEAF_WG_SMALL = 64;     // ... and when there are too few leaves to fill the chip
 constexpr uint64_t SMALL_LAUNCH_WAVES = 2048;   // two waves per SIMD on 256 CUs x 4 SIMDs
+constexpr uint64_t SPLIT_LAUNCH_WAVES = 512;    // groups of 64 leaves the two-wave split kernel takes: two per CU
+constexpr uint64_t SPLIT_SINGLE_GROUPS = 256;   // up to one group per CU: one pair per workgroup
 constexpr int RED_WG = 256;           // lanes per workgroup of the reduce kernel
 constexpr int RED_IN = 2 * RED_WG;    // nodes folded by one reduce workgroup
 
@@ -317,6 +319,196 @@ merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const
     if (tid == 0) store_digest(out + 32 * (uint64_t)g, root);
 }
 
+// Block hashing kernel for launches with very few leaves, where the run time is one lane's
+// serial chain and most SIMDs idle.  A lone wave issues an instruction every five cycles or
+// so whatever it does, so the only way to shorten the chain is to give it fewer instructions:
+// two waves share each group of 64 leaves.  The producer wave loads the blocks, swaps bytes
+// and expands the message schedule W[0..63] (which does not depend on the chaining value) into
+// LDS; the consumer wave runs only the 64 rounds.  One barrier per block, two LDS slots:
+// when the producer passes the barrier of block b+1 the consumer has finished block b, whose
+// slot is the one the producer fills next.
+constexpr int SPLIT_LEAVES = 64;
+constexpr int SPLIT_PAIR_LANES = 128;                         // one producer wave + one consumer wave
+constexpr uint64_t SPLIT_MIN_LEAF = 512;                      // below this the per-block barrier does not pay
+constexpr int SPLIT_LANE_WORDS = 68;                          // 64 schedule words + 4 of padding:
+constexpr int SPLIT_SLOT_WORDS = SPLIT_LEAVES * SPLIT_LANE_WORDS;   // 16-byte accesses stay conflict-free
+
+// producer: schedule of one block into dst[0..63]; w is consumed
+__device__ __forceinline__ void sha256_schedule_to_lds(uint32_t (&w)[16], uint32_t *dst)
+{
+    uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+#pragma unroll
+    for (int g = 0; g < 4; g++) d4[g] = make_uint4(w[4 * g], w[4 * g + 1], w[4 * g + 2], w[4 * g + 3]);
+#pragma unroll
+    for (int t = 16; t < 64; t++) {
+        w[t & 15] = w[t & 15] + ssig0(w[(t + 1) & 15]) + w[(t + 9) & 15] + ssig1(w[(t + 14) & 15]);
+        if ((t & 3) == 3)
+            d4[t >> 2] = make_uint4(w[(t - 3) & 15], w[(t - 2) & 15], w[(t - 1) & 15], w[t & 15]);
+    }
+}
+
+// consumer: the 64 rounds over a schedule held in LDS; st is updated only where apply is set
+__device__ __forceinline__ void sha256_rounds_from_lds(uint32_t (&st)[8], const uint32_t *src, bool apply)
+{
+    const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
+    uint32_t v[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = st[i];
+    uint4 x = {};
+#pragma unroll
+    for (int t = 0; t < 64; t++) {
+        if ((t & 3) == 0) x = s4[t >> 2];
+        const uint32_t wt = (t & 3) == 0 ? x.x : (t & 3) == 1 ? x.y : (t & 3) == 2 ? x.z : x.w;
+#define V(i) v[((i) - t) & 7]
+        uint32_t t1 = V(7) + bsig1(V(4)) + ch(V(4), V(5), V(6)) + k256(t) + wt;
+        V(3) += t1;
+        V(7) = t1 + bsig0(V(0)) + maj(V(0), V(1), V(2));
+#undef V
+    }
+    if (apply) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) st[i] += v[i];
+    }
+}
+
+// Workgroup = 256 lanes = two producer/consumer pairs (waves P0, C0, P1, C1), each pair with
+// its own group of 64 leaves.  Four waves of one workgroup land on the four SIMDs of a CU,
+// one each, which single- or two-wave workgroups do not guarantee once a CU holds two of
+// them; with at most one workgroup per CU every wave of the launch has a SIMD to itself.
+// All barriers are workgroup-wide, so both pairs run the trip count of the longer group.
+// PAIRS = 1 (128 lanes) is used while there is at most one group per CU: two busy SIMDs per
+// CU run a little faster than four.
+template <int PAIRS, bool FUSE, bool SEGMENTED>
+__global__ void __launch_bounds__(SPLIT_PAIR_LANES * PAIRS)
+merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, uint32_t n_groups,
+                         const SegDesc *segs, const Group *groups, uint64_t leaf_bytes, uint8_t *out)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t sched[PAIRS][2 * SPLIT_SLOT_WORDS];
+    __shared__ uint32_t lds[PAIRS][2][8][SPLIT_LEAVES];
+    __shared__ unsigned long long trip_share[2 * PAIRS];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t pr = wave >> 1;
+    const bool consumer = wave & 1;
+    const uint32_t g = PAIRS * blockIdx.x + pr;
+    const uint8_t *base = nullptr;
+    uint64_t seglen = 0, first = 0;
+    uint32_t count = 0;
+    if (g < n_groups) {
+        if (SEGMENTED) {
+            const Group gr = groups[g];
+            const SegDesc sd = segs[gr.seg];
+            base = sd.base; seglen = sd.len; first = gr.first; count = gr.count;
+        } else {
+            base = base0; seglen = len0; first = (uint64_t)g * SPLIT_LEAVES;
+            const uint64_t rem = nleaves0 - first;
+            count = rem < (uint64_t)SPLIT_LEAVES ? (uint32_t)rem : (uint32_t)SPLIT_LEAVES;
+        }
+    }
+    const bool have = lane < count;
+    uint64_t llen = 0;
+    const uint8_t *p = base;
+    if (have) {
+        const uint64_t start = (first + lane) * leaf_bytes;
+        const uint64_t left = seglen - start;
+        llen = left < leaf_bytes ? left : leaf_bytes;
+        p = base + start;
+    }
+    const uint64_t nblk = llen >> 6;
+    const uint32_t r = (uint32_t)(llen & 63);
+    const uint64_t total = have ? nblk + 1 + (r >= 56 ? 1 : 0) : 0;
+    // lane 0 holds the first leaf of its group, which no other leaf of the group exceeds; the
+    // larger of the two groups' block counts is the trip count of all four waves
+    if (lane == 0) trip_share[wave] = total;
+    __syncthreads();
+    uint64_t trips = trip_share[0];
+    if (PAIRS == 2 && trip_share[2] > trips) trips = trip_share[2];
+    uint32_t *my = &sched[pr][lane * SPLIT_LANE_WORDS];
+    uint32_t st[8] = SENTRY_H0;
+
+    if (!consumer) {
+        // two pairs of blocks (two 128-byte lines) are in flight per lane: the producer is short
+        // of work, not of registers
+        const uint4 *q = reinterpret_cast<const uint4 *>(p);
+        uint4 c[16] = {};
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            if (nblk >= (uint64_t)(k + 1)) {
+                c[4 * k] = q[4 * k]; c[4 * k + 1] = q[4 * k + 1]; c[4 * k + 2] = q[4 * k + 2]; c[4 * k + 3] = q[4 * k + 3];
+            }
+        }
+        for (uint64_t b = 0; b < trips; b++) {
+            uint32_t w[16];
+            if (b < nblk) {
+                const uint32_t slot = (uint32_t)b & 3;
+                if (slot == 0) bswap_block(w, c[0], c[1], c[2], c[3]);
+                else if (slot == 1) bswap_block(w, c[4], c[5], c[6], c[7]);
+                else if (slot == 2) bswap_block(w, c[8], c[9], c[10], c[11]);
+                else bswap_block(w, c[12], c[13], c[14], c[15]);
+                if (slot & 1) {   // a pair is used up: refill it with blocks b+3 and b+4
+                    const uint4 *n = q + 4 * (b + 3);
+                    if (slot == 1) {
+                        if (b + 3 < nblk) { c[0] = n[0]; c[1] = n[1]; c[2] = n[2]; c[3] = n[3]; }
+                        if (b + 4 < nblk) { c[4] = n[4]; c[5] = n[5]; c[6] = n[6]; c[7] = n[7]; }
+                    } else {
+                        if (b + 3 < nblk) { c[8] = n[0]; c[9] = n[1]; c[10] = n[2]; c[11] = n[3]; }
+                        if (b + 4 < nblk) { c[12] = n[4]; c[13] = n[5]; c[14] = n[6]; c[15] = n[7]; }
+                    }
+                }
+            } else if (b < total) {
+                build_tail(w, p + (nblk << 6), r, llen, (uint32_t)(b - nblk));
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; i++) w[i] = 0;   // this lane's leaf is done; the slot is not used
+            }
+            sha256_schedule_to_lds(w, my + (b & 1) * SPLIT_SLOT_WORDS);
+            __syncthreads();
+        }
+    } else {
+        for (uint64_t b = 0; b < trips; b++) {
+            __syncthreads();
+            sha256_rounds_from_lds(st, my + (b & 1) * SPLIT_SLOT_WORDS, b < total);
+        }
+    }
+    if (!FUSE) {
+        if (consumer && have) store_digest(out + 32 * (first + lane), st);
+        return;
+    }
+    // each consumer wave folds its 64 leaf digests; six levels for everybody keeps the
+    // barriers of the two pairs in step
+    if (consumer) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) lds[pr][0][i][lane] = st[i];
+    }
+    __syncthreads();
+    uint32_t cnt = count;
+    int cur = 0;
+#pragma unroll 1
+    for (int level = 0; level < 6; level++) {
+        const uint32_t pairs = cnt >> 1;
+        if (consumer && cnt > 1) {
+            if (lane < pairs) {
+                uint32_t l[8], rr[8], d[8];
+#pragma unroll
+                for (int i = 0; i < 8; i++) { l[i] = lds[pr][cur][i][2 * lane]; rr[i] = lds[pr][cur][i][2 * lane + 1]; }
+                node_hash(l, rr, d);
+#pragma unroll
+                for (int i = 0; i < 8; i++) lds[pr][cur ^ 1][i][lane] = d[i];
+            } else if (lane == pairs && (cnt & 1)) {
+#pragma unroll
+                for (int i = 0; i < 8; i++) lds[pr][cur ^ 1][i][pairs] = lds[pr][cur][i][cnt - 1];
+            }
+        }
+        __syncthreads();
+        if (cnt > 1) { cnt = pairs + (cnt & 1); cur ^= 1; }
+    }
+    if (consumer && lane == 0 && g < n_groups) {
+        uint32_t root[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) root[i] = lds[pr][cur][i][0];
+        store_digest(out + 32 * (uint64_t)g, root);
+    }
+}
+
 // Reduction kernel: each workgroup folds up to 512 consecutive nodes of one segment into one.
 template <bool SEGMENTED>
 __global__ void __launch_bounds__(RED_WG)
@@ -359,6 +551,20 @@ merkle_reduce_kernel(const uint8_t *in, uint64_t n0, const Group *groups, uint8_
 // ---------------------------------------------------------------------------
 
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+// the two-wave split kernel over n_groups groups of 64 leaves
+template <bool FUSE, bool SEGMENTED>
+void launch_split(uint32_t n_groups, hipStream_t s, const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
+                  const SegDesc *segs, const Group *groups, uint64_t leaf_bytes, uint8_t *out)
+{
+    if (n_groups <= SPLIT_SINGLE_GROUPS)
+        hipLaunchKernelGGL((merkle_leaf_split_kernel<1, FUSE, SEGMENTED>), dim3(n_groups), dim3(SPLIT_PAIR_LANES), 0, s,
+                           base0, len0, nleaves0, n_groups, segs, groups, leaf_bytes, out);
+    else
+        hipLaunchKernelGGL((merkle_leaf_split_kernel<2, FUSE, SEGMENTED>), dim3((n_groups + 1) / 2),
+                           dim3(2 * SPLIT_PAIR_LANES), 0, s, base0, len0, nleaves0, n_groups, segs, groups, leaf_bytes, out);
+}
+
 inline uint64_t leaf_count(uint64_t len, uint64_t leaf_bytes)
 {
     uint64_t n = ceil_div(len, leaf_bytes);
@@ -421,7 +627,10 @@ namespace sentry {
 int merkle_leaves_into(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *dst, hipStream_t s)
 {
     const uint64_t n = leaf_count(len, leaf_bytes);
-    if (ceil_div(n, 64) <= SMALL_LAUNCH_WAVES)
+    if (ceil_div(n, 64) <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF)
+        launch_split<false, false>((uint32_t)ceil_div(n, SPLIT_LEAVES), s, static_cast<const uint8_t *>(dev_buf),
+                                   (uint64_t)len, n, nullptr, nullptr, (uint64_t)leaf_bytes, dst);
+    else if (ceil_div(n, 64) <= SMALL_LAUNCH_WAVES)
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, false, false>), dim3((uint32_t)ceil_div(n, LEAF_WG_SMALL)),
                            dim3(LEAF_WG_SMALL), 0, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n,
                            (const SegDesc *)nullptr, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
@@ -459,7 +668,10 @@ int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
         if (rc) return rc;
         dst = static_cast<uint8_t *>(a);
     }
-    if (small)
+    if (small && ceil_div(n, 64) <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF)
+        launch_split<true, false>((uint32_t)g, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, nullptr,
+                                  nullptr, (uint64_t)leaf_bytes, dst);
+    else if (small)
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, false>), dim3((uint32_t)g), dim3(LEAF_WG_SMALL), 0, s,
                            static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
                            (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
@@ -594,7 +806,9 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
         uint8_t *dst = (k + 1 == stages.size()) ? roots : bufs[k & 1];
         const uint32_t grid = (uint32_t)stages[k].size();
         if (k == 0) {
-            if (small)
+            if (small && waves <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF)
+                launch_split<true, true>(grid, s, nullptr, 0, 0, dseg, dev_groups[0], (uint64_t)leaf_bytes, dst);
+            else if (small)
                 hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, true>), dim3(grid), dim3(LEAF_WG_SMALL), 0, s,
                                    (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dev_groups[0],
                                    (uint64_t)leaf_bytes, dst);

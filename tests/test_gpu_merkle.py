@@ -162,3 +162,20 @@ def test_segments_tiny_checkpoint_layout():
     sentry.sentry_merkle_segments([devs[0].data_ptr()], [tensors[0].size], 4096, 0, one.data_ptr())
     torch.cuda.synchronize()
     assert bytes(one.cpu().numpy()) == oracle.merkle_root(tensors[0], 4096)
+
+
+@pytest.mark.parametrize("leaf,n_leaves,tail", [
+    (512, 64 * 300 + 5, 0), (512, 64 * 257 + 1, 57), (1024, 64 * 256, 0), (1024, 64 * 256 + 1, 3),
+    (512, 64 * 511 + 63, 511), (512, 64 * 512, 0), (512, 64 * 513, 9), (576, 129, 0), (4096, 65, 56),
+])
+def test_two_wave_split_kernel_group_counts(leaf, n_leaves, tail):
+    # leaves of 512 bytes and more in launches of up to 512 groups of 64 leaves take the
+    # producer/consumer kernel: one pair per workgroup up to 256 groups, two pairs above
+    size = leaf * (n_leaves - 1) + (tail if tail else leaf)
+    buf = wl.uniform_bytes(900 + n_leaves % 11, 0, size)
+    assert gpu_root(buf, leaf) == oracle.merkle_root(buf, leaf)
+    d = to_dev(buf)
+    leaves = torch.zeros(n_leaves * 32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_leaves(d.data_ptr(), size, leaf, leaves.data_ptr())
+    torch.cuda.synchronize()
+    assert (leaves.cpu().numpy().reshape(n_leaves, 32) == oracle.merkle_leaves(buf, leaf)).all()
