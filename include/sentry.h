@@ -183,7 +183,11 @@ SENTRY_API int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stre
  * host_records  host (pinned for overlap); host_offsets: host, n+1 offsets.
  * batch_bytes   upper bound on the record bytes copied per batch (> 0); a
  *               record longer than this is an error.  Batches are cut at record
- *               boundaries.  Two device buffers of this size are held in scratch.
+ *               boundaries.  Up to three batches are in flight, each with a
+ *               device buffer of its size (held in scratch) and a stream of
+ *               its own, so that the hashing of one batch, which is bound
+ *               by its longest record, overlaps the copies and hashes of the
+ *               next ones.
  * out_lanes     device-accessible, overwritten with the sum over all n records.
  */
 SENTRY_API int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, size_t n,

@@ -483,7 +483,19 @@ namespace sentry {
 int lthash_presize(uint64_t max_records, hipStream_t s)
 {
     void *p;
-    return scratch_get(s, R_LT_H0, 64 * (max_records ? max_records : 1), &p);
+    int rc = scratch_get(s, R_LT_H0, 64 * (max_records ? max_records : 1), &p);
+    if (rc) return rc;
+    // the most partial rows any launch writes: two workgroups per CU, plus the running sum
+    return scratch_get(s, R_LT_PART, ((size_t)cu_count() * 2 + 1) * LANE_WORDS * 4, &p);
+}
+
+// out = lane-wise sum of n_rows rows of 1024 lanes (rows are 2048 bytes apart, 4-byte aligned).
+int lthash_sum_rows(const uint16_t *rows, uint32_t n_rows, uint16_t *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(lthash_fold_kernel, dim3(LANE_WORDS / FOLD_COLS), dim3(FOLD_WG), 0, s,
+                       reinterpret_cast<const uint32_t *>(rows), n_rows, out);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
 }
 
 // Lattice hash of n records at dev_records (offsets relative to offset_base); result either

@@ -30,6 +30,7 @@ struct StreamCtx {
     bool tab_pending = false;
     CopyPipe pipe = {};
     bool pipe_ready = false;
+    bool hash_streams_ready = false;
 };
 
 static std::mutex g_mu;
@@ -114,7 +115,7 @@ int table_staging_mark(hipStream_t stream)
     return SENTRY_OK;
 }
 
-int copy_pipe_get(hipStream_t stream, CopyPipe **out)
+int copy_pipe_get(hipStream_t stream, bool with_hash_streams, CopyPipe **out)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     StreamCtx *c;
@@ -123,11 +124,17 @@ int copy_pipe_get(hipStream_t stream, CopyPipe **out)
     if (!c->pipe_ready) {
         // default priority on purpose: mixed stream priorities are not used anywhere
         SENTRY_HIP_CHECK(hipStreamCreateWithFlags(&c->pipe.copy_stream, hipStreamNonBlocking));
-        for (int i = 0; i < 2; i++) {
+        SENTRY_HIP_CHECK(hipEventCreateWithFlags(&c->pipe.start, hipEventDisableTiming));
+        for (int i = 0; i < PIPE_SLOTS; i++) {
             SENTRY_HIP_CHECK(hipEventCreateWithFlags(&c->pipe.copied[i], hipEventDisableTiming));
             SENTRY_HIP_CHECK(hipEventCreateWithFlags(&c->pipe.consumed[i], hipEventDisableTiming));
         }
         c->pipe_ready = true;
+    }
+    if (with_hash_streams && !c->hash_streams_ready) {
+        for (int i = 0; i < PIPE_SLOTS - 1; i++)
+            SENTRY_HIP_CHECK(hipStreamCreateWithFlags(&c->pipe.hash_stream[i], hipStreamNonBlocking));
+        c->hash_streams_ready = true;
     }
     *out = &c->pipe;
     return SENTRY_OK;
@@ -188,7 +195,10 @@ int release_all_scratch()
         if (c.tab_event) SENTRY_HIP_CHECK(hipEventDestroy(c.tab_event));
         if (c.pipe_ready) {
             SENTRY_HIP_CHECK(hipStreamDestroy(c.pipe.copy_stream));
-            for (int i = 0; i < 2; i++) {
+            SENTRY_HIP_CHECK(hipEventDestroy(c.pipe.start));
+            if (c.hash_streams_ready)
+                for (int i = 0; i < PIPE_SLOTS - 1; i++) SENTRY_HIP_CHECK(hipStreamDestroy(c.pipe.hash_stream[i]));
+            for (int i = 0; i < PIPE_SLOTS; i++) {
                 SENTRY_HIP_CHECK(hipEventDestroy(c.pipe.copied[i]));
                 SENTRY_HIP_CHECK(hipEventDestroy(c.pipe.consumed[i]));
             }

@@ -49,8 +49,12 @@ enum Region {
     R_LT_SUM,        // running lane sum of the host-streaming entry point
     R_STAGE0,        // device staging buffers of the host-streaming entry points
     R_STAGE1,
+    R_STAGE2,
+    R_STAGE3,
     R_STAGE_OFF0,    // staged record offsets
     R_STAGE_OFF1,
+    R_STAGE_OFF2,
+    R_STAGE_OFF3,
     R_COUNT
 };
 
@@ -65,12 +69,21 @@ int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr);
 int table_staging_mark(hipStream_t stream);
 
 // Side stream and events for the host-streaming entry points (per stream).
+// Batches in flight in the lattice host-streaming call.  Slot 0 hashes on the caller's stream,
+// the others on side streams: with the copy stream that makes four streams, the number of
+// hardware queues a process gets here; with more, streams share queues and copies queue up
+// behind kernels (measured: hash-while-loading fell from 96 % to 54 % of the copy rate).
+constexpr int PIPE_SLOTS = 3;
 struct CopyPipe {
     hipStream_t copy_stream;
-    hipEvent_t copied[2];     // chunk k%2 has landed in its staging buffer
-    hipEvent_t consumed[2];   // the hash kernels have finished reading staging buffer k%2
+    hipStream_t hash_stream[PIPE_SLOTS - 1];   // side streams for batches hashed concurrently
+    hipEvent_t copied[PIPE_SLOTS];     // chunk k%slots has landed in its staging buffer
+    hipEvent_t consumed[PIPE_SLOTS];   // the hash kernels have finished reading that staging buffer
+    hipEvent_t start;                  // everything enqueued on the caller's stream before the call
 };
-int copy_pipe_get(hipStream_t stream, CopyPipe **out);
+// with_hash_streams: also create the side hash streams (only the lattice call needs them;
+// streams that exist share the few hardware queues even when idle)
+int copy_pipe_get(hipStream_t stream, bool with_hash_streams, CopyPipe **out);
 
 // Device memory that kernels already enqueued on `stream` still read: freed by a later
 // sweep once the stream has passed the point of this call.

@@ -18,6 +18,7 @@ int merkle_reduce_into(const uint8_t *dev_nodes, uint64_t n, uint8_t *out_digest
 int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
                 uint16_t *out, bool accumulate, hipStream_t s);
 int lthash_presize(uint64_t max_records, hipStream_t s);
+int lthash_sum_rows(const uint16_t *rows, uint32_t n_rows, uint16_t *out, hipStream_t s);
 }  // namespace sentry
 
 namespace {
@@ -143,7 +144,7 @@ int sentry_merkle_root_h2d(const void *host_buf, size_t len, size_t leaf_bytes, 
     rc = sentry::scratch_get(s, sentry::R_NODES_B, 32 * n_leaves, &digests);
     if (rc) return rc;
     sentry::CopyPipe *pipe;
-    rc = sentry::copy_pipe_get(s, &pipe);
+    rc = sentry::copy_pipe_get(s, false, &pipe);
     if (rc) return rc;
 
     // the side stream must not start overwriting the staging buffers before earlier work on
@@ -202,39 +203,58 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
         i = j;
     }
 
-    void *stage[2], *stage_off[2];
+    // Up to three batches are in flight: each has a staging buffer and a stream of its own (the
+    // caller's stream for slot 0, a side stream for the others), so the hash of batch k (bound by
+    // its longest record, most of the chip idle) overlaps the copies and hashes of batches k+1
+    // and k+2.  Slot i keeps a running sum of its batches; the caller's stream adds the sums at
+    // the end.
+    constexpr int NS = sentry::PIPE_SLOTS;
+    static_assert(NS <= 4, "four staging regions exist");
+    static const sentry::Region stage_r[4] = {sentry::R_STAGE0, sentry::R_STAGE1, sentry::R_STAGE2, sentry::R_STAGE3};
+    static const sentry::Region off_r[4] = {sentry::R_STAGE_OFF0, sentry::R_STAGE_OFF1, sentry::R_STAGE_OFF2,
+                                             sentry::R_STAGE_OFF3};
+    const int used = batches.size() < (size_t)NS ? (int)batches.size() : NS;
+    void *stage[NS], *stage_off[NS], *sums;
+    hipStream_t hstream[NS];
     int rc;
-    // spare bytes: the kernel reads the whole aligned word that holds a record's last byte
-    if ((rc = sentry::scratch_get(s, sentry::R_STAGE0, max_bytes + 8, &stage[0]))) return rc;
-    if ((rc = sentry::scratch_get(s, sentry::R_STAGE1, max_bytes + 8, &stage[1]))) return rc;
-    if ((rc = sentry::scratch_get(s, sentry::R_STAGE_OFF0, 8 * (max_count + 1), &stage_off[0]))) return rc;
-    if ((rc = sentry::scratch_get(s, sentry::R_STAGE_OFF1, 8 * (max_count + 1), &stage_off[1]))) return rc;
-    if ((rc = sentry::lthash_presize(max_count, s))) return rc;   // no regrowth inside the pipeline
     sentry::CopyPipe *pipe;
-    if ((rc = sentry::copy_pipe_get(s, &pipe))) return rc;
-    SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[0], s));
-    SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[1], s));
+    if ((rc = sentry::copy_pipe_get(s, true, &pipe))) return rc;
+    for (int i = 0; i < used; i++) {
+        // spare bytes: the kernel reads the whole aligned word that holds a record's last byte
+        if ((rc = sentry::scratch_get(s, stage_r[i], max_bytes + 8, &stage[i]))) return rc;
+        if ((rc = sentry::scratch_get(s, off_r[i], 8 * (max_count + 1), &stage_off[i]))) return rc;
+        hstream[i] = i == 0 ? s : pipe->hash_stream[i - 1];
+        if ((rc = sentry::lthash_presize(max_count, hstream[i]))) return rc;   // no regrowth in the pipeline
+    }
+    if ((rc = sentry::scratch_get(s, sentry::R_LT_SUM, (size_t)NS * 2 * SENTRY_LANES, &sums))) return rc;
+    // nothing of this call may start before earlier work on the caller's stream is done with
+    // the staging buffers and the sums (a previous call ends on that stream)
+    SENTRY_HIP_CHECK(hipEventRecord(pipe->start, s));
+    SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->start, 0));
+    for (int i = 1; i < used; i++) SENTRY_HIP_CHECK(hipStreamWaitEvent(hstream[i], pipe->start, 0));
 
     const uint8_t *src = static_cast<const uint8_t *>(host_records);
     for (size_t k = 0; k < batches.size(); k++) {
         const Batch &bt = batches[k];
-        const int b = (int)(k & 1);
+        const int b = (int)(k % NS);
+        hipStream_t hs = hstream[b];
         const uint64_t beg = host_offsets[bt.first], end = host_offsets[bt.first + bt.count];
-        SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->consumed[b], 0));
+        if (k >= (size_t)NS) SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->consumed[b], 0));
         if (end > beg)
             SENTRY_HIP_CHECK(hipMemcpyAsync(stage[b], src + beg, end - beg, hipMemcpyHostToDevice, pipe->copy_stream));
         SENTRY_HIP_CHECK(hipMemcpyAsync(stage_off[b], host_offsets + bt.first, 8 * (bt.count + 1),
                                         hipMemcpyHostToDevice, pipe->copy_stream));
         SENTRY_HIP_CHECK(hipEventRecord(pipe->copied[b], pipe->copy_stream));
-        SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->copied[b], 0));
+        SENTRY_HIP_CHECK(hipStreamWaitEvent(hs, pipe->copied[b], 0));
         // record i of the batch sits at stage + (offset[i] - beg); the kernel copes with any
         // byte alignment of a record
-        rc = sentry::lthash_into(stage[b], static_cast<const uint64_t *>(stage_off[b]), beg, bt.count, out_lanes,
-                                 k > 0, s);
+        rc = sentry::lthash_into(stage[b], static_cast<const uint64_t *>(stage_off[b]), beg, bt.count,
+                                 static_cast<uint16_t *>(sums) + (size_t)b * SENTRY_LANES, k >= (size_t)NS, hs);
         if (rc) return rc;
-        SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], s));
+        SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], hs));
     }
-    return SENTRY_OK;
+    for (int i = 1; i < used; i++) SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->consumed[i], 0));
+    return sentry::lthash_sum_rows(static_cast<const uint16_t *>(sums), (uint32_t)used, out_lanes, s);
 }
 
 }  // extern "C"
