@@ -63,6 +63,8 @@ def lib():
         L.oracle_lthash_one.restype = None
         L.oracle_lthash.argtypes = [vp, vp, sz, vp]
         L.oracle_lthash.restype = None
+        L.oracle_lthash_sources.argtypes = [vp, vp, vp, sz, sz, vp]
+        L.oracle_lthash_sources.restype = None
         L.oracle_lthash_combine.argtypes = [vp, vp]
         L.oracle_lthash_combine.restype = None
         L.oracle_lthash_remove.argtypes = [vp, vp]
@@ -188,6 +190,19 @@ def lthash(records, offsets):
     if n:
         assert int(off[-1]) <= a.size
     lib().oracle_lthash(_ptr(a), _ptr(off), n, out.ctypes.data)
+    return out
+
+
+def lthash_sources(records, offsets, sources, n_sources, acc=None):
+    """Per-source running sums: returns acc (n_sources x 1024 uint16) updated with this batch."""
+    a = _u8(records)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    src = np.ascontiguousarray(sources, dtype=np.uint32)
+    n = max(off.size - 1, 0)
+    assert src.size == n
+    out = np.zeros((n_sources, LANES), np.uint16) if acc is None else np.array(acc, dtype=np.uint16, copy=True)
+    assert out.shape == (n_sources, LANES)
+    lib().oracle_lthash_sources(_ptr(a), _ptr(off), _ptr(src), n, n_sources, out.ctypes.data)
     return out
 
 

@@ -17,6 +17,7 @@
  *   - lattice hash = component-wise sum of per-item digests mod 2^d, d = 16:
  *                                      section 2.2 Eq. (1), section 4.2.2.
  *   - one digest per dataset sample, running sum over batches: section 4.3.
+ *   - batches that mix data sources, one running sum per source: section 4.1.2, 4.3.
  *
  * Readings fixed where the paper leaves the point open (the build's target
  * configurations fix them):
@@ -375,6 +376,22 @@ void oracle_lthash(const uint8_t *records, const uint64_t *offsets, size_t n,
         oracle_lthash_one(records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), lanes);
         for (int l = 0; l < ORACLE_LANES; l++)
             acc[l] = (uint16_t)((acc[l] + lanes[l]) & 0xFFFFu);
+    }
+}
+
+/* Mixed-source batch (section 4.1.2, section 4.3): record i belongs to data source src[i];
+ * every source keeps a running sum, acc[s] += sum of the digests of its records in this
+ * batch.  acc holds n_sources rows of 1024 lanes and is updated in place.  Records whose
+ * source id is not below n_sources are left out. */
+void oracle_lthash_sources(const uint8_t *records, const uint64_t *offsets, const uint32_t *src,
+                           size_t n, size_t n_sources, uint16_t *acc)
+{
+    for (size_t i = 0; i < n; i++) {
+        if (src[i] >= n_sources) continue;
+        uint16_t lanes[ORACLE_LANES];
+        oracle_lthash_one(records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), lanes);
+        uint16_t *row = acc + (size_t)src[i] * ORACLE_LANES;
+        for (int l = 0; l < ORACLE_LANES; l++) row[l] = (uint16_t)((row[l] + lanes[l]) & 0xFFFFu);
     }
 }
 

@@ -93,3 +93,30 @@ def test_modulus_is_2_to_16():
     d = oracle.lthash_remove(np.zeros(1024, np.uint16), b)
     assert (d[::2] == 0xFFFF).all() and (d[1::2] == 0).all()
     assert (oracle.lthash_combine(one, one).astype(np.int64) == (2 * one.astype(np.int64)) % 65536).all()
+
+
+def test_per_source_sums_are_the_hashes_of_the_sub_multisets():
+    # section 4.1.2 / 4.3: a shuffled batch holds samples of several providers; each provider's
+    # running sum must equal the lattice hash of exactly its samples
+    rng = random.Random(26)
+    nprng = np.random.default_rng(26)
+    recs = [rng.randbytes(rng.randrange(0, 300)) for _ in range(60)]
+    src = nprng.integers(0, 5, 60).astype(np.uint32)
+    src[7] = 9                                   # an id outside the table is left out
+    data, off = pack(recs)
+    acc = oracle.lthash_sources(data, off, src, 5)
+    for s in range(5):
+        mine = [r for r, k in zip(recs, src) if k == s]
+        assert (acc[s] == oracle.lthash(*pack(mine))).all(), s
+    # the sources partition the batch (minus the dropped record)
+    total = np.zeros(1024, np.uint16)
+    for s in range(5):
+        total = oracle.lthash_combine(total, acc[s])
+    kept = [r for r, k in zip(recs, src) if k < 5]
+    assert (total == oracle.lthash(*pack(kept))).all()
+    # running sums: a second batch adds on top, batch order does not matter
+    acc2 = oracle.lthash_sources(data, off, src, 5, acc=acc)
+    assert (acc2 == (2 * acc.astype(np.int64)) % 65536).all()
+    # one source is the plain lattice hash
+    one = oracle.lthash_sources(data, off, np.zeros(60, np.uint32), 1)
+    assert (one[0] == oracle.lthash(data, off)).all()
