@@ -227,6 +227,14 @@ def main():
         ms = timed_call(lambda: sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream), 50)
         per_config["C2_lthash_50k_images"] = {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(),
                                               "samples/s": 50_000 / (ms * 1e-3)}
+        # mixed-source batches (section 4.3): the same 50,000 samples spread over 1, 16 and 128 sources
+        for n_src in (1, 16, 128):
+            ids = torch.from_numpy((wl._words_np(wl.SEED_C2 + 7, 0, 50_000) % np.uint64(n_src)).astype(np.int32)).to(dev)
+            acc = torch.zeros(n_src * 1024, dtype=torch.int16, device=dev)
+            ms = timed_call(lambda: sentry.sentry_lthash_sources(img.data_ptr(), d_ioff.data_ptr(), ids.data_ptr(),
+                                                                 50_000, n_src, acc.data_ptr(), stream), 30)
+            per_config["F1_lthash_50k_images_%d_sources" % n_src] = {"GB/s": img.numel() / ms / 1e6, "ms": ms,
+                                                                    "samples/s": 50_000 / (ms * 1e-3)}
         # host-to-device streaming: pinned host buffers, copy-only rate vs hash-while-loading rate
         hbytes = (1 << 28) if args.quick else (4 << 30)
         host = torch.empty(hbytes, dtype=torch.uint8).pin_memory()

@@ -168,6 +168,25 @@ SENTRY_API int sentry_verify(const uint8_t *root, const uint8_t *expected);
 SENTRY_API int sentry_lthash(const void *dev_records, const uint64_t *dev_offsets, size_t n,
                   uint16_t *out_lanes, void *stream);
 
+/*
+ * Batches that mix data sources (section 4.1.2: shuffled batches hold samples of
+ * several providers; section 4.3: a dictionary maps each source to its samples, one
+ * reduction per source, each result added to that source's running sum):
+ *   acc_lanes[k][l] += sum over records i with source_id[i] == k of h(record_i)[l]
+ * mod 2^16, for every source k < n_sources, in one call per batch.  With one
+ * source and acc zeroed this is sentry_lthash.
+ * dev_records, dev_offsets, n   as for sentry_lthash.
+ * dev_source_ids  device, n uint32 (4-byte aligned); a record whose id is not
+ *                 below n_sources is left out of every sum.
+ * n_sources       1 .. 4096.
+ * acc_lanes       device-accessible, n_sources rows of 1024 uint16 (2-byte
+ *                 aligned), read and updated: the caller zeroes it before the
+ *                 first batch and carries it from batch to batch.
+ */
+SENTRY_API int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets,
+                                     const uint32_t *dev_source_ids, size_t n, size_t n_sources,
+                                     uint16_t *acc_lanes, void *stream);
+
 /* acc[l] = (acc[l] + x[l]) mod 2^16 and (acc[l] - x[l]) mod 2^16 (section 2.2:
  * LtHash(S1)+LtHash(S2) = LtHash(S1 u S2), LtHash(S1 u S2)-LtHash(S1) =
  * LtHash(S2); the lattice addition of section 4.2.2).  Both device-accessible,

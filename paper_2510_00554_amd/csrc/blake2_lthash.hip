@@ -459,6 +459,209 @@ lthash_addsub_kernel(uint16_t *acc, const uint16_t *x)
     acc[2 * c + 1] = r.y;
 }
 
+// ---------------------------------------------------------------------------
+// mixed-source batches: one running sum per data source (section 4.1.2, section 4.3)
+// ---------------------------------------------------------------------------
+//
+// The paper keeps a dictionary source -> samples of the batch and spawns one reduction tree
+// per source.  Here the dictionary is a counting sort by source id done on the device (the
+// ids are device memory, the host never sees them): count, scan, scatter.  Each source's
+// records are then cut into units of `unit` records; one wave expands and sums one unit in
+// registers exactly as in lthash_expand_kernel and writes a 2 KiB partial row; the rows of a
+// source are adjacent, and a last kernel adds them to that source's running sum.
+
+constexpr int SRC_WG = 256;
+constexpr uint32_t SRC_MAX_SOURCES = 4096;
+
+// tables (uint32): count[S] | start[S+1] | unit_start[S+1] | cursor[S]
+__device__ __forceinline__ uint32_t *tab_count(uint32_t *t, uint32_t) { return t; }
+__device__ __forceinline__ uint32_t *tab_start(uint32_t *t, uint32_t S) { return t + S; }
+__device__ __forceinline__ uint32_t *tab_unit_start(uint32_t *t, uint32_t S) { return t + 2 * S + 1; }
+__device__ __forceinline__ uint32_t *tab_cursor(uint32_t *t, uint32_t S) { return t + 3 * S + 2; }
+
+__global__ void __launch_bounds__(SRC_WG)
+src_zero_kernel(uint32_t *tables, uint32_t n_words)
+{
+    for (uint32_t i = blockIdx.x * SRC_WG + threadIdx.x; i < n_words; i += gridDim.x * SRC_WG) tables[i] = 0;
+}
+
+// Counts and ranks are first taken in LDS per workgroup tile, so that a source with many
+// records costs one global atomic per tile instead of one per record.
+constexpr int SRC_ITEMS = 8;                      // records per lane
+constexpr int SRC_TILE = SRC_WG * SRC_ITEMS;      // records per workgroup
+
+__global__ void __launch_bounds__(SRC_WG)
+src_count_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t *tables)
+{
+    __shared__ uint32_t hist[SRC_MAX_SOURCES];
+    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG) hist[k] = 0;
+    __syncthreads();
+    const uint64_t tile = (uint64_t)blockIdx.x * SRC_TILE;
+#pragma unroll
+    for (int q = 0; q < SRC_ITEMS; q++) {
+        const uint64_t i = tile + (uint64_t)q * SRC_WG + threadIdx.x;
+        if (i < n) {
+            const uint32_t k = src[i];
+            if (k < S) atomicAdd(&hist[k], 1u);
+        }
+    }
+    __syncthreads();
+    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG)
+        if (hist[k]) atomicAdd(&tab_count(tables, S)[k], hist[k]);
+}
+
+// one workgroup: start[] = exclusive scan of count[], unit_start[] = exclusive scan of
+// ceil(count/unit); both get a closing total
+__global__ void __launch_bounds__(SRC_WG)
+src_plan_kernel(uint32_t S, uint32_t unit, uint32_t *tables)
+{
+    __shared__ uint32_t sum_c[SRC_WG], sum_u[SRC_WG];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t per = (S + SRC_WG - 1) / SRC_WG;
+    const uint32_t lo = tid * per, hi = lo + per < S ? lo + per : S;
+    uint32_t c = 0, u = 0;
+    for (uint32_t k = lo; k < hi; k++) {
+        const uint32_t x = tab_count(tables, S)[k];
+        c += x;
+        u += (x + unit - 1) / unit;
+    }
+    sum_c[tid] = c;
+    sum_u[tid] = u;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t ac = 0, au = 0;
+        for (int t = 0; t < SRC_WG; t++) {
+            const uint32_t xc = sum_c[t], xu = sum_u[t];
+            sum_c[t] = ac; sum_u[t] = au;
+            ac += xc; au += xu;
+        }
+        tab_start(tables, S)[S] = ac;
+        tab_unit_start(tables, S)[S] = au;
+    }
+    __syncthreads();
+    c = sum_c[tid];
+    u = sum_u[tid];
+    for (uint32_t k = lo; k < hi; k++) {
+        const uint32_t x = tab_count(tables, S)[k];
+        tab_start(tables, S)[k] = c;
+        tab_unit_start(tables, S)[k] = u;
+        c += x;
+        u += (x + unit - 1) / unit;
+    }
+}
+
+__global__ void __launch_bounds__(SRC_WG)
+src_scatter_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t *tables, uint32_t *perm)
+{
+    __shared__ uint32_t cnt[SRC_MAX_SOURCES];     // records of source k in this tile, then the tile's base
+    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG) cnt[k] = 0;
+    __syncthreads();
+    const uint64_t tile = (uint64_t)blockIdx.x * SRC_TILE;
+    uint32_t key[SRC_ITEMS], rank[SRC_ITEMS];
+#pragma unroll
+    for (int q = 0; q < SRC_ITEMS; q++) {
+        const uint64_t i = tile + (uint64_t)q * SRC_WG + threadIdx.x;
+        key[q] = 0xffffffffu;
+        rank[q] = 0;
+        if (i < n) {
+            const uint32_t k = src[i];
+            if (k < S) { key[q] = k; rank[q] = atomicAdd(&cnt[k], 1u); }
+        }
+    }
+    __syncthreads();
+    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG)
+        if (cnt[k]) cnt[k] = tab_start(tables, S)[k] + atomicAdd(&tab_cursor(tables, S)[k], cnt[k]);
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < SRC_ITEMS; q++) {
+        const uint64_t i = tile + (uint64_t)q * SRC_WG + threadIdx.x;
+        if (key[q] != 0xffffffffu) perm[cnt[key[q]] + rank[q]] = (uint32_t)i;
+    }
+}
+
+// One wave per unit.  Lane l owns output block l & 31 and takes every second record of the
+// unit; the order of the records inside a source does not matter for the sum.
+__global__ void __launch_bounds__(EXP_WG)
+lthash_expand_units_kernel(const uint64_t *h0, const uint32_t *perm, uint32_t S, uint32_t unit,
+                           uint32_t *tables, uint32_t *part_out)
+{
+    const uint32_t lane = threadIdx.x & 63, j = lane & 31;
+    const uint32_t u = blockIdx.x * EXP_WAVES + (threadIdx.x >> 6);
+    const uint32_t *unit_start = tab_unit_start(tables, S);
+    if (u >= unit_start[S]) return;                     // wave-uniform
+    // the source whose unit range holds u: last k with unit_start[k] <= u
+    uint32_t lo = 0, hi = S;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (unit_start[mid] <= u) lo = mid; else hi = mid;
+    }
+    const uint32_t k = lo;
+    const uint32_t *start = tab_start(tables, S);
+    const uint32_t first = start[k] + (u - unit_start[k]) * unit;
+    const uint32_t stop = first + unit < start[k + 1] ? first + unit : start[k + 1];
+    u16x2 acc[16];
+#pragma unroll
+    for (int q = 0; q < 16; q++) acc[q] = u16x2{0, 0};
+    for (uint32_t r = first + (lane >> 5); r < stop; r += 2) {
+        const uint64_t rec = perm[r];
+        uint64_t m[16];
+#pragma unroll
+        for (int q = 0; q < 8; q++) { m[q] = h0[8 * rec + q]; m[8 + q] = 0; }
+        uint64_t h[8];
+#pragma unroll
+        for (int q = 0; q < 8; q++) h[q] = b2_iv(q);
+        h[0] ^= EXP_P0;
+        h[1] ^= EXP_P1_HI | (uint64_t)j;
+        h[2] ^= EXP_P2;
+        blake2b_compress(h, m, 64, true);
+#pragma unroll
+        for (int q = 0; q < 8; q++) {
+            const uint32_t l32 = (uint32_t)h[q], h32 = (uint32_t)(h[q] >> 32);
+            acc[2 * q] += u16x2{(unsigned short)l32, (unsigned short)(l32 >> 16)};
+            acc[2 * q + 1] += u16x2{(unsigned short)h32, (unsigned short)(h32 >> 16)};
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 16; q++) {
+        const uint32_t x = (uint32_t)acc[q].x | ((uint32_t)acc[q].y << 16);
+        const uint32_t y = (uint32_t)__shfl_xor((int)x, 32, 64);
+        const u16x2 t = acc[q] + u16x2{(unsigned short)y, (unsigned short)(y >> 16)};
+        if (lane < 32) part_out[(uint64_t)u * LANE_WORDS + 16 * j + q] = (uint32_t)t.x | ((uint32_t)t.y << 16);
+    }
+}
+
+// acc[k][c] += sum of the partial rows of source k; grid = (512 / FOLD_COLS, S)
+__global__ void __launch_bounds__(FOLD_WG)
+lthash_fold_sources_kernel(const uint32_t *part, uint32_t S, uint32_t *tables, uint16_t *acc)
+{
+    constexpr int ROWS = FOLD_WG / FOLD_COLS;
+    const uint32_t k = blockIdx.y;
+    const uint32_t col = blockIdx.x * FOLD_COLS + (threadIdx.x % FOLD_COLS);
+    const uint32_t row0 = threadIdx.x / FOLD_COLS;
+    const uint32_t *unit_start = tab_unit_start(tables, S);
+    const uint32_t u0 = unit_start[k], u1 = unit_start[k + 1];
+    if (u0 == u1) return;                               // no record of this source in the batch
+    u16x2 s = u16x2{0, 0};
+    for (uint32_t u = u0 + row0; u < u1; u += ROWS) {
+        const uint32_t x = part[(uint64_t)u * LANE_WORDS + col];
+        s += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+    }
+    __shared__ uint32_t lds[ROWS][FOLD_COLS];
+    lds[row0][threadIdx.x % FOLD_COLS] = (uint32_t)s.x | ((uint32_t)s.y << 16);
+    __syncthreads();
+    if (row0 == 0) {
+        u16x2 t = u16x2{0, 0};
+#pragma unroll
+        for (int r = 0; r < ROWS; r++) {
+            const uint32_t x = lds[r][threadIdx.x];
+            t += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+        }
+        uint16_t *row = acc + (uint64_t)k * SENTRY_LANES;
+        row[2 * col] = (uint16_t)(row[2 * col] + t.x);
+        row[2 * col + 1] = (uint16_t)(row[2 * col + 1] + t.y);
+    }
+}
+
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 int g_cu_count = 0;
@@ -568,6 +771,57 @@ static int addsub(const char *fn, uint16_t *acc, const uint16_t *x, void *stream
         hipLaunchKernelGGL(lthash_addsub_kernel<true>, dim3(1), dim3(LANE_WORDS), 0, s, acc, x);
     else
         hipLaunchKernelGGL(lthash_addsub_kernel<false>, dim3(1), dim3(LANE_WORDS), 0, s, acc, x);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
+int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, const uint32_t *dev_source_ids,
+                          size_t n, size_t n_sources, uint16_t *acc_lanes, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(n_sources >= 1 && n_sources <= SRC_MAX_SOURCES, "sentry_lthash_sources: n_sources must be 1..%u",
+                   SRC_MAX_SOURCES);
+    SENTRY_REQUIRE(acc_lanes != nullptr && (reinterpret_cast<uintptr_t>(acc_lanes) & 1) == 0,
+                   "sentry_lthash_sources: acc_lanes must be non-NULL and 2-byte aligned");
+    if (n == 0) return SENTRY_OK;
+    SENTRY_REQUIRE(dev_offsets != nullptr && (reinterpret_cast<uintptr_t>(dev_offsets) & 7) == 0,
+                   "sentry_lthash_sources: dev_offsets must be non-NULL and 8-byte aligned");
+    SENTRY_REQUIRE(dev_source_ids != nullptr && (reinterpret_cast<uintptr_t>(dev_source_ids) & 3) == 0,
+                   "sentry_lthash_sources: dev_source_ids must be non-NULL and 4-byte aligned");
+    SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash_sources: too many records");
+    const uint32_t S = (uint32_t)n_sources;
+    // records per unit: at least 32, and few enough units to keep the partial rows small
+    uint32_t unit = 32;
+    while (ceil_div(n, unit) > 8192) unit *= 2;
+    const uint64_t max_units = ceil_div(n, unit) + S;          // every source may end in a short unit
+    void *h0, *part, *tables, *perm;
+    int rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_LT_H0, 64 * n, &h0))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_LT_PART, max_units * LANE_WORDS * 4, &part))) return rc;
+    const uint32_t table_words = 4 * S + 2;
+    if ((rc = sentry::scratch_get(s, sentry::R_SRC_TABLES, 4 * (size_t)table_words, &tables))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_SRC_PERM, 4 * n, &perm))) return rc;
+    uint32_t *tab = static_cast<uint32_t *>(tables);
+    const uint32_t *src = dev_source_ids;
+    const uint32_t scan_grid = (uint32_t)ceil_div(n, SRC_TILE);
+
+    hipLaunchKernelGGL(src_zero_kernel, dim3(1), dim3(SRC_WG), 0, s, tab, table_words);
+    hipLaunchKernelGGL(src_count_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab);
+    hipLaunchKernelGGL(src_plan_kernel, dim3(1), dim3(SRC_WG), 0, s, S, unit, tab);
+    hipLaunchKernelGGL(src_scatter_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab,
+                       static_cast<uint32_t *>(perm));
+    SENTRY_HIP_CHECK(hipGetLastError());
+    const bool full = n >= (uint64_t)cu_count() * 256 * 4;
+    const uint64_t grid_r = full ? ceil_div(n, ROOT4_WG) : ceil_div(n, ROOT4_RECORDS);
+    hipLaunchKernelGGL(lthash_root_kernel, dim3((uint32_t)grid_r), dim3(ROOT4_WG), 0, s,
+                       static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
+                       static_cast<uint64_t *>(h0), full ? 1 : 0);
+    hipLaunchKernelGGL(lthash_expand_units_kernel, dim3((uint32_t)ceil_div(max_units, EXP_WAVES)), dim3(EXP_WG), 0, s,
+                       static_cast<const uint64_t *>(h0), static_cast<const uint32_t *>(perm), S, unit, tab,
+                       static_cast<uint32_t *>(part));
+    hipLaunchKernelGGL(lthash_fold_sources_kernel, dim3(LANE_WORDS / FOLD_COLS, S), dim3(FOLD_WG), 0, s,
+                       static_cast<const uint32_t *>(part), S, tab, acc_lanes);
     SENTRY_HIP_CHECK(hipGetLastError());
     return SENTRY_OK;
 }

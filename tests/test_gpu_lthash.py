@@ -162,3 +162,75 @@ def test_many_records_take_the_one_lane_path():
     off = wl.offsets_from_lengths(lens)
     data = wl.uniform_bytes(1600, 0, int(off[-1]))
     assert (gpu_lthash(data, off) == oracle.lthash(data, off)).all()
+
+
+def gpu_sources(data_np, off_np, src_np, n_sources, acc=None):
+    n = len(off_np) - 1
+    buf = to_dev(data_np) if data_np.size else torch.zeros(16, dtype=torch.uint8, device="cuda")
+    off = to_dev(np.asarray(off_np, dtype=np.uint64))
+    src = torch.from_numpy(np.asarray(src_np, dtype=np.uint32).view(np.int32).copy()).cuda()
+    if acc is None:
+        acc = torch.zeros(n_sources * 1024, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash_sources(buf.data_ptr(), off.data_ptr(), src.data_ptr(), n, n_sources, acc.data_ptr())
+    torch.cuda.synchronize()
+    return acc
+
+
+def as_u16(acc, n_sources):
+    return acc.cpu().numpy().view(np.uint16).reshape(n_sources, 1024)
+
+
+@pytest.mark.parametrize("n,n_sources", [(1, 1), (60, 5), (1000, 16), (5000, 128), (333, 4096)])
+def test_per_source_running_sums(n, n_sources):
+    rng = np.random.default_rng(71 + n)
+    lens = rng.integers(0, 600, n).astype(np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(1700 + n, 0, int(off[-1]))
+    src = rng.integers(0, n_sources, n).astype(np.uint32)
+    if n > 10:
+        src[3] = n_sources          # ids outside the table are left out
+        src[7] = 0xFFFFFFFF
+    want = oracle.lthash_sources(data, off, src, n_sources)
+    acc = gpu_sources(data, off, src, n_sources)
+    assert (as_u16(acc, n_sources) == want).all()
+    # a second batch lands on top of the running sums
+    want2 = oracle.lthash_sources(data, off, src, n_sources, acc=want)
+    acc = gpu_sources(data, off, src, n_sources, acc=acc)
+    assert (as_u16(acc, n_sources) == want2).all()
+
+
+def test_per_source_skewed_and_single_source_equals_plain_hash():
+    n = 3000
+    rng = np.random.default_rng(81)
+    lens = rng.integers(1, 400, n).astype(np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(1800, 0, int(off[-1]))
+    src = np.zeros(n, np.uint32)
+    src[rng.choice(n, 40, replace=False)] = rng.integers(1, 8, 40)   # one source owns nearly everything
+    assert (as_u16(gpu_sources(data, off, src, 8), 8) == oracle.lthash_sources(data, off, src, 8)).all()
+    one = as_u16(gpu_sources(data, off, np.zeros(n, np.uint32), 1), 1)
+    assert (one[0] == gpu_lthash(data, off)).all() and (one[0] == oracle.lthash(data, off)).all()
+
+
+def test_per_source_many_records_larger_units():
+    # more than 8192 units of 32 records: the unit size doubles
+    n = 300_000
+    rng = np.random.default_rng(91)
+    lens = rng.integers(0, 24, n).astype(np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(1900, 0, int(off[-1]))
+    src = rng.integers(0, 16, n).astype(np.uint32)
+    assert (as_u16(gpu_sources(data, off, src, 16), 16) == oracle.lthash_sources(data, off, src, 16)).all()
+
+
+def test_per_source_image_batches_like_the_paper():
+    # 16 sources, batches of 512 image-shaped samples (section 5: batch sizes 32..512, 16 sources)
+    n_sources, batch = 16, 512
+    data, off = wl.image_records(4 * batch)
+    rng = np.random.default_rng(95)
+    src = rng.integers(0, n_sources, 4 * batch).astype(np.uint32)
+    acc = torch.zeros(n_sources * 1024, dtype=torch.int16, device="cuda")
+    for b in range(4):
+        lo, hi = b * batch, (b + 1) * batch
+        acc = gpu_sources(data, off[lo:hi + 1], src[lo:hi], n_sources, acc=acc)
+    assert (as_u16(acc, n_sources) == oracle.lthash_sources(data, off, src, n_sources)).all()
