@@ -49,6 +49,8 @@ def lib():
         L.oracle_merkle_root.restype = ctypes.c_int
         L.oracle_merkle_segments.argtypes = [vp, vp, sz, sz, vp, vp]
         L.oracle_merkle_segments.restype = ctypes.c_int
+        L.oracle_merkle_inplace.argtypes = [vp, vp, sz, sz, vp]
+        L.oracle_merkle_inplace.restype = ctypes.c_int
         L.oracle_verify.argtypes = [vp, vp]
         L.oracle_verify.restype = ctypes.c_int
         L.oracle_blake2b_constants.argtypes = [vp, vp]
@@ -136,6 +138,19 @@ def merkle_segments(segments, leaf_bytes):
     if rc:
         raise ValueError("oracle_merkle_segments rc=%d" % rc)
     return [seg[i].tobytes() for i in range(n)], out.tobytes()
+
+
+def merkle_inplace(segments, leaf_bytes):
+    """One flat tree over the blocks of all segments (Algorithm 3); returns the root."""
+    arrs = [_u8(s) for s in segments]
+    n = len(arrs)
+    ptrs = (ctypes.c_void_p * max(n, 1))(*[_ptr(a) for a in arrs])
+    lens = (ctypes.c_size_t * max(n, 1))(*[a.size for a in arrs])
+    out = np.empty(32, np.uint8)
+    rc = lib().oracle_merkle_inplace(ptrs, lens, n, leaf_bytes, out.ctypes.data)
+    if rc:
+        raise ValueError("oracle_merkle_inplace rc=%d" % rc)
+    return out.tobytes()
 
 
 def verify(a, b):

@@ -14,6 +14,7 @@
  *     padded or modified:              section 4.2.1 "In-place Hashing".
  *   - per-tensor digests, then one reduction over the list of per-tensor
  *     digests:                         Algorithm 2 (per-layer hashing).
+ *   - one flat tree over the blocks of all fragmented tensors: Algorithm 3.
  *   - lattice hash = component-wise sum of per-item digests mod 2^d, d = 16:
  *                                      section 2.2 Eq. (1), section 4.2.2.
  *   - one digest per dataset sample, running sum over batches: section 4.3.
@@ -205,6 +206,27 @@ int oracle_merkle_segments(const uint8_t *const *ptrs, const size_t *lens, size_
     if (!nodes) return -3;
     memcpy(nodes, seg_roots, 32 * n_seg);
     oracle_merkle_reduce(nodes, n_seg, out);
+    free(nodes);
+    return 0;
+}
+
+/* Algorithm 3 (in-place hashing): the blocks of all tensors, in tensor order, are the
+ * leaves of ONE tree; the last block of a tensor is short rather than padded or filled
+ * from the next tensor (section 4.2.1, "In-place Hashing").  A tensor of length 0 has no
+ * block; if no tensor has one, the tree is the single empty leaf. */
+int oracle_merkle_inplace(const uint8_t *const *ptrs, const size_t *lens, size_t n_seg,
+                          size_t leaf_bytes, uint8_t out[32])
+{
+    if (leaf_bytes == 0) return -1;
+    size_t total = 0;
+    for (size_t t = 0; t < n_seg; t++) total += (lens[t] + leaf_bytes - 1) / leaf_bytes;
+    if (total == 0) { oracle_sha256(NULL, 0, out); return 0; }
+    uint8_t *nodes = (uint8_t *)malloc(32 * total);
+    if (!nodes) return -3;
+    size_t k = 0;
+    for (size_t t = 0; t < n_seg; t++)
+        if (lens[t]) k += oracle_merkle_leaves(ptrs[t], lens[t], leaf_bytes, nodes + 32 * k);
+    oracle_merkle_reduce(nodes, total, out);
     free(nodes);
     return 0;
 }

@@ -114,3 +114,29 @@ def test_verify():
         b = bytearray(a)
         b[i] ^= 1
         assert oracle.verify(a, bytes(b)) == 1
+
+
+def test_inplace_flat_tree_over_fragmented_tensors():
+    # Algorithm 3: one tree over the blocks of all tensors, short last blocks kept short
+    rng = random.Random(9)
+    L = 128
+    # every tensor a multiple of the block size: same as hashing the concatenation (Algorithm 1)
+    segs = [rng.randbytes(L * k) for k in (3, 1, 7, 2)]
+    assert oracle.merkle_inplace(segs, L) == brute_root(b"".join(segs), L)
+    # ragged tensors: leaves are the per-tensor blocks, in order, short tails included
+    sizes = [L * 5 + 1, 17, L * 2, 0, L - 1, L * 3 + 64]
+    segs = [rng.randbytes(s) for s in sizes]
+    level = []
+    for s in segs:
+        level += [H(s[i:i + L]) for i in range(0, len(s), L)]
+    assert len(level) == 6 + 1 + 2 + 0 + 1 + 4
+    while len(level) > 1:
+        nxt = [H(level[i] + level[i + 1]) for i in range(0, len(level) - 1, 2)]
+        if len(level) % 2:
+            nxt.append(level[-1])
+        level = nxt
+    assert oracle.merkle_inplace(segs, L) == level[0]
+    assert oracle.merkle_inplace(segs, L) != oracle.merkle_segments(segs, L)[1]   # not the per-tensor scheme
+    # one tensor: the plain root; nothing at all: the empty leaf
+    assert oracle.merkle_inplace([segs[0]], L) == oracle.merkle_root(segs[0], L)
+    assert oracle.merkle_inplace([b"", b""], L) == H(b"")
