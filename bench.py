@@ -227,6 +227,11 @@ def main():
         ms = timed_call(lambda: sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream), 50)
         per_config["C2_lthash_50k_images"] = {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(),
                                               "samples/s": 50_000 / (ms * 1e-3)}
+        # the 7B checkpoint as one flat tree over all blocks of all tensors (Algorithm 3)
+        ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, LEAF7, root7.data_ptr(), stream), 5)
+        per_config["F3_merkle_7b_inplace_flat_1MiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+        ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, 8192, root7.data_ptr(), stream), 5)
+        per_config["F3_merkle_7b_inplace_flat_8KiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
         # mixed-source batches (section 4.3): the same 50,000 samples spread over 1, 16 and 128 sources
         for n_src in (1, 16, 128):
             ids = torch.from_numpy((wl._words_np(wl.SEED_C2 + 7, 0, 50_000) % np.uint64(n_src)).astype(np.int32)).to(dev)

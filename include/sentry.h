@@ -90,6 +90,21 @@ SENTRY_API int sentry_merkle_segments(const void *const *dev_ptrs, const size_t 
                            void *stream);
 
 /*
+ * In-place hashing (Algorithm 3): ONE flat tree whose leaves are the blocks of
+ * all tensors in order, hashed where they lie by one table-driven launch (the
+ * lookup table of section 4.2.1: per range of lanes the tensor's address, block
+ * size and length).  The last block of a tensor is short, never padded and
+ * never completed from the next tensor; a tensor of length 0 has no block; if no
+ * tensor has a block the root is that of the single empty leaf.  When every
+ * length is a multiple of leaf_bytes the root equals sentry_merkle_root over the
+ * concatenated tensors.
+ * Arguments as for sentry_merkle_segments (host arrays of device pointers and
+ * lengths, read before the call returns); out_root device-accessible, 32 bytes.
+ */
+SENTRY_API int sentry_merkle_inplace(const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                                     size_t leaf_bytes, uint8_t *out_root, void *stream);
+
+/*
  * The block hashing kernel alone: the max(1, ceil(len/leaf_bytes)) leaf digests
  * of a buffer, 32 bytes each, in leaf order (section 4.2.1).
  * out_leaf_digests  device, 16-byte aligned, 32 bytes per leaf.

@@ -31,6 +31,7 @@ _vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 PROTOTYPES = {
     "sentry_merkle_root": (_int, [_vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_segments": (_int, [_vp, _vp, _sz, _sz, _vp, _vp, _vp]),
+    "sentry_merkle_inplace": (_int, [_vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_leaves": (_int, [_vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_reduce": (_int, [_vp, _sz, _vp, _vp]),
     "sentry_merkle_stream_begin": (_int, [_sz, _sz, ctypes.POINTER(_vp)]),
@@ -92,6 +93,16 @@ def sentry_merkle_segments(dev_ptrs, lens, leaf_bytes, out_seg_roots, out_root, 
     ptrs = (ctypes.c_void_p * max(n, 1))(*dev_ptrs)
     ls = (ctypes.c_size_t * max(n, 1))(*lens)
     return _check(load().sentry_merkle_segments(ptrs, ls, n, leaf_bytes, out_seg_roots, out_root, stream))
+
+
+def sentry_merkle_inplace(dev_ptrs, lens, leaf_bytes, out_root, stream=0):
+    """dev_ptrs, lens: Python sequences of ints (device addresses, byte lengths)."""
+    n = len(dev_ptrs)
+    if len(lens) != n:
+        raise ValueError("dev_ptrs and lens differ in length")
+    ptrs = (ctypes.c_void_p * max(n, 1))(*dev_ptrs)
+    ls = (ctypes.c_size_t * max(n, 1))(*lens)
+    return _check(load().sentry_merkle_inplace(ptrs, ls, n, leaf_bytes, out_root, stream))
 
 
 def sentry_merkle_leaves(dev_buf, length, leaf_bytes, out_leaf_digests, stream=0):

@@ -37,9 +37,12 @@ struct SegDesc {
 
 // One workgroup's share of a stage: `count` consecutive items starting at `first`
 // (leaf index inside segment `seg` for the leaf kernel, node index in the input
-// array for the reduce kernel).
+// array for the reduce kernel).  `out` is where the leaf kernel puts its result in the
+// output array: the node index of the group when it folds its leaves, the index of the
+// group's first leaf digest when it stores them all.
 struct Group {
     uint64_t first;
+    uint64_t out;
     uint32_t count;
     uint32_t seg;
 };
@@ -289,16 +292,17 @@ merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const
 {
     const uint32_t g = blockIdx.x, tid = threadIdx.x;
     const uint8_t *base;
-    uint64_t seglen, first;
+    uint64_t seglen, first, out_at;
     uint32_t count;
     if (SEGMENTED) {
         const Group gr = groups[g];
         const SegDesc sd = segs[gr.seg];
-        base = sd.base; seglen = sd.len; first = gr.first; count = gr.count;
+        base = sd.base; seglen = sd.len; first = gr.first; count = gr.count; out_at = gr.out;
     } else {
         base = base0; seglen = len0; first = (uint64_t)g * WG;
         const uint64_t rem = nleaves0 - first;
         count = rem < (uint64_t)WG ? (uint32_t)rem : (uint32_t)WG;
+        out_at = FUSE ? (uint64_t)g : first;
     }
     uint32_t st[8] = SENTRY_H0;
     if (tid < count) {
@@ -307,7 +311,7 @@ merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const
         hash_leaf(st, base + start, left < leaf_bytes ? left : leaf_bytes);
     }
     if (!FUSE) {
-        if (tid < count) store_digest(out + 32 * (first + tid), st);
+        if (tid < count) store_digest(out + 32 * (out_at + tid), st);
         return;
     }
     __shared__ uint32_t lds[2][8][WG];
@@ -316,7 +320,7 @@ merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const
     __syncthreads();
     uint32_t root[8];
     wg_tree_fold<WG>(lds, count, tid, root);
-    if (tid == 0) store_digest(out + 32 * (uint64_t)g, root);
+    if (tid == 0) store_digest(out + 32 * out_at, root);
 }
 
 // Block hashing kernel for launches with very few leaves, where the run time is one lane's
@@ -391,17 +395,18 @@ merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
     const bool consumer = wave & 1;
     const uint32_t g = PAIRS * blockIdx.x + pr;
     const uint8_t *base = nullptr;
-    uint64_t seglen = 0, first = 0;
+    uint64_t seglen = 0, first = 0, out_at = 0;
     uint32_t count = 0;
     if (g < n_groups) {
         if (SEGMENTED) {
             const Group gr = groups[g];
             const SegDesc sd = segs[gr.seg];
-            base = sd.base; seglen = sd.len; first = gr.first; count = gr.count;
+            base = sd.base; seglen = sd.len; first = gr.first; count = gr.count; out_at = gr.out;
         } else {
             base = base0; seglen = len0; first = (uint64_t)g * SPLIT_LEAVES;
             const uint64_t rem = nleaves0 - first;
             count = rem < (uint64_t)SPLIT_LEAVES ? (uint32_t)rem : (uint32_t)SPLIT_LEAVES;
+            out_at = FUSE ? (uint64_t)g : first;
         }
     }
     const bool have = lane < count;
@@ -470,7 +475,7 @@ merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
         }
     }
     if (!FUSE) {
-        if (consumer && have) store_digest(out + 32 * (first + lane), st);
+        if (consumer && have) store_digest(out + 32 * (out_at + lane), st);
         return;
     }
     // each consumer wave folds its 64 leaf digests; six levels for everybody keeps the
@@ -505,7 +510,7 @@ merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
         uint32_t root[8];
 #pragma unroll
         for (int i = 0; i < 8; i++) root[i] = lds[pr][cur][i][0];
-        store_digest(out + 32 * (uint64_t)g, root);
+        store_digest(out + 32 * out_at, root);
     }
 }
 
@@ -735,7 +740,7 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
         for (size_t t = 0; t < n_seg; t++) {
             const uint64_t nl = leaf_count(lens[t], leaf_bytes);
             for (uint64_t f = 0; f < nl; f += wg0)
-                g0.push_back(Group{f, (uint32_t)(nl - f < wg0 ? nl - f : wg0), (uint32_t)t});
+                g0.push_back(Group{f, (uint64_t)g0.size(), (uint32_t)(nl - f < wg0 ? nl - f : wg0), (uint32_t)t});
             m[t] = ceil_div(nl, wg0);
         }
         stages.push_back(std::move(g0));
@@ -748,7 +753,7 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
         uint64_t node0 = 0;
         for (size_t t = 0; t < n_seg; t++) {
             for (uint64_t f = 0; f < m[t]; f += RED_IN)
-                gs.push_back(Group{node0 + f, (uint32_t)(m[t] - f < RED_IN ? m[t] - f : RED_IN), (uint32_t)t});
+                gs.push_back(Group{node0 + f, (uint64_t)gs.size(), (uint32_t)(m[t] - f < RED_IN ? m[t] - f : RED_IN), (uint32_t)t});
             node0 += m[t];
             m[t] = ceil_div(m[t], RED_IN);
         }
@@ -826,6 +831,68 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
     if (out_seg_roots && roots != out_seg_roots)
         SENTRY_HIP_CHECK(hipMemcpyAsync(out_seg_roots, roots, 32 * n_seg, hipMemcpyDefault, s));
     return reduce_nodes(roots, n_seg, out_root, s);
+}
+
+int sentry_merkle_inplace(const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes,
+                          uint8_t *out_root, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(n_seg >= 1, "sentry_merkle_inplace: n_seg must be at least 1");
+    SENTRY_REQUIRE(dev_ptrs && lens && out_root, "sentry_merkle_inplace: NULL argument");
+    SENTRY_REQUIRE(leaf_bytes > 0 && leaf_bytes % 64 == 0,
+                   "sentry_merkle_inplace: leaf_bytes must be a positive multiple of 64 (got %zu)", leaf_bytes);
+    SENTRY_REQUIRE(n_seg <= 0xffffffffull, "sentry_merkle_inplace: too many segments");
+    uint64_t total = 0, waves = 0;
+    for (size_t t = 0; t < n_seg; t++) {
+        SENTRY_REQUIRE(dev_ptrs[t] != nullptr || lens[t] == 0, "sentry_merkle_inplace: segment %zu is NULL", t);
+        SENTRY_REQUIRE((reinterpret_cast<uintptr_t>(dev_ptrs[t]) & 15) == 0,
+                       "sentry_merkle_inplace: segment %zu is not 16-byte aligned", t);
+        const uint64_t nl = ceil_div(lens[t], leaf_bytes);     // an empty tensor has no block
+        total += nl;
+        waves += ceil_div(nl, 64);
+    }
+    if (total == 0) return sentry_merkle_root(nullptr, 0, leaf_bytes, out_root, stream);   // the empty leaf
+
+    // the lookup table of section 4.2.1: one row per workgroup (tensor, first block, blocks,
+    // position of the first digest in the flat digest array)
+    const bool small = waves <= SMALL_LAUNCH_WAVES;
+    const bool split = small && waves <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF;
+    const uint64_t wg0 = small ? LEAF_WG_SMALL : LEAF_WG;
+    std::vector<Group> g0;
+    uint64_t leaf0 = 0;
+    for (size_t t = 0; t < n_seg; t++) {
+        const uint64_t nl = ceil_div(lens[t], leaf_bytes);
+        for (uint64_t f = 0; f < nl; f += wg0)
+            g0.push_back(Group{f, leaf0 + f, (uint32_t)(nl - f < wg0 ? nl - f : wg0), (uint32_t)t});
+        leaf0 += nl;
+    }
+    SENTRY_REQUIRE(g0.size() <= MAX_GRID, "sentry_merkle_inplace: too many leaves");
+    const size_t table_bytes = n_seg * sizeof(SegDesc) + g0.size() * sizeof(Group);
+    void *host_tab, *dev_tab, *digests;
+    int rc = sentry::table_staging_get(s, table_bytes, &host_tab);
+    if (rc) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_TABLES, table_bytes, &dev_tab))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_NODES_A, 32 * total, &digests))) return rc;
+    SegDesc *hseg = static_cast<SegDesc *>(host_tab);
+    for (size_t t = 0; t < n_seg; t++) hseg[t] = SegDesc{static_cast<const uint8_t *>(dev_ptrs[t]), lens[t]};
+    std::memcpy(static_cast<char *>(host_tab) + n_seg * sizeof(SegDesc), g0.data(), g0.size() * sizeof(Group));
+    SENTRY_HIP_CHECK(hipMemcpyAsync(dev_tab, host_tab, table_bytes, hipMemcpyHostToDevice, s));
+    if ((rc = sentry::table_staging_mark(s))) return rc;
+    const SegDesc *dseg = static_cast<const SegDesc *>(dev_tab);
+    const Group *dgroups = reinterpret_cast<const Group *>(static_cast<char *>(dev_tab) + n_seg * sizeof(SegDesc));
+    const uint32_t grid = (uint32_t)g0.size();
+    uint8_t *dst = static_cast<uint8_t *>(digests);
+    if (split)
+        launch_split<false, true>(grid, s, nullptr, 0, 0, dseg, dgroups, (uint64_t)leaf_bytes, dst);
+    else if (small)
+        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, false, true>), dim3(grid), dim3(LEAF_WG_SMALL), 0, s,
+                           (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dgroups, (uint64_t)leaf_bytes, dst);
+    else
+        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, false, true>), dim3(grid), dim3(LEAF_WG), 0, s,
+                           (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dgroups, (uint64_t)leaf_bytes, dst);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return reduce_nodes(dst, total, out_root, s);
 }
 
 }  // extern "C"

@@ -109,6 +109,11 @@ def c3(pool):
         leaves[idx][l0:l0 + d.shape[0]] = d
     roots = [oracle.merkle_reduce(lv) for lv in leaves]
     top = oracle.merkle_reduce(np.frombuffer(b"".join(roots), np.uint8).reshape(-1, 32))
+    flat = oracle.merkle_reduce(np.concatenate(leaves, axis=0))
+    write("config3_inplace_root.txt",
+          ["Root (oracle) of the ONE flat tree over the 1 MiB blocks of all 291 tensors of config 3 in order",
+           "(Algorithm 3, in-place hashing; the 8 KiB norm tensors are short leaves)"],
+          [flat.hex()])
     write("config3_roots.txt",
           ["Per-tensor Merkle roots and model root (oracle) of config 3: 7B checkpoint (workloads.layout_7b,",
            "SEED_C3), 1 MiB leaves.  line 1: model root over the 291 tensor roots; then one tensor root per line"],

@@ -151,3 +151,17 @@ def test_config5_70b_checkpoint_resident_and_streamed():
     assert sentry.sentry_verify(bytes(out.cpu().numpy()), want) == 0
     del buf, host, stage
     free_gpu()
+
+
+def test_config3_checkpoint_inplace_flat_tree():
+    # the same 291 fragmented tensors, one flat tree over all their blocks (Algorithm 3)
+    want = bytes.fromhex(golden_lines("config3_inplace_root.txt")[0])
+    lay = wl.layout_7b()
+    tensors = [wl.checkpoint_tensor(lay, i, base_seed=wl.SEED_C3, device="cuda") for i in range(len(lay))]
+    top = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_inplace([t.data_ptr() for t in tensors], [2 * t.numel() for t in tensors], 1 << 20,
+                                 top.data_ptr())
+    torch.cuda.synchronize()
+    assert bytes(top.cpu().numpy()) == want
+    del tensors
+    free_gpu()

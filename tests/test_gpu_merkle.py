@@ -179,3 +179,44 @@ def test_two_wave_split_kernel_group_counts(leaf, n_leaves, tail):
     sentry.sentry_merkle_leaves(d.data_ptr(), size, leaf, leaves.data_ptr())
     torch.cuda.synchronize()
     assert (leaves.cpu().numpy().reshape(n_leaves, 32) == oracle.merkle_leaves(buf, leaf)).all()
+
+
+def inplace_case(sizes, leaf):
+    segs = [wl.uniform_bytes(950 + i, 0, s) for i, s in enumerate(sizes)]
+    devs = [to_dev(s) if s.size else torch.empty(16, dtype=torch.uint8, device="cuda") for s in segs]
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_inplace([d.data_ptr() for d in devs], list(sizes), leaf, out.data_ptr())
+    torch.cuda.synchronize()
+    assert bytes(out.cpu().numpy()) == oracle.merkle_inplace(segs, leaf), (sizes, leaf)
+    for d, s in zip(devs, segs):
+        if s.size:
+            assert (d.cpu().numpy() == s).all()
+
+
+def test_inplace_flat_tree():
+    # Algorithm 3: one tree over the blocks of all tensors, short tails kept short
+    inplace_case([4096 * 3, 17, 4096, 0, 4096 * 2 + 1, 64], 4096)
+    inplace_case([100], 64)
+    inplace_case([0, 0], 64)
+    inplace_case([64 * 300, 64 * 256, 64 * 257 + 3, 64, 64 * 1000], 64)
+    inplace_case([512 * 70 + 9, 512 * 64, 5, 512 * 200], 512)            # two-wave kernel
+    inplace_case([64 * (256 * 512 + 5), 64 * 10, 64 * (256 * 3)], 64)    # 256-leaf groups, three reduce passes
+    # whole blocks everywhere: equal to the tree over the concatenation (Algorithm 1)
+    sizes = [4096 * 5, 4096, 4096 * 11]
+    segs = [wl.uniform_bytes(990 + i, 0, s) for i, s in enumerate(sizes)]
+    devs = [to_dev(s) for s in segs]
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_inplace([d.data_ptr() for d in devs], sizes, 4096, out.data_ptr())
+    torch.cuda.synchronize()
+    assert bytes(out.cpu().numpy()) == oracle.merkle_root(np.concatenate(segs), 4096)
+
+
+def test_inplace_tiny_checkpoint_layout():
+    lay = wl.layout_tiny()
+    tensors = wl.checkpoint_bytes_np(lay)
+    devs = [to_dev(t) for t in tensors]
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    for leaf in (8192, 4096, 1 << 20):
+        sentry.sentry_merkle_inplace([d.data_ptr() for d in devs], [t.size for t in tensors], leaf, out.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(out.cpu().numpy()) == oracle.merkle_inplace(tensors, leaf), leaf
