@@ -67,6 +67,8 @@ def lib():
         L.oracle_lthash.restype = None
         L.oracle_lthash_sources.argtypes = [vp, vp, vp, sz, sz, vp]
         L.oracle_lthash_sources.restype = None
+        L.oracle_lthash_model.argtypes = [vp, vp, sz, sz, vp, vp]
+        L.oracle_lthash_model.restype = None
         L.oracle_lthash_combine.argtypes = [vp, vp]
         L.oracle_lthash_combine.restype = None
         L.oracle_lthash_remove.argtypes = [vp, vp]
@@ -219,6 +221,18 @@ def lthash_sources(records, offsets, sources, n_sources, acc=None):
     assert out.shape == (n_sources, LANES)
     lib().oracle_lthash_sources(_ptr(a), _ptr(off), _ptr(src), n, n_sources, out.ctypes.data)
     return out
+
+
+def lthash_model(segments, block_bytes):
+    """Model lattice hash (Algorithm 4): returns (per-layer lanes n_seg x 32, model lanes 32)."""
+    arrs = [_u8(s) for s in segments]
+    n = len(arrs)
+    ptrs = (ctypes.c_void_p * max(n, 1))(*[_ptr(a) for a in arrs])
+    lens = (ctypes.c_size_t * max(n, 1))(*[a.size for a in arrs])
+    layer = np.zeros((max(n, 1), 32), np.uint16)
+    total = np.zeros(32, np.uint16)
+    lib().oracle_lthash_model(ptrs, lens, n, block_bytes, layer.ctypes.data, total.ctypes.data)
+    return layer[:n], total
 
 
 def lthash_combine(acc, x):

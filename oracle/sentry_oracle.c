@@ -19,6 +19,8 @@
  *                                      section 2.2 Eq. (1), section 4.2.2.
  *   - one digest per dataset sample, running sum over batches: section 4.3.
  *   - batches that mix data sources, one running sum per source: section 4.1.2, 4.3.
+ *   - lattice hash of a model, block index mixed into each block digest: section 4.2.2,
+ *     Algorithm 4.
  *
  * Readings fixed where the paper leaves the point open (the build's target
  * configurations fix them):
@@ -415,6 +417,48 @@ void oracle_lthash_sources(const uint8_t *records, const uint64_t *offsets, cons
         uint16_t *row = acc + (size_t)src[i] * ORACLE_LANES;
         for (int l = 0; l < ORACLE_LANES; l++) row[l] = (uint16_t)((row[l] + lanes[l]) & 0xFFFFu);
     }
+}
+
+/* Model lattice hash (section 4.2.2, Algorithm 4).  The blocks of all tensors, in tensor
+ * order, are numbered 0, 1, 2, ... across the model; block k of block_bytes bytes (the last
+ * block of a tensor may be short) has the digest BLAKE2b-512(LE64(k) || block), read as 32
+ * little-endian uint16 partitions (the 64-byte, 4 x 16 bits per 64-bit word layout of
+ * section 4.2.2).  layer_lanes[t] = sum of the digests of tensor t's blocks, lanes = sum over
+ * all blocks = sum of the layer digests, every partition mod 2^16.
+ * Reading: the text says the block is concatenated with "the block index" against
+ * reordering, Algorithm 4 prints the layer index; the block index is taken, since a layer
+ * index would not tell two blocks of one layer apart.  Width, position and byte order of
+ * the index (8 bytes, little endian, in front) are this build's choice. */
+#define ORACLE_MODEL_LANES 32
+void oracle_lthash_model(const uint8_t *const *ptrs, const size_t *lens, size_t n_seg, size_t block_bytes,
+                         uint16_t *layer_lanes /* n_seg * 32, may be NULL */, uint16_t lanes[ORACLE_MODEL_LANES])
+{
+    uint8_t param[64];
+    memset(param, 0, sizeof param);
+    param[0] = 64; param[2] = 1; param[3] = 1;      /* plain BLAKE2b-512: digest 64, fanout 1, depth 1 */
+    uint8_t *msg = (uint8_t *)malloc(block_bytes + 8);
+    memset(lanes, 0, ORACLE_MODEL_LANES * sizeof(uint16_t));
+    uint64_t k = 0;
+    for (size_t t = 0; t < n_seg; t++) {
+        uint16_t layer[ORACLE_MODEL_LANES];
+        memset(layer, 0, sizeof layer);
+        for (size_t start = 0; start < lens[t]; start += block_bytes, k++) {
+            size_t n = lens[t] - start < block_bytes ? lens[t] - start : block_bytes;
+            for (int i = 0; i < 8; i++) msg[i] = (uint8_t)(k >> (8 * i));
+            memcpy(msg + 8, ptrs[t] + start, n);
+            uint8_t dig[64];
+            oracle_blake2b_param(param, msg, n + 8, dig, 64);
+            for (int l = 0; l < ORACLE_MODEL_LANES; l++) {
+                uint16_t v = (uint16_t)(dig[2 * l] | ((uint16_t)dig[2 * l + 1] << 8));
+                layer[l] = (uint16_t)((layer[l] + v) & 0xFFFFu);
+            }
+        }
+        for (int l = 0; l < ORACLE_MODEL_LANES; l++) {
+            if (layer_lanes) layer_lanes[t * ORACLE_MODEL_LANES + l] = layer[l];
+            lanes[l] = (uint16_t)((lanes[l] + layer[l]) & 0xFFFFu);
+        }
+    }
+    free(msg);
 }
 
 void oracle_lthash_combine(uint16_t acc[ORACLE_LANES], const uint16_t x[ORACLE_LANES])

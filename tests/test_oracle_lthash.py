@@ -120,3 +120,36 @@ def test_per_source_sums_are_the_hashes_of_the_sub_multisets():
     # one source is the plain lattice hash
     one = oracle.lthash_sources(data, off, np.zeros(60, np.uint32), 1)
     assert (one[0] == oracle.lthash(data, off)).all()
+
+
+def test_model_lattice_hash_against_hashlib():
+    # section 4.2.2 / Algorithm 4 with the block index in front of every block: brute force
+    # over hashlib.blake2b (digest 64 bytes = 32 partitions of 16 bits)
+    import struct
+    rng = random.Random(27)
+    B = 256
+    sizes = [B * 3, 17, B * 2 + 9, 0, B, B * 4 - 1]
+    segs = [rng.randbytes(s) for s in sizes]
+    layer, total = oracle.lthash_model(segs, B)
+    k = 0
+    want_total = np.zeros(32, np.int64)
+    for t, s in enumerate(segs):
+        want = np.zeros(32, np.int64)
+        for start in range(0, len(s), B):
+            dig = hashlib.blake2b(struct.pack("<Q", k) + s[start:start + B]).digest()
+            want += np.frombuffer(dig, "<u2")
+            k += 1
+        assert (layer[t].astype(np.int64) == want % 65536).all(), t
+        want_total += want
+    assert (total.astype(np.int64) == want_total % 65536).all()
+    assert k == 3 + 1 + 3 + 0 + 1 + 4
+    # the index matters: swapping two equal-sized blocks of one tensor changes nothing in the
+    # multiset of blocks, but changes the digest
+    a = bytearray(segs[0])
+    a[0:B], a[B:2 * B] = segs[0][B:2 * B], segs[0][0:B]
+    assert (oracle.lthash_model([bytes(a)] + segs[1:], B)[1] != total).any()
+    # the homomorphism still holds per block: the model digest is the sum of the layer digests
+    acc = np.zeros(32, np.int64)
+    for row in layer:
+        acc += row
+    assert (acc % 65536 == total).all()
