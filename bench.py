@@ -232,6 +232,10 @@ def main():
         per_config["F3_merkle_7b_inplace_flat_1MiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
         ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, 8192, root7.data_ptr(), stream), 5)
         per_config["F3_merkle_7b_inplace_flat_8KiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+        # lattice hash of the 7B checkpoint (Algorithm 4), the paper's default 8 KiB blocks
+        mlanes = torch.zeros(32, dtype=torch.int16, device=dev)
+        ms = timed_call(lambda: sentry.sentry_lthash_model(t7_ptrs, t7_lens, 8192, 0, mlanes.data_ptr(), stream), 5)
+        per_config["F2_lthash_model_7b_8KiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
         # mixed-source batches (section 4.3): the same 50,000 samples spread over 1, 16 and 128 sources
         for n_src in (1, 16, 128):
             ids = torch.from_numpy((wl._words_np(wl.SEED_C2 + 7, 0, 50_000) % np.uint64(n_src)).astype(np.int32)).to(dev)

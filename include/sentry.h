@@ -49,6 +49,7 @@ enum {
 
 #define SENTRY_DIGEST_BYTES 32
 #define SENTRY_LANES 1024
+#define SENTRY_MODEL_LANES 32
 
 /* ------------------------------------------------------------------------ */
 /* Merkle tree over weight bytes (section 2.2 "Merkle Tree"; section 4.2.1) */
@@ -226,6 +227,26 @@ SENTRY_API int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stre
  */
 SENTRY_API int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, size_t n,
                       size_t batch_bytes, uint16_t *out_lanes, void *stream);
+
+/*
+ * Lattice hash of a model (section 4.2.2, Algorithm 4).  The blocks of all
+ * tensors, in tensor order, are numbered 0, 1, 2, ... across the model; block k
+ * (block_bytes bytes, the last block of a tensor may be short, a tensor of
+ * length 0 has none) has the digest BLAKE2b-512(LE64(k) || block), read as 32
+ * little-endian uint16 partitions (the 64-byte digest of section 4.2.2).
+ *   out_layer_lanes[t][l] = sum of the digests of tensor t's blocks,
+ *   out_lanes[l]          = sum over all blocks = sum of the tensor digests,
+ * every partition mod 2^16.  The index in front of each block is what makes the
+ * order-invariant sum sensitive to block order (section 2.2).
+ * dev_ptrs, lens   host arrays as for sentry_merkle_segments (16-byte aligned
+ *                  device pointers), read before the call returns.
+ * block_bytes      > 0 and a multiple of 16 (the paper's default is 8192).
+ * out_layer_lanes  device-accessible, n_seg rows of 32 uint16, or NULL.
+ * out_lanes        device-accessible, 32 uint16.  Both overwritten.
+ */
+SENTRY_API int sentry_lthash_model(const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                                   size_t block_bytes, uint16_t *out_layer_lanes, uint16_t *out_lanes,
+                                   void *stream);
 
 /* ------------------------------------------------------------------------ */
 

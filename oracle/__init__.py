@@ -69,6 +69,10 @@ def lib():
         L.oracle_lthash_sources.restype = None
         L.oracle_lthash_model.argtypes = [vp, vp, sz, sz, vp, vp]
         L.oracle_lthash_model.restype = None
+        L.oracle_lthash_model_from.argtypes = [vp, vp, sz, sz, ctypes.c_uint64, vp, vp]
+        L.oracle_lthash_model_from.restype = None
+        L.oracle_lanes_add.argtypes = [vp, vp, sz]
+        L.oracle_lanes_add.restype = None
         L.oracle_lthash_combine.argtypes = [vp, vp]
         L.oracle_lthash_combine.restype = None
         L.oracle_lthash_remove.argtypes = [vp, vp]
@@ -223,7 +227,15 @@ def lthash_sources(records, offsets, sources, n_sources, acc=None):
     return out
 
 
-def lthash_model(segments, block_bytes):
+def lanes_add(acc, x):
+    r = np.array(acc, dtype=np.uint16, copy=True)
+    xx = np.ascontiguousarray(x, dtype=np.uint16)
+    assert r.shape == xx.shape
+    lib().oracle_lanes_add(r.ctypes.data, xx.ctypes.data, r.size)
+    return r
+
+
+def lthash_model(segments, block_bytes, first_index=0):
     """Model lattice hash (Algorithm 4): returns (per-layer lanes n_seg x 32, model lanes 32)."""
     arrs = [_u8(s) for s in segments]
     n = len(arrs)
@@ -231,7 +243,7 @@ def lthash_model(segments, block_bytes):
     lens = (ctypes.c_size_t * max(n, 1))(*[a.size for a in arrs])
     layer = np.zeros((max(n, 1), 32), np.uint16)
     total = np.zeros(32, np.uint16)
-    lib().oracle_lthash_model(ptrs, lens, n, block_bytes, layer.ctypes.data, total.ctypes.data)
+    lib().oracle_lthash_model_from(ptrs, lens, n, block_bytes, first_index, layer.ctypes.data, total.ctypes.data)
     return layer[:n], total
 
 

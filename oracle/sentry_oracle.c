@@ -430,15 +430,33 @@ void oracle_lthash_sources(const uint8_t *records, const uint64_t *offsets, cons
  * index would not tell two blocks of one layer apart.  Width, position and byte order of
  * the index (8 bytes, little endian, in front) are this build's choice. */
 #define ORACLE_MODEL_LANES 32
+/* first_index: the model-wide index of the first block of ptrs[0] (0 for a whole model; a
+ * slice of a model can be hashed on its own and added to the other slices). */
+void oracle_lthash_model_from(const uint8_t *const *ptrs, const size_t *lens, size_t n_seg, size_t block_bytes,
+                              uint64_t first_index, uint16_t *layer_lanes /* n_seg * 32, may be NULL */,
+                              uint16_t lanes[ORACLE_MODEL_LANES]);
+
 void oracle_lthash_model(const uint8_t *const *ptrs, const size_t *lens, size_t n_seg, size_t block_bytes,
                          uint16_t *layer_lanes /* n_seg * 32, may be NULL */, uint16_t lanes[ORACLE_MODEL_LANES])
+{
+    oracle_lthash_model_from(ptrs, lens, n_seg, block_bytes, 0, layer_lanes, lanes);
+}
+
+/* acc[l] = (acc[l] + x[l]) mod 2^16 for n partitions */
+void oracle_lanes_add(uint16_t *acc, const uint16_t *x, size_t n)
+{
+    for (size_t l = 0; l < n; l++) acc[l] = (uint16_t)((acc[l] + x[l]) & 0xFFFFu);
+}
+
+void oracle_lthash_model_from(const uint8_t *const *ptrs, const size_t *lens, size_t n_seg, size_t block_bytes,
+                              uint64_t first_index, uint16_t *layer_lanes, uint16_t lanes[ORACLE_MODEL_LANES])
 {
     uint8_t param[64];
     memset(param, 0, sizeof param);
     param[0] = 64; param[2] = 1; param[3] = 1;      /* plain BLAKE2b-512: digest 64, fanout 1, depth 1 */
     uint8_t *msg = (uint8_t *)malloc(block_bytes + 8);
     memset(lanes, 0, ORACLE_MODEL_LANES * sizeof(uint16_t));
-    uint64_t k = 0;
+    uint64_t k = first_index;
     for (size_t t = 0; t < n_seg; t++) {
         uint16_t layer[ORACLE_MODEL_LANES];
         memset(layer, 0, sizeof layer);

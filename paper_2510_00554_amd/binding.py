@@ -42,6 +42,7 @@ PROTOTYPES = {
     "sentry_verify": (_int, [ctypes.c_char_p, ctypes.c_char_p]),
     "sentry_lthash": (_int, [_vp, _vp, _sz, _vp, _vp]),
     "sentry_lthash_sources": (_int, [_vp, _vp, _vp, _sz, _sz, _vp, _vp]),
+    "sentry_lthash_model": (_int, [_vp, _vp, _sz, _sz, _vp, _vp, _vp]),
     "sentry_lthash_combine": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_remove": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_h2d": (_int, [_vp, _vp, _sz, _sz, _vp, _vp]),
@@ -149,6 +150,16 @@ def sentry_lthash(dev_records, dev_offsets, n, out_lanes, stream=0):
 def sentry_lthash_sources(dev_records, dev_offsets, dev_source_ids, n, n_sources, acc_lanes, stream=0):
     return _check(load().sentry_lthash_sources(dev_records, dev_offsets, dev_source_ids, n, n_sources,
                                                acc_lanes, stream))
+
+
+def sentry_lthash_model(dev_ptrs, lens, block_bytes, out_layer_lanes, out_lanes, stream=0):
+    """dev_ptrs, lens: Python sequences of ints (device addresses, byte lengths)."""
+    n = len(dev_ptrs)
+    if len(lens) != n:
+        raise ValueError("dev_ptrs and lens differ in length")
+    ptrs = (ctypes.c_void_p * max(n, 1))(*dev_ptrs)
+    ls = (ctypes.c_size_t * max(n, 1))(*lens)
+    return _check(load().sentry_lthash_model(ptrs, ls, n, block_bytes, out_layer_lanes, out_lanes, stream))
 
 
 def sentry_lthash_combine(acc, x, stream=0):

@@ -120,6 +120,35 @@ def c3(pool):
           [top.hex()] + ["%s %s" % (lay[i][0], roots[i].hex()) for i in range(len(lay))])
 
 
+def _c3_model_task(args):
+    idx, e0, e1, first_index, block = args
+    data = wl.normal_bf16_bits(wl.tensor_seed(wl.SEED_C3, idx), e0, e1 - e0).view(np.uint8)
+    _, lanes = oracle.lthash_model([data], block, first_index=first_index)
+    return idx, lanes.tobytes()
+
+
+def c3model(pool):
+    """Model lattice hash (Algorithm 4) of the 7B checkpoint at the paper's default 8 KiB blocks."""
+    lay = wl.layout_7b()
+    block = 8192
+    per = 4096 * (block // 2)                      # elements per task: 4096 blocks
+    tasks, index = [], 0
+    for i, (_, numel) in enumerate(lay):
+        for e0 in range(0, numel, per):
+            tasks.append((i, e0, min(numel, e0 + per), index + (2 * e0) // block, block))
+        index += -(-2 * numel // block)
+    layers = np.zeros((len(lay), 32), np.uint16)
+    for idx, blob in pool.imap_unordered(_c3_model_task, tasks, chunksize=1):
+        layers[idx] = oracle.lanes_add(layers[idx], np.frombuffer(blob, np.uint16))
+    total = np.zeros(32, np.uint16)
+    for row in layers:
+        total = oracle.lanes_add(total, row)
+    write("config3_model_lthash.txt",
+          ["Model lattice hash (oracle, Algorithm 4: BLAKE2b-512 of LE64(block index) || block, 32 partitions) of the",
+           "config 3 checkpoint, 8 KiB blocks, %d blocks.  line 1: model digest; then one tensor digest per line" % index],
+          [lanes_hex(total)] + ["%s %s" % (lay[i][0], lanes_hex(layers[i])) for i in range(len(lay))])
+
+
 # ---- config 4: lattice hash of record ranges ---------------------------------------------
 
 _C4_OFF = None
@@ -168,12 +197,12 @@ def c4(pool):
 
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
-    ap.add_argument("configs", nargs="*", default=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("configs", nargs="*", default=["c1", "c2", "c3", "c3model", "c4", "c5"])
     ap.add_argument("--procs", type=int, default=os.cpu_count())
     a = ap.parse_args()
     oracle.build()
     with mp.Pool(a.procs) as pool:
         for c in a.configs:
             t = time.time()
-            {"c1": c1, "c2": c2}.get(c, lambda: {"c3": c3, "c4": c4, "c5": c5}[c](pool))()
+            {"c1": c1, "c2": c2}.get(c, lambda: {"c3": c3, "c3model": c3model, "c4": c4, "c5": c5}[c](pool))()
             print("%s done in %.0fs" % (c, time.time() - t), flush=True)

@@ -62,6 +62,10 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_lthash_sources(0x1000, 0x3000, 0x4000, 5, 5000, 0x2000),    # too many sources
     lambda: sentry.sentry_lthash_sources(0x1000, 0x3000, 0x4002, 5, 4, 0x2000),       # misaligned ids
     lambda: sentry.sentry_lthash_sources(0x1000, 0x3000, 0, 5, 4, 0x2000),            # NULL ids
+    lambda: sentry.sentry_lthash_model([], [], 8192, 0, 0x2000),                      # no tensors
+    lambda: sentry.sentry_lthash_model([0x1000], [64], 100, 0, 0x2000),               # block not a multiple of 16
+    lambda: sentry.sentry_lthash_model([0x1008], [64], 8192, 0, 0x2000),              # misaligned tensor
+    lambda: sentry.sentry_lthash_model([0x1000], [64], 8192, 0, 0),                   # NULL output
     lambda: sentry.sentry_lthash_combine(0, 0x2000),
     lambda: sentry.sentry_lthash_remove(0x2001, 0x2000),
     lambda: sentry.sentry_lthash_h2d(0x1000, 0x3000, 5, 0, 0x2000),      # batch_bytes == 0

@@ -153,3 +153,16 @@ def test_model_lattice_hash_against_hashlib():
     for row in layer:
         acc += row
     assert (acc % 65536 == total).all()
+
+
+def test_model_hash_of_slices_adds_up():
+    rng = random.Random(28)
+    B = 64
+    segs = [rng.randbytes(B * 5 + 3), rng.randbytes(B * 2), rng.randbytes(7)]
+    layer, total = oracle.lthash_model(segs, B)
+    # second and third tensor on their own, starting at block 6, plus the first tensor cut in two
+    l_a, t_a = oracle.lthash_model([segs[0][:B * 2]], B)
+    l_b, t_b = oracle.lthash_model([segs[0][B * 2:]], B, first_index=2)
+    l_c, t_c = oracle.lthash_model(segs[1:], B, first_index=6)
+    assert (oracle.lanes_add(l_a[0], l_b[0]) == layer[0]).all() and (l_c == layer[1:]).all()
+    assert (oracle.lanes_add(oracle.lanes_add(t_a, t_b), t_c) == total).all()
