@@ -51,6 +51,12 @@ def lib():
         L.oracle_merkle_segments.restype = ctypes.c_int
         L.oracle_merkle_inplace.argtypes = [vp, vp, sz, sz, vp]
         L.oracle_merkle_inplace.restype = ctypes.c_int
+        L.oracle_sha3_256.argtypes = [vp, sz, vp]
+        L.oracle_sha3_256.restype = None
+        L.oracle_keccak_constants.argtypes = [vp, vp]
+        L.oracle_keccak_constants.restype = None
+        L.oracle_merkle_root_h.argtypes = [ctypes.c_int, vp, sz, sz, vp]
+        L.oracle_merkle_root_h.restype = ctypes.c_int
         L.oracle_verify.argtypes = [vp, vp]
         L.oracle_verify.restype = ctypes.c_int
         L.oracle_blake2b_constants.argtypes = [vp, vp]
@@ -157,6 +163,32 @@ def merkle_inplace(segments, leaf_bytes):
     if rc:
         raise ValueError("oracle_merkle_inplace rc=%d" % rc)
     return out.tobytes()
+
+
+HASH_SHA256, HASH_BLAKE2B, HASH_SHA3_256 = 0, 1, 2
+
+
+def sha3_256(data):
+    a = _u8(data)
+    out = np.empty(32, np.uint8)
+    lib().oracle_sha3_256(_ptr(a), a.size, out.ctypes.data)
+    return out.tobytes()
+
+
+def keccak_constants():
+    rc = np.empty(24, np.uint64)
+    rho = np.empty(25, np.int32)
+    lib().oracle_keccak_constants(rc.ctypes.data, rho.ctypes.data)
+    return rc, rho
+
+
+def merkle_root_h(hash_id, data, leaf_bytes):
+    a = _u8(data)
+    out = np.empty(64, np.uint8)
+    dl = lib().oracle_merkle_root_h(hash_id, _ptr(a), a.size, leaf_bytes, out.ctypes.data)
+    if dl < 0:
+        raise ValueError("oracle_merkle_root_h rc=%d" % dl)
+    return out[:dl].tobytes()
 
 
 def verify(a, b):

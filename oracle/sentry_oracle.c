@@ -21,6 +21,8 @@
  *   - batches that mix data sources, one running sum per source: section 4.1.2, 4.3.
  *   - lattice hash of a model, block index mixed into each block digest: section 4.2.2,
  *     Algorithm 4.
+ *   - Merkle trees with BLAKE2b and SHA-3 as the leaf function: section 4.2.1 ("supports
+ *     SHA256, BLAKE2B, and SHA3").
  *
  * Readings fixed where the paper leaves the point open (the build's target
  * configurations fix them):
@@ -373,6 +375,138 @@ void oracle_blake2xb(const uint8_t *msg, size_t len, uint8_t *out, uint32_t xof_
         oracle_blake2b_param(p, h0, 64, out + produced, want);
         produced += want; j++;
     }
+}
+
+/* ------------------------------------------------------------------------ */
+/* SHA3-256 (FIPS 202) and Merkle trees over other leaf functions           */
+/* ------------------------------------------------------------------------ */
+
+static uint64_t keccak_RC[24];
+static int keccak_rho[5][5];     /* rotation offset of lane (x, y) */
+static int keccak_ready = 0;
+
+/* Round constants from the degree-8 LFSR and rotation offsets from the (x, y) walk, both as
+ * FIPS 202 section 3.2 defines them. */
+static void keccak_make_tables(void)
+{
+    uint8_t R = 1;   /* LFSR state, x^8 + x^6 + x^5 + x^4 + 1 */
+    for (int round = 0; round < 24; round++) {
+        uint64_t rc = 0;
+        for (int j = 0; j <= 6; j++) {
+            if (R & 1) rc |= (uint64_t)1 << ((1 << j) - 1);
+            uint8_t hi = R & 0x80;
+            R = (uint8_t)(R << 1);
+            if (hi) R ^= 0x71;
+        }
+        keccak_RC[round] = rc;
+    }
+    int x = 1, y = 0;
+    keccak_rho[0][0] = 0;
+    for (int t = 0; t < 24; t++) {
+        keccak_rho[x][y] = ((t + 1) * (t + 2) / 2) % 64;
+        int nx = y, ny = (2 * x + 3 * y) % 5;
+        x = nx; y = ny;
+    }
+    keccak_ready = 1;
+}
+
+static uint64_t rotl64(uint64_t v, int n) { return n ? (v << n) | (v >> (64 - n)) : v; }
+
+/* A[x][y] is lane x + 5y of the 1600-bit state */
+static void keccak_f1600(uint64_t A[25])
+{
+    for (int round = 0; round < 24; round++) {
+        uint64_t C[5], D[5], B[25];
+        for (int x = 0; x < 5; x++) C[x] = A[x] ^ A[x + 5] ^ A[x + 10] ^ A[x + 15] ^ A[x + 20];
+        for (int x = 0; x < 5; x++) D[x] = C[(x + 4) % 5] ^ rotl64(C[(x + 1) % 5], 1);
+        for (int i = 0; i < 25; i++) A[i] ^= D[i % 5];                               /* theta */
+        for (int x = 0; x < 5; x++)
+            for (int y = 0; y < 5; y++)
+                B[y + 5 * ((2 * x + 3 * y) % 5)] = rotl64(A[x + 5 * y], keccak_rho[x][y]);   /* rho, pi */
+        for (int y = 0; y < 5; y++)
+            for (int x = 0; x < 5; x++)
+                A[x + 5 * y] = B[x + 5 * y] ^ (~B[(x + 1) % 5 + 5 * y] & B[(x + 2) % 5 + 5 * y]);   /* chi */
+        A[0] ^= keccak_RC[round];                                                   /* iota */
+    }
+}
+
+void oracle_keccak_constants(uint64_t rc_out[24], int32_t rho_out[25])
+{
+    if (!keccak_ready) keccak_make_tables();
+    memcpy(rc_out, keccak_RC, sizeof keccak_RC);
+    for (int x = 0; x < 5; x++)
+        for (int y = 0; y < 5; y++) rho_out[x + 5 * y] = keccak_rho[x][y];
+}
+
+/* SHA3-256: rate 136 bytes, domain bits 01 then pad10*1 (first pad byte 0x06, last 0x80) */
+void oracle_sha3_256(const uint8_t *msg, size_t len, uint8_t out[32])
+{
+    if (!keccak_ready) keccak_make_tables();
+    uint64_t A[25];
+    memset(A, 0, sizeof A);
+    const size_t rate = 136;
+    while (len >= rate) {
+        for (size_t i = 0; i < rate / 8; i++) A[i] ^= load_le64(msg + 8 * i);
+        keccak_f1600(A);
+        msg += rate; len -= rate;
+    }
+    uint8_t last[136];
+    memset(last, 0, sizeof last);
+    if (len) memcpy(last, msg, len);
+    last[len] ^= 0x06;
+    last[rate - 1] ^= 0x80;
+    for (size_t i = 0; i < rate / 8; i++) A[i] ^= load_le64(last + 8 * i);
+    keccak_f1600(A);
+    for (int i = 0; i < 4; i++)
+        for (int j = 0; j < 8; j++) out[8 * i + j] = (uint8_t)(A[i] >> (8 * j));
+}
+
+/* The Merkle tree of section 4.2.1 over any of the paper's three leaf functions:
+ * hash 0 = SHA-256 (32-byte nodes), 1 = BLAKE2b-512 (64-byte nodes), 2 = SHA3-256 (32-byte
+ * nodes).  Same rules as oracle_merkle_root: node = H(left || right) with the full hash, a lone
+ * last node moves up unchanged, short last leaf, len 0 = one empty leaf.  Returns the digest
+ * length, or a negative error. */
+static void hash_any(int hash, const uint8_t *msg, size_t len, uint8_t *out)
+{
+    if (hash == 0) {
+        oracle_sha256(msg, len, out);
+    } else if (hash == 1) {
+        uint8_t param[64];
+        memset(param, 0, sizeof param);
+        param[0] = 64; param[2] = 1; param[3] = 1;
+        oracle_blake2b_param(param, msg, len, out, 64);
+    } else {
+        oracle_sha3_256(msg, len, out);
+    }
+}
+
+int oracle_merkle_root_h(int hash, const uint8_t *buf, size_t len, size_t leaf_bytes, uint8_t *out)
+{
+    if (leaf_bytes == 0 || hash < 0 || hash > 2) return -1;
+    const size_t dl = hash == 1 ? 64 : 32;
+    size_t n = (len + leaf_bytes - 1) / leaf_bytes;
+    if (n == 0) n = 1;
+    uint8_t *nodes = (uint8_t *)malloc(dl * n);
+    if (!nodes) return -3;
+    for (size_t i = 0; i < n; i++) {
+        size_t start = i * leaf_bytes, stop = start + leaf_bytes;
+        if (stop > len) stop = len;
+        hash_any(hash, buf + start, stop - start, nodes + dl * i);
+    }
+    while (n > 1) {
+        size_t pairs = n / 2;
+        for (size_t i = 0; i < pairs; i++) {
+            uint8_t cat[128], dig[64];
+            memcpy(cat, nodes + 2 * dl * i, 2 * dl);
+            hash_any(hash, cat, 2 * dl, dig);
+            memcpy(nodes + dl * i, dig, dl);
+        }
+        if (n & 1) memmove(nodes + dl * pairs, nodes + dl * (n - 1), dl);
+        n = pairs + (n & 1);
+    }
+    memcpy(out, nodes, dl);
+    free(nodes);
+    return (int)dl;
 }
 
 /* ------------------------------------------------------------------------ */

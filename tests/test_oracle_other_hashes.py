@@ -1,0 +1,66 @@
+"""Pins for the oracle's SHA3-256 and for Merkle trees over BLAKE2b-512 and SHA3-256
+(section 4.2.1 lists SHA256, BLAKE2B and SHA3 as leaf functions)."""
+import hashlib
+import random
+
+import numpy as np
+import pytest
+
+import oracle
+from conftest import golden_lines
+
+
+def test_keccak_constants_match_fips202_definitions():
+    rc, rho = oracle.keccak_constants()
+    # anchors printed in FIPS 202 / the Keccak reference: first, second and last round constant
+    assert int(rc[0]) == 0x0000000000000001 and int(rc[1]) == 0x0000000000008082
+    assert int(rc[23]) == 0x8000000080008008
+    # every constant has bits only at positions 2^j - 1
+    allowed = sum(1 << ((1 << j) - 1) for j in range(7))
+    assert all(int(c) & ~allowed == 0 for c in rc)
+    rho = rho.reshape(5, 5)           # [y][x]
+    assert rho[0][0] == 0 and rho[0][1] == 1 and rho[2][0] == 3 and rho[1][1] == 44 and rho[0][2] == 62
+    assert sorted(int(v) for v in rho.reshape(-1)) == sorted([0] + [((t + 1) * (t + 2) // 2) % 64 for t in range(24)])
+
+
+def test_sha3_fips202_examples():
+    for ln in golden_lines("sha3_fips202.txt"):
+        _, text, dig = ln.split(" ")
+        assert oracle.sha3_256(text.encode()).hex() == dig
+
+
+def test_sha3_against_hashlib():
+    rng = random.Random(41)
+    for n in list(range(0, 300)) + [135, 136, 137, 271, 272, 273, 4096, 8192, 65536, 100003]:
+        msg = rng.randbytes(n)
+        assert oracle.sha3_256(msg) == hashlib.sha3_256(msg).digest(), n
+
+
+def brute(hfun, buf, L):
+    n = max(1, -(-len(buf) // L))
+    level = [hfun(buf[i * L:(i + 1) * L]) for i in range(n)]
+    while len(level) > 1:
+        nxt = [hfun(level[i] + level[i + 1]) for i in range(0, len(level) - 1, 2)]
+        if len(level) % 2:
+            nxt.append(level[-1])
+        level = nxt
+    return level[0]
+
+
+@pytest.mark.parametrize("hid,hfun", [
+    (oracle.HASH_SHA256, lambda b: hashlib.sha256(b).digest()),
+    (oracle.HASH_BLAKE2B, lambda b: hashlib.blake2b(b).digest()),
+    (oracle.HASH_SHA3_256, lambda b: hashlib.sha3_256(b).digest()),
+])
+def test_merkle_trees_over_each_leaf_function(hid, hfun):
+    rng = random.Random(42 + hid)
+    for L in (64, 192):
+        for n in list(range(1, 20)) + [33]:
+            for tail in (0, 1, 63):
+                size = (n - 1) * L + (tail if tail else L)
+                buf = rng.randbytes(size)
+                assert oracle.merkle_root_h(hid, buf, L) == brute(hfun, buf, L), (hid, L, n, tail)
+    assert oracle.merkle_root_h(hid, b"", 64) == hfun(b"")
+    if hid == oracle.HASH_SHA256:
+        buf = rng.randbytes(5000)
+        assert oracle.merkle_root_h(hid, buf, 256) == oracle.merkle_root(buf, 256)
