@@ -232,6 +232,13 @@ def main():
         per_config["F3_merkle_7b_inplace_flat_1MiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
         ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, 8192, root7.data_ptr(), stream), 5)
         per_config["F3_merkle_7b_inplace_flat_8KiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+        # the three leaf functions of section 4.2.1 on the first 16 GiB of the 70B stream, 8 KiB leaves
+        f4_bytes = min(bytes70, 16 << 30)
+        big_root = torch.zeros(64, dtype=torch.uint8, device=dev)
+        for name, hid in (("sha256", sentry.HASH_SHA256), ("blake2b", sentry.HASH_BLAKE2B), ("sha3_256", sentry.HASH_SHA3_256)):
+            ms = timed_call(lambda: sentry.sentry_merkle_root_h(hid, ckpt70.data_ptr(), f4_bytes, 8192,
+                                                                big_root.data_ptr(), stream), 5)
+            per_config["F4_merkle_%s_16GiB_8KiB" % name] = {"GB/s": f4_bytes / ms / 1e6, "ms": ms, "bytes": f4_bytes}
         # lattice hash of the 7B checkpoint (Algorithm 4), the paper's default 8 KiB blocks
         mlanes = torch.zeros(32, dtype=torch.int16, device=dev)
         ms = timed_call(lambda: sentry.sentry_lthash_model(t7_ptrs, t7_lens, 8192, 0, mlanes.data_ptr(), stream), 5)

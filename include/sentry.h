@@ -48,6 +48,10 @@ enum {
 };
 
 #define SENTRY_DIGEST_BYTES 32
+/* leaf functions of sentry_merkle_root_h */
+#define SENTRY_HASH_SHA256 0
+#define SENTRY_HASH_BLAKE2B 1      /* BLAKE2b-512, 64-byte nodes */
+#define SENTRY_HASH_SHA3_256 2     /* 32-byte nodes */
 #define SENTRY_LANES 1024
 #define SENTRY_MODEL_LANES 32
 
@@ -72,6 +76,18 @@ enum {
  */
 SENTRY_API int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes,
                        uint8_t *out_digest, void *stream);
+
+/*
+ * The same tree over one of the paper's three leaf functions (section 4.2.1:
+ * SHA256, BLAKE2B and SHA3): node = H(left || right) with the full hash H, same
+ * leaf, short-tail, odd-node and empty-buffer rules as sentry_merkle_root.
+ * hash        SENTRY_HASH_SHA256 (identical to sentry_merkle_root),
+ *             SENTRY_HASH_BLAKE2B or SENTRY_HASH_SHA3_256.
+ * out_digest  device-accessible, 32 bytes (64 for BLAKE2b).
+ * Other arguments and errors as for sentry_merkle_root.
+ */
+SENTRY_API int sentry_merkle_root_h(int hash, const void *dev_buf, size_t len, size_t leaf_bytes,
+                                    uint8_t *out_digest, void *stream);
 
 /*
  * Per-tensor trees and the model digest over them (Algorithm 2, per-layer

@@ -4,8 +4,8 @@ samples.  All work happens in ``libsentry_hip.so`` (hand-written HIP for gfx950,
 C ABI in ``include/sentry.h``); this package only marshals arguments.
 """
 from .binding import (  # noqa: F401
-    LANES, SentryError, lib_path, load,
-    sentry_merkle_root, sentry_merkle_segments, sentry_merkle_inplace, sentry_merkle_leaves, sentry_merkle_reduce,
+    LANES, HASH_SHA256, HASH_BLAKE2B, HASH_SHA3_256, SentryError, lib_path, load,
+    sentry_merkle_root, sentry_merkle_root_h, sentry_merkle_segments, sentry_merkle_inplace, sentry_merkle_leaves, sentry_merkle_reduce,
     sentry_merkle_stream_begin, sentry_merkle_stream_update, sentry_merkle_stream_final,
     sentry_merkle_stream_abort, sentry_merkle_root_h2d, sentry_verify,
     sentry_lthash, sentry_lthash_sources, sentry_lthash_model, sentry_lthash_combine, sentry_lthash_remove, sentry_lthash_h2d,
