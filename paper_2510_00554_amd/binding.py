@@ -58,8 +58,13 @@ def load():
     if _lib is None:
         path = lib_path()
         if not os.path.exists(path):
-            raise ImportError("%s is not built: run `python -m paper_2510_00554_amd.build` "
-                              "(hipcc, gfx950); there is no CPU fallback" % path)
+            # nothing built yet: build once (hipcc, gfx950); there is no CPU fallback
+            try:
+                from . import build as _build
+                _build.build()
+            except Exception as e:
+                raise ImportError("%s is not built and building it failed (%s); run "
+                                  "`python -m paper_2510_00554_amd.build`" % (path, e))
         L = ctypes.CDLL(path)
         for name, (res, args) in PROTOTYPES.items():
             fn = getattr(L, name)
