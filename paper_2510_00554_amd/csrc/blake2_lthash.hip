@@ -649,9 +649,6 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
     rc = scratch_get(s, R_LT_PART, n_part * LANE_WORDS * 4, &part);
     if (rc) return rc;
     if (n) {
-        // With fewer records than four times the lanes of the chip the launch is bound by its
-        // longest chain, not by throughput: spend four lanes per record.  Otherwise one lane
-        // per record does the least total work.
         // With at least four records per lane of the chip the launch is throughput-bound whatever
         // the lengths are, and one lane per record does the least total work; below that the
         // kernel decides from the mean record length.

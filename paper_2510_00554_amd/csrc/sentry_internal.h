@@ -71,10 +71,9 @@ int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr);
 int table_staging_mark(hipStream_t stream);
 
 // Side stream and events for the host-streaming entry points (per stream).
-// Batches in flight in the lattice host-streaming call.  Slot 0 hashes on the caller's stream,
-// the others on side streams: with the copy stream that makes four streams, the number of
-// hardware queues a process gets here; with more, streams share queues and copies queue up
-// behind kernels (measured: hash-while-loading fell from 96 % to 54 % of the copy rate).
+// PIPE_SLOTS = batches in flight in the lattice host-streaming call.  Slot 0 hashes on the
+// caller's stream, the others on side streams: with the copy stream that makes four streams,
+// the number of hardware queues a process gets by default, so no two of them share a queue.
 constexpr int PIPE_SLOTS = 3;
 struct CopyPipe {
     hipStream_t copy_stream;

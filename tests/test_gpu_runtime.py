@@ -1,0 +1,131 @@
+"""GPU tests of the library's run-time plumbing: scratch that grows and shrinks between calls,
+calls on several streams and from several host threads, release and reuse of the scratch,
+error reporting.  Every result is still checked against the CPU oracle."""
+import threading
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_00554_amd as sentry
+from paper_2510_00554_amd import workloads as wl
+from conftest import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _records(seed, n, lo, hi):
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(lo, hi, size=n)
+    off = np.zeros(n + 1, dtype=np.uint64)
+    off[1:] = np.cumsum(lens)
+    return wl.uniform_bytes(seed, 0, int(off[-1])), off
+
+
+def test_scratch_grows_and_is_reused_with_smaller_inputs():
+    s = torch.cuda.Stream()
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    lanes = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    # sizes go up and down so that every scratch region is regrown while earlier work of the
+    # same stream may still be in flight, then reused with stale contents from a larger call
+    for n_leaves in (3, 70_000, 600, 300_000, 5, 70_000):
+        buf = wl.uniform_bytes(900 + n_leaves, 0, 64 * n_leaves - 7)
+        d = to_dev(buf)
+        sentry.sentry_merkle_root(d.data_ptr(), buf.size, 64, out.data_ptr(), s.cuda_stream)
+        s.synchronize()
+        assert bytes(out.cpu().numpy()) == oracle.merkle_root(buf, 64), n_leaves
+    for n in (10, 5000, 40, 20_000, 1):
+        data, off = _records(910 + n, n, 0, 300)
+        dd, do = to_dev(data), to_dev(off)
+        sentry.sentry_lthash(dd.data_ptr(), do.data_ptr(), n, lanes.data_ptr(), s.cuda_stream)
+        s.synchronize()
+        assert (lanes.cpu().numpy().view(np.uint16) == oracle.lthash(data, off)).all(), n
+
+
+def test_calls_interleaved_on_two_streams():
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    bufs = [wl.uniform_bytes(920 + i, 0, 4096 * (300 + 37 * i) + 11 * i) for i in range(6)]
+    devs = [to_dev(b) for b in bufs]
+    outs = torch.zeros(len(bufs), 32, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    for i, (b, d) in enumerate(zip(bufs, devs)):   # nothing waits between the calls
+        st = (s1, s2)[i & 1]
+        sentry.sentry_merkle_root(d.data_ptr(), b.size, 4096, outs[i].data_ptr(), st.cuda_stream)
+    torch.cuda.synchronize()
+    got = outs.cpu().numpy()
+    for i, b in enumerate(bufs):
+        assert bytes(got[i]) == oracle.merkle_root(b, 4096), i
+
+
+def test_host_threads_with_a_stream_each():
+    n_threads = 4
+    work = []
+    for t in range(n_threads):
+        buf = wl.uniform_bytes(930 + t, 0, 1024 * (2000 + 100 * t) + t)
+        data, off = _records(940 + t, 3000 + 10 * t, 0, 500)
+        work.append((buf, data, off))
+    staged = [(to_dev(b), to_dev(d), to_dev(o)) for b, d, o in work]
+    roots = torch.zeros(n_threads, 32, dtype=torch.uint8, device="cuda")
+    lanes = torch.zeros(n_threads, 1024, dtype=torch.int16, device="cuda")
+    streams = [torch.cuda.Stream() for _ in range(n_threads)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def run(t):
+        try:
+            db, dd, do = staged[t]
+            st = streams[t].cuda_stream
+            for _ in range(3):
+                sentry.sentry_merkle_root(db.data_ptr(), work[t][0].size, 1024, roots[t].data_ptr(), st)
+                sentry.sentry_lthash(dd.data_ptr(), do.data_ptr(), len(work[t][2]) - 1, lanes[t].data_ptr(), st)
+            streams[t].synchronize()
+        except Exception as e:   # reported in the main thread
+            errors.append((t, repr(e)))
+
+    threads = [threading.Thread(target=run, args=(t,)) for t in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    r, l = roots.cpu().numpy(), lanes.cpu().numpy().view(np.uint16)
+    for t, (buf, data, off) in enumerate(work):
+        assert bytes(r[t]) == oracle.merkle_root(buf, 1024), t
+        assert (l[t] == oracle.lthash(data, off)).all(), t
+
+
+def test_release_scratch_then_reuse():
+    buf = wl.uniform_bytes(950, 0, 64 * 5000 + 3)
+    d = to_dev(buf)
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    want = oracle.merkle_root(buf, 64)
+    for _ in range(2):
+        sentry.sentry_merkle_root(d.data_ptr(), buf.size, 64, out.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(out.cpu().numpy()) == want
+        sentry.sentry_release_scratch()
+    # the host-streaming paths own streams and events, which a release destroys as well
+    host = torch.from_numpy(buf.copy()).pin_memory()
+    for _ in range(2):
+        sentry.sentry_merkle_root_h2d(host.data_ptr(), buf.size, 64, 64 * 1024, out.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(out.cpu().numpy()) == want
+        sentry.sentry_release_scratch()
+
+
+def test_error_text_names_the_argument_and_later_calls_still_work():
+    buf = wl.uniform_bytes(960, 0, 4096)
+    d = to_dev(buf)
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    with pytest.raises(sentry.SentryError) as e:
+        sentry.sentry_merkle_root(d.data_ptr(), buf.size, 100, out.data_ptr())
+    assert e.value.code == sentry.ERR_INVALID_ARG and "leaf_bytes" in str(e.value)
+    with pytest.raises(sentry.SentryError) as e:
+        sentry.sentry_merkle_root(d.data_ptr() + 4, buf.size - 4, 64, out.data_ptr())
+    assert "aligned" in str(e.value)
+    sentry.sentry_merkle_root(d.data_ptr(), buf.size, 64, out.data_ptr())
+    torch.cuda.synchronize()
+    assert bytes(out.cpu().numpy()) == oracle.merkle_root(buf, 64)
+    assert sentry.sentry_last_error() == ""
