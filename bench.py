@@ -239,6 +239,15 @@ def main():
             ms = timed_call(lambda: sentry.sentry_merkle_root_h(hid, ckpt70.data_ptr(), f4_bytes, 8192,
                                                                 big_root.data_ptr(), stream), 5)
             per_config["F4_merkle_%s_16GiB_8KiB" % name] = {"GB/s": f4_bytes / ms / 1e6, "ms": ms, "bytes": f4_bytes}
+        # the paper's three schemes' hardest case: fragmented 7B checkpoint, per-tensor and flat trees, 8 KiB blocks
+        seg_roots = torch.zeros(64 * len(t7_ptrs), dtype=torch.uint8, device=dev)
+        for name, hid in (("blake2b", sentry.HASH_BLAKE2B), ("sha3_256", sentry.HASH_SHA3_256)):
+            ms = timed_call(lambda: sentry.sentry_merkle_segments_h(hid, t7_ptrs, t7_lens, 8192, seg_roots.data_ptr(),
+                                                                    big_root.data_ptr(), stream), 5)
+            per_config["F4_merkle_%s_7b_per_tensor_8KiB" % name] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+            ms = timed_call(lambda: sentry.sentry_merkle_inplace_h(hid, t7_ptrs, t7_lens, 8192, big_root.data_ptr(),
+                                                                   stream), 5)
+            per_config["F4_merkle_%s_7b_inplace_flat_8KiB" % name] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
         # lattice hash of the 7B checkpoint (Algorithm 4), the paper's default 8 KiB blocks
         mlanes = torch.zeros(32, dtype=torch.int16, device=dev)
         ms = timed_call(lambda: sentry.sentry_lthash_model(t7_ptrs, t7_lens, 8192, 0, mlanes.data_ptr(), stream), 5)

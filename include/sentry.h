@@ -122,6 +122,24 @@ SENTRY_API int sentry_merkle_inplace(const void *const *dev_ptrs, const size_t *
                                      size_t leaf_bytes, uint8_t *out_root, void *stream);
 
 /*
+ * Per-tensor trees (Algorithm 2) and the in-place flat tree (Algorithm 3) over any
+ * of the three leaf functions: same rules as sentry_merkle_segments and
+ * sentry_merkle_inplace with H in place of SHA-256 (an empty tensor's root is
+ * H("") in the per-tensor scheme and it has no block in the flat one).
+ * hash           as for sentry_merkle_root_h; SENTRY_HASH_SHA256 gives exactly the
+ *                two functions above.
+ * out_seg_roots  device-accessible, n_seg digests of 32 bytes (64 for BLAKE2b),
+ *                or NULL.
+ * out_root       device-accessible, one digest.
+ * Other arguments and errors as for sentry_merkle_segments.
+ */
+SENTRY_API int sentry_merkle_segments_h(int hash, const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                                        size_t leaf_bytes, uint8_t *out_seg_roots, uint8_t *out_root,
+                                        void *stream);
+SENTRY_API int sentry_merkle_inplace_h(int hash, const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                                       size_t leaf_bytes, uint8_t *out_root, void *stream);
+
+/*
  * The block hashing kernel alone: the max(1, ceil(len/leaf_bytes)) leaf digests
  * of a buffer, 32 bytes each, in leaf order (section 4.2.1).
  * out_leaf_digests  device, 16-byte aligned, 32 bytes per leaf.

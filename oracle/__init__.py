@@ -57,6 +57,10 @@ def lib():
         L.oracle_keccak_constants.restype = None
         L.oracle_merkle_root_h.argtypes = [ctypes.c_int, vp, sz, sz, vp]
         L.oracle_merkle_root_h.restype = ctypes.c_int
+        L.oracle_merkle_segments_h.argtypes = [ctypes.c_int, vp, vp, sz, sz, vp, vp]
+        L.oracle_merkle_segments_h.restype = ctypes.c_int
+        L.oracle_merkle_inplace_h.argtypes = [ctypes.c_int, vp, vp, sz, sz, vp]
+        L.oracle_merkle_inplace_h.restype = ctypes.c_int
         L.oracle_verify.argtypes = [vp, vp]
         L.oracle_verify.restype = ctypes.c_int
         L.oracle_blake2b_constants.argtypes = [vp, vp]
@@ -188,6 +192,34 @@ def merkle_root_h(hash_id, data, leaf_bytes):
     dl = lib().oracle_merkle_root_h(hash_id, _ptr(a), a.size, leaf_bytes, out.ctypes.data)
     if dl < 0:
         raise ValueError("oracle_merkle_root_h rc=%d" % dl)
+    return out[:dl].tobytes()
+
+
+def merkle_segments_h(hash_id, segments, leaf_bytes):
+    """Algorithm 2 under hash ``hash_id``: (list of per-segment roots, root over them)."""
+    arrs = [_u8(s) for s in segments]
+    n = len(arrs)
+    ptrs = (ctypes.c_void_p * max(n, 1))(*[_ptr(a) for a in arrs])
+    lens = (ctypes.c_size_t * max(n, 1))(*[a.size for a in arrs])
+    seg = np.empty((max(n, 1), 64), np.uint8)
+    out = np.empty(64, np.uint8)
+    dl = lib().oracle_merkle_segments_h(hash_id, ptrs, lens, n, leaf_bytes, seg.ctypes.data, out.ctypes.data)
+    if dl < 0:
+        raise ValueError("oracle_merkle_segments_h rc=%d" % dl)
+    flat = seg.reshape(-1)
+    return [flat[dl * i:dl * (i + 1)].tobytes() for i in range(n)], out[:dl].tobytes()
+
+
+def merkle_inplace_h(hash_id, segments, leaf_bytes):
+    """Algorithm 3 under hash ``hash_id``: the root of the flat tree over all segments' blocks."""
+    arrs = [_u8(s) for s in segments]
+    n = len(arrs)
+    ptrs = (ctypes.c_void_p * max(n, 1))(*[_ptr(a) for a in arrs])
+    lens = (ctypes.c_size_t * max(n, 1))(*[a.size for a in arrs])
+    out = np.empty(64, np.uint8)
+    dl = lib().oracle_merkle_inplace_h(hash_id, ptrs, lens, n, leaf_bytes, out.ctypes.data)
+    if dl < 0:
+        raise ValueError("oracle_merkle_inplace_h rc=%d" % dl)
     return out[:dl].tobytes()
 
 

@@ -480,19 +480,27 @@ static void hash_any(int hash, const uint8_t *msg, size_t len, uint8_t *out)
     }
 }
 
-int oracle_merkle_root_h(int hash, const uint8_t *buf, size_t len, size_t leaf_bytes, uint8_t *out)
+static size_t digest_len(int hash) { return hash == 1 ? 64 : 32; }
+
+/* leaf digests of one buffer under hash h: max(1, ceil(len/L)) of them; returns the count */
+static size_t leaves_h(int hash, const uint8_t *buf, size_t len, size_t leaf_bytes, uint8_t *digests)
 {
-    if (leaf_bytes == 0 || hash < 0 || hash > 2) return -1;
-    const size_t dl = hash == 1 ? 64 : 32;
+    const size_t dl = digest_len(hash);
     size_t n = (len + leaf_bytes - 1) / leaf_bytes;
     if (n == 0) n = 1;
-    uint8_t *nodes = (uint8_t *)malloc(dl * n);
-    if (!nodes) return -3;
     for (size_t i = 0; i < n; i++) {
         size_t start = i * leaf_bytes, stop = start + leaf_bytes;
         if (stop > len) stop = len;
-        hash_any(hash, buf + start, stop - start, nodes + dl * i);
+        hash_any(hash, buf + start, stop - start, digests + dl * i);
     }
+    return n;
+}
+
+/* n >= 1 ready-made nodes to one, in place: neighbours hashed pairwise, a lone last node
+ * moves up unchanged */
+static void reduce_h(int hash, uint8_t *nodes, size_t n, uint8_t *out)
+{
+    const size_t dl = digest_len(hash);
     while (n > 1) {
         size_t pairs = n / 2;
         for (size_t i = 0; i < pairs; i++) {
@@ -505,6 +513,57 @@ int oracle_merkle_root_h(int hash, const uint8_t *buf, size_t len, size_t leaf_b
         n = pairs + (n & 1);
     }
     memcpy(out, nodes, dl);
+}
+
+int oracle_merkle_root_h(int hash, const uint8_t *buf, size_t len, size_t leaf_bytes, uint8_t *out)
+{
+    if (leaf_bytes == 0 || hash < 0 || hash > 2) return -1;
+    const size_t dl = digest_len(hash);
+    size_t n = (len + leaf_bytes - 1) / leaf_bytes;
+    if (n == 0) n = 1;
+    uint8_t *nodes = (uint8_t *)malloc(dl * n);
+    if (!nodes) return -3;
+    leaves_h(hash, buf, len, leaf_bytes, nodes);
+    reduce_h(hash, nodes, n, out);
+    free(nodes);
+    return (int)dl;
+}
+
+/* Algorithm 2 under hash h: a tree per tensor, then the tree over the per-tensor roots taken as
+ * ready-made nodes.  seg_roots: n_seg digests.  Returns the digest length. */
+int oracle_merkle_segments_h(int hash, const uint8_t *const *ptrs, const size_t *lens, size_t n_seg,
+                             size_t leaf_bytes, uint8_t *seg_roots, uint8_t *out)
+{
+    if (n_seg == 0 || leaf_bytes == 0 || hash < 0 || hash > 2) return -1;
+    const size_t dl = digest_len(hash);
+    for (size_t t = 0; t < n_seg; t++) {
+        int rc = oracle_merkle_root_h(hash, ptrs[t], lens[t], leaf_bytes, seg_roots + dl * t);
+        if (rc < 0) return rc;
+    }
+    uint8_t *nodes = (uint8_t *)malloc(dl * n_seg);
+    if (!nodes) return -3;
+    memcpy(nodes, seg_roots, dl * n_seg);
+    reduce_h(hash, nodes, n_seg, out);
+    free(nodes);
+    return (int)dl;
+}
+
+/* Algorithm 3 under hash h: the blocks of all tensors, in tensor order, are the leaves of one
+ * tree; a tensor of length 0 has no block; no block at all = the single empty leaf. */
+int oracle_merkle_inplace_h(int hash, const uint8_t *const *ptrs, const size_t *lens, size_t n_seg,
+                            size_t leaf_bytes, uint8_t *out)
+{
+    if (leaf_bytes == 0 || hash < 0 || hash > 2) return -1;
+    const size_t dl = digest_len(hash);
+    size_t total = 0;
+    for (size_t t = 0; t < n_seg; t++) total += (lens[t] + leaf_bytes - 1) / leaf_bytes;
+    if (total == 0) { hash_any(hash, NULL, 0, out); return (int)dl; }
+    uint8_t *nodes = (uint8_t *)malloc(dl * total);
+    if (!nodes) return -3;
+    size_t k = 0;
+    for (size_t t = 0; t < n_seg; t++)
+        if (lens[t]) k += leaves_h(hash, ptrs[t], lens[t], leaf_bytes, nodes + dl * k);
+    reduce_h(hash, nodes, total, out);
     free(nodes);
     return (int)dl;
 }

@@ -33,6 +33,8 @@ PROTOTYPES = {
     "sentry_merkle_root_h": (_int, [_int, _vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_segments": (_int, [_vp, _vp, _sz, _sz, _vp, _vp, _vp]),
     "sentry_merkle_inplace": (_int, [_vp, _vp, _sz, _sz, _vp, _vp]),
+    "sentry_merkle_segments_h": (_int, [_int, _vp, _vp, _sz, _sz, _vp, _vp, _vp]),
+    "sentry_merkle_inplace_h": (_int, [_int, _vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_leaves": (_int, [_vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_reduce": (_int, [_vp, _sz, _vp, _vp]),
     "sentry_merkle_stream_begin": (_int, [_sz, _sz, ctypes.POINTER(_vp)]),
@@ -117,6 +119,25 @@ def sentry_merkle_inplace(dev_ptrs, lens, leaf_bytes, out_root, stream=0):
     ptrs = (ctypes.c_void_p * max(n, 1))(*dev_ptrs)
     ls = (ctypes.c_size_t * max(n, 1))(*lens)
     return _check(load().sentry_merkle_inplace(ptrs, ls, n, leaf_bytes, out_root, stream))
+
+
+def _segment_arrays(dev_ptrs, lens):
+    n = len(dev_ptrs)
+    if len(lens) != n:
+        raise ValueError("dev_ptrs and lens differ in length")
+    return (ctypes.c_void_p * max(n, 1))(*dev_ptrs), (ctypes.c_size_t * max(n, 1))(*lens), n
+
+
+def sentry_merkle_segments_h(hash_id, dev_ptrs, lens, leaf_bytes, out_seg_roots, out_root, stream=0):
+    """dev_ptrs, lens: Python sequences of ints (device addresses, byte lengths)."""
+    ptrs, ls, n = _segment_arrays(dev_ptrs, lens)
+    return _check(load().sentry_merkle_segments_h(hash_id, ptrs, ls, n, leaf_bytes, out_seg_roots, out_root, stream))
+
+
+def sentry_merkle_inplace_h(hash_id, dev_ptrs, lens, leaf_bytes, out_root, stream=0):
+    """dev_ptrs, lens: Python sequences of ints (device addresses, byte lengths)."""
+    ptrs, ls, n = _segment_arrays(dev_ptrs, lens)
+    return _check(load().sentry_merkle_inplace_h(hash_id, ptrs, ls, n, leaf_bytes, out_root, stream))
 
 
 def sentry_merkle_leaves(dev_buf, length, leaf_bytes, out_leaf_digests, stream=0):

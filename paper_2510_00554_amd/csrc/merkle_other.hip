@@ -4,6 +4,15 @@
 // with the full hash, a lone last node moves up unchanged, a short last leaf is hashed at its
 // true length.  These kernels are the plain version of the scheme (leaf digests to memory,
 // then 512 nodes folded per workgroup in LDS); the tuned path is the SHA-256 one.
+//
+// Fragmented tensors (per-tensor trees of Algorithm 2, the flat in-place tree of Algorithm 3)
+// are driven by small tables instead of one launch per tensor: the prefix sums of the
+// tensors' leaf counts, and of their node counts on every later level.  A lane (leaf kernel)
+// or a workgroup (reduce kernel) finds its tensor by binary search in the prefix sums, which
+// is a dozen steps next to a hash of thousands of instructions.
+#include <cstring>
+#include <vector>
+
 #include "blake2b_device.h"
 #include "sentry_internal.h"
 
@@ -225,6 +234,14 @@ struct Sha3Tree {
 // kernels
 // ---------------------------------------------------------------------------
 
+template <class H>
+__device__ __forceinline__ void store_leaf_digest(uint32_t *out, uint64_t leaf, const uint32_t (&d)[H::WORDS])
+{
+#pragma unroll
+    for (int i = 0; i < H::WORDS; i += 4)
+        *reinterpret_cast<uint4 *>(out + leaf * H::WORDS + i) = make_uint4(d[i], d[i + 1], d[i + 2], d[i + 3]);
+}
+
 template <class H, int WG>
 __global__ void __launch_bounds__(WG)
 other_leaf_kernel(const uint8_t *base, uint64_t len, uint64_t n_leaves, uint64_t leaf_bytes, uint32_t *out)
@@ -235,22 +252,52 @@ other_leaf_kernel(const uint8_t *base, uint64_t len, uint64_t n_leaves, uint64_t
     const uint64_t left = len - start;
     uint32_t d[H::WORDS];
     H::leaf(base + start, left < leaf_bytes ? left : leaf_bytes, d);
-#pragma unroll
-    for (int i = 0; i < H::WORDS; i += 4)
-        *reinterpret_cast<uint4 *>(out + leaf * H::WORDS + i) = make_uint4(d[i], d[i + 1], d[i + 2], d[i + 3]);
+    store_leaf_digest<H>(out, leaf, d);
 }
 
-// 512 consecutive nodes per workgroup -> one node (first level from memory, the rest in LDS)
+struct SegDesc {
+    const uint8_t *base;
+    uint64_t len;
+};
+
+// the last t < n with start[t] <= i, for a non-decreasing start[0..n] with start[0] <= i < start[n]
+__device__ __forceinline__ uint32_t find_segment(const uint64_t *start, uint32_t n, uint64_t i)
+{
+    uint32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (start[mid] <= i) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Leaf kernel over fragmented tensors: leaf_start[t] = number of leaves before tensor t
+// (n_seg + 1 entries); leaf i of the launch is leaf i - leaf_start[t] of its tensor and its
+// digest goes to position i, so the digests of a tensor are adjacent and in order.
+template <class H, int WG>
+__global__ void __launch_bounds__(WG)
+other_leaf_table_kernel(const SegDesc *segs, const uint64_t *leaf_start, uint32_t n_seg, uint64_t leaf_bytes,
+                        uint32_t *out)
+{
+    const uint64_t leaf = (uint64_t)blockIdx.x * WG + threadIdx.x;
+    if (leaf >= leaf_start[n_seg]) return;
+    const uint32_t t = find_segment(leaf_start, n_seg, leaf);
+    const SegDesc sd = segs[t];
+    const uint64_t start = (leaf - leaf_start[t]) * leaf_bytes;   // 0 for the empty leaf of an empty tensor
+    const uint64_t left = sd.len - start;
+    uint32_t d[H::WORDS];
+    H::leaf(sd.base + start, left < leaf_bytes ? left : leaf_bytes, d);
+    store_leaf_digest<H>(out, leaf, d);
+}
+
+// count (1..512) consecutive nodes at in + first -> one node at o (first level from memory,
+// the rest in LDS); all lanes of the workgroup call this
 template <class H>
-__global__ void __launch_bounds__(OTHER_WG)
-other_reduce_kernel(const uint32_t *in, uint64_t n, uint8_t *out)
+__device__ __forceinline__ void reduce_group(const uint32_t *in, uint64_t first, uint32_t count, uint8_t *o)
 {
     constexpr int W = H::WORDS;
     __shared__ uint32_t lds[2][W][OTHER_WG];
     const uint32_t tid = threadIdx.x;
-    const uint64_t first = (uint64_t)blockIdx.x * OTHER_RED_IN;
-    const uint64_t rem = n - first;
-    const uint32_t count = rem < (uint64_t)OTHER_RED_IN ? (uint32_t)rem : (uint32_t)OTHER_RED_IN;
     const uint32_t pairs = count >> 1;
     if (tid < pairs) {
         uint32_t l[W], r[W], d[W];
@@ -284,7 +331,6 @@ other_reduce_kernel(const uint32_t *in, uint64_t n, uint8_t *out)
         cur ^= 1;
     }
     if (tid == 0) {
-        uint8_t *o = out + (uint64_t)blockIdx.x * 4 * W;
         if ((reinterpret_cast<uintptr_t>(o) & 3) == 0) {
             for (int i = 0; i < W; i++) reinterpret_cast<uint32_t *>(o)[i] = lds[cur][i][0];
         } else {
@@ -294,7 +340,57 @@ other_reduce_kernel(const uint32_t *in, uint64_t n, uint8_t *out)
     }
 }
 
+// 512 consecutive nodes per workgroup -> one node
+template <class H>
+__global__ void __launch_bounds__(OTHER_WG)
+other_reduce_kernel(const uint32_t *in, uint64_t n, uint8_t *out)
+{
+    const uint64_t first = (uint64_t)blockIdx.x * OTHER_RED_IN;
+    const uint64_t rem = n - first;
+    reduce_group<H>(in, first, rem < (uint64_t)OTHER_RED_IN ? (uint32_t)rem : (uint32_t)OTHER_RED_IN,
+                    out + (uint64_t)blockIdx.x * 4 * H::WORDS);
+}
+
+// One level of all per-tensor trees: node_start[t] = nodes before tensor t on this level,
+// group_start[t] = workgroups (= nodes of the next level) before tensor t; a tensor with m
+// nodes has ceil(m / 512) workgroups, the last one short.  Every tensor has at least one node.
+template <class H>
+__global__ void __launch_bounds__(OTHER_WG)
+other_reduce_table_kernel(const uint32_t *in, const uint64_t *node_start, const uint64_t *group_start, uint32_t n_seg,
+                          uint8_t *out)
+{
+    const uint64_t g = blockIdx.x;
+    const uint32_t t = find_segment(group_start, n_seg, g);
+    const uint64_t local = g - group_start[t];
+    const uint64_t m = node_start[t + 1] - node_start[t];
+    const uint64_t rem = m - local * OTHER_RED_IN;
+    reduce_group<H>(in, node_start[t] + local * OTHER_RED_IN,
+                    rem < (uint64_t)OTHER_RED_IN ? (uint32_t)rem : (uint32_t)OTHER_RED_IN, out + g * 4 * H::WORDS);
+}
+
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+// few leaves: single-wave workgroups spread over all SIMDs
+inline bool few_leaves(uint64_t n) { return ceil_div(n, 64) <= 2048; }
+
+// Reduce m nodes at src to one digest at out_digest.  buf0 and buf1 hold ceil(m / 512) nodes
+// each; src may be buf1 (it is no longer read when the second pass writes there), not buf0.
+template <class H>
+int reduce_flat(const uint32_t *src, uint64_t m, uint8_t *buf0, uint8_t *buf1, uint8_t *out_digest, hipStream_t s)
+{
+    uint8_t *bufs[2] = {buf0, buf1};
+    int turn = 0;
+    do {   // at least one pass, so that the result lands in out_digest
+        const uint64_t g = ceil_div(m, OTHER_RED_IN);
+        uint8_t *dst = g == 1 ? out_digest : bufs[turn];
+        hipLaunchKernelGGL(other_reduce_kernel<H>, dim3((uint32_t)g), dim3(OTHER_WG), 0, s, src, m, dst);
+        SENTRY_HIP_CHECK(hipGetLastError());
+        src = reinterpret_cast<const uint32_t *>(dst);
+        m = g;
+        turn ^= 1;
+    } while (m > 1);
+    return SENTRY_OK;
+}
 
 template <class H>
 int tree_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *out_digest, hipStream_t s)
@@ -308,26 +404,152 @@ int tree_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *out_d
     if (rc) return rc;
     if ((rc = sentry::scratch_get(s, sentry::R_NODES_B, DL * ceil_div(n, OTHER_RED_IN), &b))) return rc;
     const uint8_t *base = static_cast<const uint8_t *>(dev_buf);
-    if (ceil_div(n, 64) <= 2048)   // few leaves: single-wave workgroups spread over all SIMDs
+    if (few_leaves(n))
         hipLaunchKernelGGL((other_leaf_kernel<H, OTHER_WG_SMALL>), dim3((uint32_t)ceil_div(n, OTHER_WG_SMALL)),
                            dim3(OTHER_WG_SMALL), 0, s, base, (uint64_t)len, n, (uint64_t)leaf_bytes, static_cast<uint32_t *>(a));
     else
         hipLaunchKernelGGL((other_leaf_kernel<H, OTHER_WG>), dim3((uint32_t)ceil_div(n, OTHER_WG)), dim3(OTHER_WG), 0, s,
                            base, (uint64_t)len, n, (uint64_t)leaf_bytes, static_cast<uint32_t *>(a));
     SENTRY_HIP_CHECK(hipGetLastError());
-    uint8_t *bufs[2] = {static_cast<uint8_t *>(b), static_cast<uint8_t *>(a)};
+    return reduce_flat<H>(static_cast<const uint32_t *>(a), n, static_cast<uint8_t *>(b), static_cast<uint8_t *>(a),
+                          out_digest, s);
+}
+
+// Tables of a launch over fragmented tensors, uploaded in one copy:
+//   SegDesc[n_seg] | level 0: start[n_seg + 1] | level 1: start[n_seg + 1] | ...
+// level 0 holds the prefix sums of the leaf counts, level k + 1 those of ceil(count_k / 512).
+struct SegTables {
+    const SegDesc *segs;                       // device
+    std::vector<const uint64_t *> level;       // device, one prefix-sum array per level
+    std::vector<uint64_t> total;               // nodes per level
+};
+
+template <bool EMPTY_HAS_LEAF, bool ALL_LEVELS>
+int upload_tables(const char *fn, const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes,
+                  hipStream_t s, SegTables *out)
+{
+    std::vector<std::vector<uint64_t>> starts;
+    {
+        std::vector<uint64_t> l0(n_seg + 1);
+        l0[0] = 0;
+        for (size_t t = 0; t < n_seg; t++) {
+            uint64_t nl = ceil_div(lens[t], leaf_bytes);
+            if (EMPTY_HAS_LEAF && nl == 0) nl = 1;
+            l0[t + 1] = l0[t] + nl;
+        }
+        starts.push_back(std::move(l0));
+    }
+    SENTRY_REQUIRE(starts[0][n_seg] <= 0xffffffffull - OTHER_WG, "%s: too many leaves", fn);
+    while (ALL_LEVELS && starts.back()[n_seg] > n_seg) {   // some tensor still has more than one node
+        const std::vector<uint64_t> &cur = starts.back();
+        std::vector<uint64_t> nxt(n_seg + 1);
+        nxt[0] = 0;
+        for (size_t t = 0; t < n_seg; t++) nxt[t + 1] = nxt[t] + ceil_div(cur[t + 1] - cur[t], OTHER_RED_IN);
+        starts.push_back(std::move(nxt));
+    }
+    const size_t level_bytes = 8 * (n_seg + 1);
+    const size_t table_bytes = n_seg * sizeof(SegDesc) + starts.size() * level_bytes;
+    void *host_tab, *dev_tab;
+    int rc = sentry::table_staging_get(s, table_bytes, &host_tab);
+    if (rc) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_TABLES, table_bytes, &dev_tab))) return rc;
+    SegDesc *hseg = static_cast<SegDesc *>(host_tab);
+    for (size_t t = 0; t < n_seg; t++) hseg[t] = SegDesc{static_cast<const uint8_t *>(dev_ptrs[t]), lens[t]};
+    char *hp = static_cast<char *>(host_tab) + n_seg * sizeof(SegDesc);
+    const char *dp = static_cast<const char *>(dev_tab) + n_seg * sizeof(SegDesc);
+    out->segs = static_cast<const SegDesc *>(dev_tab);
+    for (const std::vector<uint64_t> &lv : starts) {
+        std::memcpy(hp, lv.data(), level_bytes);
+        out->level.push_back(reinterpret_cast<const uint64_t *>(dp));
+        out->total.push_back(lv[n_seg]);
+        hp += level_bytes;
+        dp += level_bytes;
+    }
+    SENTRY_HIP_CHECK(hipMemcpyAsync(dev_tab, host_tab, table_bytes, hipMemcpyHostToDevice, s));
+    return sentry::table_staging_mark(s);
+}
+
+template <class H>
+int launch_table_leaves(const SegTables &tab, size_t n_seg, size_t leaf_bytes, uint32_t *digests, hipStream_t s)
+{
+    const uint64_t n = tab.total[0];
+    if (few_leaves(n))
+        hipLaunchKernelGGL((other_leaf_table_kernel<H, OTHER_WG_SMALL>), dim3((uint32_t)ceil_div(n, OTHER_WG_SMALL)),
+                           dim3(OTHER_WG_SMALL), 0, s, tab.segs, tab.level[0], (uint32_t)n_seg, (uint64_t)leaf_bytes, digests);
+    else
+        hipLaunchKernelGGL((other_leaf_table_kernel<H, OTHER_WG>), dim3((uint32_t)ceil_div(n, OTHER_WG)), dim3(OTHER_WG),
+                           0, s, tab.segs, tab.level[0], (uint32_t)n_seg, (uint64_t)leaf_bytes, digests);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
+// Algorithm 2 over hash H: per-tensor roots, then the tree over the roots.
+template <class H>
+int tree_segments(const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes,
+                  uint8_t *out_seg_roots, uint8_t *out_root, hipStream_t s)
+{
+    constexpr size_t DL = 4 * H::WORDS;
+    SegTables tab;
+    int rc = upload_tables<true, true>("sentry_merkle_segments_h", dev_ptrs, lens, n_seg, leaf_bytes, s, &tab);
+    if (rc) return rc;
+    const size_t levels = tab.level.size();   // level 0 = leaves, the last level has one node per tensor
+    void *a, *b = nullptr, *roots, *r0, *r1;
+    if ((rc = sentry::scratch_get(s, sentry::R_SEG_ROOTS, DL * n_seg, &roots))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_RED_0, DL * ceil_div(n_seg, OTHER_RED_IN), &r0))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_RED_1, DL * ceil_div(n_seg, OTHER_RED_IN), &r1))) return rc;
+    if (levels == 1) {
+        a = roots;   // every tensor is a single leaf
+    } else {
+        if ((rc = sentry::scratch_get(s, sentry::R_NODES_A, DL * tab.total[0], &a))) return rc;
+        if (levels > 2 && (rc = sentry::scratch_get(s, sentry::R_NODES_B, DL * tab.total[1], &b))) return rc;
+    }
+    if ((rc = launch_table_leaves<H>(tab, n_seg, leaf_bytes, static_cast<uint32_t *>(a), s))) return rc;
     const uint32_t *src = static_cast<const uint32_t *>(a);
-    uint64_t m = n;
-    int turn = 0;
-    do {   // at least one pass, so that the result lands in out_digest
-        const uint64_t g = ceil_div(m, OTHER_RED_IN);
-        uint8_t *dst = g == 1 ? out_digest : bufs[turn];
-        hipLaunchKernelGGL(other_reduce_kernel<H>, dim3((uint32_t)g), dim3(OTHER_WG), 0, s, src, m, dst);
+    for (size_t k = 0; k + 1 < levels; k++) {
+        // level k -> level k + 1: outputs alternate between the two node buffers, the last goes to roots
+        uint8_t *dst = (k + 2 == levels) ? static_cast<uint8_t *>(roots) : static_cast<uint8_t *>((k & 1) ? a : b);
+        hipLaunchKernelGGL(other_reduce_table_kernel<H>, dim3((uint32_t)tab.total[k + 1]), dim3(OTHER_WG), 0, s, src,
+                           tab.level[k], tab.level[k + 1], (uint32_t)n_seg, dst);
         SENTRY_HIP_CHECK(hipGetLastError());
         src = reinterpret_cast<const uint32_t *>(dst);
-        m = g;
-        turn ^= 1;
-    } while (m > 1);
+    }
+    if (out_seg_roots) SENTRY_HIP_CHECK(hipMemcpyAsync(out_seg_roots, roots, DL * n_seg, hipMemcpyDefault, s));
+    return reduce_flat<H>(static_cast<const uint32_t *>(roots), n_seg, static_cast<uint8_t *>(r0),
+                          static_cast<uint8_t *>(r1), out_root, s);
+}
+
+// Algorithm 3 over hash H: one flat tree over the blocks of all tensors.
+template <class H>
+int tree_inplace(const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes, uint8_t *out_root,
+                 hipStream_t s)
+{
+    constexpr size_t DL = 4 * H::WORDS;
+    uint64_t total = 0;
+    for (size_t t = 0; t < n_seg; t++) total += ceil_div(lens[t], leaf_bytes);
+    if (total == 0) return tree_root<H>(nullptr, 0, leaf_bytes, out_root, s);   // the single empty leaf
+    SegTables tab;
+    int rc = upload_tables<false, false>("sentry_merkle_inplace_h", dev_ptrs, lens, n_seg, leaf_bytes, s, &tab);
+    if (rc) return rc;
+    void *a, *b;
+    if ((rc = sentry::scratch_get(s, sentry::R_NODES_A, DL * total, &a))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_NODES_B, DL * ceil_div(total, OTHER_RED_IN), &b))) return rc;
+    if ((rc = launch_table_leaves<H>(tab, n_seg, leaf_bytes, static_cast<uint32_t *>(a), s))) return rc;
+    return reduce_flat<H>(static_cast<const uint32_t *>(a), total, static_cast<uint8_t *>(b), static_cast<uint8_t *>(a),
+                          out_root, s);
+}
+
+int check_segment_args(const char *fn, int hash, const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                       size_t leaf_bytes, const uint8_t *out_root)
+{
+    SENTRY_REQUIRE(hash == SENTRY_HASH_BLAKE2B || hash == SENTRY_HASH_SHA3_256, "%s: unknown hash %d", fn, hash);
+    SENTRY_REQUIRE(n_seg >= 1 && n_seg <= 0xfffffffeull, "%s: n_seg must be 1 .. 2^32 - 2", fn);
+    SENTRY_REQUIRE(dev_ptrs && lens && out_root, "%s: NULL argument", fn);
+    SENTRY_REQUIRE(leaf_bytes > 0 && leaf_bytes % 64 == 0, "%s: leaf_bytes must be a positive multiple of 64 (got %zu)", fn,
+                   leaf_bytes);
+    for (size_t t = 0; t < n_seg; t++) {
+        SENTRY_REQUIRE(dev_ptrs[t] != nullptr || lens[t] == 0, "%s: segment %zu is NULL", fn, t);
+        SENTRY_REQUIRE((reinterpret_cast<uintptr_t>(dev_ptrs[t]) & 15) == 0, "%s: segment %zu is not 16-byte aligned", fn, t);
+    }
     return SENTRY_OK;
 }
 
@@ -350,6 +572,32 @@ int sentry_merkle_root_h(int hash, const void *dev_buf, size_t len, size_t leaf_
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (hash == SENTRY_HASH_BLAKE2B) return tree_root<Blake2bTree>(dev_buf, len, leaf_bytes, out_digest, s);
     return tree_root<Sha3Tree>(dev_buf, len, leaf_bytes, out_digest, s);
+}
+
+int sentry_merkle_segments_h(int hash, const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes,
+                             uint8_t *out_seg_roots, uint8_t *out_root, void *stream)
+{
+    sentry::clear_error();
+    if (hash == SENTRY_HASH_SHA256)
+        return sentry_merkle_segments(dev_ptrs, lens, n_seg, leaf_bytes, out_seg_roots, out_root, stream);
+    int rc = check_segment_args("sentry_merkle_segments_h", hash, dev_ptrs, lens, n_seg, leaf_bytes, out_root);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hash == SENTRY_HASH_BLAKE2B)
+        return tree_segments<Blake2bTree>(dev_ptrs, lens, n_seg, leaf_bytes, out_seg_roots, out_root, s);
+    return tree_segments<Sha3Tree>(dev_ptrs, lens, n_seg, leaf_bytes, out_seg_roots, out_root, s);
+}
+
+int sentry_merkle_inplace_h(int hash, const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes,
+                            uint8_t *out_root, void *stream)
+{
+    sentry::clear_error();
+    if (hash == SENTRY_HASH_SHA256) return sentry_merkle_inplace(dev_ptrs, lens, n_seg, leaf_bytes, out_root, stream);
+    int rc = check_segment_args("sentry_merkle_inplace_h", hash, dev_ptrs, lens, n_seg, leaf_bytes, out_root);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hash == SENTRY_HASH_BLAKE2B) return tree_inplace<Blake2bTree>(dev_ptrs, lens, n_seg, leaf_bytes, out_root, s);
+    return tree_inplace<Sha3Tree>(dev_ptrs, lens, n_seg, leaf_bytes, out_root, s);
 }
 
 }  // extern "C"

@@ -57,6 +57,12 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_merkle_inplace([], [], 64, 0x2000),            # no segments
     lambda: sentry.sentry_merkle_inplace([0x1000, 0x3008], [64, 64], 64, 0x2000),
     lambda: sentry.sentry_merkle_inplace([0x1000], [64], 64, 0),         # NULL output
+    lambda: sentry.sentry_merkle_segments_h(1, [], [], 64, 0, 0x2000),   # BLAKE2b, no segments
+    lambda: sentry.sentry_merkle_segments_h(2, [0x1000, 0x3008], [64, 64], 64, 0, 0x2000),
+    lambda: sentry.sentry_merkle_segments_h(5, [0x1000], [64], 64, 0, 0x2000),        # unknown leaf function
+    lambda: sentry.sentry_merkle_inplace_h(1, [0x1000], [64], 100, 0x2000),           # bad leaf size
+    lambda: sentry.sentry_merkle_inplace_h(2, [0], [64], 64, 0x2000),                 # NULL tensor with bytes
+    lambda: sentry.sentry_merkle_inplace_h(2, [0x1000], [64], 64, 0),                 # NULL output
     lambda: sentry.sentry_merkle_root_h2d(0x1000, 4096, 64, 100, 0x2000),  # chunk not a leaf multiple
     lambda: sentry.sentry_lthash(0x1000, 0, 5, 0x2000),                  # NULL offsets with n > 0
     lambda: sentry.sentry_lthash(0x1000, 0x3004, 5, 0x2000),             # misaligned offsets

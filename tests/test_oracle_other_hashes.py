@@ -64,3 +64,40 @@ def test_merkle_trees_over_each_leaf_function(hid, hfun):
     if hid == oracle.HASH_SHA256:
         buf = rng.randbytes(5000)
         assert oracle.merkle_root_h(hid, buf, 256) == oracle.merkle_root(buf, 256)
+
+
+HASHES = [
+    (oracle.HASH_SHA256, lambda b: hashlib.sha256(b).digest()),
+    (oracle.HASH_BLAKE2B, lambda b: hashlib.blake2b(b).digest()),
+    (oracle.HASH_SHA3_256, lambda b: hashlib.sha3_256(b).digest()),
+]
+
+
+def brute_nodes(hfun, level):
+    while len(level) > 1:
+        nxt = [hfun(level[i] + level[i + 1]) for i in range(0, len(level) - 1, 2)]
+        if len(level) % 2:
+            nxt.append(level[-1])
+        level = nxt
+    return level[0]
+
+
+@pytest.mark.parametrize("hid,hfun", HASHES)
+def test_per_tensor_and_flat_trees_over_each_leaf_function(hid, hfun):
+    # Algorithm 2 (a tree per tensor, then a tree over the roots as ready-made nodes) and
+    # Algorithm 3 (one flat tree over all blocks, short blocks kept short, empty tensors skipped)
+    rng = random.Random(50 + hid)
+    L = 128
+    for sizes in ([1], [0], [L], [L + 1, 0, 3 * L, 5], [0, 0], [7 * L - 1, L, 2 * L + 9, 0, 64, 33 * L],
+                  [rng.randrange(0, 6 * L) for _ in range(13)]):
+        segs = [rng.randbytes(n) for n in sizes]
+        roots, root = oracle.merkle_segments_h(hid, segs, L)
+        want_roots = [brute(hfun, s, L) for s in segs]
+        assert roots == want_roots, (hid, sizes)
+        assert root == brute_nodes(hfun, list(want_roots)), (hid, sizes)
+        leaves = [hfun(s[i:i + L]) for s in segs for i in range(0, len(s), L)]
+        want_flat = brute_nodes(hfun, leaves) if leaves else hfun(b"")
+        assert oracle.merkle_inplace_h(hid, segs, L) == want_flat, (hid, sizes)
+        if hid == oracle.HASH_SHA256:
+            assert (roots, root) == oracle.merkle_segments(segs, L)
+            assert want_flat == oracle.merkle_inplace(segs, L)
