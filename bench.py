@@ -40,6 +40,70 @@ def merkle_ops(n_leaves, leaf_bytes, n_nodes):
     return n_leaves * per_leaf + n_nodes * (SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS)
 
 
+# BLAKE2b on gfx950, counted in 32-bit lane operations (a 64-bit add or xor = 2, a 64-bit rotate
+# = 2, by 32 = 0): 96 G functions x 26 + state set-up and feed-forward ~ 2500 per 128-byte
+# compression; the one-block expansion calls, whose message is half zero, ~ 1860.
+# Keccak-f[1600]: 24 rounds x ~190 (theta 90, rho 48, chi 50, iota 2) = 4560 per 136-byte block.
+B2_BLOCK_OPS, B2_EXPAND_OPS, KECCAK_BLOCK_OPS = 2500, 1860, 4560
+
+
+def sha_tree_ops(lens, leaf_bytes, flat=False):
+    """SHA-256 trees over buffers of the given byte lengths: per-buffer trees plus the tree over
+    their roots, or (flat) one tree over all their leaves."""
+    ops, leaves_total = 0, 0
+    for ln in lens:
+        n = -(-ln // leaf_bytes) if (ln or flat) else 1
+        if ln == 0 and not flat:
+            ops += SHA_BLOCK_OPS
+        for size, count in ((leaf_bytes, ln // leaf_bytes), (ln % leaf_bytes, 1 if ln % leaf_bytes else 0)):
+            # full blocks, then the padding block(s): constant when the leaf is a whole number of blocks
+            if count:
+                pad = SHA_CONST_BLOCK_OPS if size % 64 == 0 else (2 if size % 64 > 55 else 1) * SHA_BLOCK_OPS
+                ops += count * ((size // 64) * SHA_BLOCK_OPS + pad)
+        leaves_total += n
+        if not flat:
+            ops += (n - 1) * (SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS)
+    top = leaves_total if flat else len(lens)
+    return ops + (max(top, 1) - 1) * (SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS)
+
+
+def other_tree_ops(hash_name, lens, leaf_bytes, flat=False):
+    ops, leaves_total = 0, 0
+    for ln in lens:
+        sizes = [(leaf_bytes, ln // leaf_bytes)] + ([(ln % leaf_bytes, 1)] if ln % leaf_bytes or (ln == 0 and not flat) else [])
+        n = sum(c for _, c in sizes)
+        for size, count in sizes:
+            per = max(1, -(-size // 128)) * B2_BLOCK_OPS if hash_name == "blake2b" else (size // 136 + 1) * KECCAK_BLOCK_OPS
+            ops += count * per
+        leaves_total += n
+        if not flat:
+            ops += max(n - 1, 0) * (B2_BLOCK_OPS if hash_name == "blake2b" else KECCAK_BLOCK_OPS)
+    top = leaves_total if flat else len(lens)
+    return ops + (max(top, 1) - 1) * (B2_BLOCK_OPS if hash_name == "blake2b" else KECCAK_BLOCK_OPS)
+
+
+def lthash_ops(record_lengths):
+    import numpy as np
+    blocks = np.maximum(1, -(-np.asarray(record_lengths, dtype=np.int64) // 128))
+    return int(blocks.sum()) * B2_BLOCK_OPS + len(record_lengths) * 32 * B2_EXPAND_OPS
+
+
+def model_lthash_ops(lens, block_bytes):
+    ops = 0
+    for ln in lens:
+        for size, count in ((block_bytes, ln // block_bytes), (ln % block_bytes, 1 if ln % block_bytes else 0)):
+            ops += count * (-(-(size + 8) // 128)) * B2_BLOCK_OPS
+    return ops
+
+
+def rated(entry, ops, hbm_bytes=None):
+    """Add the fractions of the integer-ALU and HBM rooflines to a per-config entry."""
+    sec = entry["ms"] * 1e-3
+    entry["alu_frac"] = ops / sec / ALU_PEAK_OPS
+    entry["hbm_frac"] = (hbm_bytes if hbm_bytes is not None else entry["bytes"]) / sec / HBM_PEAK
+    return entry
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -193,13 +257,18 @@ def main():
                 "algorithmic_bytes_per_launch": bytes70 + 32 * groups,
                 "hbm_frac": (bytes70 + 32 * groups) / (ms70 * 1e-3) / HBM_PEAK}
 
+    # every entry: GB/s hashed, and the fractions of the integer-ALU roofline (algorithmic 32-bit
+    # lane-ops / time / 39.3 T) and of the HBM roofline (bytes hashed / time / 8 TB/s)
     per_config = {
-        "C5_merkle_70b_64KiB_resident": {"GB/s": bytes70 / ms70 / 1e6, "ms": ms70, "bytes": bytes70},
-        "C3_merkle_7b_segments_1MiB": {"GB/s": bytes7 / ms7 / 1e6, "ms": ms7, "bytes": bytes7,
-                                       "leaves": sum(max(1, -(-l // LEAF7)) for l in t7_lens)},
-        "C4_lthash_one_8GB_batch_resident": {"GB/s": rec_bytes / mslt / 1e6, "ms": mslt, "bytes": rec_bytes,
-                                             "samples/s": n_rec / (mslt * 1e-3), "records": n_rec,
-                                             "longest_record": int(lengths[b0:b1].max())},
+        "C5_merkle_70b_64KiB_resident": rated({"GB/s": bytes70 / ms70 / 1e6, "ms": ms70, "bytes": bytes70},
+                                              sha_tree_ops([bytes70], LEAF70, flat=True)),
+        "C3_merkle_7b_segments_1MiB": rated({"GB/s": bytes7 / ms7 / 1e6, "ms": ms7, "bytes": bytes7,
+                                             "leaves": sum(max(1, -(-l // LEAF7)) for l in t7_lens)},
+                                            sha_tree_ops(t7_lens, LEAF7)),
+        "C4_lthash_one_8GB_batch_resident": rated({"GB/s": rec_bytes / mslt / 1e6, "ms": mslt, "bytes": rec_bytes,
+                                                   "samples/s": n_rec / (mslt * 1e-3), "records": n_rec,
+                                                   "longest_record": int(lengths[b0:b1].max())},
+                                                  lthash_ops(lengths[b0:b1])),
     }
 
     def timed_call(fn, reps):
@@ -221,45 +290,54 @@ def main():
         log("side measurements: configs 1 and 2, streaming legs")
         c1 = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20, device=dev)
         ms = timed_call(lambda: sentry.sentry_merkle_root(c1.data_ptr(), c1.numel(), 4096, root7.data_ptr(), stream), 50)
-        per_config["C1_merkle_16MiB_4KiB"] = {"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()}
+        per_config["C1_merkle_16MiB_4KiB"] = rated({"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()},
+                                                   sha_tree_ops([c1.numel()], 4096, flat=True))
         img, ioff = wl.image_records(50_000, device=dev)
         d_ioff = torch.from_numpy(ioff.view(np.int64).copy()).to(dev)
         ms = timed_call(lambda: sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream), 50)
-        per_config["C2_lthash_50k_images"] = {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(),
-                                              "samples/s": 50_000 / (ms * 1e-3)}
+        per_config["C2_lthash_50k_images"] = rated({"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(),
+                                                    "samples/s": 50_000 / (ms * 1e-3)}, lthash_ops([3072] * 50_000))
         # the 7B checkpoint as one flat tree over all blocks of all tensors (Algorithm 3)
         ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, LEAF7, root7.data_ptr(), stream), 5)
-        per_config["F3_merkle_7b_inplace_flat_1MiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+        per_config["F3_merkle_7b_inplace_flat_1MiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
+                                                             sha_tree_ops(t7_lens, LEAF7, flat=True))
         ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, 8192, root7.data_ptr(), stream), 5)
-        per_config["F3_merkle_7b_inplace_flat_8KiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+        per_config["F3_merkle_7b_inplace_flat_8KiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
+                                                             sha_tree_ops(t7_lens, 8192, flat=True))
         # the three leaf functions of section 4.2.1 on the first 16 GiB of the 70B stream, 8 KiB leaves
         f4_bytes = min(bytes70, 16 << 30)
         big_root = torch.zeros(64, dtype=torch.uint8, device=dev)
         for name, hid in (("sha256", sentry.HASH_SHA256), ("blake2b", sentry.HASH_BLAKE2B), ("sha3_256", sentry.HASH_SHA3_256)):
             ms = timed_call(lambda: sentry.sentry_merkle_root_h(hid, ckpt70.data_ptr(), f4_bytes, 8192,
                                                                 big_root.data_ptr(), stream), 5)
-            per_config["F4_merkle_%s_16GiB_8KiB" % name] = {"GB/s": f4_bytes / ms / 1e6, "ms": ms, "bytes": f4_bytes}
+            ops = (sha_tree_ops([f4_bytes], 8192, flat=True) if name == "sha256"
+                   else other_tree_ops(name, [f4_bytes], 8192, flat=True))
+            per_config["F4_merkle_%s_16GiB_8KiB" % name] = rated({"GB/s": f4_bytes / ms / 1e6, "ms": ms, "bytes": f4_bytes}, ops)
         # the paper's three schemes' hardest case: fragmented 7B checkpoint, per-tensor and flat trees, 8 KiB blocks
         seg_roots = torch.zeros(64 * len(t7_ptrs), dtype=torch.uint8, device=dev)
         for name, hid in (("blake2b", sentry.HASH_BLAKE2B), ("sha3_256", sentry.HASH_SHA3_256)):
             ms = timed_call(lambda: sentry.sentry_merkle_segments_h(hid, t7_ptrs, t7_lens, 8192, seg_roots.data_ptr(),
                                                                     big_root.data_ptr(), stream), 5)
-            per_config["F4_merkle_%s_7b_per_tensor_8KiB" % name] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+            per_config["F4_merkle_%s_7b_per_tensor_8KiB" % name] = rated(
+                {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}, other_tree_ops(name, t7_lens, 8192))
             ms = timed_call(lambda: sentry.sentry_merkle_inplace_h(hid, t7_ptrs, t7_lens, 8192, big_root.data_ptr(),
                                                                    stream), 5)
-            per_config["F4_merkle_%s_7b_inplace_flat_8KiB" % name] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+            per_config["F4_merkle_%s_7b_inplace_flat_8KiB" % name] = rated(
+                {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}, other_tree_ops(name, t7_lens, 8192, flat=True))
         # lattice hash of the 7B checkpoint (Algorithm 4), the paper's default 8 KiB blocks
         mlanes = torch.zeros(32, dtype=torch.int16, device=dev)
         ms = timed_call(lambda: sentry.sentry_lthash_model(t7_ptrs, t7_lens, 8192, 0, mlanes.data_ptr(), stream), 5)
-        per_config["F2_lthash_model_7b_8KiB"] = {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}
+        per_config["F2_lthash_model_7b_8KiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
+                                                      model_lthash_ops(t7_lens, 8192))
         # mixed-source batches (section 4.3): the same 50,000 samples spread over 1, 16 and 128 sources
         for n_src in (1, 16, 128):
             ids = torch.from_numpy((wl._words_np(wl.SEED_C2 + 7, 0, 50_000) % np.uint64(n_src)).astype(np.int32)).to(dev)
             acc = torch.zeros(n_src * 1024, dtype=torch.int16, device=dev)
             ms = timed_call(lambda: sentry.sentry_lthash_sources(img.data_ptr(), d_ioff.data_ptr(), ids.data_ptr(),
                                                                  50_000, n_src, acc.data_ptr(), stream), 30)
-            per_config["F1_lthash_50k_images_%d_sources" % n_src] = {"GB/s": img.numel() / ms / 1e6, "ms": ms,
-                                                                    "samples/s": 50_000 / (ms * 1e-3)}
+            per_config["F1_lthash_50k_images_%d_sources" % n_src] = rated(
+                {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
+                lthash_ops([3072] * 50_000))
         # host-to-device streaming: pinned host buffers, copy-only rate vs hash-while-loading rate
         hbytes = (1 << 28) if args.quick else (4 << 30)
         host = torch.empty(hbytes, dtype=torch.uint8).pin_memory()
