@@ -91,3 +91,15 @@ def test_stream_state_checks():
         sentry.sentry_merkle_stream_begin(1000, 65)
     with pytest.raises(sentry.SentryError):
         sentry.sentry_merkle_stream_update(None, 0x1000, 64)
+
+
+def test_header_is_plain_c_and_a_c_program_can_use_the_library(tmp_path):
+    import subprocess
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "abi_smoke.c")
+    exe = str(tmp_path / "abi_smoke")
+    libdir = os.path.dirname(binding.lib_path())
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    src, "-o", exe, "-L", libdir, "-l:libsentry_hip.so", "-Wl,-rpath," + libdir],
+                   check=True, capture_output=True, text=True)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "abi smoke ok" in r.stdout, r.stdout + r.stderr
