@@ -153,7 +153,10 @@ def main():
             if acc >= args.merkle_prefix_gib << 30:
                 break
         lay70 = cut
+    # resident inputs, plus (side measurements) a 16 GB copy target and two 8 GB staging buffers
     need = 2 * sum(n for _, n in lay70) + 2 * sum(n for _, n in lay7) + batch_bytes + (2 << 30)
+    if not args.no_extras and not args.quick:
+        need += (16 << 30) + 2 * batch_bytes + (2 << 30)
     free, _ = torch.cuda.mem_get_info()
     if free < need:
         sys.exit("bench.py: needs %.1f GB of free HBM, %.1f GB available" % (need / 1e9, free / 1e9))
@@ -338,25 +341,45 @@ def main():
             per_config["F1_lthash_50k_images_%d_sources" % n_src] = rated(
                 {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
                 lthash_ops([3072] * 50_000))
-        # host-to-device streaming: pinned host buffers, copy-only rate vs hash-while-loading rate
-        hbytes = (1 << 28) if args.quick else (4 << 30)
+        # host-to-device streaming in the shape of configs 5 and 4: a pinned host buffer of 16 GB;
+        # Merkle while loading it in 1 GiB chunks, and the lattice hash of two 8 GB batches (the
+        # resident batch twice), each against the plain copy of the same bytes
+        if args.quick:
+            hbytes, chunk, lt_batch = 1 << 28, 1 << 26, rec_bytes
+        else:
+            hbytes, chunk, lt_batch = 16 << 30, 1 << 30, rec_bytes
+        hbytes = max(hbytes, 2 * rec_bytes)
         host = torch.empty(hbytes, dtype=torch.uint8).pin_memory()
-        host.copy_(ckpt70[:hbytes])
         stage = torch.empty(hbytes, dtype=torch.uint8, device=dev)
-        ms_copy = timed_call(lambda: stage.copy_(host, non_blocking=True), 3)
-        chunk = min(hbytes, 256 << 20)
-        ms_m = timed_call(lambda: sentry.sentry_merkle_root_h2d(host.data_ptr(), hbytes, LEAF70, chunk,
+        m_bytes = min(hbytes, bytes70) // LEAF70 * LEAF70
+        host[:m_bytes].copy_(ckpt70[:m_bytes])
+        ms_copy = timed_call(lambda: stage[:m_bytes].copy_(host[:m_bytes], non_blocking=True), 3)
+        ms_m = timed_call(lambda: sentry.sentry_merkle_root_h2d(host.data_ptr(), m_bytes, LEAF70, chunk,
                                                                 root7.data_ptr(), stream), 3)
-        nb = int(np.searchsorted(rec_off - rec_off[0], np.uint64(hbytes), side="right")) - 1
-        lt_bytes = int(rec_off[nb] - rec_off[0])
-        host[:lt_bytes].copy_(records[:lt_bytes])
-        h_off = torch.from_numpy((rec_off[:nb + 1] - rec_off[0]).view(np.int64).copy()).pin_memory()
-        ms_l = timed_call(lambda: sentry.sentry_lthash_h2d(host.data_ptr(), h_off.data_ptr(), nb, chunk,
-                                                           lanes.data_ptr(), stream), 3)
-        streaming = {"pinned_bytes": hbytes, "copy_only_GB/s": hbytes / ms_copy / 1e6,
-                     "merkle_h2d_GB/s": hbytes / ms_m / 1e6, "merkle_overlap_efficiency": ms_copy / ms_m,
-                     "lthash_h2d_GB/s": lt_bytes / ms_l / 1e6,
-                     "lthash_overlap_efficiency": (lt_bytes / hbytes) * ms_copy / ms_l, "chunk_bytes": chunk}
+        sentry.sentry_merkle_root(ckpt70.data_ptr(), m_bytes, LEAF70, root70.data_ptr(), stream)
+        torch.cuda.synchronize()
+        if bytes(root7.cpu().numpy()) != bytes(root70.cpu().numpy()):
+            sys.exit("bench.py: Merkle root while loading differs from the root of the resident bytes")
+        lt_bytes = 2 * rec_bytes
+        host[:rec_bytes].copy_(records)
+        host[rec_bytes:lt_bytes].copy_(records)
+        rel = rec_off - rec_off[0]
+        h_off = torch.from_numpy(np.concatenate([rel, rel[1:] + np.uint64(rec_bytes)]).view(np.int64).copy()).pin_memory()
+        ms_copy_l = timed_call(lambda: stage[:lt_bytes].copy_(host[:lt_bytes], non_blocking=True), 3)
+        lanes2 = torch.zeros(1024, dtype=torch.int16, device=dev)
+        ms_l = timed_call(lambda: sentry.sentry_lthash_h2d(host.data_ptr(), h_off.data_ptr(), 2 * n_rec, lt_batch,
+                                                           lanes2.data_ptr(), stream), 3)
+        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), stream)
+        sentry.sentry_lthash_combine(lanes.data_ptr(), lanes.data_ptr(), stream)      # the batch twice
+        torch.cuda.synchronize()
+        if (lanes.cpu() != lanes2.cpu()).any():
+            sys.exit("bench.py: lattice hash while loading differs from the hash of the resident batch")
+        streaming = {"pinned_bytes": hbytes,
+                     "merkle": {"bytes": m_bytes, "chunk_bytes": chunk, "copy_only_GB/s": m_bytes / ms_copy / 1e6,
+                                "h2d_GB/s": m_bytes / ms_m / 1e6, "overlap_efficiency": ms_copy / ms_m},
+                     "lthash": {"bytes": lt_bytes, "batch_bytes": lt_batch, "batches": 2,
+                                "copy_only_GB/s": lt_bytes / ms_copy_l / 1e6, "h2d_GB/s": lt_bytes / ms_l / 1e6,
+                                "overlap_efficiency": ms_copy_l / ms_l}}
         del host, stage
 
     # ---------------- CPU baseline: the oracle, one thread, on a bounded sample ----------------

@@ -174,12 +174,14 @@ SENTRY_API int sentry_merkle_stream_abort(void *state);
 
 /*
  * Hash while loading (section 4.4: authentication on the fly as the model is
- * loaded; pinned hipMemcpyAsync stands in for the paper's GPUDirect loads):
- * the root of the tree over a host buffer, copied in chunks on a side stream
+ * loaded; a load on a side stream stands in for the paper's GPUDirect loads):
+ * the root of the tree over a host buffer, loaded in chunks on a side stream
  * into two device staging buffers while the previous chunk is hashed on
  * `stream`.  Equal to sentry_merkle_root over the same bytes.
- * host_buf     host, pinned for the copies to overlap (pageable memory works
- *              but serialises), 16-byte aligned.
+ * host_buf     host, 16-byte aligned.  Pinned memory (hipHostMalloc) is read
+ *              directly by a small load kernel at the PCIe rate and overlaps
+ *              with the hashing; pageable memory goes through hipMemcpyAsync,
+ *              which works but serialises.  A device pointer is accepted too.
  * chunk_bytes  > 0 and a multiple of leaf_bytes; two device buffers of this
  *              size are held in the library's scratch.
  * The call returns after enqueuing everything; host_buf must stay unchanged
@@ -246,7 +248,8 @@ SENTRY_API int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stre
 
 /*
  * Lattice hash of records that sit in host memory, loaded in batches on a side
- * stream while the previous batch is hashed, the running sum carried across
+ * stream (by the load kernel or hipMemcpyAsync, as for sentry_merkle_root_h2d)
+ * while the previous batch is hashed, the running sum carried across
  * batches (section 4.3: per-batch digests added to a running sum).  Equal to
  * sentry_lthash over the same records.
  * host_records  host (pinned for overlap); host_offsets: host, n+1 offsets.

@@ -99,3 +99,48 @@ def test_lthash_h2d_batches_and_running_sum():
         sentry.sentry_lthash_combine(acc.data_ptr(), part.data_ptr())
     torch.cuda.synchronize()
     assert (acc.cpu().numpy().view(np.uint16) == want).all()
+
+
+def test_h2d_from_pageable_pinned_and_device_memory():
+    # pinned memory is read by the load kernel, pageable memory goes through hipMemcpyAsync,
+    # and a device pointer in place of the host buffer is accepted as well
+    total, leaf, chunk = 64 * 5000 + 37, 64, 64 * 512
+    buf = wl.uniform_bytes(2300, 0, total)
+    want = oracle.merkle_root(buf, leaf)
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    pageable = np.zeros(total + 64, dtype=np.uint8)
+    base = (-pageable.ctypes.data) % 16                      # numpy gives no 16-byte guarantee
+    pageable[base:base + total] = buf
+    pinned = torch.from_numpy(buf.copy()).pin_memory()
+    device = to_dev(buf)
+    for name, ptr in (("pageable", pageable.ctypes.data + base), ("pinned", pinned.data_ptr()), ("device", device.data_ptr())):
+        out.zero_()
+        sentry.sentry_merkle_root_h2d(ptr, total, leaf, chunk, out.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(out.cpu().numpy()) == want, name
+
+    lens = wl.lognormal_record_lengths(300, seed=7, median=3_000, lo=0, hi=40_000)
+    off = wl.offsets_from_lengths(lens)
+    n_bytes = int(off[-1])
+    data = wl.uniform_bytes(2310, 0, n_bytes)
+    want_l = oracle.lthash(data, off)
+    lanes = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    hoff = off.copy()                                         # pageable offsets
+    pg = np.zeros(n_bytes + 32, dtype=np.uint8)
+    pin = torch.zeros(n_bytes + 32, dtype=torch.uint8).pin_memory()
+    for shift in (0, 3, 15, 16):
+        pg[shift:shift + n_bytes] = data
+        pin[shift:shift + n_bytes] = torch.from_numpy(data)
+        for name, ptr in (("pageable", pg.ctypes.data + shift), ("pinned", pin.data_ptr() + shift)):
+            for batch in (50_000, 77_777, n_bytes):
+                lanes.zero_()
+                sentry.sentry_lthash_h2d(ptr, hoff.ctypes.data, 300, batch, lanes.data_ptr())
+                torch.cuda.synchronize()
+                assert (lanes.cpu().numpy().view(np.uint16) == want_l).all(), (name, shift, batch)
+    # offsets that do not start at 0: only [offsets[0], offsets[n]) of the buffer is touched
+    sub = off[100:251].copy()
+    want_sub = oracle.lthash(data[int(sub[0]):int(sub[-1])], sub - sub[0])
+    pin[:n_bytes] = torch.from_numpy(data)
+    sentry.sentry_lthash_h2d(pin.data_ptr(), sub.ctypes.data, 150, 60_000, lanes.data_ptr())
+    torch.cuda.synchronize()
+    assert (lanes.cpu().numpy().view(np.uint16) == want_sub).all()
