@@ -110,13 +110,11 @@ __device__ __forceinline__ void sha256_compress(uint32_t (&st)[8], uint32_t (&w)
     for (int i = 0; i < 8; i++) v[i] = st[i];
 #pragma unroll
     for (int t = 0; t < 64; t++) {
-        uint32_t wt;
-        if (t < 16) {
-            wt = w[t];
-        } else {
-            wt = w[t & 15] + ssig0(w[(t + 1) & 15]) + w[(t + 9) & 15] + ssig1(w[(t + 14) & 15]);
-            w[t & 15] = wt;
-        }
+        // the word of round t is ready; the word of round t + 16 is made here, off this
+        // round's critical path, and takes the place of the one just used
+        const uint32_t wt = w[t & 15];
+        if (t + 16 < 64)
+            w[t & 15] = wt + ssig0(w[(t + 1) & 15]) + w[(t + 9) & 15] + ssig1(w[(t + 14) & 15]);
 #define V(i) v[((i) - t) & 7]
         uint32_t t1 = V(7) + bsig1(V(4)) + ch(V(4), V(5), V(6)) + k256(t) + wt;
         V(3) += t1;
