@@ -115,9 +115,11 @@ __device__ __forceinline__ void root_one_lane(const uint8_t *records, const uint
 // BLAKE2b's state is a 4x4 matrix of 64-bit words; a round applies G to the four columns,
 // then to the four diagonals, and the four G calls of a step are independent.  Here lane j
 // of a quad holds column j (a = v[j], b = v[4+j], c = v[8+j], d = v[12+j]); the column step
-// runs in all four lanes at once, the diagonal step after rotating b, c, d by one, two and
-// three lanes inside the quad (DPP quad_perm).  This cuts the serial chain of a long record
-// to about a third, which is what bounds a launch with fewer records than lanes.
+// runs in all four lanes at once, the diagonal step after rotating a, c, d inside the quad
+// (DPP quad_perm) so that lane j holds the diagonal that contains its own b: b is the value
+// a step produces last and needs first, so it is the one that stays where it is.  This cuts
+// the serial chain of a long record to about a third, which is what bounds a launch with
+// fewer records than lanes.
 //
 // Each lane needs different message words in every step (the sigma permutation), which
 // static register indexing cannot give; the quad therefore stages the 128-byte block in LDS
@@ -148,32 +150,50 @@ constexpr int QP_FROM_NEXT1 = 1 | (2 << 2) | (3 << 4) | (0 << 6);   // lane j re
 constexpr int QP_FROM_NEXT2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);   // lane j reads lane (j+2)&3
 constexpr int QP_FROM_NEXT3 = 3 | (0 << 2) | (1 << 4) | (2 << 6);   // lane j reads lane (j+3)&3
 
+// A launch of this kernel is bound by the chain of dependent instructions of its longest
+// record, so G is written for the shortest chain rather than the fewest instructions:
+// a + x and a + y are formed before b, the last value of the previous step, is needed, so
+// one add instead of two follows b.  The 64-bit add is spelled out so that it stays one
+// instruction on a register pair in exactly this association.
+__device__ __forceinline__ uint64_t add64(uint64_t a, uint64_t b)
+{
+    uint64_t r;
+    asm("v_lshl_add_u64 %0, %1, 0, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+#define B2_G_CHAIN(a, b, c, d, x, y)                                  \
+    do {                                                              \
+        const uint64_t ax_ = add64(a, x);                             \
+        a = add64(ax_, b); d = rotr64_32(d ^ a);                      \
+        c = add64(c, d);   b = rotr64_lt32<24>(b ^ c);                \
+        const uint64_t ay_ = add64(a, y);                             \
+        a = add64(ay_, b); d = rotr64_lt32<16>(d ^ a);                \
+        c = add64(c, d);   b = rotr64_63(b ^ c);                      \
+    } while (0)
+
 // Sixteen records per wave, four lanes each: the wave's records are first_rec .. first_rec + 15.
 __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base,
-                                                uint64_t n, uint64_t *h0_out, uint64_t first_rec, unsigned char *stage)
+                                                uint64_t n, const uint32_t *order, uint64_t *h0_out, uint64_t first_rec,
+                                                unsigned char *stage)
 {
     const uint32_t lane = threadIdx.x, quad = lane >> 2, j = lane & 3;
-    const uint64_t rec = first_rec + quad;
-    const bool active = rec < n;
+    const uint64_t slot = first_rec + quad;
+    const bool active = slot < n;
+    const uint64_t rec = (active && order) ? order[slot] : slot;   // longest records first when ordered
     uint64_t beg = 0, len = 0;
     if (active) {
         beg = offsets[rec] - offset_base;
         len = offsets[rec + 1] - offsets[rec];
     }
-    // the longest record of the wave sets the wave's issue priority: in a launch with few
-    // long records, their chains decide the run time and should not wait for short ones
-    {
-        uint32_t nb = (uint32_t)((len + 127) >> 7 > 0xffffffffull ? 0xffffffffull : (len + 127) >> 7);
+    // blocks of this lane's record (the empty record has one)
+    const uint32_t my_blocks = (uint32_t)(((len + 127) >> 7) > 0xffffffffull ? 0xffffffffull : (len ? (len + 127) >> 7 : 1));
+    uint32_t wave_blocks = active ? my_blocks : 0u;   // the longest record of the wave
 #pragma unroll
-        for (int sft = 32; sft >= 4; sft >>= 1) {
-            const uint32_t o = (uint32_t)__shfl_xor((int)nb, sft, 64);
-            nb = o > nb ? o : nb;
-        }
-        nb = __builtin_amdgcn_readfirstlane(nb);
-        if (nb >= 2048) __builtin_amdgcn_s_setprio(3);
-        else if (nb >= 512) __builtin_amdgcn_s_setprio(2);
-        else if (nb >= 128) __builtin_amdgcn_s_setprio(1);
+    for (int sft = 32; sft >= 4; sft >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)wave_blocks, sft, 64);
+        wave_blocks = o > wave_blocks ? o : wave_blocks;
     }
+    wave_blocks = __builtin_amdgcn_readfirstlane(wave_blocks);
     if (!active) return;   // whole quads leave together, so quad_perm never reads a dead lane
 
     const uint32_t al = (uint32_t)((reinterpret_cast<uintptr_t>(records) + beg) & 3);
@@ -188,8 +208,10 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
     for (int r = 0; r < 10; r++) {
 #pragma unroll
         for (int st = 0; st < 2; st++) {
-            const uint32_t x = qbase + 8u * B2_SIGMA_TABLE[r][8 * st + 2 * j];
-            const uint32_t y = qbase + 8u * B2_SIGMA_TABLE[r][8 * st + 2 * j + 1];
+            // column step: column j; diagonal step: the diagonal through b of column j, number j - 1
+            const uint32_t g = st == 0 ? j : ((j + 3) & 3);
+            const uint32_t x = qbase + 8u * B2_SIGMA_TABLE[r][8 * st + 2 * g];
+            const uint32_t y = qbase + 8u * B2_SIGMA_TABLE[r][8 * st + 2 * g + 1];
             maddr[r][st] = x | (y << 16);
         }
     }
@@ -207,7 +229,17 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
 #pragma unroll
         for (int k = 0; k < 9; k++) d[k] = q[k];
     }
-    for (;;) {
+    for (uint32_t blk = 0;; blk++) {
+        // The launch ends when its longest chain ends, so the wave with the most blocks still to
+        // go should never wait for an issue slot: every 256 blocks the wave sets its priority
+        // from what is left of its longest record (all its live lanes are at the same block).
+        if ((blk & 255u) == 0) {
+            const uint32_t left = wave_blocks - blk;
+            if (left >= 4096) __builtin_amdgcn_s_setprio(3);
+            else if (left >= 2048) __builtin_amdgcn_s_setprio(2);
+            else if (left >= 768) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         const bool last = len - done <= 128;
         uint32_t w[8];
         uint64_t t;
@@ -250,14 +282,14 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
             const uint64_t mc1 = *reinterpret_cast<const uint64_t *>(stage + (pc >> 16));
             const uint64_t md0 = *reinterpret_cast<const uint64_t *>(stage + (pd & 0xffffu));
             const uint64_t md1 = *reinterpret_cast<const uint64_t *>(stage + (pd >> 16));
-            B2_G(a, b, c, dd, mc0, mc1);
-            b = quad_rotate<QP_FROM_NEXT1>(b);
-            c = quad_rotate<QP_FROM_NEXT2>(c);
-            dd = quad_rotate<QP_FROM_NEXT3>(dd);
-            B2_G(a, b, c, dd, md0, md1);
-            b = quad_rotate<QP_FROM_NEXT3>(b);
-            c = quad_rotate<QP_FROM_NEXT2>(c);
-            dd = quad_rotate<QP_FROM_NEXT1>(dd);
+            B2_G_CHAIN(a, b, c, dd, mc0, mc1);
+            a = quad_rotate<QP_FROM_NEXT3>(a);     // a of column j - 1
+            c = quad_rotate<QP_FROM_NEXT1>(c);     // c of column j + 1
+            dd = quad_rotate<QP_FROM_NEXT2>(dd);   // d of column j + 2
+            B2_G_CHAIN(a, b, c, dd, md0, md1);
+            a = quad_rotate<QP_FROM_NEXT1>(a);
+            c = quad_rotate<QP_FROM_NEXT3>(c);
+            dd = quad_rotate<QP_FROM_NEXT2>(dd);
         }
         h_lo ^= a ^ c;
         h_hi ^= b ^ dd;
@@ -275,16 +307,66 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
 // the grid is sized for mode 4 and the surplus workgroups of mode 1 leave at once.
 constexpr uint64_t FOUR_LANE_MEAN_BYTES = 16384;
 
+__device__ __forceinline__ bool four_lane_mode(const uint64_t *offsets, uint64_t n)
+{
+    return (offsets[n] - offsets[0]) >= FOUR_LANE_MEAN_BYTES * n;
+}
+
 __global__ void __launch_bounds__(ROOT4_WG)
 lthash_root_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
-                   uint64_t *h0_out, int mode)
+                   const uint32_t *order, uint64_t *h0_out, int mode)
 {
     __shared__ __attribute__((aligned(16))) unsigned char stage[ROOT4_RECORDS * 128];
-    if (mode == 0) mode = (offsets[n] - offsets[0]) >= FOUR_LANE_MEAN_BYTES * n ? 4 : 1;
+    if (mode == 0) mode = four_lane_mode(offsets, n) ? 4 : 1;
     if (mode == 4)
-        root_four_lanes(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT4_RECORDS, stage);
+        root_four_lanes(records, offsets, offset_base, n, order, h0_out, (uint64_t)blockIdx.x * ROOT4_RECORDS, stage);
     else
         root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT4_WG + threadIdx.x);
+}
+
+// Order of the records for the four-lane path: longest first (a counting sort by length in
+// units of 256 bytes, done by one workgroup; the order inside a bin is arbitrary, which the
+// order-invariant sum does not see).  A wave then holds sixteen records of about the same
+// length, so it issues no instructions for quads that finished long ago (in the given order
+// a wave lives as long as the longest of its sixteen records: twice the instructions), and
+// consecutive waves, which the dispatcher deals out over the SIMDs, carry the long chains
+// first, one per SIMD, before the next tier follows.  Launched for n below SORT_MAX_RECORDS
+// only; returns at once when the batch takes the one-lane path.
+constexpr int SORT_WG = 1024;
+constexpr uint32_t SORT_BINS = 4096;
+constexpr uint64_t SORT_MAX_RECORDS = 1u << 20;
+
+__device__ __forceinline__ uint32_t length_bin(uint64_t len)   // 0 = longest
+{
+    const uint64_t k = len >> 8;
+    return SORT_BINS - 1 - (uint32_t)(k < SORT_BINS - 1 ? k : SORT_BINS - 1);
+}
+
+__global__ void __launch_bounds__(SORT_WG)
+lthash_order_kernel(const uint64_t *offsets, uint64_t n, uint32_t *order)
+{
+    if (!four_lane_mode(offsets, n)) return;
+    __shared__ uint32_t bin[SORT_BINS];
+    __shared__ uint32_t part[SORT_WG];
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t k = tid; k < SORT_BINS; k += SORT_WG) bin[k] = 0;
+    __syncthreads();
+    for (uint64_t i = tid; i < n; i += SORT_WG) atomicAdd(&bin[length_bin(offsets[i + 1] - offsets[i])], 1u);
+    __syncthreads();
+    // exclusive scan: thread t owns bins 4t .. 4t+3
+    constexpr uint32_t PER = SORT_BINS / SORT_WG;
+    uint32_t c[PER], sum = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < PER; k++) { c[k] = bin[PER * tid + k]; sum += c[k]; }
+    part[tid] = sum;
+    __syncthreads();
+    uint32_t before = 0;
+    for (uint32_t u = 0; u < tid; u++) before += part[u];
+#pragma unroll
+    for (uint32_t k = 0; k < PER; k++) { bin[PER * tid + k] = before; before += c[k]; }
+    __syncthreads();
+    for (uint64_t i = tid; i < n; i += SORT_WG)
+        order[atomicAdd(&bin[length_bin(offsets[i + 1] - offsets[i])], 1u)] = (uint32_t)i;
 }
 
 // ---------------------------------------------------------------------------
@@ -618,6 +700,7 @@ int lthash_presize(uint64_t max_records, hipStream_t s)
     void *p;
     int rc = scratch_get(s, R_LT_H0, 64 * (max_records ? max_records : 1), &p);
     if (rc) return rc;
+    if ((rc = scratch_get(s, R_LT_ORDER, 4 * (max_records ? max_records : 1), &p))) return rc;
     // the most partial rows any launch writes: two workgroups per CU, plus the running sum
     return scratch_get(s, R_LT_PART, ((size_t)cu_count() * 2 + 1) * LANE_WORDS * 4, &p);
 }
@@ -654,9 +737,14 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
         // kernel decides from the mean record length.
         const bool full = n >= (uint64_t)cu_count() * 256 * 4;
         const uint64_t grid_r = full ? ceil_div(n, ROOT4_WG) : ceil_div(n, ROOT4_RECORDS);
+        void *order = nullptr;
+        if (!full && n < SORT_MAX_RECORDS) {
+            if ((rc = scratch_get(s, R_LT_ORDER, 4 * n, &order))) return rc;
+            hipLaunchKernelGGL(lthash_order_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(order));
+        }
         hipLaunchKernelGGL(lthash_root_kernel, dim3((uint32_t)grid_r), dim3(ROOT4_WG), 0, s,
                            static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
-                           static_cast<uint64_t *>(h0), full ? 1 : 0);
+                           static_cast<const uint32_t *>(order), static_cast<uint64_t *>(h0), full ? 1 : 0);
         SENTRY_HIP_CHECK(hipGetLastError());
     }
     hipLaunchKernelGGL(lthash_expand_kernel, dim3((uint32_t)grid), dim3(EXP_WG), 0, s,
@@ -743,7 +831,7 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
     const uint64_t grid_r = full ? ceil_div(n, ROOT4_WG) : ceil_div(n, ROOT4_RECORDS);
     hipLaunchKernelGGL(lthash_root_kernel, dim3((uint32_t)grid_r), dim3(ROOT4_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
-                       static_cast<uint64_t *>(h0), full ? 1 : 0);
+                       (const uint32_t *)nullptr, static_cast<uint64_t *>(h0), full ? 1 : 0);
     hipLaunchKernelGGL(lthash_expand_units_kernel, dim3((uint32_t)ceil_div(max_units, EXP_WAVES)), dim3(EXP_WG), 0, s,
                        static_cast<const uint64_t *>(h0), static_cast<const uint32_t *>(perm), S, unit, tab,
                        static_cast<uint32_t *>(part));
