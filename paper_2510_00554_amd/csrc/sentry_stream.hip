@@ -293,7 +293,7 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
         // spare bytes: a batch sits at the same offset modulo 16 as in host memory, and the hash
         // kernel reads the whole aligned word that holds a record's last byte
         if ((rc = sentry::scratch_get(s, stage_r[i], max_bytes + 32, &stage[i]))) return rc;
-        if ((rc = sentry::scratch_get(s, off_r[i], 8 * (max_count + 1), &stage_off[i]))) return rc;
+        if ((rc = sentry::scratch_get(s, off_r[i], 8 * (max_count + 1) + 16, &stage_off[i]))) return rc;
         hstream[i] = i == 0 ? s : pipe->hash_stream[i - 1];
         if ((rc = sentry::lthash_presize(max_count, hstream[i]))) return rc;   // no regrowth in the pipeline
     }
@@ -307,6 +307,7 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
     const uint8_t *src = static_cast<const uint8_t *>(host_records);
     const uint64_t lo = host_offsets[0], hi = host_offsets[n];
     const uint8_t *readable = hi > lo ? kernel_readable(src + lo, hi - lo) : nullptr;   // view of src + lo
+    const uint8_t *off_readable = kernel_readable(host_offsets, 8 * (n + 1));
     for (size_t k = 0; k < batches.size(); k++) {
         const Batch &bt = batches[k];
         const int b = (int)(k % NS);
@@ -317,13 +318,17 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
         const uint8_t *from = readable ? readable + (beg - lo) : src + beg;
         uint8_t *to = static_cast<uint8_t *>(stage[b]) + (reinterpret_cast<uintptr_t>(from) & 15);
         if ((rc = enqueue_load(to, src + beg, readable ? from : nullptr, end - beg, pipe->copy_stream))) return rc;
-        SENTRY_HIP_CHECK(hipMemcpyAsync(stage_off[b], host_offsets + bt.first, 8 * (bt.count + 1),
-                                        hipMemcpyHostToDevice, pipe->copy_stream));
+        // the offsets of the batch, staged at the same offset modulo 16 as in host memory (0 or 8)
+        const uint8_t *off_from = off_readable ? off_readable + 8 * bt.first : reinterpret_cast<const uint8_t *>(host_offsets + bt.first);
+        uint8_t *off_to = static_cast<uint8_t *>(stage_off[b]) + (reinterpret_cast<uintptr_t>(off_from) & 15);
+        if ((rc = enqueue_load(off_to, reinterpret_cast<const uint8_t *>(host_offsets + bt.first),
+                               off_readable ? off_from : nullptr, 8 * (bt.count + 1), pipe->copy_stream)))
+            return rc;
         SENTRY_HIP_CHECK(hipEventRecord(pipe->copied[b], pipe->copy_stream));
         SENTRY_HIP_CHECK(hipStreamWaitEvent(hs, pipe->copied[b], 0));
         // record i of the batch sits at to + (offset[i] - beg); the kernel copes with any
         // byte alignment of a record
-        rc = sentry::lthash_into(to, static_cast<const uint64_t *>(stage_off[b]), beg, bt.count,
+        rc = sentry::lthash_into(to, reinterpret_cast<const uint64_t *>(off_to), beg, bt.count,
                                  static_cast<uint16_t *>(sums) + (size_t)b * SENTRY_LANES, k >= (size_t)NS, hs);
         if (rc) return rc;
         SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], hs));

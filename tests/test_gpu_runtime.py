@@ -129,3 +129,47 @@ def test_error_text_names_the_argument_and_later_calls_still_work():
     torch.cuda.synchronize()
     assert bytes(out.cpu().numpy()) == oracle.merkle_root(buf, 64)
     assert sentry.sentry_last_error() == ""
+
+
+def test_h2d_pipeline_with_many_streams_alive():
+    # HIP maps streams onto a few hardware queues; with dozens of streams alive the library's side
+    # streams share queues with the caller's stream.  Kernels of streams on one queue still run
+    # side by side, copies do not, which is one reason the loads are kernels; results are the same
+    # either way, the time is printed for the record.
+    import time
+    streams = [torch.cuda.Stream() for _ in range(40)]          # fills torch's stream pool
+    total, leaf, chunk = 1 << 28, 65536, 1 << 25
+    buf = wl.uniform_bytes(970, 0, total)
+    want = oracle.merkle_root(buf, leaf)
+    host = torch.from_numpy(buf).pin_memory()
+    stage = torch.empty(total, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    lens = wl.lognormal_record_lengths(2000, seed=5, median=100_000, lo=1000, hi=400_000)
+    off = wl.offsets_from_lengths(lens)
+    lt_total = int(off[-1])
+    data = wl.uniform_bytes(971, 0, lt_total)
+    want_l = oracle.lthash(data, off)
+    lhost = torch.from_numpy(data).pin_memory()
+    lanes = torch.zeros(1024, dtype=torch.int16, device="cuda")
+
+    def wall(fn):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t)
+
+    t_copy = min(wall(lambda: stage.copy_(host, non_blocking=True)) for _ in range(3))
+    for s in [torch.cuda.default_stream()] + streams[:6]:
+        out.zero_()
+        with torch.cuda.stream(s):
+            sentry.sentry_merkle_root_h2d(host.data_ptr(), total, leaf, chunk, out.data_ptr(), s.cuda_stream)   # creates the streams
+            t = min(wall(lambda: sentry.sentry_merkle_root_h2d(host.data_ptr(), total, leaf, chunk, out.data_ptr(),
+                                                               s.cuda_stream)) for _ in range(2))
+        assert bytes(out.cpu().numpy()) == want
+        print("merkle_h2d on stream %#x: %.2f ms (plain copy %.2f ms)" % (s.cuda_stream, t, t_copy))
+    for s in [torch.cuda.default_stream()] + streams[6:9]:
+        lanes.zero_()
+        sentry.sentry_lthash_h2d(lhost.data_ptr(), off.ctypes.data, 2000, 1 << 25, lanes.data_ptr(), s.cuda_stream)
+        torch.cuda.synchronize()
+        assert (lanes.cpu().numpy().view(np.uint16) == want_l).all()
