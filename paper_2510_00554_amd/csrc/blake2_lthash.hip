@@ -347,26 +347,54 @@ lthash_order_kernel(const uint64_t *offsets, uint64_t n, uint32_t *order)
 {
     if (!four_lane_mode(offsets, n)) return;
     __shared__ uint32_t bin[SORT_BINS];
-    __shared__ uint32_t part[SORT_WG];
+    __shared__ uint32_t part[SORT_WG / 64];
     const uint32_t tid = threadIdx.x;
     for (uint32_t k = tid; k < SORT_BINS; k += SORT_WG) bin[k] = 0;
     __syncthreads();
-    for (uint64_t i = tid; i < n; i += SORT_WG) atomicAdd(&bin[length_bin(offsets[i + 1] - offsets[i])], 1u);
+    // eight records per lane and trip, so that their offsets are in flight together
+    constexpr int BATCH = 8;
+    for (uint64_t i0 = tid; i0 < n; i0 += (uint64_t)BATCH * SORT_WG) {
+        uint32_t b[BATCH];
+#pragma unroll
+        for (int k = 0; k < BATCH; k++) {
+            const uint64_t i = i0 + (uint64_t)k * SORT_WG;
+            b[k] = i < n ? length_bin(offsets[i + 1] - offsets[i]) : SORT_BINS;
+        }
+#pragma unroll
+        for (int k = 0; k < BATCH; k++)
+            if (b[k] < SORT_BINS) atomicAdd(&bin[b[k]], 1u);
+    }
     __syncthreads();
-    // exclusive scan: thread t owns bins 4t .. 4t+3
+    // exclusive scan: thread t owns bins 4t .. 4t+3; prefix inside each wave by shuffles, then
+    // the totals of the waves before it
     constexpr uint32_t PER = SORT_BINS / SORT_WG;
     uint32_t c[PER], sum = 0;
 #pragma unroll
     for (uint32_t k = 0; k < PER; k++) { c[k] = bin[PER * tid + k]; sum += c[k]; }
-    part[tid] = sum;
+    uint32_t incl = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, d, 64);
+        if ((tid & 63) >= (uint32_t)d) incl += o;
+    }
+    if ((tid & 63) == 63) part[tid >> 6] = incl;
     __syncthreads();
-    uint32_t before = 0;
-    for (uint32_t u = 0; u < tid; u++) before += part[u];
+    uint32_t before = incl - sum;
+    for (uint32_t w = 0; w < (tid >> 6); w++) before += part[w];
 #pragma unroll
     for (uint32_t k = 0; k < PER; k++) { bin[PER * tid + k] = before; before += c[k]; }
     __syncthreads();
-    for (uint64_t i = tid; i < n; i += SORT_WG)
-        order[atomicAdd(&bin[length_bin(offsets[i + 1] - offsets[i])], 1u)] = (uint32_t)i;
+    for (uint64_t i0 = tid; i0 < n; i0 += (uint64_t)BATCH * SORT_WG) {
+        uint32_t b[BATCH];
+#pragma unroll
+        for (int k = 0; k < BATCH; k++) {
+            const uint64_t i = i0 + (uint64_t)k * SORT_WG;
+            b[k] = i < n ? length_bin(offsets[i + 1] - offsets[i]) : SORT_BINS;
+        }
+#pragma unroll
+        for (int k = 0; k < BATCH; k++)
+            if (b[k] < SORT_BINS) order[atomicAdd(&bin[b[k]], 1u)] = (uint32_t)(i0 + (uint64_t)k * SORT_WG);
+    }
 }
 
 // ---------------------------------------------------------------------------

@@ -53,11 +53,9 @@ enum Region {
     R_STAGE0,        // device staging buffers of the host-streaming entry points
     R_STAGE1,
     R_STAGE2,
-    R_STAGE3,
     R_STAGE_OFF0,    // staged record offsets
     R_STAGE_OFF1,
     R_STAGE_OFF2,
-    R_STAGE_OFF3,
     R_COUNT
 };
 

@@ -279,10 +279,9 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
     // and k+2.  Slot i keeps a running sum of its batches; the caller's stream adds the sums at
     // the end.
     constexpr int NS = sentry::PIPE_SLOTS;
-    static_assert(NS <= 4, "four staging regions exist");
-    static const sentry::Region stage_r[4] = {sentry::R_STAGE0, sentry::R_STAGE1, sentry::R_STAGE2, sentry::R_STAGE3};
-    static const sentry::Region off_r[4] = {sentry::R_STAGE_OFF0, sentry::R_STAGE_OFF1, sentry::R_STAGE_OFF2,
-                                             sentry::R_STAGE_OFF3};
+    static_assert(NS <= 3, "three staging regions exist");
+    static const sentry::Region stage_r[3] = {sentry::R_STAGE0, sentry::R_STAGE1, sentry::R_STAGE2};
+    static const sentry::Region off_r[3] = {sentry::R_STAGE_OFF0, sentry::R_STAGE_OFF1, sentry::R_STAGE_OFF2};
     const int used = batches.size() < (size_t)NS ? (int)batches.size() : NS;
     void *stage[NS], *stage_off[NS], *sums;
     hipStream_t hstream[NS];

@@ -16,12 +16,6 @@
 
 namespace {
 
-#ifdef SENTRY_LEAF_WAVES
-#define SENTRY_LEAF_OCCUPANCY __attribute__((amdgpu_waves_per_eu(SENTRY_LEAF_WAVES, 8)))
-#else
-#define SENTRY_LEAF_OCCUPANCY
-#endif
-
 constexpr int LEAF_WG = 256;          // lanes = leaves per workgroup of the leaf kernel ...
 constexpr int LEAF_WG_SMALL = 64;     // ... and when there are too few leaves to fill the chip
 constexpr uint64_t SMALL_LAUNCH_WAVES = 2048;   // two waves per SIMD on 256 CUs x 4 SIMDs
@@ -284,7 +278,7 @@ __device__ __forceinline__ void wg_tree_fold(uint32_t (&lds)[2][8][WG], uint32_t
 // every SIMD two waves is cut into single-wave workgroups, which the dispatcher spreads over
 // all SIMDs of the chip.
 template <int WG, bool FUSE, bool SEGMENTED>
-__global__ void __launch_bounds__(WG) SENTRY_LEAF_OCCUPANCY
+__global__ void __launch_bounds__(WG)
 merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const SegDesc *segs,
                    const Group *groups, uint64_t leaf_bytes, uint8_t *out)
 {
