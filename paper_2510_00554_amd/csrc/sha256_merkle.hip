@@ -343,23 +343,51 @@ __device__ __forceinline__ void sha256_schedule_to_lds(uint32_t (&w)[16], uint32
     }
 }
 
+// The consumer is alone on its SIMD, so nothing hides the latency of an LDS read that is
+// issued right before its use, which is where the compiler puts them (eight stalls of a
+// hundred cycles per block).  The reads are therefore spelled out and pinned: the words of
+// rounds 8g+8 .. 8g+15 are requested before the arithmetic of rounds 8g .. 8g+7 and waited
+// for after it.  `pin` passes through unchanged and ties the request to that place.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void lds_request_8_words(uint32_t lds_addr, u32x4 &x0, u32x4 &x1, uint32_t &pin)
+{
+    asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:16"
+                 : "=&v"(x0), "=&v"(x1), "+v"(pin)
+                 : "v"(lds_addr)
+                 : "memory");
+}
+__device__ __forceinline__ void lds_wait_8_words(u32x4 &x0, u32x4 &x1)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x0), "+v"(x1));
+}
+
 // consumer: the 64 rounds over a schedule held in LDS; st is updated only where apply is set
 __device__ __forceinline__ void sha256_rounds_from_lds(uint32_t (&st)[8], const uint32_t *src, bool apply)
 {
-    const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
+    // LDS byte address of this lane's schedule: the low half of the flat address
+    const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>(src);
     uint32_t v[8];
 #pragma unroll
     for (int i = 0; i < 8; i++) v[i] = st[i];
-    uint4 x = {};
+    u32x4 c0, c1, n0 = {}, n1 = {};
+    lds_request_8_words(base, c0, c1, v[0]);
 #pragma unroll
-    for (int t = 0; t < 64; t++) {
-        if ((t & 3) == 0) x = s4[t >> 2];
-        const uint32_t wt = (t & 3) == 0 ? x.x : (t & 3) == 1 ? x.y : (t & 3) == 2 ? x.z : x.w;
+    for (int g = 0; g < 8; g++) {
+        lds_wait_8_words(c0, c1);
+        if (g < 7) lds_request_8_words(base + 32u * (uint32_t)(g + 1), n0, n1, v[0]);
+        const uint32_t w8[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const int t = 8 * g + k;
 #define V(i) v[((i) - t) & 7]
-        uint32_t t1 = V(7) + bsig1(V(4)) + ch(V(4), V(5), V(6)) + k256(t) + wt;
-        V(3) += t1;
-        V(7) = t1 + bsig0(V(0)) + maj(V(0), V(1), V(2));
+            uint32_t t1 = V(7) + bsig1(V(4)) + ch(V(4), V(5), V(6)) + k256(t) + w8[k];
+            V(3) += t1;
+            V(7) = t1 + bsig0(V(0)) + maj(V(0), V(1), V(2));
 #undef V
+        }
+        c0 = n0;
+        c1 = n1;
     }
     if (apply) {
 #pragma unroll
