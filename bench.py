@@ -8,8 +8,14 @@ One step = one pass of the whole path over inputs already resident in HBM:
     1 MiB leaves)                                      -> sentry_merkle_segments
   * lattice hash of one 8 GB batch of variable-length records (log-normal lengths),
     folded into the running sum                        -> sentry_lthash, sentry_lthash_combine
-`value` = bytes hashed per step / step time (GB = 1e9 bytes).  The host-to-device streaming
-legs are PCIe-bound and are reported beside it (`streaming`), never inside `value`.
+`value` = bytes hashed per step / step time (GB = 1e9 bytes).
+
+Beside it, in the same JSON line: `roofline` (the SHA-256 leaf kernel on the 70B stream against
+the integer-ALU peak), `per_config` (the five target configurations and the widened entry
+points, each with GB/s and its fractions of the ALU and HBM rooflines), `streaming` (hashing
+while loading from 16 GB of pinned host memory in the shape of configs 5 and 4, against the
+plain copy of the same bytes; PCIe-bound, never part of `value`) and `cpu_baseline` (the
+single-threaded oracle on a bounded sample of the same inputs).
 
 Prints one JSON line.  --quick shrinks every input (for smoke runs; the workload name says so).
 """
