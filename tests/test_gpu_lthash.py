@@ -154,6 +154,22 @@ def test_four_lane_path_edge_lengths_and_alignments():
     assert (gpu_lthash(data2, off2, 1) == oracle.lthash(data2, off2)).all()
 
 
+def test_four_lane_path_many_records_in_length_order():
+    # tens of thousands of records with a mean above 16 KiB: the device orders them by length
+    # (many records per lane of the ordering workgroup, every bin of the top range in use, ties,
+    # records beyond the last bin) and hashes sixteen per wave in that order
+    n = 40_001
+    rng = np.random.default_rng(62)
+    lens = rng.integers(6_000, 42_000, n).astype(np.uint64)
+    lens[::97] = 0
+    lens[5::1013] = 20_480                 # ties on a bin boundary
+    lens[7] = 1_300_000                    # beyond the last bin
+    off = wl.offsets_from_lengths(lens)
+    assert int(off[-1]) >= 16384 * n
+    data = wl.uniform_bytes(1550, 0, int(off[-1]))
+    assert (gpu_lthash(data, off, 3) == oracle.lthash(data, off)).all()
+
+
 def test_many_records_take_the_one_lane_path():
     # at least four records per lane of the chip: one lane per record regardless of lengths
     n = 262_144 + 37
