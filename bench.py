@@ -102,6 +102,32 @@ def model_lthash_ops(lens, block_bytes):
     return ops
 
 
+# A launch with fewer leaves (records) than lanes is bound by the serial chain of its longest leaf:
+# a wave that has a SIMD to itself issues one VALU instruction per ~5.3 cycles on this chip, whatever
+# the instruction (measured), so chain_floor = instructions on the longest chain x 5.3
+# cycles / 2.4 GHz.  Instructions per block on the critical wave: 930 for the SHA-256 rounds-only
+# consumer wave, 2304 for one tree level (two compressions by one lane), 700 for one BLAKE2b
+# compression spread over four lanes.
+LONE_WAVE_CYCLES_PER_INSTR, CLOCK_HZ = 5.3, 2.4e9
+SHA_CONSUMER_INSTRS, SHA_NODE_INSTRS, B2_FOUR_LANE_INSTRS = 930, 2304, 700
+
+
+def chain_bound(entry, instrs):
+    floor_ms = instrs * LONE_WAVE_CYCLES_PER_INSTR / CLOCK_HZ * 1e3
+    entry["bound"] = "chain"
+    entry["chain_floor_ms"] = floor_ms
+    entry["chain_frac"] = floor_ms / entry["ms"]
+    return entry
+
+
+def tree_levels(n):
+    lv = 0
+    while n > 1:
+        n = (n + 1) // 2
+        lv += 1
+    return lv
+
+
 def rated(entry, ops, hbm_bytes=None):
     """Add the fractions of the integer-ALU and HBM rooflines to a per-config entry."""
     sec = entry["ms"] * 1e-3
@@ -279,6 +305,13 @@ def main():
                                                    "longest_record": int(lengths[b0:b1].max())},
                                                   lthash_ops(lengths[b0:b1])),
     }
+    # the chain floors of the two chain-bound parts of the step: a full 1 MiB leaf and its tensor's tree
+    # levels; the longest record of the batch
+    max_leaves7 = max(-(-l // LEAF7) for l in t7_lens)
+    chain_bound(per_config["C3_merkle_7b_segments_1MiB"],
+                (LEAF7 // 64 + 1) * SHA_CONSUMER_INSTRS + (tree_levels(max_leaves7) + tree_levels(len(t7_lens))) * SHA_NODE_INSTRS)
+    chain_bound(per_config["C4_lthash_one_8GB_batch_resident"],
+                -(-int(lengths[b0:b1].max()) // 128) * B2_FOUR_LANE_INSTRS)
 
     def timed_call(fn, reps):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -299,8 +332,9 @@ def main():
         log("side measurements: configs 1 and 2, streaming legs")
         c1 = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20, device=dev)
         ms = timed_call(lambda: sentry.sentry_merkle_root(c1.data_ptr(), c1.numel(), 4096, root7.data_ptr(), stream), 50)
-        per_config["C1_merkle_16MiB_4KiB"] = rated({"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()},
-                                                   sha_tree_ops([c1.numel()], 4096, flat=True))
+        per_config["C1_merkle_16MiB_4KiB"] = chain_bound(
+            rated({"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()}, sha_tree_ops([c1.numel()], 4096, flat=True)),
+            (4096 // 64 + 1) * SHA_CONSUMER_INSTRS + tree_levels(c1.numel() // 4096) * SHA_NODE_INSTRS)
         img, ioff = wl.image_records(50_000, device=dev)
         d_ioff = torch.from_numpy(ioff.view(np.int64).copy()).to(dev)
         ms = timed_call(lambda: sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream), 50)
