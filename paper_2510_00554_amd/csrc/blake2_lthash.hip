@@ -2,10 +2,11 @@
 // section 4.3): per-record digest h(M) = BLAKE2Xb(M) with 2048 output bytes read as
 // 1024 little-endian uint16 lanes, summed lane-wise mod 2^16.
 //
-// Three kernels:
-//   lthash_root_kernel    the sequential BLAKE2b-512 root hash H0 of every record (the only
-//                         serial part), one lane per record or four lanes per record,
-//                         64 bytes per record to scratch;
+// The kernels:
+//   lthash_root1_kernel,  the sequential BLAKE2b-512 root hash H0 of every record (the only
+//   lthash_root4_kernel   serial part), one lane per record or four lanes per record (with
+//                         lthash_order_kernel, which orders the records by length for the
+//                         latter), 64 bytes per record to scratch;
 //   lthash_expand_kernel  one (record, output block) pair per lane: the 32 expansion
 //                         compressions of a record are independent, so they are spread
 //                         over all lanes of the chip; each lane keeps the 16 packed words
@@ -153,14 +154,8 @@ constexpr int QP_FROM_NEXT3 = 3 | (0 << 2) | (1 << 4) | (2 << 6);   // lane j re
 // A launch of this kernel is bound by the chain of dependent instructions of its longest
 // record, so G is written for the shortest chain rather than the fewest instructions:
 // a + x and a + y are formed before b, the last value of the previous step, is needed, so
-// one add instead of two follows b.  The 64-bit add is spelled out so that it stays one
-// instruction on a register pair in exactly this association.
-__device__ __forceinline__ uint64_t add64(uint64_t a, uint64_t b)
-{
-    uint64_t r;
-    asm("v_lshl_add_u64 %0, %1, 0, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
+// one add instead of two follows b.
+__device__ __forceinline__ uint64_t add64(uint64_t a, uint64_t b) { return a + b; }
 #define B2_G_CHAIN(a, b, c, d, x, y)                                  \
     do {                                                              \
         const uint64_t ax_ = add64(a, x);                             \
@@ -223,13 +218,23 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
     uint64_t h_lo = iv_lo ^ (j == 0 ? ROOT_P0 : j == 1 ? ROOT_P1 : 0ull);
     uint64_t h_hi = iv_hi;
 
-    uint32_t d[9];
+    // Four blocks of this lane's slice are in flight: a global load takes about as long as one
+    // compression, longer while the bulk of a batch streams through the chip, and with one
+    // block in flight the chain of the longest record waited for its data on every block
+    // (one 707 KB record alone: 9.4 ms with one block in flight, 8.1 ms with four).
+    constexpr int AHEAD = 4;
+    uint32_t db[AHEAD][9];
     uint64_t done = 0;
-    if (len > 128) {
+    uint32_t blk = 0;
 #pragma unroll
-        for (int k = 0; k < 9; k++) d[k] = q[k];
+    for (int u = 0; u < AHEAD; u++) {
+        if (len > 128ull * (u + 1)) {
+#pragma unroll
+            for (int k = 0; k < 9; k++) db[u][k] = q[32 * u + k];
+        }
     }
-    for (uint32_t blk = 0;; blk++) {
+    // one block; d is the buffer that holds it if it is full and not the last; true when done
+    auto step = [&](uint32_t (&d)[9]) -> bool {
         // The launch ends when its longest chain ends, so the wave with the most blocks still to
         // go should never wait for an issue slot: every 256 blocks the wave sets its priority
         // from what is left of its longest record (all its live lanes are at the same block).
@@ -240,6 +245,7 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
             else if (left >= 768) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
         }
+        blk++;
         const bool last = len - done <= 128;
         uint32_t w[8];
         uint64_t t;
@@ -247,22 +253,23 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
 #pragma unroll
             for (int k = 0; k < 8; k++) w[k] = __builtin_amdgcn_alignbit(d[k + 1], d[k], sh);
             done += 128;
-            q += 32;
+            q += 32;                        // q: the next block
             t = done;
-            if (len - done > 128) {   // the next block is full too: fetch it during this compression
+            if (len - done > 128ull * AHEAD) {   // the block AHEAD blocks on is full and not the last: fetch it now
 #pragma unroll
-                for (int k = 0; k < 9; k++) d[k] = q[k];
+                for (int k = 0; k < 9; k++) d[k] = q[32 * (AHEAD - 1) + k];
             }
         } else {
             // 1..128 bytes (0 for the empty record), zero padded; words without a record byte are not read
             const uint32_t rem = (uint32_t)(len - done);
             const uint32_t span = rem ? al + rem : 0u;
+            uint32_t e[9];
 #pragma unroll
-            for (int k = 0; k < 9; k++) d[k] = ((uint32_t)(4 * (8 * j + k)) < span) ? q[k] : 0u;
+            for (int k = 0; k < 9; k++) e[k] = ((uint32_t)(4 * (8 * j + k)) < span) ? q[k] : 0u;
 #pragma unroll
             for (int k = 0; k < 8; k++) {
                 const uint32_t lo = 4u * (8u * j + (uint32_t)k);
-                uint32_t x = __builtin_amdgcn_alignbit(d[k + 1], d[k], sh);
+                uint32_t x = __builtin_amdgcn_alignbit(e[k + 1], e[k], sh);
                 if (rem < lo + 4) x = (rem <= lo) ? 0u : (x & ((1u << (8 * (rem - lo))) - 1u));
                 w[k] = x;
             }
@@ -293,18 +300,23 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
         }
         h_lo ^= a ^ c;
         h_hi ^= b ^ dd;
-        if (last) break;
+        return last;
+    };
+    for (bool fin = false; !fin;) {
+#pragma unroll
+        for (int u = 0; u < AHEAD; u++) {
+            if (step(db[u])) { fin = true; break; }
+        }
     }
     h0_out[8 * rec + j] = h_lo;
     h0_out[8 * rec + 4 + j] = h_hi;
 }
 
-// Root hashes of n records.  mode 1: one lane per record; mode 4: four lanes per record;
-// mode 0: chosen here from the mean record length, which the kernel can read from the
-// offsets while the host cannot (the offsets are device memory and the call does not
-// wait): records of 16 KiB and more on average make a launch chain-bound, so they get four
-// lanes; short records get one lane, whose start-up is cheaper.  Workgroups are single waves;
-// the grid is sized for mode 4 and the surplus workgroups of mode 1 leave at once.
+// Root hashes of n records: one lane per record, or four lanes per record.  Which, is chosen
+// on the device from the mean record length, which a kernel can read from the offsets while
+// the host cannot (the offsets are device memory and the call does not wait): records of
+// 16 KiB and more on average make a launch chain-bound, so they get four lanes; short records
+// get one lane, whose start-up is cheaper.  Workgroups are single waves.
 constexpr uint64_t FOUR_LANE_MEAN_BYTES = 16384;
 
 __device__ __forceinline__ bool four_lane_mode(const uint64_t *offsets, uint64_t n)
@@ -312,16 +324,25 @@ __device__ __forceinline__ bool four_lane_mode(const uint64_t *offsets, uint64_t
     return (offsets[n] - offsets[0]) >= FOUR_LANE_MEAN_BYTES * n;
 }
 
+// Two kernels, so that each path gets its own register budget and code footprint (the
+// four-lane path keeps four blocks in flight and unrolls its loop four times; inside one
+// kernel that slowed the one-lane path down by a third).  Both are launched when the choice
+// is left to the device; the one whose mode is not taken returns at once.
 __global__ void __launch_bounds__(ROOT4_WG)
-lthash_root_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
-                   const uint32_t *order, uint64_t *h0_out, int mode)
+lthash_root1_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
+                    uint64_t *h0_out, int mode)
+{
+    if (mode == 0 && four_lane_mode(offsets, n)) return;
+    root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT4_WG + threadIdx.x);
+}
+
+__global__ void __launch_bounds__(ROOT4_WG)
+lthash_root4_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
+                    const uint32_t *order, uint64_t *h0_out)
 {
     __shared__ __attribute__((aligned(16))) unsigned char stage[ROOT4_RECORDS * 128];
-    if (mode == 0) mode = four_lane_mode(offsets, n) ? 4 : 1;
-    if (mode == 4)
-        root_four_lanes(records, offsets, offset_base, n, order, h0_out, (uint64_t)blockIdx.x * ROOT4_RECORDS, stage);
-    else
-        root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT4_WG + threadIdx.x);
+    if (!four_lane_mode(offsets, n)) return;
+    root_four_lanes(records, offsets, offset_base, n, order, h0_out, (uint64_t)blockIdx.x * ROOT4_RECORDS, stage);
 }
 
 // Order of the records for the four-lane path: longest first (a counting sort by length in
@@ -330,11 +351,10 @@ lthash_root_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t off
 // length, so it issues no instructions for quads that finished long ago (in the given order
 // a wave lives as long as the longest of its sixteen records: twice the instructions), and
 // consecutive waves, which the dispatcher deals out over the SIMDs, carry the long chains
-// first, one per SIMD, before the next tier follows.  Launched for n below SORT_MAX_RECORDS
-// only; returns at once when the batch takes the one-lane path.
+// first, one per SIMD, before the next tier follows.  Launched only when the device chooses
+// the path (fewer than four records per lane of the chip, so under 2^20 records); returns at once when the batch takes the one-lane path.
 constexpr int SORT_WG = 1024;
 constexpr uint32_t SORT_BINS = 4096;
-constexpr uint64_t SORT_MAX_RECORDS = 1u << 20;
 
 __device__ __forceinline__ uint32_t length_bin(uint64_t len)   // 0 = longest
 {
@@ -764,15 +784,17 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
         // the lengths are, and one lane per record does the least total work; below that the
         // kernel decides from the mean record length.
         const bool full = n >= (uint64_t)cu_count() * 256 * 4;
-        const uint64_t grid_r = full ? ceil_div(n, ROOT4_WG) : ceil_div(n, ROOT4_RECORDS);
-        void *order = nullptr;
-        if (!full && n < SORT_MAX_RECORDS) {
+        hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT4_WG)), dim3(ROOT4_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
+                           static_cast<uint64_t *>(h0), full ? 1 : 0);
+        if (!full) {
+            void *order;
             if ((rc = scratch_get(s, R_LT_ORDER, 4 * n, &order))) return rc;
             hipLaunchKernelGGL(lthash_order_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(order));
+            hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
+                               static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
+                               static_cast<const uint32_t *>(order), static_cast<uint64_t *>(h0));
         }
-        hipLaunchKernelGGL(lthash_root_kernel, dim3((uint32_t)grid_r), dim3(ROOT4_WG), 0, s,
-                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
-                           static_cast<const uint32_t *>(order), static_cast<uint64_t *>(h0), full ? 1 : 0);
         SENTRY_HIP_CHECK(hipGetLastError());
     }
     hipLaunchKernelGGL(lthash_expand_kernel, dim3((uint32_t)grid), dim3(EXP_WG), 0, s,
@@ -856,10 +878,13 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
                        static_cast<uint32_t *>(perm));
     SENTRY_HIP_CHECK(hipGetLastError());
     const bool full = n >= (uint64_t)cu_count() * 256 * 4;
-    const uint64_t grid_r = full ? ceil_div(n, ROOT4_WG) : ceil_div(n, ROOT4_RECORDS);
-    hipLaunchKernelGGL(lthash_root_kernel, dim3((uint32_t)grid_r), dim3(ROOT4_WG), 0, s,
+    hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT4_WG)), dim3(ROOT4_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
-                       (const uint32_t *)nullptr, static_cast<uint64_t *>(h0), full ? 1 : 0);
+                       static_cast<uint64_t *>(h0), full ? 1 : 0);
+    if (!full)
+        hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
+                           (const uint32_t *)nullptr, static_cast<uint64_t *>(h0));
     hipLaunchKernelGGL(lthash_expand_units_kernel, dim3((uint32_t)ceil_div(max_units, EXP_WAVES)), dim3(EXP_WG), 0, s,
                        static_cast<const uint64_t *>(h0), static_cast<const uint32_t *>(perm), S, unit, tab,
                        static_cast<uint32_t *>(part));

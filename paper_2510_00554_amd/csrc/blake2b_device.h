@@ -10,7 +10,13 @@ namespace {
 
 // 64-bit values live in register pairs
 
-__device__ __forceinline__ uint64_t pack64(uint32_t lo, uint32_t hi) { return ((uint64_t)hi << 32) | lo; }
+// (as a vector cast, not shift-and-or: the compiler turns "x + (lo | hi << 32)" into two adds)
+typedef uint32_t b2_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint64_t pack64(uint32_t lo, uint32_t hi)
+{
+    const b2_u32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint64_t, v);
+}
 
 // rotations as two 32-bit funnel shifts on the halves; by 32 it is a swap of the halves
 __device__ __forceinline__ uint64_t rotr64_32(uint64_t x) { return pack64((uint32_t)(x >> 32), (uint32_t)x); }

@@ -350,11 +350,14 @@ __device__ __forceinline__ void sha256_schedule_to_lds(uint32_t (&w)[16], uint32
 // for after it.  `pin` passes through unchanged and ties the request to that place.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ void lds_request_8_words(uint32_t lds_addr, u32x4 &x0, u32x4 &x1, uint32_t &pin)
+// `array` is not used by the instructions: naming the pointer tells the compiler that the
+// statement reads the memory behind it, so that the stores that fill it stay.
+__device__ __forceinline__ void lds_request_8_words(uint32_t lds_addr, const uint32_t *array, u32x4 &x0, u32x4 &x1,
+                                                    uint32_t &pin)
 {
     asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:16"
                  : "=&v"(x0), "=&v"(x1), "+v"(pin)
-                 : "v"(lds_addr)
+                 : "v"(lds_addr), "v"(array)
                  : "memory");
 }
 __device__ __forceinline__ void lds_wait_8_words(u32x4 &x0, u32x4 &x1)
@@ -371,11 +374,11 @@ __device__ __forceinline__ void sha256_rounds_from_lds(uint32_t (&st)[8], const 
 #pragma unroll
     for (int i = 0; i < 8; i++) v[i] = st[i];
     u32x4 c0, c1, n0 = {}, n1 = {};
-    lds_request_8_words(base, c0, c1, v[0]);
+    lds_request_8_words(base, src, c0, c1, v[0]);
 #pragma unroll
     for (int g = 0; g < 8; g++) {
         lds_wait_8_words(c0, c1);
-        if (g < 7) lds_request_8_words(base + 32u * (uint32_t)(g + 1), n0, n1, v[0]);
+        if (g < 7) lds_request_8_words(base + 32u * (uint32_t)(g + 1), src, n0, n1, v[0]);
         const uint32_t w8[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
         for (int k = 0; k < 8; k++) {
