@@ -1,7 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the artifact-hashing hot path on one MI355X.
 
-One step = one pass of the whole path over inputs already resident in HBM:
+One step = one pass of the whole path over inputs already resident in HBM (the first part fills
+the chip and runs alone; the other two are bound by single serial chains, leave most of the chip
+idle and belong to independent artifacts, so they run side by side on two streams; --serial runs
+all three back to back on one stream):
   * Merkle root of the 70B-parameter bf16 checkpoint laid out as one byte stream
     (137.95 GB, 64 KiB leaves)                         -> sentry_merkle_root, sentry_verify
   * per-tensor roots + model root of the 7B checkpoint (291 tensors, 13.48 GB,
@@ -143,6 +146,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--quick", action="store_true", help="1/64-size inputs (not the reported workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial", action="store_true", help="all three parts of the step on one stream, one after the other")
     ap.add_argument("--no-extras", action="store_true", help="skip per-config and streaming side measurements")
     ap.add_argument("--merkle-prefix-gib", type=int, default=0,
                     help="hash only the first N GiB of the 70B stream (for counter runs; the workload name says so)")
@@ -222,29 +226,53 @@ def main():
     if args.merkle_prefix_gib:
         bytes70 = min(bytes70, args.merkle_prefix_gib << 30)
     step_bytes = bytes70 + bytes7 + rec_bytes
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    # The per-tensor pass over the 7B checkpoint and the lattice hash of the batch are both bound by
+    # single serial chains and leave most of the chip idle, and they are independent artifacts (a model,
+    # a dataset): the step runs them side by side on two streams once the 70B root, which fills the
+    # chip, is done.  --serial puts everything on one stream.
+    side = torch.cuda.Stream()
+    side_stream = stream if args.serial else side.cuda_stream
 
     def step(expected=None, timed=None):
-        if timed is not None:
-            ev[0].record()
+        ev[0].record()
         sentry.sentry_merkle_root(ckpt70.data_ptr(), bytes70, LEAF70, root70.data_ptr(), stream)
-        if timed is not None:
-            ev[1].record()
+        ev[1].record()
+        if not args.serial:
+            side.wait_event(ev[1])
         sentry.sentry_merkle_segments(t7_ptrs, t7_lens, LEAF7, seg_roots.data_ptr(), root7.data_ptr(), stream)
-        if timed is not None:
-            ev[2].record()
-        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), stream)
-        sentry.sentry_lthash_combine(running.data_ptr(), lanes.data_ptr(), stream)
-        if timed is not None:
+        ev[2].record()
+        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), side_stream)
+        sentry.sentry_lthash_combine(running.data_ptr(), lanes.data_ptr(), side_stream)
+        if args.serial:
             ev[3].record()
+        else:
+            ev[3].record(side)
+            torch.cuda.current_stream().wait_event(ev[3])
+        ev[4].record()
         host_root.copy_(root70, non_blocking=True)
         torch.cuda.synchronize()
         got = bytes(host_root.numpy())
         if expected is not None and sentry.sentry_verify(got, expected) != 0:
             sys.exit("bench.py: root changed between steps")
         if timed is not None:
-            timed.append((ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])))
+            # 70B root alone; 7B pass and batch hash measured from the end of the 70B root (they overlap
+            # unless --serial); all three parts
+            timed.append((ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]),
+                          ev[2 if args.serial else 1].elapsed_time(ev[3]), ev[0].elapsed_time(ev[4])))
         return got
+
+    def alone(fn, reps=3):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            a.record()
+            fn()
+            b.record()
+            b.synchronize()
+            ts.append(a.elapsed_time(b))
+        return statistics.median(ts)
 
     if args.copy_probe:
         # a plain copy of known size: 2^30 int32 elements read and written once by one kernel
@@ -269,8 +297,13 @@ def main():
     ms_per_step = 1e3 * dt / args.steps
     value = step_bytes / (dt / args.steps) / 1e9
     ms70 = statistics.mean(p[0] for p in parts)
-    ms7 = statistics.mean(p[1] for p in parts)
-    mslt = statistics.mean(p[2] for p in parts)
+    ms_gpu_step = statistics.mean(p[3] for p in parts)
+    # the two chain-bound parts on their own (inside the step they run side by side)
+    ms7 = alone(lambda: sentry.sentry_merkle_segments(t7_ptrs, t7_lens, LEAF7, seg_roots.data_ptr(), root7.data_ptr(), stream))
+    mslt = alone(lambda: (sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), stream),
+                          sentry.sentry_lthash_combine(running.data_ptr(), lanes.data_ptr(), stream)))
+    ms7_in_step = statistics.mean(p[1] for p in parts)
+    mslt_in_step = statistics.mean(p[2] for p in parts)
 
     # ---------------- roofline of the dominant kernel (SHA-256 leaf kernel, 70B stream) ----------------
     n_leaves70 = -(-bytes70 // LEAF70)
@@ -470,7 +503,11 @@ def main():
                    "Merkle root of the 70B bf16 checkpoint stream resident in HBM (config 5 shape, 64 KiB leaves) + "
                    "per-tensor roots and model root of the 7B checkpoint (config 3, 1 MiB leaves) + lattice hash of "
                    "one 8 GB batch of log-normal records folded into the running sum (config 4 shape)",
-                   "bytes_per_step": step_bytes, "records_per_step": n_rec},
+                   "bytes_per_step": step_bytes, "records_per_step": n_rec,
+                   "schedule": ("one stream, parts back to back" if args.serial else
+                                "70B root, then the 7B per-tensor pass and the batch hash side by side on two streams"),
+                   "step_parts_ms": {"merkle_70b": ms70, "merkle_7b_in_step": ms7_in_step,
+                                     "lthash_batch_in_step": mslt_in_step, "all_on_gpu": ms_gpu_step}},
         "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config, "streaming": streaming,
         "root_70b": expected.hex(),
     }
