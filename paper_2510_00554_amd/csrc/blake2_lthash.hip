@@ -327,12 +327,11 @@ __device__ __forceinline__ bool four_lane_mode(const uint64_t *offsets, uint64_t
 // Two kernels, so that each path gets its own register budget and code footprint (the
 // four-lane path keeps four blocks in flight and unrolls its loop four times; inside one
 // kernel that slowed the one-lane path down by a third).  Both are launched when the choice
-// is left to the device; the one whose mode is not taken returns at once.
+// launched; the one whose mode is not taken returns at once.
 __global__ void __launch_bounds__(ROOT4_WG)
-lthash_root1_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
-                    uint64_t *h0_out, int mode)
+lthash_root1_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n, uint64_t *h0_out)
 {
-    if (mode == 0 && four_lane_mode(offsets, n)) return;
+    if (four_lane_mode(offsets, n)) return;
     root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT4_WG + threadIdx.x);
 }
 
@@ -351,8 +350,8 @@ lthash_root4_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t of
 // length, so it issues no instructions for quads that finished long ago (in the given order
 // a wave lives as long as the longest of its sixteen records: twice the instructions), and
 // consecutive waves, which the dispatcher deals out over the SIMDs, carry the long chains
-// first, one per SIMD, before the next tier follows.  Launched only when the device chooses
-// the path (fewer than four records per lane of the chip, so under 2^20 records); returns at once when the batch takes the one-lane path.
+// first, one per SIMD, before the next tier follows.  Returns at once when the batch takes the
+// one-lane path.
 constexpr int SORT_WG = 1024;
 constexpr uint32_t SORT_BINS = 4096;
 
@@ -780,21 +779,18 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
     rc = scratch_get(s, R_LT_PART, n_part * LANE_WORDS * 4, &part);
     if (rc) return rc;
     if (n) {
-        // With at least four records per lane of the chip the launch is throughput-bound whatever
-        // the lengths are, and one lane per record does the least total work; below that the
-        // kernel decides from the mean record length.
-        const bool full = n >= (uint64_t)cu_count() * 256 * 4;
+        // Both root kernels are launched; the device takes one path (see four_lane_mode).  The
+        // four-lane path is kept for any number of long records: in length order it sustains
+        // 1.7 TB/s, while one lane per record, which issues fewer instructions, has chains three
+        // times as long and reaches that rate only with millions of records.
+        void *order;
+        if ((rc = scratch_get(s, R_LT_ORDER, 4 * n, &order))) return rc;
+        hipLaunchKernelGGL(lthash_order_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(order));
         hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT4_WG)), dim3(ROOT4_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, static_cast<uint64_t *>(h0));
+        hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
                            static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
-                           static_cast<uint64_t *>(h0), full ? 1 : 0);
-        if (!full) {
-            void *order;
-            if ((rc = scratch_get(s, R_LT_ORDER, 4 * n, &order))) return rc;
-            hipLaunchKernelGGL(lthash_order_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(order));
-            hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
-                               static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
-                               static_cast<const uint32_t *>(order), static_cast<uint64_t *>(h0));
-        }
+                           static_cast<const uint32_t *>(order), static_cast<uint64_t *>(h0));
         SENTRY_HIP_CHECK(hipGetLastError());
     }
     hipLaunchKernelGGL(lthash_expand_kernel, dim3((uint32_t)grid), dim3(EXP_WG), 0, s,
@@ -877,14 +873,11 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
     hipLaunchKernelGGL(src_scatter_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab,
                        static_cast<uint32_t *>(perm));
     SENTRY_HIP_CHECK(hipGetLastError());
-    const bool full = n >= (uint64_t)cu_count() * 256 * 4;
     hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT4_WG)), dim3(ROOT4_WG), 0, s,
+                       static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n, static_cast<uint64_t *>(h0));
+    hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
-                       static_cast<uint64_t *>(h0), full ? 1 : 0);
-    if (!full)
-        hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
-                           static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
-                           (const uint32_t *)nullptr, static_cast<uint64_t *>(h0));
+                       (const uint32_t *)nullptr, static_cast<uint64_t *>(h0));
     hipLaunchKernelGGL(lthash_expand_units_kernel, dim3((uint32_t)ceil_div(max_units, EXP_WAVES)), dim3(EXP_WG), 0, s,
                        static_cast<const uint64_t *>(h0), static_cast<const uint32_t *>(perm), S, unit, tab,
                        static_cast<uint32_t *>(part));

@@ -170,8 +170,8 @@ def test_four_lane_path_many_records_in_length_order():
     assert (gpu_lthash(data, off, 3) == oracle.lthash(data, off)).all()
 
 
-def test_many_records_take_the_one_lane_path():
-    # at least four records per lane of the chip: one lane per record regardless of lengths
+def test_more_short_records_than_lanes_on_the_chip():
+    # short records, one lane each, several rounds of waves per SIMD
     n = 262_144 + 37
     rng = np.random.default_rng(61)
     lens = rng.integers(0, 48, n).astype(np.uint64)
