@@ -1,10 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the artifact-hashing hot path on one MI355X.
 
-One step = one pass of the whole path over inputs already resident in HBM (the first part fills
-the chip and runs alone; the other two are bound by single serial chains, leave most of the chip
-idle and belong to independent artifacts, so they run side by side on two streams; --serial runs
-all three back to back on one stream):
+One step = one pass of the whole path over inputs already resident in HBM.  The three parts
+belong to independent artifacts; the second and third are bound by single serial chains and
+leave most of the chip idle, so they run on a second stream (one after the other) beside the
+first, which can use every issue slot they leave (--schedule serial runs all three back to back
+on one stream; --schedule pair runs the first alone, then the other two side by side):
   * Merkle root of the 70B-parameter bf16 checkpoint laid out as one byte stream
     (137.95 GB, 64 KiB leaves)                         -> sentry_merkle_root, sentry_verify
   * per-tensor roots + model root of the 7B checkpoint (291 tensors, 13.48 GB,
@@ -14,7 +15,8 @@ all three back to back on one stream):
 `value` = bytes hashed per step / step time (GB = 1e9 bytes).
 
 Beside it, in the same JSON line: `roofline` (the SHA-256 leaf kernel on the 70B stream against
-the integer-ALU peak), `per_config` (the five target configurations and the widened entry
+the integer-ALU peak: as it runs inside the step, sharing the chip with the other two parts, with
+the same kernel timed alone and the whole step's operations over the step time beside it), `per_config` (the five target configurations and the widened entry
 points, each with GB/s and its fractions of the ALU and HBM rooflines), `streaming` (hashing
 while loading from 16 GB of pinned host memory in the shape of configs 5 and 4, against the
 plain copy of the same bytes; PCIe-bound, never part of `value`) and `cpu_baseline` (the
@@ -146,7 +148,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--quick", action="store_true", help="1/64-size inputs (not the reported workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--serial", action="store_true", help="all three parts of the step on one stream, one after the other")
+    ap.add_argument("--schedule", choices=("overlap", "pair", "serial"), default="overlap",
+                    help="overlap: the 70B root on one stream, the other two parts one after the other on a second; "
+                         "pair: the 70B root alone, then the other two side by side; serial: one stream")
     ap.add_argument("--no-extras", action="store_true", help="skip per-config and streaming side measurements")
     ap.add_argument("--merkle-prefix-gib", type=int, default=0,
                     help="hash only the first N GiB of the 70B stream (for counter runs; the workload name says so)")
@@ -228,27 +232,54 @@ def main():
     step_bytes = bytes70 + bytes7 + rec_bytes
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
     # The per-tensor pass over the 7B checkpoint and the lattice hash of the batch are both bound by
-    # single serial chains and leave most of the chip idle, and they are independent artifacts (a model,
-    # a dataset): the step runs them side by side on two streams once the 70B root, which fills the
-    # chip, is done.  --serial puts everything on one stream.
+    # single serial chains and leave most of the chip idle; the 70B root is bound by instruction issue.
+    # They are independent artifacts (two models, a dataset), so the step runs the chain-bound parts
+    # on a second stream while the 70B root fills whatever they leave free.
     side = torch.cuda.Stream()
-    side_stream = stream if args.serial else side.cuda_stream
+    main = torch.cuda.current_stream()
+
+    def part_7b(st):
+        sentry.sentry_merkle_segments(t7_ptrs, t7_lens, LEAF7, seg_roots.data_ptr(), root7.data_ptr(), st)
+
+    def part_batch(st):
+        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), st)
+        sentry.sentry_lthash_combine(running.data_ptr(), lanes.data_ptr(), st)
+
+    def part_70b(st):
+        sentry.sentry_merkle_root(ckpt70.data_ptr(), bytes70, LEAF70, root70.data_ptr(), st)
 
     def step(expected=None, timed=None):
         ev[0].record()
-        sentry.sentry_merkle_root(ckpt70.data_ptr(), bytes70, LEAF70, root70.data_ptr(), stream)
-        ev[1].record()
-        if not args.serial:
-            side.wait_event(ev[1])
-        sentry.sentry_merkle_segments(t7_ptrs, t7_lens, LEAF7, seg_roots.data_ptr(), root7.data_ptr(), stream)
-        ev[2].record()
-        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), side_stream)
-        sentry.sentry_lthash_combine(running.data_ptr(), lanes.data_ptr(), side_stream)
-        if args.serial:
+        if args.schedule == "serial":
+            part_70b(stream)
+            ev[1].record()
+            part_7b(stream)
+            ev[2].record()
+            part_batch(stream)
             ev[3].record()
-        else:
+            spans = ((0, 1), (1, 2), (2, 3))
+        elif args.schedule == "pair":
+            part_70b(stream)
+            ev[1].record()
+            side.wait_event(ev[1])
+            part_7b(stream)
+            ev[2].record()
+            part_batch(side.cuda_stream)
             ev[3].record(side)
-            torch.cuda.current_stream().wait_event(ev[3])
+            main.wait_event(ev[3])
+            spans = ((0, 1), (1, 2), (1, 3))
+        else:
+            # the two chain-bound parts, one after the other, on the side stream; they are queued first
+            # so that their few waves are resident when the 70B root's workgroups fill the rest of the chip
+            side.wait_event(ev[0])
+            part_7b(side.cuda_stream)
+            ev[2].record(side)
+            part_batch(side.cuda_stream)
+            ev[3].record(side)
+            part_70b(stream)
+            ev[1].record()
+            main.wait_event(ev[3])
+            spans = ((0, 1), (0, 2), (2, 3))
         ev[4].record()
         host_root.copy_(root70, non_blocking=True)
         torch.cuda.synchronize()
@@ -256,10 +287,8 @@ def main():
         if expected is not None and sentry.sentry_verify(got, expected) != 0:
             sys.exit("bench.py: root changed between steps")
         if timed is not None:
-            # 70B root alone; 7B pass and batch hash measured from the end of the 70B root (they overlap
-            # unless --serial); all three parts
-            timed.append((ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]),
-                          ev[2 if args.serial else 1].elapsed_time(ev[3]), ev[0].elapsed_time(ev[4])))
+            # per part: from the event it starts after to its own end; then all three parts
+            timed.append(tuple(ev[a].elapsed_time(ev[b]) for a, b in spans) + (ev[0].elapsed_time(ev[4]),))
         return got
 
     def alone(fn, reps=3):
@@ -296,55 +325,71 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = 1e3 * dt / args.steps
     value = step_bytes / (dt / args.steps) / 1e9
-    ms70 = statistics.mean(p[0] for p in parts)
+    ms70_in_step = statistics.mean(p[0] for p in parts)
     ms_gpu_step = statistics.mean(p[3] for p in parts)
-    # the two chain-bound parts on their own (inside the step they run side by side)
-    ms7 = alone(lambda: sentry.sentry_merkle_segments(t7_ptrs, t7_lens, LEAF7, seg_roots.data_ptr(), root7.data_ptr(), stream))
-    mslt = alone(lambda: (sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), stream),
-                          sentry.sentry_lthash_combine(running.data_ptr(), lanes.data_ptr(), stream)))
     ms7_in_step = statistics.mean(p[1] for p in parts)
     mslt_in_step = statistics.mean(p[2] for p in parts)
+    # each part on its own, the chip to itself (--no-extras: the step and nothing else is launched)
+    ms70 = ms7 = mslt = None
+    if not args.no_extras:
+        ms70 = alone(lambda: part_70b(stream))
+        ms7 = alone(lambda: part_7b(stream))
+        mslt = alone(lambda: part_batch(stream))
 
     # ---------------- roofline of the dominant kernel (SHA-256 leaf kernel, 70B stream) ----------------
     n_leaves70 = -(-bytes70 // LEAF70)
     full_leaves = bytes70 // LEAF70
-    # the leaf kernel hashes every leaf and folds each group of 256 leaf digests in LDS
-    groups = -(-n_leaves70 // 256)
+    # the leaf kernel hashes every leaf and folds each group of 64 leaf digests (one wave) in LDS
+    groups = -(-n_leaves70 // 64)
     ops_leaf_kernel = merkle_ops(full_leaves, LEAF70, n_leaves70 - groups)
     if n_leaves70 != full_leaves:
         ops_leaf_kernel += ((bytes70 - full_leaves * LEAF70) // 64) * SHA_BLOCK_OPS + SHA_BLOCK_OPS
-    achieved = ops_leaf_kernel / (ms70 * 1e-3)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath) and not args.quick:
         traffic = json.load(open(tpath)).get("merkle_leaf_kernel_c5_bytes_per_launch")
-    roofline = {"kernel": "merkle_leaf_kernel (SHA-256 leaves + 8 in-LDS tree levels), 70B stream, 64 KiB leaves",
+    # Inside the step the kernel shares the chip with the other two parts (unless --schedule serial or
+    # pair), so its launch takes longer than it does alone while the chip as a whole does more: the
+    # kernel's own figures come first, as it runs in the timed region; beside them the same launch with
+    # the chip to itself, and all the operations of the step over the step's time.
+    achieved = ops_leaf_kernel / (ms70_in_step * 1e-3)
+    ops_step = (sha_tree_ops([bytes70], LEAF70, flat=True) + sha_tree_ops(t7_lens, LEAF7) + lthash_ops(lengths[b0:b1]))
+    roofline = {"kernel": "merkle_leaf_kernel (SHA-256 leaves + 6 in-LDS tree levels), 70B stream, 64 KiB leaves",
                 "bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_OPS / 1e12, "unit": "TOP/s",
                 "frac": achieved / ALU_PEAK_OPS, "traffic": traffic,
-                "ms_per_launch": ms70, "algorithmic_ops_per_launch": ops_leaf_kernel,
+                "ms_per_launch": ms70_in_step, "algorithmic_ops_per_launch": ops_leaf_kernel,
                 "algorithmic_bytes_per_launch": bytes70 + 32 * groups,
-                "hbm_frac": (bytes70 + 32 * groups) / (ms70 * 1e-3) / HBM_PEAK}
+                "hbm_frac": (bytes70 + 32 * groups) / (ms70_in_step * 1e-3) / HBM_PEAK,
+                "shares_the_chip": args.schedule == "overlap",
+                "alone": None if ms70 is None else {"ms_per_launch": ms70, "achieved": ops_leaf_kernel / (ms70 * 1e-3) / 1e12,
+                                                    "frac": ops_leaf_kernel / (ms70 * 1e-3) / ALU_PEAK_OPS},
+                "whole_step": {"algorithmic_ops": ops_step, "ms": ms_gpu_step,
+                               "achieved": ops_step / (ms_gpu_step * 1e-3) / 1e12,
+                               "frac": ops_step / (ms_gpu_step * 1e-3) / ALU_PEAK_OPS}}
 
     # every entry: GB/s hashed, and the fractions of the integer-ALU roofline (algorithmic 32-bit
     # lane-ops / time / 39.3 T) and of the HBM roofline (bytes hashed / time / 8 TB/s)
-    per_config = {
-        "C5_merkle_70b_64KiB_resident": rated({"GB/s": bytes70 / ms70 / 1e6, "ms": ms70, "bytes": bytes70},
-                                              sha_tree_ops([bytes70], LEAF70, flat=True)),
-        "C3_merkle_7b_segments_1MiB": rated({"GB/s": bytes7 / ms7 / 1e6, "ms": ms7, "bytes": bytes7,
-                                             "leaves": sum(max(1, -(-l // LEAF7)) for l in t7_lens)},
-                                            sha_tree_ops(t7_lens, LEAF7)),
-        "C4_lthash_one_8GB_batch_resident": rated({"GB/s": rec_bytes / mslt / 1e6, "ms": mslt, "bytes": rec_bytes,
-                                                   "samples/s": n_rec / (mslt * 1e-3), "records": n_rec,
-                                                   "longest_record": int(lengths[b0:b1].max())},
-                                                  lthash_ops(lengths[b0:b1])),
-    }
-    # the chain floors of the two chain-bound parts of the step: a full 1 MiB leaf and its tensor's tree
-    # levels; the longest record of the batch
-    max_leaves7 = max(-(-l // LEAF7) for l in t7_lens)
-    chain_bound(per_config["C3_merkle_7b_segments_1MiB"],
-                (LEAF7 // 64 + 1) * SHA_CONSUMER_INSTRS + (tree_levels(max_leaves7) + tree_levels(len(t7_lens))) * SHA_NODE_INSTRS)
-    chain_bound(per_config["C4_lthash_one_8GB_batch_resident"],
-                -(-int(lengths[b0:b1].max()) // 128) * B2_FOUR_LANE_INSTRS)
+    per_config = {}
+    if not args.no_extras:
+        per_config = {
+            "C5_merkle_70b_64KiB_resident": rated({"GB/s": bytes70 / ms70 / 1e6, "ms": ms70, "bytes": bytes70},
+                                                  sha_tree_ops([bytes70], LEAF70, flat=True)),
+            "C3_merkle_7b_segments_1MiB": rated({"GB/s": bytes7 / ms7 / 1e6, "ms": ms7, "bytes": bytes7,
+                                                 "leaves": sum(max(1, -(-l // LEAF7)) for l in t7_lens)},
+                                                sha_tree_ops(t7_lens, LEAF7)),
+            "C4_lthash_one_8GB_batch_resident": rated({"GB/s": rec_bytes / mslt / 1e6, "ms": mslt, "bytes": rec_bytes,
+                                                       "samples/s": n_rec / (mslt * 1e-3), "records": n_rec,
+                                                       "longest_record": int(lengths[b0:b1].max())},
+                                                      lthash_ops(lengths[b0:b1])),
+        }
+        # the chain floors of the two chain-bound parts of the step: a full 1 MiB leaf and its tensor's tree
+        # levels; the longest record of the batch
+        max_leaves7 = max(-(-l // LEAF7) for l in t7_lens)
+        chain_bound(per_config["C3_merkle_7b_segments_1MiB"],
+                    (LEAF7 // 64 + 1) * SHA_CONSUMER_INSTRS + (tree_levels(max_leaves7) + tree_levels(len(t7_lens))) * SHA_NODE_INSTRS)
+        chain_bound(per_config["C4_lthash_one_8GB_batch_resident"],
+                    -(-int(lengths[b0:b1].max()) // 128) * B2_FOUR_LANE_INSTRS)
+
 
     def timed_call(fn, reps):
         """Median time of one call in ms.  Short calls (reps >= 30) are timed in three series and the
@@ -504,9 +549,11 @@ def main():
                    "per-tensor roots and model root of the 7B checkpoint (config 3, 1 MiB leaves) + lattice hash of "
                    "one 8 GB batch of log-normal records folded into the running sum (config 4 shape)",
                    "bytes_per_step": step_bytes, "records_per_step": n_rec,
-                   "schedule": ("one stream, parts back to back" if args.serial else
-                                "70B root, then the 7B per-tensor pass and the batch hash side by side on two streams"),
-                   "step_parts_ms": {"merkle_70b": ms70, "merkle_7b_in_step": ms7_in_step,
+                   "schedule": {"serial": "one stream, parts back to back",
+                                "pair": "70B root, then the 7B per-tensor pass and the batch hash side by side on two streams",
+                                "overlap": "70B root on one stream; beside it, on a second stream, the 7B per-tensor pass, "
+                                           "then the batch hash"}[args.schedule],
+                   "step_parts_ms": {"merkle_70b_in_step": ms70_in_step, "merkle_7b_in_step": ms7_in_step,
                                      "lthash_batch_in_step": mslt_in_step, "all_on_gpu": ms_gpu_step}},
         "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config, "streaming": streaming,
         "root_70b": expected.hex(),

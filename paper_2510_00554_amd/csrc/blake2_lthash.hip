@@ -352,7 +352,7 @@ lthash_root4_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t of
 // consecutive waves, which the dispatcher deals out over the SIMDs, carry the long chains
 // first, one per SIMD, before the next tier follows.  Returns at once when the batch takes the
 // one-lane path.
-constexpr int SORT_WG = 1024;
+constexpr int SORT_WG = 512;
 constexpr uint32_t SORT_BINS = 4096;
 
 __device__ __forceinline__ uint32_t length_bin(uint64_t len)   // 0 = longest
@@ -384,7 +384,7 @@ lthash_order_kernel(const uint64_t *offsets, uint64_t n, uint32_t *order)
             if (b[k] < SORT_BINS) atomicAdd(&bin[b[k]], 1u);
     }
     __syncthreads();
-    // exclusive scan: thread t owns bins 4t .. 4t+3; prefix inside each wave by shuffles, then
+    // exclusive scan: thread t owns PER consecutive bins; prefix inside each wave by shuffles, then
     // the totals of the waves before it
     constexpr uint32_t PER = SORT_BINS / SORT_WG;
     uint32_t c[PER], sum = 0;

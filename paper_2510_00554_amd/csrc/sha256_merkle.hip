@@ -19,6 +19,7 @@ namespace {
 constexpr int LEAF_WG = 256;          // lanes = leaves per workgroup of the leaf kernel ...
 constexpr int LEAF_WG_SMALL = 64;     // ... and when there are too few leaves to fill the chip
 constexpr uint64_t SMALL_LAUNCH_WAVES = 2048;   // two waves per SIMD on 256 CUs x 4 SIMDs
+constexpr uint64_t LONG_LEAF_BYTES = 32768;     // leaves this long: single-wave workgroups whatever the launch size
 constexpr uint64_t SPLIT_LAUNCH_WAVES = 512;    // groups of 64 leaves the two-wave split kernel takes: two per CU
 constexpr uint64_t SPLIT_SINGLE_GROUPS = 256;   // up to one group per CU: one pair per workgroup
 constexpr int RED_WG = 256;           // lanes per workgroup of the reduce kernel
@@ -273,10 +274,19 @@ __device__ __forceinline__ void wg_tree_fold(uint32_t (&lds)[2][8][WG], uint32_t
 
 // Block hashing kernel.  FUSE: fold the workgroup's leaves in LDS and store one node per
 // workgroup at out + 32*blockIdx; otherwise store every leaf digest at out + 32*leaf.
-// WG = leaves per workgroup: 256, or 64 (one wave per workgroup) for launches with few leaves.
-// A lone wave on a SIMD issues faster than two that share it, so a launch that cannot give
-// every SIMD two waves is cut into single-wave workgroups, which the dispatcher spreads over
-// all SIMDs of the chip.
+// WG = leaves per workgroup: 256, or 64 (one wave per workgroup).  A lone wave on a SIMD issues
+// faster than two that share it, so a launch that cannot give every SIMD two waves is cut into
+// single-wave workgroups, which the dispatcher spreads over all SIMDs of the chip.  Long leaves
+// get single-wave workgroups as well: a workgroup then lives for milliseconds, and when other
+// kernels share the chip a single wave fits any free wave slot, where a workgroup of four
+// waves needs one on every SIMD of a CU at once (70B stream beside two chain-bound launches:
+// 103.8 -> 99.4 ms); with the chip to itself the launch takes the same time either way, and
+// with short leaves the deeper fold of 256 digests in LDS is worth 2-3 %.
+__host__ inline bool single_wave_groups(uint64_t waves, uint64_t leaf_bytes)
+{
+    return waves <= SMALL_LAUNCH_WAVES || leaf_bytes >= LONG_LEAF_BYTES;
+}
+
 template <int WG, bool FUSE, bool SEGMENTED>
 __global__ void __launch_bounds__(WG)
 merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const SegDesc *segs,
@@ -608,7 +618,9 @@ int check_leaf_args(const char *fn, const void *buf, size_t len, size_t leaf_byt
                    "%s: leaf_bytes must be a positive multiple of 64 (got %zu)", fn, leaf_bytes);
     SENTRY_REQUIRE(buf != nullptr || len == 0, "%s: NULL buffer with len %zu", fn, len);
     SENTRY_REQUIRE((reinterpret_cast<uintptr_t>(buf) & 15) == 0, "%s: buffer %p is not 16-byte aligned", fn, buf);
-    SENTRY_REQUIRE(ceil_div(leaf_count(len, leaf_bytes), LEAF_WG) <= MAX_GRID, "%s: too many leaves", fn);
+    const uint64_t n_leaves = leaf_count(len, leaf_bytes);
+    SENTRY_REQUIRE(ceil_div(n_leaves, single_wave_groups(ceil_div(n_leaves, 64), leaf_bytes) ? LEAF_WG_SMALL : LEAF_WG) <= MAX_GRID,
+                   "%s: too many leaves", fn);
     return SENTRY_OK;
 }
 
@@ -658,7 +670,7 @@ int merkle_leaves_into(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
     if (ceil_div(n, 64) <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF)
         launch_split<false, false>((uint32_t)ceil_div(n, SPLIT_LEAVES), s, static_cast<const uint8_t *>(dev_buf),
                                    (uint64_t)len, n, nullptr, nullptr, (uint64_t)leaf_bytes, dst);
-    else if (ceil_div(n, 64) <= SMALL_LAUNCH_WAVES)
+    else if (single_wave_groups(ceil_div(n, 64), leaf_bytes))
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, false, false>), dim3((uint32_t)ceil_div(n, LEAF_WG_SMALL)),
                            dim3(LEAF_WG_SMALL), 0, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n,
                            (const SegDesc *)nullptr, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
@@ -687,7 +699,7 @@ int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
     if (rc) return rc;
     SENTRY_REQUIRE(out_digest != nullptr, "sentry_merkle_root: NULL out_digest");
     const uint64_t n = leaf_count(len, leaf_bytes);
-    const bool small = ceil_div(n, 64) <= SMALL_LAUNCH_WAVES;
+    const bool small = single_wave_groups(ceil_div(n, 64), leaf_bytes);
     const uint64_t g = ceil_div(n, small ? LEAF_WG_SMALL : LEAF_WG);
     uint8_t *dst = out_digest;
     if (g > 1) {
@@ -756,7 +768,7 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
     std::vector<uint64_t> m(n_seg);   // nodes per segment after the current stage
     uint64_t waves = 0;
     for (size_t t = 0; t < n_seg; t++) waves += ceil_div(leaf_count(lens[t], leaf_bytes), 64);
-    const bool small = waves <= SMALL_LAUNCH_WAVES;
+    const bool small = single_wave_groups(waves, leaf_bytes);
     const uint64_t wg0 = small ? LEAF_WG_SMALL : LEAF_WG;
     {
         std::vector<Group> g0;
@@ -879,7 +891,7 @@ int sentry_merkle_inplace(const void *const *dev_ptrs, const size_t *lens, size_
 
     // the lookup table of section 4.2.1: one row per workgroup (tensor, first block, blocks,
     // position of the first digest in the flat digest array)
-    const bool small = waves <= SMALL_LAUNCH_WAVES;
+    const bool small = single_wave_groups(waves, leaf_bytes);
     const bool split = small && waves <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF;
     const uint64_t wg0 = small ? LEAF_WG_SMALL : LEAF_WG;
     std::vector<Group> g0;
