@@ -28,7 +28,31 @@ constexpr int RED_IN = 2 * RED_WG;    // nodes folded by one reduce workgroup
 struct SegDesc {
     const uint8_t *base;
     uint64_t len;
+    uint64_t first_leaf;   // leaves of all segments before this one (used by the packed leaf stage)
 };
+
+// Packed leaf stage: lane L of the launch takes leaf L of the concatenated leaf list of all
+// segments, whatever segment it belongs to, instead of every segment starting a workgroup of
+// its own.  With few leaves per segment that halves the waves of a launch (291 tensors of a 7B
+// checkpoint in 1 MiB leaves: 394 groups of at most 64 leaves become 202 full ones).  The
+// segment is found by bisection over first_leaf (the last segment whose first_leaf is <= L,
+// which skips segments without leaves).
+struct PackedLeaf {
+    const uint8_t *p;
+    uint64_t len;
+};
+__device__ __forceinline__ PackedLeaf find_packed_leaf(const SegDesc *segs, uint32_t n_seg, uint64_t leaf, uint64_t leaf_bytes)
+{
+    uint32_t lo = 0, hi = n_seg;
+    while (hi - lo > 1) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (segs[mid].first_leaf <= leaf) lo = mid; else hi = mid;
+    }
+    const SegDesc sd = segs[lo];
+    const uint64_t start = (leaf - sd.first_leaf) * leaf_bytes;
+    const uint64_t left = sd.len - start;                // 0 only for an empty segment's single leaf
+    return PackedLeaf{sd.base + start, left < leaf_bytes ? left : leaf_bytes};
+}
 
 // One workgroup's share of a stage: `count` consecutive items starting at `first`
 // (leaf index inside segment `seg` for the leaf kernel, node index in the input
@@ -287,12 +311,24 @@ __host__ inline bool single_wave_groups(uint64_t waves, uint64_t leaf_bytes)
     return waves <= SMALL_LAUNCH_WAVES || leaf_bytes >= LONG_LEAF_BYTES;
 }
 
-template <int WG, bool FUSE, bool SEGMENTED>
+// PACKED (with SEGMENTED, without FUSE): nleaves0 = leaves of all segments, n_seg = segments;
+// digest L goes to out + 32 L.
+template <int WG, bool FUSE, bool SEGMENTED, bool PACKED = false>
 __global__ void __launch_bounds__(WG)
-merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const SegDesc *segs,
+merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const SegDesc *segs, uint32_t n_seg,
                    const Group *groups, uint64_t leaf_bytes, uint8_t *out)
 {
     const uint32_t g = blockIdx.x, tid = threadIdx.x;
+    if (PACKED) {
+        static_assert(!PACKED || (SEGMENTED && !FUSE), "the packed leaf stage writes leaf digests");
+        const uint64_t leaf = (uint64_t)g * WG + tid;
+        if (leaf >= nleaves0) return;
+        const PackedLeaf pl = find_packed_leaf(segs, n_seg, leaf, leaf_bytes);
+        uint32_t st[8] = SENTRY_H0;
+        hash_leaf(st, pl.p, pl.len);
+        store_digest(out + 32 * leaf, st);
+        return;
+    }
     const uint8_t *base;
     uint64_t seglen, first, out_at;
     uint32_t count;
@@ -415,11 +451,12 @@ __device__ __forceinline__ void sha256_rounds_from_lds(uint32_t (&st)[8], const 
 // All barriers are workgroup-wide, so both pairs run the trip count of the longer group.
 // PAIRS = 1 (128 lanes) is used while there is at most one group per CU: two busy SIMDs per
 // CU run a little faster than four.
-template <int PAIRS, bool FUSE, bool SEGMENTED>
+template <int PAIRS, bool FUSE, bool SEGMENTED, bool PACKED = false>
 __global__ void __launch_bounds__(SPLIT_PAIR_LANES * PAIRS)
 merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, uint32_t n_groups,
-                         const SegDesc *segs, const Group *groups, uint64_t leaf_bytes, uint8_t *out)
+                         const SegDesc *segs, uint32_t n_seg, const Group *groups, uint64_t leaf_bytes, uint8_t *out)
 {
+    static_assert(!PACKED || (SEGMENTED && !FUSE), "the packed leaf stage writes leaf digests");
     __shared__ __attribute__((aligned(16))) uint32_t sched[PAIRS][2 * SPLIT_SLOT_WORDS];
     __shared__ uint32_t lds[PAIRS][2][8][SPLIT_LEAVES];
     __shared__ unsigned long long trip_share[2 * PAIRS];
@@ -431,32 +468,45 @@ merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
     uint64_t seglen = 0, first = 0, out_at = 0;
     uint32_t count = 0;
     if (g < n_groups) {
-        if (SEGMENTED) {
-            const Group gr = groups[g];
-            const SegDesc sd = segs[gr.seg];
-            base = sd.base; seglen = sd.len; first = gr.first; count = gr.count; out_at = gr.out;
-        } else {
+        if (PACKED || !SEGMENTED) {
             base = base0; seglen = len0; first = (uint64_t)g * SPLIT_LEAVES;
             const uint64_t rem = nleaves0 - first;
             count = rem < (uint64_t)SPLIT_LEAVES ? (uint32_t)rem : (uint32_t)SPLIT_LEAVES;
             out_at = FUSE ? (uint64_t)g : first;
+        } else {
+            const Group gr = groups[g];
+            const SegDesc sd = segs[gr.seg];
+            base = sd.base; seglen = sd.len; first = gr.first; count = gr.count; out_at = gr.out;
         }
     }
     const bool have = lane < count;
     uint64_t llen = 0;
     const uint8_t *p = base;
     if (have) {
-        const uint64_t start = (first + lane) * leaf_bytes;
-        const uint64_t left = seglen - start;
-        llen = left < leaf_bytes ? left : leaf_bytes;
-        p = base + start;
+        if (PACKED) {
+            const PackedLeaf pl = find_packed_leaf(segs, n_seg, first + lane, leaf_bytes);
+            p = pl.p; llen = pl.len;
+        } else {
+            const uint64_t start = (first + lane) * leaf_bytes;
+            const uint64_t left = seglen - start;
+            llen = left < leaf_bytes ? left : leaf_bytes;
+            p = base + start;
+        }
     }
     const uint64_t nblk = llen >> 6;
     const uint32_t r = (uint32_t)(llen & 63);
     const uint64_t total = have ? nblk + 1 + (r >= 56 ? 1 : 0) : 0;
-    // lane 0 holds the first leaf of its group, which no other leaf of the group exceeds; the
-    // larger of the two groups' block counts is the trip count of all four waves
-    if (lane == 0) trip_share[wave] = total;
+    // the longest leaf of the group (lane 0 holds it unless the group is packed from several
+    // segments); the larger of the two groups' block counts is the trip count of all four waves
+    uint64_t longest = total;
+    if (PACKED) {
+#pragma unroll
+        for (int d = 32; d; d >>= 1) {
+            const uint64_t o = __shfl_xor(longest, d, 64);
+            longest = o > longest ? o : longest;
+        }
+    }
+    if (lane == 0) trip_share[wave] = longest;
     __syncthreads();
     uint64_t trips = trip_share[0];
     if (PAIRS == 2 && trip_share[2] > trips) trips = trip_share[2];
@@ -591,16 +641,25 @@ merkle_reduce_kernel(const uint8_t *in, uint64_t n0, const Group *groups, uint8_
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 // the two-wave split kernel over n_groups groups of 64 leaves
-template <bool FUSE, bool SEGMENTED>
+template <bool FUSE, bool SEGMENTED, bool PACKED = false>
 void launch_split(uint32_t n_groups, hipStream_t s, const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
-                  const SegDesc *segs, const Group *groups, uint64_t leaf_bytes, uint8_t *out)
+                  const SegDesc *segs, uint32_t n_seg, const Group *groups, uint64_t leaf_bytes, uint8_t *out)
 {
     if (n_groups <= SPLIT_SINGLE_GROUPS)
-        hipLaunchKernelGGL((merkle_leaf_split_kernel<1, FUSE, SEGMENTED>), dim3(n_groups), dim3(SPLIT_PAIR_LANES), 0, s,
-                           base0, len0, nleaves0, n_groups, segs, groups, leaf_bytes, out);
+        hipLaunchKernelGGL((merkle_leaf_split_kernel<1, FUSE, SEGMENTED, PACKED>), dim3(n_groups), dim3(SPLIT_PAIR_LANES), 0, s,
+                           base0, len0, nleaves0, n_groups, segs, n_seg, groups, leaf_bytes, out);
     else
-        hipLaunchKernelGGL((merkle_leaf_split_kernel<2, FUSE, SEGMENTED>), dim3((n_groups + 1) / 2),
-                           dim3(2 * SPLIT_PAIR_LANES), 0, s, base0, len0, nleaves0, n_groups, segs, groups, leaf_bytes, out);
+        hipLaunchKernelGGL((merkle_leaf_split_kernel<2, FUSE, SEGMENTED, PACKED>), dim3((n_groups + 1) / 2),
+                           dim3(2 * SPLIT_PAIR_LANES), 0, s, base0, len0, nleaves0, n_groups, segs, n_seg, groups,
+                           leaf_bytes, out);
+}
+
+// The packed leaf stage pays where per-segment groups would leave at least a ninth of the
+// waves' lanes without a leaf (waves = groups of 64 when every segment starts its own).
+inline bool packed_leaf_stage(uint64_t waves, uint64_t total_leaves)
+{
+    const uint64_t full = ceil_div(total_leaves, 64);
+    return waves - full >= ceil_div(full, 8);
 }
 
 inline uint64_t leaf_count(uint64_t len, uint64_t leaf_bytes)
@@ -669,15 +728,15 @@ int merkle_leaves_into(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
     const uint64_t n = leaf_count(len, leaf_bytes);
     if (ceil_div(n, 64) <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF)
         launch_split<false, false>((uint32_t)ceil_div(n, SPLIT_LEAVES), s, static_cast<const uint8_t *>(dev_buf),
-                                   (uint64_t)len, n, nullptr, nullptr, (uint64_t)leaf_bytes, dst);
+                                   (uint64_t)len, n, nullptr, 0, nullptr, (uint64_t)leaf_bytes, dst);
     else if (single_wave_groups(ceil_div(n, 64), leaf_bytes))
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, false, false>), dim3((uint32_t)ceil_div(n, LEAF_WG_SMALL)),
                            dim3(LEAF_WG_SMALL), 0, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n,
-                           (const SegDesc *)nullptr, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+                           (const SegDesc *)nullptr, 0u, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
     else
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, false, false>), dim3((uint32_t)ceil_div(n, LEAF_WG)),
                            dim3(LEAF_WG), 0, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n,
-                           (const SegDesc *)nullptr, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+                           (const SegDesc *)nullptr, 0u, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
     SENTRY_HIP_CHECK(hipGetLastError());
     return SENTRY_OK;
 }
@@ -709,16 +768,16 @@ int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
         dst = static_cast<uint8_t *>(a);
     }
     if (small && ceil_div(n, 64) <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF)
-        launch_split<true, false>((uint32_t)g, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, nullptr,
+        launch_split<true, false>((uint32_t)g, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, nullptr, 0,
                                   nullptr, (uint64_t)leaf_bytes, dst);
     else if (small)
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, false>), dim3((uint32_t)g), dim3(LEAF_WG_SMALL), 0, s,
                            static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
-                           (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+                           0u, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
     else
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, true, false>), dim3((uint32_t)g), dim3(LEAF_WG), 0, s,
                            static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
-                           (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+                           0u, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
     SENTRY_HIP_CHECK(hipGetLastError());
     if (g > 1) return reduce_nodes(dst, g, out_digest, s);
     return SENTRY_OK;
@@ -761,25 +820,40 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
     }
     SENTRY_REQUIRE(n_seg <= 0xffffffffull, "sentry_merkle_segments: too many segments");
 
-    // Stage tables, built on the host: stage 0 splits every segment's leaves into groups of
-    // 256; each later stage splits every segment's nodes into groups of 512, until every
-    // segment is down to one node.
+    // Stage tables, built on the host: stage 0 splits every segment's leaves into groups of 256
+    // (or 64), each folded to one node by its workgroup; or, where that would leave many groups
+    // part-filled, stage 0 is packed (one leaf per lane across segments, leaf digests written out).
+    // Each later stage splits every segment's nodes into groups of 512, until every segment is
+    // down to one node.
     std::vector<std::vector<Group>> stages;
     std::vector<uint64_t> m(n_seg);   // nodes per segment after the current stage
-    uint64_t waves = 0;
-    for (size_t t = 0; t < n_seg; t++) waves += ceil_div(leaf_count(lens[t], leaf_bytes), 64);
+    uint64_t waves = 0, total_leaves = 0;
+    for (size_t t = 0; t < n_seg; t++) {
+        const uint64_t nl = leaf_count(lens[t], leaf_bytes);
+        waves += ceil_div(nl, 64);
+        total_leaves += nl;
+    }
+    const bool packed = packed_leaf_stage(waves, total_leaves);
+    if (packed) waves = ceil_div(total_leaves, 64);
     const bool small = single_wave_groups(waves, leaf_bytes);
     const uint64_t wg0 = small ? LEAF_WG_SMALL : LEAF_WG;
     {
         std::vector<Group> g0;
         for (size_t t = 0; t < n_seg; t++) {
             const uint64_t nl = leaf_count(lens[t], leaf_bytes);
+            if (packed) {
+                m[t] = nl;
+                continue;
+            }
             for (uint64_t f = 0; f < nl; f += wg0)
                 g0.push_back(Group{f, (uint64_t)g0.size(), (uint32_t)(nl - f < wg0 ? nl - f : wg0), (uint32_t)t});
             m[t] = ceil_div(nl, wg0);
         }
         stages.push_back(std::move(g0));
     }
+    const uint64_t grid0 = packed ? ceil_div(total_leaves, wg0) : stages[0].size();
+    const uint64_t nodes0 = packed ? total_leaves : stages[0].size();   // digests stage 0 writes
+    SENTRY_REQUIRE(grid0 <= MAX_GRID, "sentry_merkle_segments: too many leaves");
     for (;;) {
         bool more = false;
         for (size_t t = 0; t < n_seg; t++) more |= m[t] > 1;
@@ -806,7 +880,13 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
     rc = sentry::scratch_get(s, sentry::R_TABLES, table_bytes, &dev_tab);
     if (rc) return rc;
     SegDesc *hseg = static_cast<SegDesc *>(host_tab);
-    for (size_t t = 0; t < n_seg; t++) hseg[t] = SegDesc{static_cast<const uint8_t *>(dev_ptrs[t]), lens[t]};
+    {
+        uint64_t leaf0 = 0;
+        for (size_t t = 0; t < n_seg; t++) {
+            hseg[t] = SegDesc{static_cast<const uint8_t *>(dev_ptrs[t]), lens[t], leaf0};
+            leaf0 += leaf_count(lens[t], leaf_bytes);
+        }
+    }
     std::vector<const Group *> dev_groups;
     {
         char *hp = static_cast<char *>(host_tab) + n_seg * sizeof(SegDesc);
@@ -833,7 +913,7 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
     uint8_t *bufs[2] = {nullptr, nullptr};
     if (stages.size() > 1) {
         void *a, *b;
-        rc = sentry::scratch_get(s, sentry::R_NODES_A, 32 * stages[0].size(), &a);
+        rc = sentry::scratch_get(s, sentry::R_NODES_A, 32 * nodes0, &a);
         if (rc) return rc;
         rc = sentry::scratch_get(s, sentry::R_NODES_B, 32 * stages[1].size(), &b);
         if (rc) return rc;
@@ -844,17 +924,30 @@ int sentry_merkle_segments(const void *const *dev_ptrs, const size_t *lens, size
     const uint8_t *src = nullptr;
     for (size_t k = 0; k < stages.size(); k++) {
         uint8_t *dst = (k + 1 == stages.size()) ? roots : bufs[k & 1];
-        const uint32_t grid = (uint32_t)stages[k].size();
-        if (k == 0) {
-            if (small && waves <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF)
-                launch_split<true, true>(grid, s, nullptr, 0, 0, dseg, dev_groups[0], (uint64_t)leaf_bytes, dst);
+        const uint32_t grid = (uint32_t)(k == 0 ? grid0 : stages[k].size());
+        const bool split = small && waves <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF;
+        if (k == 0 && packed) {
+            if (split)
+                launch_split<false, true, true>((uint32_t)waves, s, nullptr, 0, total_leaves, dseg, (uint32_t)n_seg, nullptr,
+                                                (uint64_t)leaf_bytes, dst);
+            else if (small)
+                hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, false, true, true>), dim3(grid), dim3(LEAF_WG_SMALL), 0, s,
+                                   (const uint8_t *)nullptr, (uint64_t)0, total_leaves, dseg, (uint32_t)n_seg,
+                                   (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+            else
+                hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, false, true, true>), dim3(grid), dim3(LEAF_WG), 0, s,
+                                   (const uint8_t *)nullptr, (uint64_t)0, total_leaves, dseg, (uint32_t)n_seg,
+                                   (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
+        } else if (k == 0) {
+            if (split)
+                launch_split<true, true>(grid, s, nullptr, 0, 0, dseg, (uint32_t)n_seg, dev_groups[0], (uint64_t)leaf_bytes, dst);
             else if (small)
                 hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, true>), dim3(grid), dim3(LEAF_WG_SMALL), 0, s,
-                                   (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dev_groups[0],
+                                   (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, (uint32_t)n_seg, dev_groups[0],
                                    (uint64_t)leaf_bytes, dst);
             else
                 hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, true, true>), dim3(grid), dim3(LEAF_WG), 0, s,
-                                   (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dev_groups[0],
+                                   (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, (uint32_t)n_seg, dev_groups[0],
                                    (uint64_t)leaf_bytes, dst);
         } else {
             hipLaunchKernelGGL(merkle_reduce_kernel<true>, dim3(grid), dim3(RED_WG), 0, s, src, (uint64_t)0,
@@ -890,19 +983,25 @@ int sentry_merkle_inplace(const void *const *dev_ptrs, const size_t *lens, size_
     if (total == 0) return sentry_merkle_root(nullptr, 0, leaf_bytes, out_root, stream);   // the empty leaf
 
     // the lookup table of section 4.2.1: one row per workgroup (tensor, first block, blocks,
-    // position of the first digest in the flat digest array)
+    // position of the first digest in the flat digest array); or, where many workgroups would be
+    // part-filled, one row per tensor (its first block's index) and a bisection per lane
+    const bool packed = packed_leaf_stage(waves, total);
+    if (packed) waves = ceil_div(total, 64);
     const bool small = single_wave_groups(waves, leaf_bytes);
     const bool split = small && waves <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF;
     const uint64_t wg0 = small ? LEAF_WG_SMALL : LEAF_WG;
     std::vector<Group> g0;
-    uint64_t leaf0 = 0;
-    for (size_t t = 0; t < n_seg; t++) {
-        const uint64_t nl = ceil_div(lens[t], leaf_bytes);
-        for (uint64_t f = 0; f < nl; f += wg0)
-            g0.push_back(Group{f, leaf0 + f, (uint32_t)(nl - f < wg0 ? nl - f : wg0), (uint32_t)t});
-        leaf0 += nl;
+    if (!packed) {
+        uint64_t leaf0 = 0;
+        for (size_t t = 0; t < n_seg; t++) {
+            const uint64_t nl = ceil_div(lens[t], leaf_bytes);
+            for (uint64_t f = 0; f < nl; f += wg0)
+                g0.push_back(Group{f, leaf0 + f, (uint32_t)(nl - f < wg0 ? nl - f : wg0), (uint32_t)t});
+            leaf0 += nl;
+        }
     }
-    SENTRY_REQUIRE(g0.size() <= MAX_GRID, "sentry_merkle_inplace: too many leaves");
+    const uint64_t grid0 = packed ? ceil_div(total, wg0) : g0.size();
+    SENTRY_REQUIRE(grid0 <= MAX_GRID, "sentry_merkle_inplace: too many leaves");
     const size_t table_bytes = n_seg * sizeof(SegDesc) + g0.size() * sizeof(Group);
     void *host_tab, *dev_tab, *digests;
     int rc = sentry::table_staging_get(s, table_bytes, &host_tab);
@@ -910,22 +1009,43 @@ int sentry_merkle_inplace(const void *const *dev_ptrs, const size_t *lens, size_
     if ((rc = sentry::scratch_get(s, sentry::R_TABLES, table_bytes, &dev_tab))) return rc;
     if ((rc = sentry::scratch_get(s, sentry::R_NODES_A, 32 * total, &digests))) return rc;
     SegDesc *hseg = static_cast<SegDesc *>(host_tab);
-    for (size_t t = 0; t < n_seg; t++) hseg[t] = SegDesc{static_cast<const uint8_t *>(dev_ptrs[t]), lens[t]};
-    std::memcpy(static_cast<char *>(host_tab) + n_seg * sizeof(SegDesc), g0.data(), g0.size() * sizeof(Group));
+    {
+        uint64_t leaf0 = 0;
+        for (size_t t = 0; t < n_seg; t++) {
+            hseg[t] = SegDesc{static_cast<const uint8_t *>(dev_ptrs[t]), lens[t], leaf0};
+            leaf0 += ceil_div(lens[t], leaf_bytes);
+        }
+    }
+    if (!g0.empty())
+        std::memcpy(static_cast<char *>(host_tab) + n_seg * sizeof(SegDesc), g0.data(), g0.size() * sizeof(Group));
     SENTRY_HIP_CHECK(hipMemcpyAsync(dev_tab, host_tab, table_bytes, hipMemcpyHostToDevice, s));
     if ((rc = sentry::table_staging_mark(s))) return rc;
     const SegDesc *dseg = static_cast<const SegDesc *>(dev_tab);
     const Group *dgroups = reinterpret_cast<const Group *>(static_cast<char *>(dev_tab) + n_seg * sizeof(SegDesc));
-    const uint32_t grid = (uint32_t)g0.size();
+    const uint32_t grid = (uint32_t)grid0;
     uint8_t *dst = static_cast<uint8_t *>(digests);
-    if (split)
-        launch_split<false, true>(grid, s, nullptr, 0, 0, dseg, dgroups, (uint64_t)leaf_bytes, dst);
+    if (packed) {
+        if (split)
+            launch_split<false, true, true>((uint32_t)waves, s, nullptr, 0, total, dseg, (uint32_t)n_seg, nullptr,
+                                            (uint64_t)leaf_bytes, dst);
+        else if (small)
+            hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, false, true, true>), dim3(grid), dim3(LEAF_WG_SMALL), 0, s,
+                               (const uint8_t *)nullptr, (uint64_t)0, total, dseg, (uint32_t)n_seg, (const Group *)nullptr,
+                               (uint64_t)leaf_bytes, dst);
+        else
+            hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, false, true, true>), dim3(grid), dim3(LEAF_WG), 0, s,
+                               (const uint8_t *)nullptr, (uint64_t)0, total, dseg, (uint32_t)n_seg, (const Group *)nullptr,
+                               (uint64_t)leaf_bytes, dst);
+    } else if (split)
+        launch_split<false, true>(grid, s, nullptr, 0, 0, dseg, (uint32_t)n_seg, dgroups, (uint64_t)leaf_bytes, dst);
     else if (small)
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, false, true>), dim3(grid), dim3(LEAF_WG_SMALL), 0, s,
-                           (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dgroups, (uint64_t)leaf_bytes, dst);
+                           (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, (uint32_t)n_seg, dgroups,
+                           (uint64_t)leaf_bytes, dst);
     else
         hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, false, true>), dim3(grid), dim3(LEAF_WG), 0, s,
-                           (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, dgroups, (uint64_t)leaf_bytes, dst);
+                           (const uint8_t *)nullptr, (uint64_t)0, (uint64_t)0, dseg, (uint32_t)n_seg, dgroups,
+                           (uint64_t)leaf_bytes, dst);
     SENTRY_HIP_CHECK(hipGetLastError());
     return reduce_nodes(dst, total, out_root, s);
 }

@@ -211,6 +211,25 @@ def test_inplace_flat_tree():
     assert bytes(out.cpu().numpy()) == oracle.merkle_root(np.concatenate(segs), 4096)
 
 
+@pytest.mark.parametrize("n_seg,leaf,max_leaves", [
+    (300, 1024, 5),      # under 512 waves of 1 KiB leaves: the two-wave kernel, one pair per workgroup and two
+    (700, 512, 60),
+    (3000, 64, 70),      # single-wave workgroups of the plain kernel
+    (9000, 64, 40),      # 256-lane workgroups
+])
+def test_packed_leaf_stage_many_small_tensors(n_seg, leaf, max_leaves):
+    # few leaves per tensor: the leaf stage packs leaves of different tensors into one wave and
+    # finds each lane's tensor by bisection; empty tensors, short tails, runs of one-leaf tensors
+    rng = np.random.default_rng(n_seg)
+    sizes = (rng.integers(0, max_leaves, n_seg) * leaf + rng.integers(0, leaf, n_seg) * (rng.random(n_seg) < 0.5)).astype(np.int64)
+    sizes[rng.integers(0, n_seg, n_seg // 20)] = 0
+    sizes[5:25] = leaf - 3                     # one short leaf each
+    sizes[-1] = 0                              # the list ends with an empty tensor
+    sizes = [int(x) for x in sizes]
+    segments_case(sizes, leaf)
+    inplace_case(sizes, leaf)
+
+
 def test_inplace_tiny_checkpoint_layout():
     lay = wl.layout_tiny()
     tensors = wl.checkpoint_bytes_np(lay)
