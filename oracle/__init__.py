@@ -75,6 +75,10 @@ def lib():
         L.oracle_lthash_one.restype = None
         L.oracle_lthash.argtypes = [vp, vp, sz, vp]
         L.oracle_lthash.restype = None
+        L.oracle_lthash_digests.argtypes = [vp, vp, sz, vp]
+        L.oracle_lthash_digests.restype = None
+        L.oracle_lthash_sum.argtypes = [vp, sz, vp]
+        L.oracle_lthash_sum.restype = None
         L.oracle_lthash_sources.argtypes = [vp, vp, vp, sz, sz, vp]
         L.oracle_lthash_sources.restype = None
         L.oracle_lthash_model.argtypes = [vp, vp, sz, sz, vp, vp]
@@ -275,6 +279,26 @@ def lthash(records, offsets):
     if n:
         assert int(off[-1]) <= a.size
     lib().oracle_lthash(_ptr(a), _ptr(off), n, out.ctypes.data)
+    return out
+
+
+def lthash_digests(records, offsets):
+    """The digest of every record: n x 1024 uint16."""
+    a = _u8(records)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    n = max(off.size - 1, 0)
+    out = np.full((n, LANES), 0xAAAA, np.uint16)
+    if n:
+        assert int(off[-1]) <= a.size
+        lib().oracle_lthash_digests(_ptr(a), _ptr(off), n, out.ctypes.data)
+    return out
+
+
+def lthash_sum(digests):
+    """Lane-wise sum mod 2^16 of n digests (n x 1024 uint16) that are already computed."""
+    d = np.ascontiguousarray(digests, dtype=np.uint16).reshape(-1, LANES)
+    out = np.full(LANES, 0xAAAA, np.uint16)
+    lib().oracle_lthash_sum(d.ctypes.data if d.size else None, d.shape[0], out.ctypes.data)
     return out
 
 

@@ -596,6 +596,22 @@ void oracle_lthash(const uint8_t *records, const uint64_t *offsets, size_t n,
     }
 }
 
+/* The digests of Eq. (1) one by one: row i of out = the 1024 lanes of record i. */
+void oracle_lthash_digests(const uint8_t *records, const uint64_t *offsets, size_t n, uint16_t *out)
+{
+    for (size_t i = 0; i < n; i++)
+        oracle_lthash_one(records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), out + i * ORACLE_LANES);
+}
+
+/* Eq. (1) over digests that are already there: acc[l] = sum over rows of digests[row][l] mod 2^16 */
+void oracle_lthash_sum(const uint16_t *digests, size_t n, uint16_t acc[ORACLE_LANES])
+{
+    memset(acc, 0, ORACLE_LANES * sizeof(uint16_t));
+    for (size_t i = 0; i < n; i++)
+        for (int l = 0; l < ORACLE_LANES; l++)
+            acc[l] = (uint16_t)((acc[l] + digests[i * ORACLE_LANES + l]) & 0xFFFFu);
+}
+
 /* Mixed-source batch (section 4.1.2, section 4.3): record i belongs to data source src[i];
  * every source keeps a running sum, acc[s] += sum of the digests of its records in this
  * batch.  acc holds n_sources rows of 1024 lanes and is updated in place.  Records whose

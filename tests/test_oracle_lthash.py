@@ -166,3 +166,35 @@ def test_model_hash_of_slices_adds_up():
     l_c, t_c = oracle.lthash_model(segs[1:], B, first_index=6)
     assert (oracle.lanes_add(l_a[0], l_b[0]) == layer[0]).all() and (l_c == layer[1:]).all()
     assert (oracle.lanes_add(oracle.lanes_add(t_a, t_b), t_c) == total).all()
+
+
+def test_digests_one_by_one_and_their_sum():
+    # row i of the digest matrix is the XOF output of record i (H0 pinned by hashlib above), in
+    # the order given; summing the rows is Eq. (1) again
+    rng = random.Random(29)
+    recs = [rng.randbytes(rng.randrange(0, 500)) for _ in range(37)] + [b"", b"same", b"same"]
+    data, off = pack(recs)
+    d = oracle.lthash_digests(data, off)
+    assert d.shape == (40, 1024) and d.dtype == np.uint16
+    for i, r in enumerate(recs):
+        assert (d[i] == lanes_via_xof(r)).all(), i
+    assert (d[38] == d[39]).all() and (d[37] != d[38]).any()
+    assert (oracle.lthash_sum(d) == oracle.lthash(data, off)).all()
+    assert oracle.lthash_digests(b"", np.zeros(1, np.uint64)).shape == (0, 1024)
+
+
+def test_sum_of_given_digests_in_python_integers():
+    rng = np.random.default_rng(30)
+    for n in (0, 1, 2, 255, 1000):
+        d = rng.integers(0, 65536, size=(n, 1024)).astype(np.uint16)
+        want = [sum(int(x) for x in d[:, l]) % 65536 for l in range(1024)]
+        assert oracle.lthash_sum(d).tolist() == want, n
+    # carries stay inside their lane; 65,536 equal rows cancel; row order does not matter
+    d = np.zeros((3, 1024), np.uint16)
+    d[:, 0::2] = 0xFFFF
+    s = oracle.lthash_sum(d)
+    assert (s[0::2] == 0xFFFD).all() and (s[1::2] == 0).all()
+    row = rng.integers(0, 65536, size=1024).astype(np.uint16)
+    assert not oracle.lthash_sum(np.tile(row, (65536, 1))).any()
+    d = rng.integers(0, 65536, size=(50, 1024)).astype(np.uint16)
+    assert (oracle.lthash_sum(d) == oracle.lthash_sum(d[::-1].copy())).all()
