@@ -466,6 +466,20 @@ def main():
             per_config["F1_lthash_50k_images_%d_sources" % n_src] = rated(
                 {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
                 lthash_ops([3072] * 50_000))
+        # the lane sum taken alone, over digests that are already in memory (any 2048 bytes are a valid
+        # digest row: the first 2 GiB of the 70B stream stand in for 2^20 of them): bound by HBM
+        n_rows = min(1 << 20, bytes70 // 2048)
+        ms = timed_call(lambda: sentry.sentry_lthash_sum(ckpt70.data_ptr(), n_rows, lanes.data_ptr(), stream), 20)
+        per_config["L3_lane_sum_alone_%d_digests" % n_rows] = rated(
+            {"GB/s": 2048 * n_rows / ms / 1e6, "ms": ms, "bytes": 2048 * n_rows, "samples/s": n_rows / (ms * 1e-3),
+             "bound": "hbm"}, 512 * n_rows)
+        # and the digests of the 50,000 images written out one by one (2048 bytes per sample)
+        rows = torch.empty(50_000 * 2048, dtype=torch.uint8, device=dev)
+        ms = timed_call(lambda: sentry.sentry_lthash_digests(img.data_ptr(), d_ioff.data_ptr(), 50_000, rows.data_ptr(), stream), 50)
+        per_config["L2_digests_50k_images"] = rated(
+            {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
+            lthash_ops([3072] * 50_000), hbm_bytes=img.numel() + rows.numel())
+        del rows
         # host-to-device streaming in the shape of configs 5 and 4: a pinned host buffer of 16 GB;
         # Merkle while loading it in 1 GiB chunks, and the lattice hash of two 8 GB batches (the
         # resident batch twice), each against the plain copy of the same bytes

@@ -239,6 +239,25 @@ SENTRY_API int sentry_lthash_sources(const void *dev_records, const uint64_t *de
                                      const uint32_t *dev_source_ids, size_t n, size_t n_sources,
                                      uint16_t *acc_lanes, void *stream);
 
+/*
+ * The digests of Eq. (1) one by one, and Eq. (1) over digests that are already
+ * in memory.  A provider that keeps every sample's digest can take a sample out
+ * of a dataset hash, or build the hash of any subset, without the samples' bytes
+ * (section 2.2: add and remove by lattice addition).
+ *   sentry_lthash_digests: out_digests[i][l] = h(record_i)[l], i < n, l < 1024
+ *   sentry_lthash_sum:     out_lanes[l] = sum over i < n of dev_digests[i][l] mod 2^16
+ * so that sum(digests(records)) == sentry_lthash(records).
+ * dev_records, dev_offsets, n   as for sentry_lthash.
+ * out_digests  device, n rows of 1024 uint16 (2048 bytes each, 16-byte aligned),
+ *              overwritten; nothing is written for n == 0.
+ * dev_digests  device, n rows of 1024 uint16, 16-byte aligned; not modified.  May
+ *              be NULL when n == 0, which gives all-zero lanes.
+ * out_lanes    device-accessible, 1024 uint16 (2-byte aligned), overwritten.
+ */
+SENTRY_API int sentry_lthash_digests(const void *dev_records, const uint64_t *dev_offsets, size_t n,
+                                     uint16_t *out_digests, void *stream);
+SENTRY_API int sentry_lthash_sum(const uint16_t *dev_digests, size_t n, uint16_t *out_lanes, void *stream);
+
 /* acc[l] = (acc[l] + x[l]) mod 2^16 and (acc[l] - x[l]) mod 2^16 (section 2.2:
  * LtHash(S1)+LtHash(S2) = LtHash(S1 u S2), LtHash(S1 u S2)-LtHash(S1) =
  * LtHash(S2); the lattice addition of section 4.2.2).  Both device-accessible,

@@ -44,6 +44,8 @@ PROTOTYPES = {
     "sentry_merkle_root_h2d": (_int, [_vp, _sz, _sz, _sz, _vp, _vp]),
     "sentry_verify": (_int, [ctypes.c_char_p, ctypes.c_char_p]),
     "sentry_lthash": (_int, [_vp, _vp, _sz, _vp, _vp]),
+    "sentry_lthash_digests": (_int, [_vp, _vp, _sz, _vp, _vp]),
+    "sentry_lthash_sum": (_int, [_vp, _sz, _vp, _vp]),
     "sentry_lthash_sources": (_int, [_vp, _vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_lthash_model": (_int, [_vp, _vp, _sz, _sz, _vp, _vp, _vp]),
     "sentry_lthash_combine": (_int, [_vp, _vp, _vp]),
@@ -179,6 +181,14 @@ def sentry_verify(root, expected):
 
 def sentry_lthash(dev_records, dev_offsets, n, out_lanes, stream=0):
     return _check(load().sentry_lthash(dev_records, dev_offsets, n, out_lanes, stream))
+
+
+def sentry_lthash_digests(dev_records, dev_offsets, n, out_digests, stream=0):
+    return _check(load().sentry_lthash_digests(dev_records, dev_offsets, n, out_digests, stream))
+
+
+def sentry_lthash_sum(dev_digests, n, out_lanes, stream=0):
+    return _check(load().sentry_lthash_sum(dev_digests, n, out_lanes, stream))
 
 
 def sentry_lthash_sources(dev_records, dev_offsets, dev_source_ids, n, n_sources, acc_lanes, stream=0):

@@ -476,18 +476,116 @@ lthash_expand_kernel(const uint64_t *h0, uint64_t n, uint32_t *part_out)
     }
 }
 
-// out[c] = sum over partial sums p of part[p][c] (packed uint16 pairs), c < 512.
-// Each workgroup owns FOLD_COLS columns; its lanes split the rows eight ways.
+// The digests themselves, one row of 2048 bytes per record, for callers that keep them (a
+// sample can later be taken out of a sum without its bytes: sentry_lthash_remove).  Same lane
+// assignment as lthash_expand_kernel; each lane writes the 64 bytes of its block.
+__global__ void __launch_bounds__(EXP_WG)
+lthash_digests_kernel(const uint64_t *h0, uint64_t n, uint4 *out)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t j = lane & 31;
+    const uint64_t total_waves = (uint64_t)gridDim.x * EXP_WAVES;
+    for (uint64_t slot = (uint64_t)blockIdx.x * EXP_WAVES + wave; 2 * slot < n; slot += total_waves) {
+        const uint64_t rec = 2 * slot + (lane >> 5);
+        if (rec >= n) continue;
+        uint64_t m[16];
+#pragma unroll
+        for (int k = 0; k < 8; k++) { m[k] = h0[8 * rec + k]; m[8 + k] = 0; }
+        uint64_t h[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) h[k] = b2_iv(k);
+        h[0] ^= EXP_P0;
+        h[1] ^= EXP_P1_HI | (uint64_t)j;
+        h[2] ^= EXP_P2;
+        blake2b_compress(h, m, 64, true);
+        uint4 *dst = out + rec * (XOF_BYTES / 16) + 4 * j;
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+            dst[k] = make_uint4((uint32_t)h[2 * k], (uint32_t)(h[2 * k] >> 32), (uint32_t)h[2 * k + 1], (uint32_t)(h[2 * k + 1] >> 32));
+    }
+}
+
+// Eq. (1) over digests that are in memory: part_out[workgroup] = lane-wise sum of the rows the
+// workgroup takes.  2048 bytes are read per row and four packed adds are done per 16 of them,
+// so this kernel is bound by HBM: lane t of a half-workgroup owns 16-byte column t & 127, the
+// two halves take alternate rows, every lane has eight rows in flight, and a workgroup takes
+// a contiguous run of rows (2^20 rows: 7.0 TB/s; with the rows dealt out round-robin over the
+// workgroups 5.6 TB/s, with plain instead of streaming loads 5.3 TB/s).
+constexpr int SUM_WG = 256;
+constexpr int SUM_AHEAD = 8;
+constexpr int SUM_COLS = XOF_BYTES / 16;   // 128 columns of 16 bytes
+constexpr int SUM_HALVES = SUM_WG / SUM_COLS;
+
+typedef uint32_t sum_u32x4 __attribute__((ext_vector_type(4)));
+
+// streaming load: every digest byte is read once
+__device__ __forceinline__ uint4 load_once(const uint4 *p)
+{
+    const sum_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const sum_u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ void add_packed(u16x2 (&acc)[4], const uint4 v)
+{
+    acc[0] += u16x2{(unsigned short)v.x, (unsigned short)(v.x >> 16)};
+    acc[1] += u16x2{(unsigned short)v.y, (unsigned short)(v.y >> 16)};
+    acc[2] += u16x2{(unsigned short)v.z, (unsigned short)(v.z >> 16)};
+    acc[3] += u16x2{(unsigned short)v.w, (unsigned short)(v.w >> 16)};
+}
+
+__global__ void __launch_bounds__(SUM_WG)
+lthash_sum_kernel(const uint4 *rows, uint64_t n, uint4 *part_out)
+{
+    const uint32_t c = threadIdx.x % SUM_COLS, half = threadIdx.x / SUM_COLS;
+    const uint64_t per = (n + gridDim.x - 1) / gridDim.x;
+    const uint64_t lo = per * blockIdx.x < n ? per * blockIdx.x : n;
+    const uint64_t hi = lo + per < n ? lo + per : n;
+    u16x2 acc[4] = {u16x2{0, 0}, u16x2{0, 0}, u16x2{0, 0}, u16x2{0, 0}};
+    uint64_t r = lo + half;
+    for (; r + (SUM_AHEAD - 1) * SUM_HALVES < hi; r += SUM_AHEAD * SUM_HALVES) {
+        uint4 v[SUM_AHEAD];
+#pragma unroll
+        for (int k = 0; k < SUM_AHEAD; k++) v[k] = load_once(&rows[(r + k * SUM_HALVES) * SUM_COLS + c]);
+#pragma unroll
+        for (int k = 0; k < SUM_AHEAD; k++) add_packed(acc, v[k]);
+    }
+    for (; r < hi; r += SUM_HALVES) add_packed(acc, load_once(&rows[r * SUM_COLS + c]));
+    __shared__ uint4 lds[SUM_COLS];
+    const uint4 mine = make_uint4((uint32_t)acc[0].x | ((uint32_t)acc[0].y << 16), (uint32_t)acc[1].x | ((uint32_t)acc[1].y << 16),
+                                  (uint32_t)acc[2].x | ((uint32_t)acc[2].y << 16), (uint32_t)acc[3].x | ((uint32_t)acc[3].y << 16));
+    if (half == 1) lds[c] = mine;
+    __syncthreads();
+    if (half == 0) {
+        add_packed(acc, lds[c]);
+        part_out[(uint64_t)blockIdx.x * SUM_COLS + c] =
+            make_uint4((uint32_t)acc[0].x | ((uint32_t)acc[0].y << 16), (uint32_t)acc[1].x | ((uint32_t)acc[1].y << 16),
+                       (uint32_t)acc[2].x | ((uint32_t)acc[2].y << 16), (uint32_t)acc[3].x | ((uint32_t)acc[3].y << 16));
+    }
+}
+
+// out[g][c] = sum over the partial sums p of group g of part[p][c] (packed uint16 pairs), c < 512;
+// group g = rows [g * rows_per_group, (g + 1) * rows_per_group), g = blockIdx.y.  Each workgroup
+// owns FOLD_COLS columns; its lanes split the rows eight ways and keep eight loads in flight
+// (one at a time, 513 rows took 21 us: a load's latency per eight rows).
 __global__ void __launch_bounds__(FOLD_WG)
-lthash_fold_kernel(const uint32_t *part, uint32_t n_part, uint16_t *out)
+lthash_fold_kernel(const uint32_t *part, uint32_t n_part, uint32_t rows_per_group, uint16_t *out)
 {
     constexpr int ROWS = FOLD_WG / FOLD_COLS;
+    constexpr int AHEAD = 8;
     const uint32_t col = blockIdx.x * FOLD_COLS + (threadIdx.x % FOLD_COLS);
     const uint32_t row0 = threadIdx.x / FOLD_COLS;
+    const uint64_t first = (uint64_t)blockIdx.y * rows_per_group;
+    const uint64_t end = first + rows_per_group < n_part ? first + rows_per_group : n_part;
     u16x2 s = u16x2{0, 0};
-    for (uint32_t p = row0; p < n_part; p += ROWS) {
-        const uint32_t x = part[(uint64_t)p * LANE_WORDS + col];
-        s += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+    for (uint64_t p = first + row0; p < end; p += ROWS * AHEAD) {
+        uint32_t x[AHEAD];
+#pragma unroll
+        for (int k = 0; k < AHEAD; k++) {
+            const uint64_t q = p + (uint64_t)k * ROWS;
+            x[k] = q < end ? part[q * LANE_WORDS + col] : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < AHEAD; k++) s += u16x2{(unsigned short)x[k], (unsigned short)(x[k] >> 16)};
     }
     __shared__ uint32_t lds[ROWS][FOLD_COLS];
     lds[row0][threadIdx.x % FOLD_COLS] = (uint32_t)s.x | ((uint32_t)s.y << 16);
@@ -499,8 +597,9 @@ lthash_fold_kernel(const uint32_t *part, uint32_t n_part, uint16_t *out)
             const uint32_t x = lds[r][threadIdx.x];
             t += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
         }
-        out[2 * col] = t.x;          // 16-bit stores: out needs no more than 2-byte alignment
-        out[2 * col + 1] = t.y;
+        uint16_t *o = out + (uint64_t)blockIdx.y * SENTRY_LANES;
+        o[2 * col] = t.x;            // 16-bit stores: out needs no more than 2-byte alignment
+        o[2 * col + 1] = t.y;
     }
 }
 
@@ -753,10 +852,55 @@ int lthash_presize(uint64_t max_records, hipStream_t s)
 }
 
 // out = lane-wise sum of n_rows rows of 1024 lanes (rows are 2048 bytes apart, 4-byte aligned).
+// Many rows are folded in two steps, groups of FOLD_GROUP rows first; `spare` then holds the group
+// sums (ceil(n_rows / FOLD_GROUP) rows) and is not used otherwise.
+constexpr uint32_t FOLD_GROUP = 64;
+constexpr uint32_t FOLD_DIRECT = 640;     // up to here one launch (ten trips of 64 rows per workgroup)
+
+static uint32_t fold_spare_rows(uint64_t n_rows) { return n_rows > FOLD_DIRECT ? (uint32_t)ceil_div(n_rows, FOLD_GROUP) : 0; }
+
+static int fold_rows(const uint32_t *rows, uint32_t n_rows, uint32_t *spare, uint16_t *out, hipStream_t s)
+{
+    if (n_rows > FOLD_DIRECT) {
+        const uint32_t groups = fold_spare_rows(n_rows);
+        hipLaunchKernelGGL(lthash_fold_kernel, dim3(LANE_WORDS / FOLD_COLS, groups), dim3(FOLD_WG), 0, s, rows, n_rows,
+                           FOLD_GROUP, reinterpret_cast<uint16_t *>(spare));
+        rows = spare;
+        n_rows = groups;
+    }
+    hipLaunchKernelGGL(lthash_fold_kernel, dim3(LANE_WORDS / FOLD_COLS, 1), dim3(FOLD_WG), 0, s, rows, n_rows,
+                       n_rows ? n_rows : 1u, out);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
 int lthash_sum_rows(const uint16_t *rows, uint32_t n_rows, uint16_t *out, hipStream_t s)
 {
-    hipLaunchKernelGGL(lthash_fold_kernel, dim3(LANE_WORDS / FOLD_COLS), dim3(FOLD_WG), 0, s,
-                       reinterpret_cast<const uint32_t *>(rows), n_rows, out);
+    if (n_rows > FOLD_DIRECT) {
+        set_error("lthash_sum_rows: at most %u rows", FOLD_DIRECT);
+        return SENTRY_ERR_INVALID_ARG;
+    }
+    return fold_rows(reinterpret_cast<const uint32_t *>(rows), n_rows, nullptr, out, s);
+}
+
+// Root hashes (64 bytes each) of n records at dev_records (offsets relative to offset_base).
+static int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
+                        uint64_t *h0, hipStream_t s)
+{
+    if (n == 0) return SENTRY_OK;
+    // Both root kernels are launched; the device takes one path (see four_lane_mode).  The
+    // four-lane path is kept for any number of long records: in length order it sustains
+    // 1.7 TB/s, while one lane per record, which issues fewer instructions, has chains three
+    // times as long and reaches that rate only with millions of records.
+    void *order;
+    int rc = scratch_get(s, R_LT_ORDER, 4 * n, &order);
+    if (rc) return rc;
+    hipLaunchKernelGGL(lthash_order_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(order));
+    hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT4_WG)), dim3(ROOT4_WG), 0, s,
+                       static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, h0);
+    hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
+                       static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
+                       static_cast<const uint32_t *>(order), h0);
     SENTRY_HIP_CHECK(hipGetLastError());
     return SENTRY_OK;
 }
@@ -778,31 +922,14 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
     const uint64_t n_part = grid + (accumulate ? 1 : 0);
     rc = scratch_get(s, R_LT_PART, n_part * LANE_WORDS * 4, &part);
     if (rc) return rc;
-    if (n) {
-        // Both root kernels are launched; the device takes one path (see four_lane_mode).  The
-        // four-lane path is kept for any number of long records: in length order it sustains
-        // 1.7 TB/s, while one lane per record, which issues fewer instructions, has chains three
-        // times as long and reaches that rate only with millions of records.
-        void *order;
-        if ((rc = scratch_get(s, R_LT_ORDER, 4 * n, &order))) return rc;
-        hipLaunchKernelGGL(lthash_order_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(order));
-        hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT4_WG)), dim3(ROOT4_WG), 0, s,
-                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, static_cast<uint64_t *>(h0));
-        hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
-                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
-                           static_cast<const uint32_t *>(order), static_cast<uint64_t *>(h0));
-        SENTRY_HIP_CHECK(hipGetLastError());
-    }
+    if ((rc = lthash_roots(dev_records, dev_offsets, offset_base, n, static_cast<uint64_t *>(h0), s))) return rc;
     hipLaunchKernelGGL(lthash_expand_kernel, dim3((uint32_t)grid), dim3(EXP_WG), 0, s,
                        static_cast<const uint64_t *>(h0), n, static_cast<uint32_t *>(part));
     SENTRY_HIP_CHECK(hipGetLastError());
     if (accumulate)   // the running sum joins as one more partial row
         SENTRY_HIP_CHECK(hipMemcpyAsync(static_cast<uint32_t *>(part) + grid * LANE_WORDS, out, XOF_BYTES,
                                         hipMemcpyDefault, s));
-    hipLaunchKernelGGL(lthash_fold_kernel, dim3(LANE_WORDS / FOLD_COLS), dim3(FOLD_WG), 0, s,
-                       static_cast<const uint32_t *>(part), (uint32_t)n_part, out);
-    SENTRY_HIP_CHECK(hipGetLastError());
-    return SENTRY_OK;
+    return fold_rows(static_cast<const uint32_t *>(part), (uint32_t)n_part, nullptr, out, s);   // n_part <= 513
 }
 
 }  // namespace sentry
@@ -819,6 +946,53 @@ int sentry_lthash(const void *dev_records, const uint64_t *dev_offsets, size_t n
     // a launch holds fewer than 2^32 work-items in all
     SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash: too many records");
     return sentry::lthash_into(dev_records, dev_offsets, 0, n, out_lanes, false, static_cast<hipStream_t>(stream));
+}
+
+int sentry_lthash_digests(const void *dev_records, const uint64_t *dev_offsets, size_t n, uint16_t *out_digests,
+                          void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n == 0) return SENTRY_OK;
+    SENTRY_REQUIRE(out_digests != nullptr && (reinterpret_cast<uintptr_t>(out_digests) & 15) == 0,
+                   "sentry_lthash_digests: out_digests must be non-NULL and 16-byte aligned");
+    SENTRY_REQUIRE(dev_offsets != nullptr && (reinterpret_cast<uintptr_t>(dev_offsets) & 7) == 0,
+                   "sentry_lthash_digests: dev_offsets must be non-NULL and 8-byte aligned");
+    SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash_digests: too many records");
+    void *h0;
+    int rc = sentry::scratch_get(s, sentry::R_LT_H0, 64 * n, &h0);
+    if (rc) return rc;
+    if ((rc = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s))) return rc;
+    uint64_t grid = ceil_div(ceil_div(n, 2), EXP_WAVES);
+    const uint64_t cap = (uint64_t)cu_count() * 8;
+    if (grid > cap) grid = cap;
+    hipLaunchKernelGGL(lthash_digests_kernel, dim3((uint32_t)grid), dim3(EXP_WG), 0, s, static_cast<const uint64_t *>(h0),
+                       (uint64_t)n, reinterpret_cast<uint4 *>(out_digests));
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
+int sentry_lthash_sum(const uint16_t *dev_digests, size_t n, uint16_t *out_lanes, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(out_lanes != nullptr && (reinterpret_cast<uintptr_t>(out_lanes) & 1) == 0,
+                   "sentry_lthash_sum: out_lanes must be non-NULL and 2-byte aligned");
+    SENTRY_REQUIRE(n == 0 || (dev_digests != nullptr && (reinterpret_cast<uintptr_t>(dev_digests) & 15) == 0),
+                   "sentry_lthash_sum: dev_digests must be non-NULL and 16-byte aligned when n > 0");
+    // enough workgroups to keep HBM busy (four per CU), each with at least one full trip of rows
+    uint64_t grid = ceil_div(n, SUM_HALVES * SUM_AHEAD);
+    const uint64_t cap = (uint64_t)cu_count() * 4;
+    if (grid > cap) grid = cap;
+    if (grid == 0) grid = 1;
+    void *part;
+    int rc = sentry::scratch_get(s, sentry::R_LT_PART, (grid + sentry::fold_spare_rows(grid)) * LANE_WORDS * 4, &part);
+    if (rc) return rc;
+    if (n)
+        hipLaunchKernelGGL(lthash_sum_kernel, dim3((uint32_t)grid), dim3(SUM_WG), 0, s,
+                           reinterpret_cast<const uint4 *>(dev_digests), (uint64_t)n, static_cast<uint4 *>(part));
+    return sentry::fold_rows(static_cast<const uint32_t *>(part), (uint32_t)(n ? grid : 0),
+                             static_cast<uint32_t *>(part) + grid * LANE_WORDS, out_lanes, s);
 }
 
 static int addsub(const char *fn, uint16_t *acc, const uint16_t *x, void *stream, bool sub)

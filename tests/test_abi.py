@@ -67,6 +67,11 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_lthash(0x1000, 0, 5, 0x2000),                  # NULL offsets with n > 0
     lambda: sentry.sentry_lthash(0x1000, 0x3004, 5, 0x2000),             # misaligned offsets
     lambda: sentry.sentry_lthash(0x1000, 0x3000, 5, 0),                  # NULL lanes
+    lambda: sentry.sentry_lthash_digests(0x1000, 0x3000, 5, 0x2004),     # misaligned digest rows
+    lambda: sentry.sentry_lthash_digests(0x1000, 0, 5, 0x2000),          # NULL offsets
+    lambda: sentry.sentry_lthash_sum(0, 5, 0x2000),                      # NULL digests with n > 0
+    lambda: sentry.sentry_lthash_sum(0x1008, 5, 0x2000),                 # misaligned digests
+    lambda: sentry.sentry_lthash_sum(0x1000, 5, 0),                      # NULL lanes
     lambda: sentry.sentry_lthash_sources(0x1000, 0x3000, 0x4000, 5, 0, 0x2000),       # no sources
     lambda: sentry.sentry_lthash_sources(0x1000, 0x3000, 0x4000, 5, 5000, 0x2000),    # too many sources
     lambda: sentry.sentry_lthash_sources(0x1000, 0x3000, 0x4002, 5, 4, 0x2000),       # misaligned ids
