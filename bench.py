@@ -312,6 +312,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # what the other two parts give when each runs with the chip to itself, to hold the overlapped
+    # steps against
+    part_7b(stream)
+    part_batch(stream)
+    torch.cuda.synchronize()
+    alone_out = [t.clone() for t in (root7, seg_roots, lanes)]
+
     log("warm-up")
     expected = step()
     for _ in range(max(args.warmup - 1, 0)):
@@ -324,6 +331,9 @@ def main():
         step(expected, parts)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    for t, ref, what in zip((root7, seg_roots, lanes), alone_out, ("model root", "per-tensor roots", "batch lanes")):
+        if not torch.equal(t, ref):
+            sys.exit("bench.py: %s of the overlapped step differ from the same call run alone" % what)
     ms_per_step = 1e3 * dt / args.steps
     value = step_bytes / (dt / args.steps) / 1e9
     ms70_in_step = statistics.mean(p[0] for p in parts)

@@ -173,3 +173,27 @@ def test_h2d_pipeline_with_many_streams_alive():
         sentry.sentry_lthash_h2d(lhost.data_ptr(), off.ctypes.data, 2000, 1 << 25, lanes.data_ptr(), s.cuda_stream)
         torch.cuda.synchronize()
         assert (lanes.cpu().numpy().view(np.uint16) == want_l).all()
+
+
+@pytest.mark.parametrize("schedule", ["overlap", "pair", "serial"])
+def test_bench_quick_run_prints_one_valid_line(schedule):
+    # bench.py at 1/64 size in a process of its own: one JSON line with the fields the contract
+    # names; the run itself checks the overlapped parts against the same calls run alone and the
+    # GPU against the oracle on the CPU-baseline sample
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--quick", "--steps", "2", "--warmup", "1",
+                        "--schedule", schedule], capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [ln for ln in p.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 2 and d["value"] > 0 and d["config"]["workload"].startswith("QUICK")
+    assert d["roofline"]["bound"] == "alu" and 0 < d["roofline"]["frac"] and d["roofline"]["shares_the_chip"] == (schedule == "overlap")
+    assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["cores"] == 1
