@@ -23,6 +23,15 @@
  *     partials, tables), allocated lazily per stream and reused; concurrent
  *     calls on one stream from several host threads are not supported.
  *     sentry_release_scratch() frees it.
+ *   - Graph capture: sentry_merkle_root, sentry_merkle_root_h, sentry_merkle_leaves,
+ *     sentry_merkle_reduce, sentry_lthash, sentry_lthash_digests, sentry_lthash_sum,
+ *     sentry_lthash_combine and sentry_lthash_remove only launch kernels once the
+ *     stream's scratch is large enough, so a caller may capture them into a HIP
+ *     graph after one plain call with the same sizes on the same stream; the graph
+ *     then refers to that stream's scratch, which must not be released, or grown
+ *     by a larger plain call, while the graph is in use.  The entry points that
+ *     take tensor lists or host memory upload tables or run their own pipeline of
+ *     streams and are not meant for capture.
  *   - Digests are the 32 bytes of FIPS 180-4 SHA-256 in their usual byte order.
  *     Lattice digests are SENTRY_LANES uint16 values.
  */

@@ -197,3 +197,48 @@ def test_bench_quick_run_prints_one_valid_line(schedule):
     assert d["n_gpus"] == 1 and d["steps"] == 2 and d["value"] > 0 and d["config"]["workload"].startswith("QUICK")
     assert d["roofline"]["bound"] == "alu" and 0 < d["roofline"]["frac"] and d["roofline"]["shares_the_chip"] == (schedule == "overlap")
     assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["cores"] == 1
+
+
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    # once a stream's scratch has its size (one eager call), the calls only launch kernels, so a
+    # caller may capture them; every replay is checked against the oracle, with the inputs
+    # rewritten, other work of the library and synchronisations between the replays
+    s = torch.cuda.Stream()
+    n_bytes, leaf, n_rec = 4096 * 700 + 100, 4096, 3000
+    buf = torch.zeros(n_bytes, dtype=torch.uint8, device="cuda")
+    data0, off = _records(980, n_rec, 0, 2000)
+    rec = torch.zeros(data0.size, dtype=torch.uint8, device="cuda")
+    d_off = to_dev(off)
+    root = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    lanes = torch.zeros(1024, dtype=torch.int16, device="cuda")
+
+    def calls():
+        sentry.sentry_merkle_root(buf.data_ptr(), n_bytes, leaf, root.data_ptr(), s.cuda_stream)
+        sentry.sentry_lthash(rec.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), s.cuda_stream)
+        sentry.sentry_lthash_combine(lanes.data_ptr(), lanes.data_ptr(), s.cuda_stream)    # lanes doubled
+
+    with torch.cuda.stream(s):
+        calls()
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        calls()
+    other = wl.uniform_bytes(981, 0, 64 * 900)
+    d_other, out_other = to_dev(other), torch.zeros(32, dtype=torch.uint8, device="cuda")
+    for k in range(4):
+        b = wl.uniform_bytes(990 + k, 0, n_bytes)
+        r = wl.uniform_bytes(995 + k, 0, data0.size)
+        buf.copy_(torch.from_numpy(b))
+        rec.copy_(torch.from_numpy(r))
+        root.zero_()
+        lanes.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert bytes(root.cpu().numpy()) == oracle.merkle_root(b, leaf), k
+        one = oracle.lthash(r, off)
+        assert (lanes.cpu().numpy().view(np.uint16) == oracle.lthash_combine(one, one)).all(), k
+        # eager work of the library between the replays, on another stream
+        sentry.sentry_merkle_root(d_other.data_ptr(), other.size, 64, out_other.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(out_other.cpu().numpy()) == oracle.merkle_root(other, 64)
