@@ -37,6 +37,24 @@ def test_leaf_counts_across_group_boundaries(n_leaves):
         assert gpu_root(buf, 64) == oracle.merkle_root(buf, 64), (n_leaves, tail)
 
 
+def test_very_long_leaves():
+    # 16 MiB leaves (262,144 blocks per lane): three full leaves and a short one; one leaf that
+    # is the whole buffer; through the root, the leaf digests and the BLAKE2b tree
+    leaf = 16 << 20
+    buf = wl.uniform_bytes(210, 0, 3 * leaf + 12345)
+    assert gpu_root(buf, leaf) == oracle.merkle_root(buf, leaf)
+    d = to_dev(buf)
+    leaves = torch.zeros(4 * 32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_leaves(d.data_ptr(), buf.size, leaf, leaves.data_ptr())
+    out = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_root_h(sentry.HASH_BLAKE2B, d.data_ptr(), buf.size, leaf, out.data_ptr())
+    torch.cuda.synchronize()
+    assert (leaves.cpu().numpy().reshape(4, 32) == oracle.merkle_leaves(buf, leaf)).all()
+    assert bytes(out.cpu().numpy()) == oracle.merkle_root_h(sentry.HASH_BLAKE2B, buf, leaf)
+    one = buf[:leaf // 2 + 77]
+    assert gpu_root(one, leaf) == oracle.sha256(one)
+
+
 def test_config1_16mib_4k_leaves():
     buf = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20)
     want = oracle.merkle_root(buf, 4096)
