@@ -5,15 +5,17 @@
 // The kernels:
 //   lthash_root1_kernel,  the sequential BLAKE2b-512 root hash H0 of every record (the only
 //   lthash_root4_kernel   serial part), one lane per record or four lanes per record (with
-//                         lthash_order_kernel, which orders the records by length for the
-//                         latter), 64 bytes per record to scratch;
+//                         lthash_order_count/scan/place_kernel, which order the records by
+//                         length for the latter), 64 bytes per record to scratch;
 //   lthash_expand_kernel  one (record, output block) pair per lane: the 32 expansion
 //                         compressions of a record are independent, so they are spread
 //                         over all lanes of the chip; each lane keeps the 16 packed words
 //                         of "its" output block in registers and adds every record's
 //                         block to them (v_pk_add_u16), so the 2048-byte digests never
 //                         exist in memory; per-workgroup partial sums go to scratch;
-//   lthash_fold_kernel    adds the partial sums column-wise into the 1024 lanes.
+//   lthash_fold_kernel    adds the partial sums column-wise into the 1024 lanes;
+//   lthash_digests_kernel, lthash_sum_kernel   the digests written out one by one, and the
+//                         lane sum over digests that are in memory.
 #include "blake2b_device.h"
 #include "sentry_internal.h"
 
@@ -130,6 +132,11 @@ __device__ __forceinline__ void root_one_lane(const uint8_t *records, const uint
 
 constexpr int ROOT4_WG = 64;               // one wave per workgroup, 16 records per wave
 constexpr int ROOT4_RECORDS = ROOT4_WG / 4;
+// One lane per record: workgroups of four waves, which land on the four SIMDs of a CU, one each.
+// With single-wave workgroups the dispatcher now and then put two waves on one SIMD of a CU
+// whose other SIMDs were idle, and a launch with fewer waves than SIMDs (50,000 images) then
+// took 176 us instead of 101 us, in about every second launch.
+constexpr int ROOT1_WG = 256;
 
 __device__ const unsigned char B2_SIGMA_TABLE[10][16] = {
     {0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15}, {14, 10, 4, 8, 9, 15, 13, 6, 1, 12, 0, 2, 11, 7, 5, 3},
@@ -312,27 +319,58 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
     h0_out[8 * rec + 4 + j] = h_hi;
 }
 
-// Root hashes of n records: one lane per record, or four lanes per record.  Which, is chosen
-// on the device from the mean record length, which a kernel can read from the offsets while
-// the host cannot (the offsets are device memory and the call does not wait): records of
-// 16 KiB and more on average make a launch chain-bound, so they get four lanes; short records
-// get one lane, whose start-up is cheaper.  Workgroups are single waves.
+// Root hashes of n records: one lane per record, or four lanes per record, in length order or
+// not.  Which, is chosen on the device from the record lengths, which a kernel can read from
+// the offsets while the host cannot (the offsets are device memory and the call does not wait).
+// One lane per record is the cheaper form for many records of one size (images): every lane of
+// a wave ends together and the start-up per record is small.  Four lanes in length order are
+// for long records (16 KiB and more on average), whose serial chains bound the launch, and for
+// batches of unequal records, where one lane per record makes a wave live as long as the
+// longest of its 64 records and a launch as long as its longest record hashed by a single lane
+// (1 M records, log-normal around 6 KB: 25.5 ms against 8.6 ms).  Unequal means: of 256 records
+// at fixed positions of the batch the longest is at least 4 KiB and at least 1.5 times the mean.
+// Four lanes without the ordering are for batches of few records (up to half the lanes of the
+// chip), which are bound by one record's chain whatever its length: four lanes make it a third
+// as long (10,000 images: 0.075 ms against 0.128 ms).  Every workgroup of every kernel evaluates
+// this for itself (two loads per lane) and gets the same answer.
 constexpr uint64_t FOUR_LANE_MEAN_BYTES = 16384;
+constexpr uint64_t UNEQUAL_MIN_BYTES = 4096;
+constexpr uint64_t FEW_RECORDS = 32768;
+
+__device__ __forceinline__ bool ordered_mode(const uint64_t *offsets, uint64_t n)
+{
+    const uint64_t total = offsets[n] - offsets[0];
+    if (total >= FOUR_LANE_MEAN_BYTES * n) return true;
+    const uint32_t lane = threadIdx.x & 63;
+    uint64_t longest = 0;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const uint64_t i = ((uint64_t)(64 * k + lane) * n) >> 8;     // n < 2^32 (checked by the host)
+        const uint64_t len = offsets[i + 1] - offsets[i];
+        longest = len > longest ? len : longest;
+    }
+#pragma unroll
+    for (int d = 32; d; d >>= 1) {
+        const uint64_t o = __shfl_xor(longest, d, 64);
+        longest = o > longest ? o : longest;
+    }
+    return longest >= UNEQUAL_MIN_BYTES && 2 * longest * n >= 3 * total;
+}
 
 __device__ __forceinline__ bool four_lane_mode(const uint64_t *offsets, uint64_t n)
 {
-    return (offsets[n] - offsets[0]) >= FOUR_LANE_MEAN_BYTES * n;
+    return n <= FEW_RECORDS || ordered_mode(offsets, n);
 }
 
 // Two kernels, so that each path gets its own register budget and code footprint (the
 // four-lane path keeps four blocks in flight and unrolls its loop four times; inside one
 // kernel that slowed the one-lane path down by a third).  Both are launched when the choice
 // launched; the one whose mode is not taken returns at once.
-__global__ void __launch_bounds__(ROOT4_WG)
+__global__ void __launch_bounds__(ROOT1_WG)
 lthash_root1_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n, uint64_t *h0_out)
 {
     if (four_lane_mode(offsets, n)) return;
-    root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT4_WG + threadIdx.x);
+    root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT1_WG + threadIdx.x);
 }
 
 __global__ void __launch_bounds__(ROOT4_WG)
@@ -341,19 +379,24 @@ lthash_root4_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t of
 {
     __shared__ __attribute__((aligned(16))) unsigned char stage[ROOT4_RECORDS * 128];
     if (!four_lane_mode(offsets, n)) return;
-    root_four_lanes(records, offsets, offset_base, n, order, h0_out, (uint64_t)blockIdx.x * ROOT4_RECORDS, stage);
+    root_four_lanes(records, offsets, offset_base, n, ordered_mode(offsets, n) ? order : nullptr, h0_out,
+                    (uint64_t)blockIdx.x * ROOT4_RECORDS, stage);
 }
 
 // Order of the records for the four-lane path: longest first (a counting sort by length in
-// units of 256 bytes, done by one workgroup; the order inside a bin is arbitrary, which the
-// order-invariant sum does not see).  A wave then holds sixteen records of about the same
-// length, so it issues no instructions for quads that finished long ago (in the given order
-// a wave lives as long as the longest of its sixteen records: twice the instructions), and
-// consecutive waves, which the dispatcher deals out over the SIMDs, carry the long chains
-// first, one per SIMD, before the next tier follows.  Returns at once when the batch takes the
-// one-lane path.
-constexpr int SORT_WG = 512;
+// units of 256 bytes; the order inside a bin is arbitrary, which the order-invariant sum does
+// not see).  A wave then holds sixteen records of about the same length, so it issues no
+// instructions for quads that finished long ago (in the given order a wave lives as long as the
+// longest of its sixteen records: twice the instructions), and consecutive waves, which the
+// dispatcher deals out over the SIMDs, carry the long chains first, one per SIMD, before the
+// next tier follows.  Three kernels, as in one pass of a radix sort: every workgroup counts the
+// bins of its run of records; one workgroup turns the counts into the place where each
+// (workgroup, bin) starts; every workgroup puts its records there.  (One workgroup doing all of
+// it took 1.7 ms for a million records.)  All return at once when the batch is not ordered.
+constexpr int SORT_WG = 512;              // eight waves find room on a CU that other kernels fill
 constexpr uint32_t SORT_BINS = 4096;
+constexpr uint32_t SORT_MAX_GROUPS = 64;
+constexpr uint32_t SORT_MIN_RUN = 4096;   // records per workgroup before a second one is worth it
 
 __device__ __forceinline__ uint32_t length_bin(uint64_t len)   // 0 = longest
 {
@@ -361,35 +404,68 @@ __device__ __forceinline__ uint32_t length_bin(uint64_t len)   // 0 = longest
     return SORT_BINS - 1 - (uint32_t)(k < SORT_BINS - 1 ? k : SORT_BINS - 1);
 }
 
-__global__ void __launch_bounds__(SORT_WG)
-lthash_order_kernel(const uint64_t *offsets, uint64_t n, uint32_t *order)
+// the run of records of workgroup g of `groups`
+__device__ __forceinline__ void sort_run(uint64_t n, uint32_t g, uint32_t groups, uint64_t &lo, uint64_t &hi)
 {
-    if (!four_lane_mode(offsets, n)) return;
-    __shared__ uint32_t bin[SORT_BINS];
-    __shared__ uint32_t part[SORT_WG / 64];
-    const uint32_t tid = threadIdx.x;
-    for (uint32_t k = tid; k < SORT_BINS; k += SORT_WG) bin[k] = 0;
-    __syncthreads();
-    // eight records per lane and trip, so that their offsets are in flight together
+    const uint64_t per = (n + groups - 1) / groups;
+    lo = per * g < n ? per * g : n;
+    hi = lo + per < n ? lo + per : n;
+}
+
+// bins of records [lo, hi), eight records per lane and trip so that their offsets are in flight
+// together: f(record, bin) for each
+template <typename F>
+__device__ __forceinline__ void for_each_bin(const uint64_t *offsets, uint64_t lo, uint64_t hi, F f)
+{
     constexpr int BATCH = 8;
-    for (uint64_t i0 = tid; i0 < n; i0 += (uint64_t)BATCH * SORT_WG) {
+    for (uint64_t i0 = lo + threadIdx.x; i0 < hi; i0 += (uint64_t)BATCH * SORT_WG) {
         uint32_t b[BATCH];
 #pragma unroll
         for (int k = 0; k < BATCH; k++) {
             const uint64_t i = i0 + (uint64_t)k * SORT_WG;
-            b[k] = i < n ? length_bin(offsets[i + 1] - offsets[i]) : SORT_BINS;
+            b[k] = i < hi ? length_bin(offsets[i + 1] - offsets[i]) : SORT_BINS;
         }
 #pragma unroll
         for (int k = 0; k < BATCH; k++)
-            if (b[k] < SORT_BINS) atomicAdd(&bin[b[k]], 1u);
+            if (b[k] < SORT_BINS) f(i0 + (uint64_t)k * SORT_WG, b[k]);
     }
+}
+
+// counts[g][bin] = records of workgroup g's run that fall into bin
+__global__ void __launch_bounds__(SORT_WG)
+lthash_order_count_kernel(const uint64_t *offsets, uint64_t n, uint32_t *counts)
+{
+    if (!ordered_mode(offsets, n)) return;
+    __shared__ uint32_t bin[SORT_BINS];
+    for (uint32_t k = threadIdx.x; k < SORT_BINS; k += SORT_WG) bin[k] = 0;
     __syncthreads();
-    // exclusive scan: thread t owns PER consecutive bins; prefix inside each wave by shuffles, then
-    // the totals of the waves before it
+    uint64_t lo, hi;
+    sort_run(n, blockIdx.x, gridDim.x, lo, hi);
+    for_each_bin(offsets, lo, hi, [&](uint64_t, uint32_t b) { atomicAdd(&bin[b], 1u); });
+    __syncthreads();
+    for (uint32_t k = threadIdx.x; k < SORT_BINS; k += SORT_WG) counts[(uint64_t)blockIdx.x * SORT_BINS + k] = bin[k];
+}
+
+// counts[g][bin] <- first place in the order of workgroup g's records of that bin: bins in
+// ascending number (longest records first), inside a bin the workgroups in ascending number.
+// One workgroup; lane t owns PER consecutive bins.
+__global__ void __launch_bounds__(SORT_WG)
+lthash_order_scan_kernel(const uint64_t *offsets, uint64_t n, uint32_t *counts, uint32_t groups)
+{
+    if (!ordered_mode(offsets, n)) return;
     constexpr uint32_t PER = SORT_BINS / SORT_WG;
+    __shared__ uint32_t part[SORT_WG / 64];
+    const uint32_t tid = threadIdx.x;
     uint32_t c[PER], sum = 0;
 #pragma unroll
-    for (uint32_t k = 0; k < PER; k++) { c[k] = bin[PER * tid + k]; sum += c[k]; }
+    for (uint32_t k = 0; k < PER; k++) c[k] = 0;
+    for (uint32_t g = 0; g < groups; g++)
+#pragma unroll
+        for (uint32_t k = 0; k < PER; k++) c[k] += counts[(uint64_t)g * SORT_BINS + PER * tid + k];
+#pragma unroll
+    for (uint32_t k = 0; k < PER; k++) sum += c[k];
+    // exclusive scan of the lanes' sums: prefix inside each wave by shuffles, then the totals
+    // of the waves before it
     uint32_t incl = sum;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -400,20 +476,29 @@ lthash_order_kernel(const uint64_t *offsets, uint64_t n, uint32_t *order)
     __syncthreads();
     uint32_t before = incl - sum;
     for (uint32_t w = 0; w < (tid >> 6); w++) before += part[w];
+    uint32_t at[PER];
 #pragma unroll
-    for (uint32_t k = 0; k < PER; k++) { bin[PER * tid + k] = before; before += c[k]; }
-    __syncthreads();
-    for (uint64_t i0 = tid; i0 < n; i0 += (uint64_t)BATCH * SORT_WG) {
-        uint32_t b[BATCH];
+    for (uint32_t k = 0; k < PER; k++) { at[k] = before; before += c[k]; }
+    for (uint32_t g = 0; g < groups; g++)
 #pragma unroll
-        for (int k = 0; k < BATCH; k++) {
-            const uint64_t i = i0 + (uint64_t)k * SORT_WG;
-            b[k] = i < n ? length_bin(offsets[i + 1] - offsets[i]) : SORT_BINS;
+        for (uint32_t k = 0; k < PER; k++) {
+            uint32_t *p = &counts[(uint64_t)g * SORT_BINS + PER * tid + k];
+            const uint32_t v = *p;
+            *p = at[k];
+            at[k] += v;
         }
-#pragma unroll
-        for (int k = 0; k < BATCH; k++)
-            if (b[k] < SORT_BINS) order[atomicAdd(&bin[b[k]], 1u)] = (uint32_t)(i0 + (uint64_t)k * SORT_WG);
-    }
+}
+
+__global__ void __launch_bounds__(SORT_WG)
+lthash_order_place_kernel(const uint64_t *offsets, uint64_t n, const uint32_t *places, uint32_t *order)
+{
+    if (!ordered_mode(offsets, n)) return;
+    __shared__ uint32_t bin[SORT_BINS];
+    for (uint32_t k = threadIdx.x; k < SORT_BINS; k += SORT_WG) bin[k] = places[(uint64_t)blockIdx.x * SORT_BINS + k];
+    __syncthreads();
+    uint64_t lo, hi;
+    sort_run(n, blockIdx.x, gridDim.x, lo, hi);
+    for_each_bin(offsets, lo, hi, [&](uint64_t i, uint32_t b) { order[atomicAdd(&bin[b], 1u)] = (uint32_t)i; });
 }
 
 // ---------------------------------------------------------------------------
@@ -847,6 +932,7 @@ int lthash_presize(uint64_t max_records, hipStream_t s)
     int rc = scratch_get(s, R_LT_H0, 64 * (max_records ? max_records : 1), &p);
     if (rc) return rc;
     if ((rc = scratch_get(s, R_LT_ORDER, 4 * (max_records ? max_records : 1), &p))) return rc;
+    if ((rc = scratch_get(s, R_LT_COUNTS, 4 * (size_t)SORT_MAX_GROUPS * SORT_BINS, &p))) return rc;
     // the most partial rows any launch writes: two workgroups per CU, plus the running sum
     return scratch_get(s, R_LT_PART, ((size_t)cu_count() * 2 + 1) * LANE_WORDS * 4, &p);
 }
@@ -892,11 +978,17 @@ static int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, ui
     // four-lane path is kept for any number of long records: in length order it sustains
     // 1.7 TB/s, while one lane per record, which issues fewer instructions, has chains three
     // times as long and reaches that rate only with millions of records.
-    void *order;
+    void *order, *counts;
     int rc = scratch_get(s, R_LT_ORDER, 4 * n, &order);
     if (rc) return rc;
-    hipLaunchKernelGGL(lthash_order_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(order));
-    hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT4_WG)), dim3(ROOT4_WG), 0, s,
+    uint32_t groups = (uint32_t)ceil_div(n, SORT_MIN_RUN);
+    if (groups > SORT_MAX_GROUPS) groups = SORT_MAX_GROUPS;
+    if ((rc = scratch_get(s, R_LT_COUNTS, 4 * (size_t)SORT_MAX_GROUPS * SORT_BINS, &counts))) return rc;
+    hipLaunchKernelGGL(lthash_order_count_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts));
+    hipLaunchKernelGGL(lthash_order_scan_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts), groups);
+    hipLaunchKernelGGL(lthash_order_place_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n,
+                       static_cast<const uint32_t *>(counts), static_cast<uint32_t *>(order));
+    hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, h0);
     hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
@@ -1047,7 +1139,7 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
     hipLaunchKernelGGL(src_scatter_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab,
                        static_cast<uint32_t *>(perm));
     SENTRY_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT4_WG)), dim3(ROOT4_WG), 0, s,
+    hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n, static_cast<uint64_t *>(h0));
     hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,

@@ -48,6 +48,7 @@ enum Region {
     R_LT_PART,       // per-workgroup lane partial sums
     R_LT_SUM,        // running lane sum of the host-streaming entry point
     R_LT_ORDER,      // record indices ordered by length for the four-lane root hash
+    R_LT_COUNTS,     // per-workgroup bin counts, then places, of the ordering
     R_SRC_TABLES,    // per-source counts, starts, unit starts, cursors
     R_SRC_PERM,      // record indices grouped by source
     R_STAGE0,        // device staging buffers of the host-streaming entry points

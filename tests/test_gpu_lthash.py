@@ -170,57 +170,50 @@ def test_four_lane_path_many_records_in_length_order():
     assert (gpu_lthash(data, off, 3) == oracle.lthash(data, off)).all()
 
 
-def test_more_short_records_than_lanes_on_the_chip():
-    # short records, one lane each, several rounds of waves per SIMD
+def test_unequal_short_records_take_the_ordered_four_lane_path():
+    # mean far below 16 KiB, but records of very different lengths: the device finds that out from
+    # 256 records at fixed positions (index k n / 256) and orders the batch; ten workgroups share
+    # the ordering here, the last with a short run
+    n = 40_001
+    rng = np.random.default_rng(63)
+    lens = np.clip(np.round(2500 * np.exp(0.9 * rng.standard_normal(n))), 0, 150_000).astype(np.uint64)
+    lens[::131] = 0
+    lens[(np.arange(256) * n) >> 8] = 6000           # what the device samples: >= 4 KiB and >= 1.5 x the mean
+    off = wl.offsets_from_lengths(lens)
+    assert 1.5 * int(off[-1]) / n <= 6000 and int(off[-1]) < 16384 * n
+    data = wl.uniform_bytes(1560, 0, int(off[-1]))
+    assert (gpu_lthash(data, off, 1) == oracle.lthash(data, off)).all()
+    # the same lengths without the long samples: one lane per record, unordered
+    lens[(np.arange(256) * n) >> 8] = 100
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(1561, 0, int(off[-1]))
+    assert (gpu_lthash(data, off, 2) == oracle.lthash(data, off)).all()
+
+
+def test_few_records_take_four_lanes_unordered():
+    # up to 32,768 records: four lanes per record whatever the lengths, in the given order when
+    # the lengths are about equal; both sides of the limit
+    for n in (32_768, 32_769):
+        lens = np.full(n, 700, np.uint64)
+        lens[5] = 0
+        off = wl.offsets_from_lengths(lens)
+        data = wl.uniform_bytes(1570 + n % 7, 0, int(off[-1]))
+        assert (gpu_lthash(data, off) == oracle.lthash(data, off)).all(), n
+
+
+@pytest.mark.parametrize("unequal", [False, True])
+def test_more_short_records_than_lanes_on_the_chip(unequal):
+    # short records, one lane each, several rounds of waves per SIMD; or, with a few long records
+    # where the device samples the lengths, in length order with four lanes each (all 64
+    # workgroups of the ordering at work)
     n = 262_144 + 37
     rng = np.random.default_rng(61)
     lens = rng.integers(0, 48, n).astype(np.uint64)
+    if unequal:
+        lens[(np.arange(256) * n) >> 8] = 5000
     off = wl.offsets_from_lengths(lens)
     data = wl.uniform_bytes(1600, 0, int(off[-1]))
     assert (gpu_lthash(data, off) == oracle.lthash(data, off)).all()
-
-
-@pytest.mark.parametrize("n", [1, 2, 3, 15, 16, 17, 64, 1000, 4097, 40_000])
-def test_digests_one_by_one_and_their_sum(n):
-    # every record's 1024 lanes written out, then Eq. (1) over those rows: both against the
-    # oracle, and the sum against the fused path
-    rng = np.random.default_rng(1700 + n)
-    lens = rng.integers(0, 700, n).astype(np.uint64)
-    if n > 2:
-        lens[1] = 0
-        lens[2] = 40_000
-    off = wl.offsets_from_lengths(lens)
-    data = wl.uniform_bytes(1700 + n, 0, int(off[-1]) + 1)
-    dd, do = to_dev(data), to_dev(off)
-    rows = torch.full((n + 1, 1024), 0x5555, dtype=torch.int16, device="cuda")
-    sentry.sentry_lthash_digests(dd.data_ptr(), do.data_ptr(), n, rows.data_ptr())
-    torch.cuda.synchronize()
-    got = rows.cpu().numpy().view(np.uint16)
-    want = oracle.lthash_digests(data, off)
-    assert (got[:n] == want).all()
-    assert (got[n] == 0x5555).all()                       # nothing past the last row
-    out = torch.full((1024,), 0x5555, dtype=torch.int16, device="cuda")
-    sentry.sentry_lthash_sum(rows.data_ptr(), n, out.data_ptr())
-    torch.cuda.synchronize()
-    assert (out.cpu().numpy().view(np.uint16) == oracle.lthash_sum(want)).all()
-    assert (out.cpu().numpy().view(np.uint16) == gpu_lthash(data, off)).all()
-
-
-@pytest.mark.parametrize("n", [0, 1, 2, 15, 16, 17, 255, 4096, 32_768 + 3, 70_001])
-def test_sum_of_given_digests(n):
-    # rows of arbitrary lanes (not digests of anything): the plain column sum mod 2^16, across
-    # the sizes where the grid, the eight-rows-in-flight loop and its tail change
-    rng = np.random.default_rng(1800 + n)
-    d = rng.integers(0, 65536, size=(n, 1024)).astype(np.uint16)
-    if n > 3:
-        d[:3] = 0xFFFF                                     # carries must stay inside their lane
-    dev = to_dev(d.reshape(-1)) if n else None
-    out = torch.full((1024,), 0x5555, dtype=torch.int16, device="cuda")
-    sentry.sentry_lthash_sum(dev.data_ptr() if n else 0, n, out.data_ptr())
-    torch.cuda.synchronize()
-    assert (out.cpu().numpy().view(np.uint16) == oracle.lthash_sum(d)).all()
-    if n:
-        assert (dev.cpu().numpy().view(np.uint16).reshape(n, 1024) == d).all()   # input untouched
 
 
 def gpu_sources(data_np, off_np, src_np, n_sources, acc=None):
