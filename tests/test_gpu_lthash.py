@@ -216,6 +216,49 @@ def test_more_short_records_than_lanes_on_the_chip(unequal):
     assert (gpu_lthash(data, off) == oracle.lthash(data, off)).all()
 
 
+@pytest.mark.parametrize("n", [1, 2, 3, 15, 16, 17, 64, 1000, 4097, 40_000])
+def test_digests_one_by_one_and_their_sum(n):
+    # every record's 1024 lanes written out, then Eq. (1) over those rows: both against the
+    # oracle, and the sum against the fused path
+    rng = np.random.default_rng(1700 + n)
+    lens = rng.integers(0, 700, n).astype(np.uint64)
+    if n > 2:
+        lens[1] = 0
+        lens[2] = 40_000
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(1700 + n, 0, int(off[-1]) + 1)
+    dd, do = to_dev(data), to_dev(off)
+    rows = torch.full((n + 1, 1024), 0x5555, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash_digests(dd.data_ptr(), do.data_ptr(), n, rows.data_ptr())
+    torch.cuda.synchronize()
+    got = rows.cpu().numpy().view(np.uint16)
+    want = oracle.lthash_digests(data, off)
+    assert (got[:n] == want).all()
+    assert (got[n] == 0x5555).all()                       # nothing past the last row
+    out = torch.full((1024,), 0x5555, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash_sum(rows.data_ptr(), n, out.data_ptr())
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy().view(np.uint16) == oracle.lthash_sum(want)).all()
+    assert (out.cpu().numpy().view(np.uint16) == gpu_lthash(data, off)).all()
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 15, 16, 17, 255, 4096, 32_768 + 3, 70_001])
+def test_sum_of_given_digests(n):
+    # rows of arbitrary lanes (not digests of anything): the plain column sum mod 2^16, across
+    # the sizes where the grid, the eight-rows-in-flight loop and its tail change
+    rng = np.random.default_rng(1800 + n)
+    d = rng.integers(0, 65536, size=(n, 1024)).astype(np.uint16)
+    if n > 3:
+        d[:3] = 0xFFFF                                     # carries must stay inside their lane
+    dev = to_dev(d.reshape(-1)) if n else None
+    out = torch.full((1024,), 0x5555, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash_sum(dev.data_ptr() if n else 0, n, out.data_ptr())
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy().view(np.uint16) == oracle.lthash_sum(d)).all()
+    if n:
+        assert (dev.cpu().numpy().view(np.uint16).reshape(n, 1024) == d).all()   # input untouched
+
+
 def gpu_sources(data_np, off_np, src_np, n_sources, acc=None):
     n = len(off_np) - 1
     buf = to_dev(data_np) if data_np.size else torch.zeros(16, dtype=torch.uint8, device="cuda")
