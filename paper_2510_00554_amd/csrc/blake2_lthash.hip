@@ -1139,11 +1139,8 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
     hipLaunchKernelGGL(src_scatter_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab,
                        static_cast<uint32_t *>(perm));
     SENTRY_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
-                       static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n, static_cast<uint64_t *>(h0));
-    hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
-                       static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
-                       (const uint32_t *)nullptr, static_cast<uint64_t *>(h0));
+    // the root hashes do not depend on the sources: the same launches as for one sum
+    if ((rc = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s))) return rc;
     hipLaunchKernelGGL(lthash_expand_units_kernel, dim3((uint32_t)ceil_div(max_units, EXP_WAVES)), dim3(EXP_WG), 0, s,
                        static_cast<const uint64_t *>(h0), static_cast<const uint32_t *>(perm), S, unit, tab,
                        static_cast<uint32_t *>(part));
