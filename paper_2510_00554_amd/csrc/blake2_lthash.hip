@@ -354,7 +354,7 @@ __device__ __forceinline__ bool ordered_mode(const uint64_t *offsets, uint64_t n
         const uint64_t o = __shfl_xor(longest, d, 64);
         longest = o > longest ? o : longest;
     }
-    return longest >= UNEQUAL_MIN_BYTES && 2 * longest * n >= 3 * total;
+    return longest >= UNEQUAL_MIN_BYTES && 2 * longest >= 3 * (total / n);   // 1.5 x the (whole-byte) mean
 }
 
 __device__ __forceinline__ bool four_lane_mode(const uint64_t *offsets, uint64_t n)
