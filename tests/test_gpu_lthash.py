@@ -259,6 +259,34 @@ def test_sum_of_given_digests(n):
         assert (dev.cpu().numpy().view(np.uint16).reshape(n, 1024) == d).all()   # input untouched
 
 
+def test_a_million_unequal_records_by_properties_and_samples():
+    # too many for the oracle in full: the halves add up to the whole, the digests written out add
+    # up to it too, and sampled digests (the longest record among them) equal the oracle's
+    n = 1_000_000
+    rng = np.random.default_rng(64)
+    lens = np.clip(np.round(900 * np.exp(0.9 * rng.standard_normal(n))), 0, 120_000).astype(np.uint64)
+    lens[(np.arange(256) * n) >> 8] = 7000           # the sampled lengths say "unequal"
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(1580, 0, int(off[-1]), device="cuda")
+    d_off = to_dev(off)
+    whole, a, b, s = (torch.zeros(1024, dtype=torch.int16, device="cuda") for _ in range(4))
+    half = n // 2 + 17
+    sentry.sentry_lthash(data.data_ptr(), d_off.data_ptr(), n, whole.data_ptr())
+    sentry.sentry_lthash(data.data_ptr(), d_off.data_ptr(), half, a.data_ptr())
+    sentry.sentry_lthash(data.data_ptr(), d_off.data_ptr() + 8 * half, n - half, b.data_ptr())
+    sentry.sentry_lthash_combine(a.data_ptr(), b.data_ptr())
+    rows = torch.empty((n, 1024), dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash_digests(data.data_ptr(), d_off.data_ptr(), n, rows.data_ptr())
+    sentry.sentry_lthash_sum(rows.data_ptr(), n, s.data_ptr())
+    torch.cuda.synchronize()
+    assert whole.cpu().numpy().any()
+    assert torch.equal(whole, a) and torch.equal(whole, s)
+    picks = [0, 1, n - 1, int(np.argmax(lens)), int(np.argmin(lens))] + [int(x) for x in rng.integers(0, n, 40)]
+    for i in picks:
+        rec = data[int(off[i]):int(off[i + 1])].cpu().numpy()
+        assert (rows[i].cpu().numpy().view(np.uint16) == oracle.lthash_one(rec)).all(), i
+
+
 def gpu_sources(data_np, off_np, src_np, n_sources, acc=None):
     n = len(off_np) - 1
     buf = to_dev(data_np) if data_np.size else torch.zeros(16, dtype=torch.uint8, device="cuda")
