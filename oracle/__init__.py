@@ -35,7 +35,13 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        _lib = _bind(ctypes.CDLL(build()))
+    return _lib
+
+
+def _bind(L):
+    """Set the prototypes of every oracle function on a loaded library."""
+    if True:
         vp, sz, u32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32
         L.oracle_sha256.argtypes = [vp, sz, vp]
         L.oracle_sha256.restype = None
@@ -91,8 +97,27 @@ def lib():
         L.oracle_lthash_combine.restype = None
         L.oracle_lthash_remove.argtypes = [vp, vp]
         L.oracle_lthash_remove.restype = None
-        _lib = L
-    return _lib
+    return L
+
+
+class use_library:
+    """Context manager for tests of the pins themselves: inside it every wrapper of this module
+    calls the library at `path` (a build of an edited copy of sentry_oracle.c) instead."""
+
+    def __init__(self, path):
+        self.path = path
+
+    def __enter__(self):
+        global _lib
+        lib()
+        self.saved = _lib
+        _lib = _bind(ctypes.CDLL(self.path))
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.saved
+        return False
 
 
 def _u8(data):
