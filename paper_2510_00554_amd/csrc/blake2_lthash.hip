@@ -884,10 +884,17 @@ lthash_fold_sources_kernel(const uint32_t *part, uint32_t S, uint32_t *tables, u
     const uint32_t *unit_start = tab_unit_start(tables, S);
     const uint32_t u0 = unit_start[k], u1 = unit_start[k + 1];
     if (u0 == u1) return;                               // no record of this source in the batch
+    constexpr int AHEAD = 8;                            // loads in flight per lane, as in lthash_fold_kernel
     u16x2 s = u16x2{0, 0};
-    for (uint32_t u = u0 + row0; u < u1; u += ROWS) {
-        const uint32_t x = part[(uint64_t)u * LANE_WORDS + col];
-        s += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+    for (uint32_t u = u0 + row0; u < u1; u += ROWS * AHEAD) {
+        uint32_t x[AHEAD];
+#pragma unroll
+        for (int a = 0; a < AHEAD; a++) {
+            const uint32_t q = u + (uint32_t)a * ROWS;
+            x[a] = q < u1 ? part[(uint64_t)q * LANE_WORDS + col] : 0u;
+        }
+#pragma unroll
+        for (int a = 0; a < AHEAD; a++) s += u16x2{(unsigned short)x[a], (unsigned short)(x[a] >> 16)};
     }
     __shared__ uint32_t lds[ROWS][FOLD_COLS];
     lds[row0][threadIdx.x % FOLD_COLS] = (uint32_t)s.x | ((uint32_t)s.y << 16);
