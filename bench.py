@@ -110,7 +110,7 @@ def model_lthash_ops(lens, block_bytes):
 # A launch with fewer leaves (records) than lanes is bound by the serial chain of its longest leaf:
 # a wave that has a SIMD to itself issues one VALU instruction per 5.0 to 5.4 cycles on this chip,
 # whatever the instruction (measured: 5.0 with the rest of its CU idle, 5.3 - 5.4 with the other SIMDs
-# of the CU busy; see DESIGN.md), so chain_floor = instructions on the longest chain x 5.0 cycles /
+# of the CU busy), so chain_floor = instructions on the longest chain x 5.0 cycles /
 # 2.4 GHz.  Instructions per block on the critical wave: 930 for the SHA-256 rounds-only
 # consumer wave, 2304 for one tree level (two compressions by one lane), 700 for one BLAKE2b
 # compression spread over four lanes.
