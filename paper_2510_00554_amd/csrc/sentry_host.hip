@@ -46,7 +46,14 @@ static int ctx_for(hipStream_t stream, StreamCtx **out)
 
 int scratch_get(hipStream_t stream, Region r, size_t bytes, void **out)
 {
+    bool fresh;
+    return scratch_get_fresh(stream, r, bytes, out, &fresh);
+}
+
+int scratch_get_fresh(hipStream_t stream, Region r, size_t bytes, void **out, bool *fresh)
+{
     std::lock_guard<std::mutex> lock(g_mu);
+    *fresh = false;
     StreamCtx *c;
     int rc = ctx_for(stream, &c);
     if (rc) return rc;
@@ -69,6 +76,7 @@ int scratch_get(hipStream_t stream, Region r, size_t bytes, void **out)
         }
         c->region[r] = p;
         c->cap[r] = want;
+        *fresh = true;
     }
     *out = c->region[r];
     return SENTRY_OK;

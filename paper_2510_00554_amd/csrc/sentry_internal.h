@@ -57,12 +57,15 @@ enum Region {
     R_STAGE_OFF0,    // staged record offsets
     R_STAGE_OFF1,
     R_STAGE_OFF2,
+    R_TICKET,        // "last workgroup" counter of the one-launch Merkle tree (zero between launches)
     R_COUNT
 };
 
 // Returns a device pointer of at least `bytes` bytes for (current device, stream, region).
 // Growing a region frees the old allocation, which synchronises the device.
 int scratch_get(hipStream_t stream, Region r, size_t bytes, void **out);
+// The same; *fresh is set when the memory was allocated by this call (its contents are undefined).
+int scratch_get_fresh(hipStream_t stream, Region r, size_t bytes, void **out, bool *fresh);
 
 // Pinned host staging for tables (per stream): returns a host pointer of >= bytes.  Before
 // the memory is reused the previous upload from it has completed (tracked by an event).

@@ -296,6 +296,70 @@ __device__ __forceinline__ void wg_tree_fold(uint32_t (&lds)[2][8][WG], uint32_t
     }
 }
 
+// One-launch tree for launches of at most 512 workgroups (TAIL): every workgroup stores its node,
+// makes it visible to the device and takes a ticket; the workgroup that draws the last ticket
+// folds all the nodes itself, so that no second launch is needed (the launch gap and the start of
+// a kernel are a twentieth of a 16 MiB call).  The ticket counter is zero before the launch and
+// the last workgroup puts it back to zero.
+//
+// tail_ticket: called by all lanes of the workgroup after its node is stored (by lane 0, before
+// the call); true in all lanes of the workgroup that finishes last.
+__device__ __forceinline__ bool tail_ticket(uint32_t *ticket, uint32_t tid, uint32_t *flag)
+{
+    __syncthreads();          // every node store of this workgroup precedes the ticket
+    if (tid == 0) {
+        __threadfence();      // release: the node is visible to the whole device first
+        *flag = atomicAdd(ticket, 1u) == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!*flag) return false;
+    __threadfence();          // acquire: nothing read below comes from a stale cache line
+    return true;
+}
+
+// Fold cnt (2 .. 512) nodes at `nodes` (device memory, written by other workgroups) to one digest
+// at `out` by the pairwise rule; all NT lanes of the workgroup call this.  t = LDS, 2 x 8 x 512 words.
+template <int NT>
+__device__ __forceinline__ void tail_fold(const uint8_t *nodes, uint32_t cnt, uint8_t *out, uint32_t *ticket,
+                                          uint32_t tid, uint32_t (*t)[8][RED_IN])
+{
+    for (uint32_t i = tid; i < cnt; i += NT) {
+        uint32_t d[8];
+        load_digest(nodes + 32 * (uint64_t)i, d);
+#pragma unroll
+        for (int k = 0; k < 8; k++) t[0][k][i] = d[k];
+    }
+    __syncthreads();
+    int cur = 0;
+#pragma unroll 1
+    while (cnt > 1) {
+        const uint32_t pairs = cnt >> 1;
+#pragma unroll 1
+        for (uint32_t i = tid; i < pairs; i += NT) {
+            uint32_t l[8], r[8], d[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) { l[k] = t[cur][k][2 * i]; r[k] = t[cur][k][2 * i + 1]; }
+            node_hash(l, r, d);
+#pragma unroll
+            for (int k = 0; k < 8; k++) t[cur ^ 1][k][i] = d[k];
+        }
+        if (tid == 0 && (cnt & 1)) {
+#pragma unroll
+            for (int k = 0; k < 8; k++) t[cur ^ 1][k][pairs] = t[cur][k][cnt - 1];
+        }
+        __syncthreads();
+        cnt = pairs + (cnt & 1);
+        cur ^= 1;
+    }
+    if (tid == 0) {
+        uint32_t root[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) root[k] = t[cur][k][0];
+        store_digest(out, root);
+        *ticket = 0;          // ready for the next launch
+    }
+}
+
 // Block hashing kernel.  FUSE: fold the workgroup's leaves in LDS and store one node per
 // workgroup at out + 32*blockIdx; otherwise store every leaf digest at out + 32*leaf.
 // WG = leaves per workgroup: 256, or 64 (one wave per workgroup).  A lone wave on a SIMD issues
@@ -313,11 +377,14 @@ __host__ inline bool single_wave_groups(uint64_t waves, uint64_t leaf_bytes)
 
 // PACKED (with SEGMENTED, without FUSE): nleaves0 = leaves of all segments, n_seg = segments;
 // digest L goes to out + 32 L.
-template <int WG, bool FUSE, bool SEGMENTED, bool PACKED = false>
+// TAIL (with FUSE, one buffer): the one-launch tree; `out` holds gridDim.x nodes, root to final_out.
+template <int WG, bool FUSE, bool SEGMENTED, bool PACKED = false, bool TAIL = false>
 __global__ void __launch_bounds__(WG)
 merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const SegDesc *segs, uint32_t n_seg,
-                   const Group *groups, uint64_t leaf_bytes, uint8_t *out)
+                   const Group *groups, uint64_t leaf_bytes, uint8_t *out, uint32_t *ticket = nullptr,
+                   uint8_t *final_out = nullptr)
 {
+    static_assert(!TAIL || (FUSE && !SEGMENTED && !PACKED), "the one-launch tree is for one buffer");
     const uint32_t g = blockIdx.x, tid = threadIdx.x;
     if (PACKED) {
         static_assert(!PACKED || (SEGMENTED && !FUSE), "the packed leaf stage writes leaf digests");
@@ -359,6 +426,11 @@ merkle_leaf_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, const
     uint32_t root[8];
     wg_tree_fold<WG>(lds, count, tid, root);
     if (tid == 0) store_digest(out + 32 * out_at, root);
+    if constexpr (TAIL) {
+        __shared__ uint32_t last;
+        __shared__ uint32_t tail_lds[2][8][RED_IN];
+        if (tail_ticket(ticket, tid, &last)) tail_fold<WG>(out, gridDim.x, final_out, ticket, tid, tail_lds);
+    }
 }
 
 // Block hashing kernel for launches with very few leaves, where the run time is one lane's
@@ -451,12 +523,16 @@ __device__ __forceinline__ void sha256_rounds_from_lds(uint32_t (&st)[8], const 
 // All barriers are workgroup-wide, so both pairs run the trip count of the longer group.
 // PAIRS = 1 (128 lanes) is used while there is at most one group per CU: two busy SIMDs per
 // CU run a little faster than four.
-template <int PAIRS, bool FUSE, bool SEGMENTED, bool PACKED = false>
+// TAIL (with FUSE, one buffer): the one-launch tree; `out` holds n_groups nodes, root to final_out.
+template <int PAIRS, bool FUSE, bool SEGMENTED, bool PACKED = false, bool TAIL = false>
 __global__ void __launch_bounds__(SPLIT_PAIR_LANES * PAIRS)
 merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0, uint32_t n_groups,
-                         const SegDesc *segs, uint32_t n_seg, const Group *groups, uint64_t leaf_bytes, uint8_t *out)
+                         const SegDesc *segs, uint32_t n_seg, const Group *groups, uint64_t leaf_bytes, uint8_t *out,
+                         uint32_t *ticket = nullptr, uint8_t *final_out = nullptr)
 {
     static_assert(!PACKED || (SEGMENTED && !FUSE), "the packed leaf stage writes leaf digests");
+    static_assert(!TAIL || (FUSE && !SEGMENTED && !PACKED), "the one-launch tree is for one buffer");
+    static_assert(2 * SPLIT_SLOT_WORDS >= 2 * 8 * RED_IN, "the tail folds in the schedule slots of pair 0");
     __shared__ __attribute__((aligned(16))) uint32_t sched[PAIRS][2 * SPLIT_SLOT_WORDS];
     __shared__ uint32_t lds[PAIRS][2][8][SPLIT_LEAVES];
     __shared__ unsigned long long trip_share[2 * PAIRS];
@@ -594,6 +670,14 @@ merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
 #pragma unroll
         for (int i = 0; i < 8; i++) root[i] = lds[pr][cur][i][0];
         store_digest(out + 32 * out_at, root);
+        if constexpr (TAIL) __threadfence();   // released by the lane that stored it
+    }
+    if constexpr (TAIL) {
+        // the schedule slots are free now (tail_ticket starts with a barrier)
+        __shared__ uint32_t last;
+        if (tail_ticket(ticket, threadIdx.x, &last))
+            tail_fold<SPLIT_PAIR_LANES * PAIRS>(out, n_groups, final_out, ticket, threadIdx.x,
+                                                reinterpret_cast<uint32_t (*)[8][RED_IN]>(&sched[0][0]));
     }
 }
 
@@ -641,17 +725,19 @@ merkle_reduce_kernel(const uint8_t *in, uint64_t n0, const Group *groups, uint8_
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 // the two-wave split kernel over n_groups groups of 64 leaves
-template <bool FUSE, bool SEGMENTED, bool PACKED = false>
+template <bool FUSE, bool SEGMENTED, bool PACKED = false, bool TAIL = false>
 void launch_split(uint32_t n_groups, hipStream_t s, const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
-                  const SegDesc *segs, uint32_t n_seg, const Group *groups, uint64_t leaf_bytes, uint8_t *out)
+                  const SegDesc *segs, uint32_t n_seg, const Group *groups, uint64_t leaf_bytes, uint8_t *out,
+                  uint32_t *ticket = nullptr, uint8_t *final_out = nullptr)
 {
     if (n_groups <= SPLIT_SINGLE_GROUPS)
-        hipLaunchKernelGGL((merkle_leaf_split_kernel<1, FUSE, SEGMENTED, PACKED>), dim3(n_groups), dim3(SPLIT_PAIR_LANES), 0, s,
-                           base0, len0, nleaves0, n_groups, segs, n_seg, groups, leaf_bytes, out);
+        hipLaunchKernelGGL((merkle_leaf_split_kernel<1, FUSE, SEGMENTED, PACKED, TAIL>), dim3(n_groups),
+                           dim3(SPLIT_PAIR_LANES), 0, s, base0, len0, nleaves0, n_groups, segs, n_seg, groups, leaf_bytes,
+                           out, ticket, final_out);
     else
-        hipLaunchKernelGGL((merkle_leaf_split_kernel<2, FUSE, SEGMENTED, PACKED>), dim3((n_groups + 1) / 2),
+        hipLaunchKernelGGL((merkle_leaf_split_kernel<2, FUSE, SEGMENTED, PACKED, TAIL>), dim3((n_groups + 1) / 2),
                            dim3(2 * SPLIT_PAIR_LANES), 0, s, base0, len0, nleaves0, n_groups, segs, n_seg, groups,
-                           leaf_bytes, out);
+                           leaf_bytes, out, ticket, final_out);
 }
 
 // The packed leaf stage pays where per-segment groups would leave at least a ninth of the
@@ -683,31 +769,18 @@ int check_leaf_args(const char *fn, const void *buf, size_t len, size_t leaf_byt
     return SENTRY_OK;
 }
 
-// Reduce n nodes at `in` (device, 16-byte aligned, not one of the R_RED regions) to one
-// digest at out_digest; intermediate levels ping-pong between the two R_RED regions.
-int reduce_nodes(const uint8_t *in, uint64_t n, uint8_t *out_digest, hipStream_t s)
+// Reduce n nodes at `in` (device, 16-byte aligned) to one digest at out_digest; intermediate
+// levels ping-pong between red0 and red1 (device, 16-byte aligned, 32 * ceil(n / 512) bytes each,
+// distinct from `in`; not touched when n <= 512).
+int reduce_nodes_in(const uint8_t *in, uint64_t n, uint8_t *out_digest, hipStream_t s, uint8_t *red0, uint8_t *red1)
 {
     const uint8_t *src = in;
-    uint8_t *bufs[2] = {nullptr, nullptr};
+    uint8_t *bufs[2] = {red0, red1};
     uint64_t m = n;
     int turn = 0;
     do {   // at least one pass so that the result lands in out_digest
         const uint64_t g = ceil_div(m, RED_IN);
-        uint8_t *dst;
-        if (g == 1) {
-            dst = out_digest;
-        } else {
-            if (!bufs[0]) {   // first pass is the largest
-                void *a, *b;
-                int rc = sentry::scratch_get(s, sentry::R_RED_0, 32 * g, &a);
-                if (rc) return rc;
-                rc = sentry::scratch_get(s, sentry::R_RED_1, 32 * g, &b);
-                if (rc) return rc;
-                bufs[0] = static_cast<uint8_t *>(a);
-                bufs[1] = static_cast<uint8_t *>(b);
-            }
-            dst = bufs[turn];
-        }
+        uint8_t *dst = g == 1 ? out_digest : bufs[turn];
         hipLaunchKernelGGL(merkle_reduce_kernel<false>, dim3((uint32_t)g), dim3(RED_WG), 0, s, src, m,
                            (const Group *)nullptr, dst);
         SENTRY_HIP_CHECK(hipGetLastError());
@@ -715,6 +788,82 @@ int reduce_nodes(const uint8_t *in, uint64_t n, uint8_t *out_digest, hipStream_t
         m = g;
         turn ^= 1;
     } while (m > 1);
+    return SENTRY_OK;
+}
+
+// The same with the level buffers taken from the two R_RED regions of the stream's scratch
+// (`in` is not one of them).
+int reduce_nodes(const uint8_t *in, uint64_t n, uint8_t *out_digest, hipStream_t s)
+{
+    void *a = nullptr, *b = nullptr;
+    if (n > RED_IN) {   // the first pass is the largest
+        const uint64_t g = ceil_div(n, RED_IN);
+        int rc = sentry::scratch_get(s, sentry::R_RED_0, 32 * g, &a);
+        if (rc) return rc;
+        if ((rc = sentry::scratch_get(s, sentry::R_RED_1, 32 * g, &b))) return rc;
+    }
+    return reduce_nodes_in(in, n, out_digest, s, static_cast<uint8_t *>(a), static_cast<uint8_t *>(b));
+}
+
+// How sentry_merkle_root cuts a buffer into workgroups, and the scratch that needs.
+struct RootPlan {
+    uint64_t leaves, groups;   // groups = workgroups of the leaf kernel = nodes it writes
+    bool small;                // single-wave workgroups of 64 leaves (else 256)
+    bool split;                // the two-wave producer/consumer kernel
+    bool tail;                 // 2 .. 512 groups: the last workgroup folds the nodes, one launch in all
+};
+
+RootPlan plan_root(uint64_t len, uint64_t leaf_bytes)
+{
+    RootPlan p;
+    p.leaves = leaf_count(len, leaf_bytes);
+    p.small = single_wave_groups(ceil_div(p.leaves, 64), leaf_bytes);
+    p.groups = ceil_div(p.leaves, p.small ? LEAF_WG_SMALL : LEAF_WG);
+    p.split = p.small && p.groups <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF;
+    p.tail = p.small && p.groups > 1 && p.groups <= RED_IN;
+    return p;
+}
+
+// nodes: 32 * groups bytes (not used for one group); ticket: one zeroed word (tail plans only);
+// red0, red1: 32 * ceil(groups / 512) bytes each (plans with more than 512 groups only)
+struct RootScratch {
+    uint8_t *nodes;
+    uint32_t *ticket;
+    uint8_t *red0, *red1;
+};
+
+__global__ void zero_words_kernel(uint32_t *p, uint32_t n)
+{
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
+}
+
+int merkle_root_launch(const RootPlan &plan, const void *dev_buf, uint64_t len, uint64_t leaf_bytes, uint8_t *out_digest,
+                       hipStream_t s, const RootScratch &sc)
+{
+    const uint8_t *buf = static_cast<const uint8_t *>(dev_buf);
+    const uint32_t g = (uint32_t)plan.groups;
+    uint8_t *dst = g > 1 ? sc.nodes : out_digest;
+    if (plan.tail) {
+        if (plan.split)
+            launch_split<true, false, false, true>(g, s, buf, len, plan.leaves, nullptr, 0, nullptr, leaf_bytes, dst,
+                                                   sc.ticket, out_digest);
+        else
+            hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, false, false, true>), dim3(g), dim3(LEAF_WG_SMALL),
+                               0, s, buf, len, plan.leaves, (const SegDesc *)nullptr, 0u, (const Group *)nullptr,
+                               leaf_bytes, dst, sc.ticket, out_digest);
+        SENTRY_HIP_CHECK(hipGetLastError());
+        return SENTRY_OK;
+    }
+    if (plan.split)
+        launch_split<true, false>(g, s, buf, len, plan.leaves, nullptr, 0, nullptr, leaf_bytes, dst);
+    else if (plan.small)
+        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, false>), dim3(g), dim3(LEAF_WG_SMALL), 0, s, buf, len,
+                           plan.leaves, (const SegDesc *)nullptr, 0u, (const Group *)nullptr, leaf_bytes, dst);
+    else
+        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, true, false>), dim3(g), dim3(LEAF_WG), 0, s, buf, len,
+                           plan.leaves, (const SegDesc *)nullptr, 0u, (const Group *)nullptr, leaf_bytes, dst);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    if (g > 1) return reduce_nodes_in(dst, g, out_digest, s, sc.red0, sc.red1);
     return SENTRY_OK;
 }
 
@@ -757,30 +906,31 @@ int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
     int rc = check_leaf_args("sentry_merkle_root", dev_buf, len, leaf_bytes);
     if (rc) return rc;
     SENTRY_REQUIRE(out_digest != nullptr, "sentry_merkle_root: NULL out_digest");
-    const uint64_t n = leaf_count(len, leaf_bytes);
-    const bool small = single_wave_groups(ceil_div(n, 64), leaf_bytes);
-    const uint64_t g = ceil_div(n, small ? LEAF_WG_SMALL : LEAF_WG);
-    uint8_t *dst = out_digest;
-    if (g > 1) {
-        void *a;
-        rc = sentry::scratch_get(s, sentry::R_NODES_A, 32 * g, &a);
-        if (rc) return rc;
-        dst = static_cast<uint8_t *>(a);
+    const RootPlan plan = plan_root(len, leaf_bytes);
+    RootScratch sc = {};
+    if (plan.groups > 1) {
+        void *p;
+        if ((rc = sentry::scratch_get(s, sentry::R_NODES_A, 32 * plan.groups, &p))) return rc;
+        sc.nodes = static_cast<uint8_t *>(p);
     }
-    if (small && ceil_div(n, 64) <= SPLIT_LAUNCH_WAVES && leaf_bytes >= SPLIT_MIN_LEAF)
-        launch_split<true, false>((uint32_t)g, s, static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, nullptr, 0,
-                                  nullptr, (uint64_t)leaf_bytes, dst);
-    else if (small)
-        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG_SMALL, true, false>), dim3((uint32_t)g), dim3(LEAF_WG_SMALL), 0, s,
-                           static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
-                           0u, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
-    else
-        hipLaunchKernelGGL((merkle_leaf_kernel<LEAF_WG, true, false>), dim3((uint32_t)g), dim3(LEAF_WG), 0, s,
-                           static_cast<const uint8_t *>(dev_buf), (uint64_t)len, n, (const SegDesc *)nullptr,
-                           0u, (const Group *)nullptr, (uint64_t)leaf_bytes, dst);
-    SENTRY_HIP_CHECK(hipGetLastError());
-    if (g > 1) return reduce_nodes(dst, g, out_digest, s);
-    return SENTRY_OK;
+    if (plan.tail) {
+        void *p;
+        bool fresh;
+        if ((rc = sentry::scratch_get_fresh(s, sentry::R_TICKET, 256, &p, &fresh))) return rc;
+        sc.ticket = static_cast<uint32_t *>(p);
+        if (fresh) {   // from then on the last workgroup of every launch leaves it at zero
+            hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, sc.ticket, 64u);
+            SENTRY_HIP_CHECK(hipGetLastError());
+        }
+    } else if (plan.groups > RED_IN) {
+        void *a, *b;
+        const uint64_t g1 = ceil_div(plan.groups, RED_IN);
+        if ((rc = sentry::scratch_get(s, sentry::R_RED_0, 32 * g1, &a))) return rc;
+        if ((rc = sentry::scratch_get(s, sentry::R_RED_1, 32 * g1, &b))) return rc;
+        sc.red0 = static_cast<uint8_t *>(a);
+        sc.red1 = static_cast<uint8_t *>(b);
+    }
+    return merkle_root_launch(plan, dev_buf, len, leaf_bytes, out_digest, s, sc);
 }
 
 int sentry_merkle_leaves(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *out_leaf_digests, void *stream)
