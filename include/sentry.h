@@ -87,6 +87,23 @@ SENTRY_API int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_b
                        uint8_t *out_digest, void *stream);
 
 /*
+ * sentry_merkle_root for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * result, same kernels, but the workgroup nodes, level buffers and the ticket
+ * counter live in one fixed device array of the library (about 2 MiB, held on
+ * every GPU the library runs on until the process ends) instead of the
+ * per-stream scratch, and the call makes no hipMalloc, hipFree or other
+ * allocating call, first call included.
+ * Limit: at most 4,194,304 leaves (len <= 4,194,304 * leaf_bytes); more is
+ * SENTRY_ERR_INVALID_ARG, and sentry_merkle_root takes such inputs.
+ * All calls on one GPU share the array, whatever their stream: calls that
+ * overlap in time on one GPU race and give undefined digests; calls ordered one
+ * after the other (one stream, or events) are safe.
+ */
+SENTRY_API int sentry_merkle_root_noalloc(const void *dev_buf, size_t len, size_t leaf_bytes,
+                                          uint8_t *out_digest, void *stream);
+
+/*
  * The same tree over one of the paper's three leaf functions (section 4.2.1:
  * SHA256, BLAKE2B and SHA3): node = H(left || right) with the full hash H, same
  * leaf, short-tail, odd-node and empty-buffer rules as sentry_merkle_root.

@@ -30,6 +30,7 @@ _lib = None
 _vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 PROTOTYPES = {
     "sentry_merkle_root": (_int, [_vp, _sz, _sz, _vp, _vp]),
+    "sentry_merkle_root_noalloc": (_int, [_vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_root_h": (_int, [_int, _vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_segments": (_int, [_vp, _vp, _sz, _sz, _vp, _vp, _vp]),
     "sentry_merkle_inplace": (_int, [_vp, _vp, _sz, _sz, _vp, _vp]),
@@ -94,6 +95,10 @@ def sentry_release_scratch():
 
 def sentry_merkle_root(dev_buf, length, leaf_bytes, out_digest, stream=0):
     return _check(load().sentry_merkle_root(dev_buf, length, leaf_bytes, out_digest, stream))
+
+
+def sentry_merkle_root_noalloc(dev_buf, length, leaf_bytes, out_digest, stream=0):
+    return _check(load().sentry_merkle_root_noalloc(dev_buf, length, leaf_bytes, out_digest, stream))
 
 
 HASH_SHA256, HASH_BLAKE2B, HASH_SHA3_256 = 0, 1, 2

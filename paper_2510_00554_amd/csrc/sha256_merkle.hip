@@ -10,9 +10,24 @@
 // rule, and only the last group of a buffer can be partial, so the promoted odd
 // node lands where the plain rule puts it.
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "sentry_internal.h"
+
+// Scratch of sentry_merkle_root_noalloc (the entry point that allocates nothing).
+// Largest input: 2^22 leaves, that is at most 65,536 workgroup nodes whichever kernel is chosen.
+constexpr uint64_t NOALLOC_MAX_LEAVES = 1ull << 22;
+constexpr uint64_t NOALLOC_MAX_GROUPS = NOALLOC_MAX_LEAVES / 64;
+constexpr size_t NOALLOC_NODES_BYTES = 32 * NOALLOC_MAX_GROUPS;                         // 2 MiB
+constexpr size_t NOALLOC_RED_BYTES = 32 * ((NOALLOC_MAX_GROUPS + 511) / 512);   // 4 KiB, twice
+constexpr size_t NOALLOC_TICKET_AT = NOALLOC_NODES_BYTES + 2 * NOALLOC_RED_BYTES;
+constexpr size_t NOALLOC_BYTES = NOALLOC_TICKET_AT + 256;
+
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress: kernels get the
+// address that call returns, never the name.
+static __device__ __align__(256) unsigned char scratch[NOALLOC_BYTES];
 
 namespace {
 
@@ -24,6 +39,7 @@ constexpr uint64_t SPLIT_LAUNCH_WAVES = 512;    // groups of 64 leaves the two-w
 constexpr uint64_t SPLIT_SINGLE_GROUPS = 256;   // up to one group per CU: one pair per workgroup
 constexpr int RED_WG = 256;           // lanes per workgroup of the reduce kernel
 constexpr int RED_IN = 2 * RED_WG;    // nodes folded by one reduce workgroup
+static_assert(LEAF_WG_SMALL == 64 && RED_IN == 512, "the fixed scratch array is sized for these");
 
 struct SegDesc {
     const uint8_t *base;
@@ -867,6 +883,37 @@ int merkle_root_launch(const RootPlan &plan, const void *dev_buf, uint64_t len, 
     return SENTRY_OK;
 }
 
+// ---------------------------------------------------------------------------
+// sentry_merkle_root_noalloc: the same launches with their scratch in a fixed device array
+// ---------------------------------------------------------------------------
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_noalloc_mu;
+unsigned char *g_noalloc_ptr[NOALLOC_MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int noalloc_scratch(unsigned char **out)
+{
+    int dev = 0;
+    SENTRY_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) {
+        sentry::set_error("sentry_merkle_root_noalloc: device %d is beyond the %d devices supported", dev, NOALLOC_MAX_DEVICES);
+        return SENTRY_ERR_INVALID_ARG;
+    }
+    std::lock_guard<std::mutex> lock(g_noalloc_mu);
+    if (!g_noalloc_ptr[dev]) {
+        unsigned char *ptr = nullptr;
+        SENTRY_HIP_CHECK(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) {
+            sentry::set_error("sentry_merkle_root_noalloc: no device address for the scratch array on device %d", dev);
+            return SENTRY_ERR_HIP;
+        }
+        g_noalloc_ptr[dev] = ptr;
+    }
+    *out = g_noalloc_ptr[dev];
+    return SENTRY_OK;
+}
+
 }  // namespace
 
 namespace sentry {
@@ -929,6 +976,33 @@ int sentry_merkle_root(const void *dev_buf, size_t len, size_t leaf_bytes, uint8
         if ((rc = sentry::scratch_get(s, sentry::R_RED_1, 32 * g1, &b))) return rc;
         sc.red0 = static_cast<uint8_t *>(a);
         sc.red1 = static_cast<uint8_t *>(b);
+    }
+    return merkle_root_launch(plan, dev_buf, len, leaf_bytes, out_digest, s, sc);
+}
+
+int sentry_merkle_root_noalloc(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *out_digest, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = check_leaf_args("sentry_merkle_root_noalloc", dev_buf, len, leaf_bytes);
+    if (rc) return rc;
+    SENTRY_REQUIRE(out_digest != nullptr, "sentry_merkle_root_noalloc: NULL out_digest");
+    const RootPlan plan = plan_root(len, leaf_bytes);
+    SENTRY_REQUIRE(plan.leaves <= NOALLOC_MAX_LEAVES,
+                   "sentry_merkle_root_noalloc: %llu leaves, the fixed scratch holds at most %llu (use sentry_merkle_root)",
+                   (unsigned long long)plan.leaves, (unsigned long long)NOALLOC_MAX_LEAVES);
+    unsigned char *ptr;
+    if ((rc = noalloc_scratch(&ptr))) return rc;
+    RootScratch sc;
+    sc.nodes = ptr;
+    sc.red0 = ptr + NOALLOC_NODES_BYTES;
+    sc.red1 = sc.red0 + NOALLOC_RED_BYTES;
+    sc.ticket = reinterpret_cast<uint32_t *>(ptr + NOALLOC_TICKET_AT);
+    if (plan.tail) {
+        // the array keeps what the last call left: the ticket must start at zero (a fill kernel, so
+        // that the call can be captured into a graph)
+        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, sc.ticket, 64u);
+        SENTRY_HIP_CHECK(hipGetLastError());
     }
     return merkle_root_launch(plan, dev_buf, len, leaf_bytes, out_digest, s, sc);
 }

@@ -45,6 +45,8 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_merkle_root(0x1004, 4096, 64, 0x2000),         # misaligned buffer
     lambda: sentry.sentry_merkle_root(0, 4096, 64, 0x2000),              # NULL with len > 0
     lambda: sentry.sentry_merkle_root(0x1000, 4096, 64, 0),              # NULL output
+    lambda: sentry.sentry_merkle_root_noalloc(0x1000, 64 * ((1 << 22) + 1), 64, 0x2000),   # beyond the fixed scratch
+    lambda: sentry.sentry_merkle_root_noalloc(0x1000, 4096, 96, 0x2000),  # bad leaf size
     lambda: sentry.sentry_merkle_root_h(1, 0x1000, 4096, 100, 0x2000),   # BLAKE2b tree, bad leaf size
     lambda: sentry.sentry_merkle_root_h(2, 0x1008, 4096, 64, 0x2000),    # SHA-3 tree, misaligned buffer
     lambda: sentry.sentry_merkle_root_h(9, 0x1000, 4096, 64, 0x2000),    # unknown leaf function
