@@ -35,76 +35,134 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-ALU_PEAK_OPS = 256 * 4 * 16 * 2.4e9          # CUs x SIMDs x lanes x clock: 32-bit VALU lane-ops/s
+ALU_PEAK_OPS = 256 * 4 * 16 * 2.4e9          # CUs x SIMDs x lanes x clock: 32-bit VALU lane-ops/s (nominal)
 HBM_PEAK = 8.0e12
 
-# algorithmic 32-bit VALU operations of SHA-256 on gfx950 (rotate, 3-input boolean and
-# 3-input add are one instruction each): 64 rounds x 14 + 48 schedule steps x 10 + 16 byte
-# swaps + 8 feed-forward adds; a block whose message schedule is a constant (the padding
-# block of a fixed-size leaf, the second block of an inner node) needs rounds and adds only
-SHA_BLOCK_OPS = 64 * 14 + 48 * 10 + 16 + 8
-SHA_CONST_BLOCK_OPS = 64 * 14 + 8
+
+class Mix(dict):
+    """VALU instructions by opcode: the work of a hash, counted as the instructions its hot loop
+    needs on gfx950 (one instruction = one operation of each of a wave's 64 lanes)."""
+
+    def __add__(self, other):
+        out = Mix(self)
+        for k, v in other.items():
+            out[k] = out.get(k, 0) + v
+        return out
+
+    def __mul__(self, n):
+        return Mix({k: v * n for k, v in self.items()})
+
+    __rmul__ = __mul__
+
+    def total(self):
+        return sum(self.values())
 
 
-def merkle_ops(n_leaves, leaf_bytes, n_nodes):
-    per_leaf = (leaf_bytes // 64) * SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS
-    return n_leaves * per_leaf + n_nodes * (SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS)
+# SHA-256 on gfx950 (rotate = v_alignbit_b32, xor3/Ch/Maj = v_bitop3_b32, three-input add = v_add3_u32).
+# One 64-byte block: 64 rounds x (6 rotates, 4 three-input booleans, 3 add3, 1 add) + 48 schedule steps x
+# (4 rotates, 2 xor3, 2 shifts, add3 + add) + 16 byte swaps + 8 feed-forward adds = 1400; the compiled
+# loop has exactly these (1384 in the loop body + the 16 v_perm_b32 of the loads).
+SHA_BLOCK_MIX = Mix({"v_alignbit_b32": 64 * 6 + 48 * 4, "v_bitop3_b32": 64 * 4 + 48 * 2, "v_add3_u32": 64 * 3 + 48,
+                     "v_add_u32": 64 + 48 + 8, "v_lshrrev_b32": 48 * 2, "v_perm_b32": 16})
+# A block whose message schedule is a constant (the padding block of a leaf that is a whole number of
+# blocks, the second block of an inner node): rounds with K + W folded into one literal, and the adds.
+SHA_CONST_BLOCK_MIX = Mix({"v_alignbit_b32": 64 * 6, "v_bitop3_b32": 64 * 4, "v_add3_u32": 64 * 2, "v_add_u32": 64 * 2 + 8})
+# BLAKE2b: 96 G functions x (6 64-bit adds as v_lshl_add_u64, 4 64-bit xors = 8 v_xor_b32, 3 rotations by
+# 24/16/63 = 6 v_alignbit_b32; the rotation by 32 is a renaming) + 16 64-bit xors of the feed-forward.
+# A 64-bit add is ONE instruction here, not two.  The one-block expansion calls have eight zero message
+# words (96 of the 192 message adds vanish) and 16 packed 16-bit adds into the lane sums.
+B2_BLOCK_MIX = Mix({"v_lshl_add_u64": 96 * 6, "v_xor_b32": 96 * 8 + 32, "v_alignbit_b32": 96 * 6})
+B2_EXPAND_MIX = Mix({"v_lshl_add_u64": 96 * 6 - 96, "v_xor_b32": 96 * 8 + 32, "v_alignbit_b32": 96 * 6, "v_pk_add_u16": 16})
+# Keccak-f[1600] on 32-bit halves: per round theta 20 xor3 + 10 rotate halves + 60 xor, rho 48 rotate halves,
+# chi 50 three-input booleans, iota 2 xor; 24 rounds, plus 34 xors to absorb a 136-byte block.
+KECCAK_BLOCK_MIX = Mix({"v_bitop3_b32": 24 * 70, "v_xor_b32": 24 * 62 + 34, "v_alignbit_b32": 24 * 58})
+SHA_BLOCK_OPS, SHA_CONST_BLOCK_OPS = SHA_BLOCK_MIX.total(), SHA_CONST_BLOCK_MIX.total()            # 1400, 904
+B2_BLOCK_OPS, B2_EXPAND_OPS, KECCAK_BLOCK_OPS = B2_BLOCK_MIX.total(), B2_EXPAND_MIX.total(), KECCAK_BLOCK_MIX.total()
+SHA_NODE_MIX = SHA_BLOCK_MIX + SHA_CONST_BLOCK_MIX
+
+# Measured issue rates of single opcodes on this chip, T lane-ops/s with four waves per SIMD (the table
+# `python bench.py --valu-probe` prints; profiles/valu_issue_rates.md holds a run of it).  Two classes: the
+# two-operand integer and boolean ops and v_bitop3_b32 issue at about 57 T, the three-operand adds, funnel
+# shifts, byte permutes, 64-bit and packed adds at about 36 T; the nominal 39.32 T is neither.  The
+# ceiling of a kernel is that of its mix: total instructions / sum(instructions of opcode / its rate).
+ISSUE_RATE_TOPS = {"v_xor_b32": 57.0, "v_add_u32": 57.0, "v_lshrrev_b32": 57.0, "v_bitop3_b32": 57.0,
+                   "v_alignbit_b32": 36.0, "v_add3_u32": 36.0, "v_perm_b32": 36.0, "v_lshl_add_u64": 36.0,
+                   "v_pk_add_u16": 36.0}
 
 
-# BLAKE2b on gfx950, counted in 32-bit lane operations (a 64-bit add or xor = 2, a 64-bit rotate
-# = 2, by 32 = 0): 96 G functions x 26 + state set-up and feed-forward ~ 2500 per 128-byte
-# compression; the one-block expansion calls, whose message is half zero, ~ 1860.
-# Keccak-f[1600]: 24 rounds x ~190 (theta 90, rho 48, chi 50, iota 2) = 4560 per 136-byte block.
-B2_BLOCK_OPS, B2_EXPAND_OPS, KECCAK_BLOCK_OPS = 2500, 1860, 4560
+def issue_bound(mix):
+    """Lane-ops/s the chip can issue for this instruction mix (every opcode at its measured rate)."""
+    return mix.total() / sum(n / (ISSUE_RATE_TOPS[op] * 1e12) for op, n in mix.items() if n)
 
 
-def sha_tree_ops(lens, leaf_bytes, flat=False):
+def merkle_mix(n_leaves, leaf_bytes, n_nodes):
+    per_leaf = (leaf_bytes // 64) * SHA_BLOCK_MIX + SHA_CONST_BLOCK_MIX
+    return n_leaves * per_leaf + n_nodes * SHA_NODE_MIX
+
+
+def sha_tree_mix(lens, leaf_bytes, flat=False):
     """SHA-256 trees over buffers of the given byte lengths: per-buffer trees plus the tree over
     their roots, or (flat) one tree over all their leaves."""
-    ops, leaves_total = 0, 0
+    mix, leaves_total = Mix(), 0
     for ln in lens:
         n = -(-ln // leaf_bytes) if (ln or flat) else 1
         if ln == 0 and not flat:
-            ops += SHA_BLOCK_OPS
+            mix = mix + SHA_BLOCK_MIX
         for size, count in ((leaf_bytes, ln // leaf_bytes), (ln % leaf_bytes, 1 if ln % leaf_bytes else 0)):
             # full blocks, then the padding block(s): constant when the leaf is a whole number of blocks
             if count:
-                pad = SHA_CONST_BLOCK_OPS if size % 64 == 0 else (2 if size % 64 > 55 else 1) * SHA_BLOCK_OPS
-                ops += count * ((size // 64) * SHA_BLOCK_OPS + pad)
+                pad = SHA_CONST_BLOCK_MIX if size % 64 == 0 else (2 if size % 64 > 55 else 1) * SHA_BLOCK_MIX
+                mix = mix + count * ((size // 64) * SHA_BLOCK_MIX + pad)
         leaves_total += n
         if not flat:
-            ops += (n - 1) * (SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS)
+            mix = mix + (n - 1) * SHA_NODE_MIX
     top = leaves_total if flat else len(lens)
-    return ops + (max(top, 1) - 1) * (SHA_BLOCK_OPS + SHA_CONST_BLOCK_OPS)
+    return mix + (max(top, 1) - 1) * SHA_NODE_MIX
 
 
-def other_tree_ops(hash_name, lens, leaf_bytes, flat=False):
-    ops, leaves_total = 0, 0
+def sha_tree_ops(lens, leaf_bytes, flat=False):
+    return sha_tree_mix(lens, leaf_bytes, flat).total()
+
+
+def other_tree_mix(hash_name, lens, leaf_bytes, flat=False):
+    unit = B2_BLOCK_MIX if hash_name == "blake2b" else KECCAK_BLOCK_MIX
+    blocks, leaves_total = 0, 0
     for ln in lens:
         sizes = [(leaf_bytes, ln // leaf_bytes)] + ([(ln % leaf_bytes, 1)] if ln % leaf_bytes or (ln == 0 and not flat) else [])
         n = sum(c for _, c in sizes)
         for size, count in sizes:
-            per = max(1, -(-size // 128)) * B2_BLOCK_OPS if hash_name == "blake2b" else (size // 136 + 1) * KECCAK_BLOCK_OPS
-            ops += count * per
+            blocks += count * (max(1, -(-size // 128)) if hash_name == "blake2b" else size // 136 + 1)
         leaves_total += n
         if not flat:
-            ops += max(n - 1, 0) * (B2_BLOCK_OPS if hash_name == "blake2b" else KECCAK_BLOCK_OPS)
+            blocks += max(n - 1, 0)
     top = leaves_total if flat else len(lens)
-    return ops + (max(top, 1) - 1) * (B2_BLOCK_OPS if hash_name == "blake2b" else KECCAK_BLOCK_OPS)
+    return (blocks + max(top, 1) - 1) * unit
+
+
+def other_tree_ops(hash_name, lens, leaf_bytes, flat=False):
+    return other_tree_mix(hash_name, lens, leaf_bytes, flat).total()
+
+
+def lthash_mix(record_lengths):
+    import numpy as np
+    blocks = np.maximum(1, -(-np.asarray(record_lengths, dtype=np.int64) // 128))
+    return int(blocks.sum()) * B2_BLOCK_MIX + (len(record_lengths) * 32) * B2_EXPAND_MIX
 
 
 def lthash_ops(record_lengths):
-    import numpy as np
-    blocks = np.maximum(1, -(-np.asarray(record_lengths, dtype=np.int64) // 128))
-    return int(blocks.sum()) * B2_BLOCK_OPS + len(record_lengths) * 32 * B2_EXPAND_OPS
+    return lthash_mix(record_lengths).total()
+
+
+def model_lthash_mix(lens, block_bytes):
+    blocks = 0
+    for ln in lens:
+        for size, count in ((block_bytes, ln // block_bytes), (ln % block_bytes, 1 if ln % block_bytes else 0)):
+            blocks += count * (-(-(size + 8) // 128))
+    return blocks * B2_BLOCK_MIX
 
 
 def model_lthash_ops(lens, block_bytes):
-    ops = 0
-    for ln in lens:
-        for size, count in ((block_bytes, ln // block_bytes), (ln % block_bytes, 1 if ln % block_bytes else 0)):
-            ops += count * (-(-(size + 8) // 128)) * B2_BLOCK_OPS
-    return ops
+    return model_lthash_mix(lens, block_bytes).total()
 
 
 # A launch with fewer leaves (records) than lanes is bound by the serial chain of its longest leaf:
@@ -134,12 +192,71 @@ def tree_levels(n):
     return lv
 
 
-def rated(entry, ops, hbm_bytes=None):
-    """Add the fractions of the integer-ALU and HBM rooflines to a per-config entry."""
+class Timed(float):
+    """A time in ms that remembers the spread of the calls it is the median of."""
+    spread = None
+
+
+def rated(entry, mix, hbm_bytes=None):
+    """Add the roofline fractions to a per-config entry: alu_frac against the nominal integer-ALU peak
+    (instructions of the mix x 64 lanes / time / 39.32 T), issue_frac against the rate at which the chip
+    can issue this mix (issue_bound), hbm_frac against 8 TB/s (bytes hashed unless hbm_bytes is given)."""
+    if isinstance(entry["ms"], Timed) and entry["ms"].spread:
+        entry.update(entry["ms"].spread)
+        entry["ms"] = float(entry["ms"])
     sec = entry["ms"] * 1e-3
+    ops = mix.total()
+    bound = issue_bound(mix)
     entry["alu_frac"] = ops / sec / ALU_PEAK_OPS
+    entry["issue_bound_TOP/s"] = bound / 1e12
+    entry["issue_frac"] = ops / sec / bound
     entry["hbm_frac"] = (hbm_bytes if hbm_bytes is not None else entry["bytes"]) / sec / HBM_PEAK
     return entry
+
+
+def load_probe():
+    import ctypes
+    path = os.path.join(ROOT, "paper_2510_00554_amd", "libsentry_probe.so")
+    if not os.path.exists(path):
+        from paper_2510_00554_amd import build as _build
+        _build.build()
+    lib = ctypes.CDLL(path)
+    lib.sentry_probe_op_name.restype = ctypes.c_char_p
+    lib.sentry_probe_valu.argtypes = [ctypes.c_int, ctypes.c_int] + [ctypes.POINTER(ctypes.c_double)] * 3
+    return lib
+
+
+def probe_issue_rates(only=None, waves=(4,)):
+    """{opcode name: {waves per SIMD: (T lane-ops/s, shader MHz, cycles between a wave's instructions)}},
+    measured now on the current device by the probe kernels (four independent chains of one opcode)."""
+    import ctypes
+    lib = load_probe()
+    out = {}
+    for op in range(lib.sentry_probe_op_count()):
+        name = lib.sentry_probe_op_name(op).decode()
+        if only is not None and name not in only:
+            continue
+        for w in waves:
+            t, f, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+            rc = lib.sentry_probe_valu(op, w, ctypes.byref(t), ctypes.byref(f), ctypes.byref(c))
+            if rc:
+                sys.exit("bench.py: VALU probe failed on %s (HIP error %d)" % (name, rc))
+            out.setdefault(name, {})[w] = (t.value, f.value, c.value)
+    return out
+
+
+def print_valu_probe():
+    """The table behind ISSUE_RATE_TOPS (profiles/valu_issue_rates.md is one run of this)."""
+    rates = probe_issue_rates(waves=(1, 2, 4, 8))
+    print("| opcode | " + " | ".join("%d waves/SIMD: T lane-ops/s (MHz, clk/instr/wave)" % w for w in (1, 2, 4, 8)) + " |")
+    print("|---|---|---|---|---|")
+    for name, by_w in rates.items():
+        print("| %s | " % name + " | ".join("%.1f (%.0f, %.2f)" % by_w[w] for w in (1, 2, 4, 8)) + " |")
+    for label, mix in (("sha-256 block", SHA_BLOCK_MIX), ("blake2b compression", B2_BLOCK_MIX), ("keccak block", KECCAK_BLOCK_MIX)):
+        live = {k: v[4][0] for k, v in rates.items()}
+        measured = mix.total() / sum(n / live[op] for op, n in mix.items())
+        print("mix ceiling, %s: %.1f T lane-ops/s from this run's single-opcode rates at 4 waves/SIMD, %.1f from the table in bench.py"
+              % (label, measured, issue_bound(mix) / 1e12))
 
 
 def main():
@@ -155,6 +272,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip per-config and streaming side measurements")
     ap.add_argument("--merkle-prefix-gib", type=int, default=0,
                     help="hash only the first N GiB of the 70B stream (for counter runs; the workload name says so)")
+    ap.add_argument("--valu-probe", action="store_true",
+                    help="print the measured issue rate of every VALU opcode the hash kernels use, and exit")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 4 GiB device copy kernel (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -172,6 +291,12 @@ def main():
     sentry.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.valu_probe:
+        print_valu_probe()
+        return
+    # the issue rates of the opcodes in the hash kernels' mixes, measured now (a few ms each): printed
+    # beside the table the fractions are computed against, as a check on that table
+    live_rates = {k: round(v[4][0], 2) for k, v in probe_issue_rates(only=set(ISSUE_RATE_TOPS)).items()}
     stream = torch.cuda.current_stream().cuda_stream
     t_setup = time.time()
 
@@ -352,9 +477,10 @@ def main():
     full_leaves = bytes70 // LEAF70
     # the leaf kernel hashes every leaf and folds each group of 64 leaf digests (one wave) in LDS
     groups = -(-n_leaves70 // 64)
-    ops_leaf_kernel = merkle_ops(full_leaves, LEAF70, n_leaves70 - groups)
+    mix_leaf_kernel = merkle_mix(full_leaves, LEAF70, n_leaves70 - groups)
     if n_leaves70 != full_leaves:
-        ops_leaf_kernel += ((bytes70 - full_leaves * LEAF70) // 64) * SHA_BLOCK_OPS + SHA_BLOCK_OPS
+        mix_leaf_kernel = mix_leaf_kernel + ((bytes70 - full_leaves * LEAF70) // 64 + 1) * SHA_BLOCK_MIX
+    ops_leaf_kernel = mix_leaf_kernel.total()
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath) and not args.quick:
@@ -362,36 +488,46 @@ def main():
     # Inside the step the kernel shares the chip with the other two parts (unless --schedule serial or
     # pair), so its launch takes longer than it does alone while the chip as a whole does more: the
     # kernel's own figures come first, as it runs in the timed region; beside them the same launch with
-    # the chip to itself, and all the operations of the step over the step's time.
+    # the chip to itself, and all the operations of the step over the step's time.  `frac` is against the
+    # nominal peak (one instruction per SIMD per four cycles at 2.4 GHz), `issue_frac` against
+    # `issue_bound`, the rate at which the chip can issue this kernel's instruction mix.
     achieved = ops_leaf_kernel / (ms70_in_step * 1e-3)
-    ops_step = (sha_tree_ops([bytes70], LEAF70, flat=True) + sha_tree_ops(t7_lens, LEAF7) + lthash_ops(lengths[b0:b1]))
+    bound_leaf = issue_bound(mix_leaf_kernel)
+    mix_step = (sha_tree_mix([bytes70], LEAF70, flat=True) + sha_tree_mix(t7_lens, LEAF7) + lthash_mix(lengths[b0:b1]))
+    ops_step, bound_step = mix_step.total(), issue_bound(mix_step)
     roofline = {"kernel": "merkle_leaf_kernel (SHA-256 leaves + 6 in-LDS tree levels), 70B stream, 64 KiB leaves",
                 "bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_OPS / 1e12, "unit": "TOP/s",
-                "frac": achieved / ALU_PEAK_OPS, "traffic": traffic,
+                "frac": achieved / ALU_PEAK_OPS, "issue_bound": bound_leaf / 1e12, "issue_frac": achieved / bound_leaf,
+                "traffic": traffic,
                 "ms_per_launch": ms70_in_step, "algorithmic_ops_per_launch": ops_leaf_kernel,
                 "algorithmic_bytes_per_launch": bytes70 + 32 * groups,
                 "hbm_frac": (bytes70 + 32 * groups) / (ms70_in_step * 1e-3) / HBM_PEAK,
                 "shares_the_chip": args.schedule == "overlap",
                 "alone": None if ms70 is None else {"ms_per_launch": ms70, "achieved": ops_leaf_kernel / (ms70 * 1e-3) / 1e12,
-                                                    "frac": ops_leaf_kernel / (ms70 * 1e-3) / ALU_PEAK_OPS},
+                                                    "frac": ops_leaf_kernel / (ms70 * 1e-3) / ALU_PEAK_OPS,
+                                                    "issue_frac": ops_leaf_kernel / (ms70 * 1e-3) / bound_leaf},
                 "whole_step": {"algorithmic_ops": ops_step, "ms": ms_gpu_step,
                                "achieved": ops_step / (ms_gpu_step * 1e-3) / 1e12,
-                               "frac": ops_step / (ms_gpu_step * 1e-3) / ALU_PEAK_OPS}}
+                               "frac": ops_step / (ms_gpu_step * 1e-3) / ALU_PEAK_OPS,
+                               "issue_bound": bound_step / 1e12,
+                               "issue_frac": ops_step / (ms_gpu_step * 1e-3) / bound_step},
+                "issue_rates_TOP/s": {"table": ISSUE_RATE_TOPS, "this_run": live_rates}}
 
-    # every entry: GB/s hashed, and the fractions of the integer-ALU roofline (algorithmic 32-bit
-    # lane-ops / time / 39.3 T) and of the HBM roofline (bytes hashed / time / 8 TB/s)
+    # every entry: GB/s hashed, and the fractions of the integer-ALU roofline (instructions of the hash's
+    # mix x 64 lanes / time: against the nominal 39.3 T and against the issue rate of that mix) and of the
+    # HBM roofline (bytes hashed / time / 8 TB/s)
     per_config = {}
     if not args.no_extras:
         per_config = {
             "C5_merkle_70b_64KiB_resident": rated({"GB/s": bytes70 / ms70 / 1e6, "ms": ms70, "bytes": bytes70},
-                                                  sha_tree_ops([bytes70], LEAF70, flat=True)),
+                                                  sha_tree_mix([bytes70], LEAF70, flat=True)),
             "C3_merkle_7b_segments_1MiB": rated({"GB/s": bytes7 / ms7 / 1e6, "ms": ms7, "bytes": bytes7,
                                                  "leaves": sum(max(1, -(-l // LEAF7)) for l in t7_lens)},
-                                                sha_tree_ops(t7_lens, LEAF7)),
+                                                sha_tree_mix(t7_lens, LEAF7)),
             "C4_lthash_one_8GB_batch_resident": rated({"GB/s": rec_bytes / mslt / 1e6, "ms": mslt, "bytes": rec_bytes,
                                                        "samples/s": n_rec / (mslt * 1e-3), "records": n_rec,
                                                        "longest_record": int(lengths[b0:b1].max())},
-                                                      lthash_ops(lengths[b0:b1])),
+                                                      lthash_mix(lengths[b0:b1])),
         }
         # the chain floors of the two chain-bound parts of the step: a full 1 MiB leaf and its tensor's tree
         # levels; the longest record of the batch
@@ -403,14 +539,15 @@ def main():
 
 
     def timed_call(fn, reps):
-        """Median time of one call in ms.  Short calls (reps >= 30) are timed in three series and the
-        best median is taken: now and then a whole series of sub-millisecond calls runs about 75 us
-        per call slower than the next one in the same process, whatever the library does."""
+        """Time of one call in ms: the median over all timed calls.  Short calls (reps >= 30) are timed in
+        three series, because now and then a whole series of sub-millisecond calls runs some 10 us per call
+        slower than the next one in the same process; the medians of the series and the fastest and slowest
+        single call go into the entry beside the overall median (rated() copies them)."""
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         fn()
         fn()
         torch.cuda.synchronize()
-        medians = []
+        series = []
         for _ in range(3 if reps >= 30 else 1):
             ts = []
             for _ in range(reps):
@@ -419,8 +556,12 @@ def main():
                 b.record()
                 b.synchronize()
                 ts.append(a.elapsed_time(b))
-            medians.append(statistics.median(ts))
-        return min(medians)
+            series.append(ts)
+        every = [t for ts in series for t in ts]
+        ms = Timed(statistics.median(every))
+        ms.spread = {"ms_min": min(every), "ms_max": max(every), "calls": len(every),
+                     "ms_series_medians": [statistics.median(ts) for ts in series]}
+        return ms
 
     streaming = None
     if not args.no_extras:
@@ -428,28 +569,28 @@ def main():
         c1 = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20, device=dev)
         ms = timed_call(lambda: sentry.sentry_merkle_root(c1.data_ptr(), c1.numel(), 4096, root7.data_ptr(), stream), 50)
         per_config["C1_merkle_16MiB_4KiB"] = chain_bound(
-            rated({"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()}, sha_tree_ops([c1.numel()], 4096, flat=True)),
+            rated({"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()}, sha_tree_mix([c1.numel()], 4096, flat=True)),
             (4096 // 64 + 1) * SHA_CONSUMER_INSTRS + tree_levels(c1.numel() // 4096) * SHA_NODE_INSTRS)
         img, ioff = wl.image_records(50_000, device=dev)
         d_ioff = torch.from_numpy(ioff.view(np.int64).copy()).to(dev)
         ms = timed_call(lambda: sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream), 50)
         per_config["C2_lthash_50k_images"] = rated({"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(),
-                                                    "samples/s": 50_000 / (ms * 1e-3)}, lthash_ops([3072] * 50_000))
+                                                    "samples/s": 50_000 / (ms * 1e-3)}, lthash_mix([3072] * 50_000))
         # the 7B checkpoint as one flat tree over all blocks of all tensors (Algorithm 3)
         ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, LEAF7, root7.data_ptr(), stream), 5)
         per_config["F3_merkle_7b_inplace_flat_1MiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
-                                                             sha_tree_ops(t7_lens, LEAF7, flat=True))
+                                                             sha_tree_mix(t7_lens, LEAF7, flat=True))
         ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, 8192, root7.data_ptr(), stream), 5)
         per_config["F3_merkle_7b_inplace_flat_8KiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
-                                                             sha_tree_ops(t7_lens, 8192, flat=True))
+                                                             sha_tree_mix(t7_lens, 8192, flat=True))
         # the three leaf functions of section 4.2.1 on the first 16 GiB of the 70B stream, 8 KiB leaves
         f4_bytes = min(bytes70, 16 << 30)
         big_root = torch.zeros(64, dtype=torch.uint8, device=dev)
         for name, hid in (("sha256", sentry.HASH_SHA256), ("blake2b", sentry.HASH_BLAKE2B), ("sha3_256", sentry.HASH_SHA3_256)):
             ms = timed_call(lambda: sentry.sentry_merkle_root_h(hid, ckpt70.data_ptr(), f4_bytes, 8192,
                                                                 big_root.data_ptr(), stream), 5)
-            ops = (sha_tree_ops([f4_bytes], 8192, flat=True) if name == "sha256"
-                   else other_tree_ops(name, [f4_bytes], 8192, flat=True))
+            ops = (sha_tree_mix([f4_bytes], 8192, flat=True) if name == "sha256"
+                   else other_tree_mix(name, [f4_bytes], 8192, flat=True))
             per_config["F4_merkle_%s_16GiB_8KiB" % name] = rated({"GB/s": f4_bytes / ms / 1e6, "ms": ms, "bytes": f4_bytes}, ops)
         # the paper's three schemes' hardest case: fragmented 7B checkpoint, per-tensor and flat trees, 8 KiB blocks
         seg_roots = torch.zeros(64 * len(t7_ptrs), dtype=torch.uint8, device=dev)
@@ -457,16 +598,16 @@ def main():
             ms = timed_call(lambda: sentry.sentry_merkle_segments_h(hid, t7_ptrs, t7_lens, 8192, seg_roots.data_ptr(),
                                                                     big_root.data_ptr(), stream), 5)
             per_config["F4_merkle_%s_7b_per_tensor_8KiB" % name] = rated(
-                {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}, other_tree_ops(name, t7_lens, 8192))
+                {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}, other_tree_mix(name, t7_lens, 8192))
             ms = timed_call(lambda: sentry.sentry_merkle_inplace_h(hid, t7_ptrs, t7_lens, 8192, big_root.data_ptr(),
                                                                    stream), 5)
             per_config["F4_merkle_%s_7b_inplace_flat_8KiB" % name] = rated(
-                {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}, other_tree_ops(name, t7_lens, 8192, flat=True))
+                {"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7}, other_tree_mix(name, t7_lens, 8192, flat=True))
         # lattice hash of the 7B checkpoint (Algorithm 4), the paper's default 8 KiB blocks
         mlanes = torch.zeros(32, dtype=torch.int16, device=dev)
         ms = timed_call(lambda: sentry.sentry_lthash_model(t7_ptrs, t7_lens, 8192, 0, mlanes.data_ptr(), stream), 5)
         per_config["F2_lthash_model_7b_8KiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
-                                                      model_lthash_ops(t7_lens, 8192))
+                                                      model_lthash_mix(t7_lens, 8192))
         # mixed-source batches (section 4.3): the same 50,000 samples spread over 1, 16 and 128 sources
         for n_src in (1, 16, 128):
             ids = torch.from_numpy((wl._words_np(wl.SEED_C2 + 7, 0, 50_000) % np.uint64(n_src)).astype(np.int32)).to(dev)
@@ -475,20 +616,20 @@ def main():
                                                                  50_000, n_src, acc.data_ptr(), stream), 30)
             per_config["F1_lthash_50k_images_%d_sources" % n_src] = rated(
                 {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
-                lthash_ops([3072] * 50_000))
+                lthash_mix([3072] * 50_000))
         # the lane sum taken alone, over digests that are already in memory (any 2048 bytes are a valid
         # digest row: the first 2 GiB of the 70B stream stand in for 2^20 of them): bound by HBM
         n_rows = min(1 << 20, bytes70 // 2048)
         ms = timed_call(lambda: sentry.sentry_lthash_sum(ckpt70.data_ptr(), n_rows, lanes.data_ptr(), stream), 20)
         per_config["L3_lane_sum_alone_%d_digests" % n_rows] = rated(
             {"GB/s": 2048 * n_rows / ms / 1e6, "ms": ms, "bytes": 2048 * n_rows, "samples/s": n_rows / (ms * 1e-3),
-             "bound": "hbm"}, 512 * n_rows)
+             "bound": "hbm"}, Mix({"v_pk_add_u16": 512 * n_rows}))
         # and the digests of the 50,000 images written out one by one (2048 bytes per sample)
         rows = torch.empty(50_000 * 2048, dtype=torch.uint8, device=dev)
         ms = timed_call(lambda: sentry.sentry_lthash_digests(img.data_ptr(), d_ioff.data_ptr(), 50_000, rows.data_ptr(), stream), 50)
         per_config["L2_digests_50k_images"] = rated(
             {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
-            lthash_ops([3072] * 50_000), hbm_bytes=img.numel() + rows.numel())
+            lthash_mix([3072] * 50_000), hbm_bytes=img.numel() + rows.numel())
         del rows
         # host-to-device streaming in the shape of configs 5 and 4: a pinned host buffer of 16 GB;
         # Merkle while loading it in 1 GiB chunks, and the lattice hash of two 8 GB batches (the

@@ -11,6 +11,9 @@ SOURCES = ["sentry_host.hip", "sha256_merkle.hip", "blake2_lthash.hip", "blake2_
 # synthetic-input fill kernels for tests and bench.py: a library of its own, not part of the product
 WORKLOADS_LIB = os.path.join(HERE, "libsentry_workloads.so")
 WORKLOADS_SOURCE = "workloads_fill.hip"
+# VALU issue-rate probe behind bench.py's roofline denominators: measurement plumbing, its own library too
+PROBE_LIB = os.path.join(HERE, "libsentry_probe.so")
+PROBE_SOURCE = "valu_probe.hip"
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
@@ -57,6 +60,13 @@ def build(verbose=False):
         sys.stderr.write(p.stdout)
         raise RuntimeError("hipcc failed on " + WORKLOADS_SOURCE)
     os.replace(tmp, WORKLOADS_LIB)
+    tmp = PROBE_LIB + ".tmp.%d" % os.getpid()
+    cmd = [hipcc()] + FLAGS + ["-shared", os.path.join(CSRC, PROBE_SOURCE), "-o", tmp]
+    p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if p.returncode != 0:
+        sys.stderr.write(p.stdout)
+        raise RuntimeError("hipcc failed on " + PROBE_SOURCE)
+    os.replace(tmp, PROBE_LIB)
     return LIB
 
 

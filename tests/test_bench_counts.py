@@ -54,6 +54,33 @@ def test_sha_tree_ops_match_a_walk_over_the_definitions():
     assert [bench.tree_levels(n) for n in (1, 2, 3, 4, 5, 64, 65, 4096)] == [0, 1, 2, 2, 3, 6, 7, 12]
 
 
+def test_instruction_mixes_and_issue_bound():
+    # totals per unit, as the hot loops compile (cross-checked against SQ_INSTS_VALU in profiles/)
+    assert bench.SHA_BLOCK_OPS == 64 * 14 + 48 * 10 + 16 + 8 == 1400
+    assert bench.SHA_CONST_BLOCK_OPS == 64 * 14 + 8 == 904
+    assert bench.B2_BLOCK_OPS == 96 * 20 + 32 == 1952          # a 64-bit add is one instruction
+    assert bench.B2_EXPAND_OPS == 1952 - 96 + 16 == 1872
+    assert bench.KECCAK_BLOCK_OPS == 24 * 190 + 34 == 4594
+    # a mix of one opcode is bound by that opcode's rate; a mix of two by their harmonic blend
+    for op, rate in bench.ISSUE_RATE_TOPS.items():
+        assert abs(bench.issue_bound(bench.Mix({op: 123})) - rate * 1e12) < 1e3
+    m = bench.Mix({"v_xor_b32": 100, "v_alignbit_b32": 100})
+    want = 200 / (100 / bench.ISSUE_RATE_TOPS["v_xor_b32"] + 100 / bench.ISSUE_RATE_TOPS["v_alignbit_b32"]) * 1e12
+    assert abs(bench.issue_bound(m) - want) < 1e3
+    # every hash's ceiling lies between its slowest and its fastest opcode, and every opcode of every
+    # mix has a measured rate
+    for mix in (bench.SHA_BLOCK_MIX, bench.SHA_CONST_BLOCK_MIX, bench.B2_BLOCK_MIX, bench.B2_EXPAND_MIX, bench.KECCAK_BLOCK_MIX):
+        rates = [bench.ISSUE_RATE_TOPS[op] for op in mix]
+        assert min(rates) * 1e12 <= bench.issue_bound(mix) <= max(rates) * 1e12
+    # mixes add and scale like the counts they stand for
+    assert (3 * bench.SHA_BLOCK_MIX + bench.SHA_CONST_BLOCK_MIX).total() == 3 * 1400 + 904
+    assert bench.sha_tree_mix([4096 * 5 + 3], 4096).total() == bench.sha_tree_ops([4096 * 5 + 3], 4096)
+    # fractions: an entry that runs exactly at its issue bound has issue_frac 1 and alu_frac = bound / nominal
+    mix = 1000 * bench.B2_BLOCK_MIX
+    e = bench.rated({"ms": mix.total() / bench.issue_bound(mix) * 1e3, "bytes": 128000}, mix)
+    assert abs(e["issue_frac"] - 1) < 1e-9 and abs(e["alu_frac"] - bench.issue_bound(mix) / bench.ALU_PEAK_OPS) < 1e-9
+
+
 def test_blake2b_and_keccak_counts():
     rng = random.Random(6)
     lens = [rng.randrange(0, 5000) for _ in range(50)] + [0, 1, 127, 128, 129, 256]

@@ -197,6 +197,13 @@ def test_bench_quick_run_prints_one_valid_line(schedule):
     assert d["n_gpus"] == 1 and d["steps"] == 2 and d["value"] > 0 and d["config"]["workload"].startswith("QUICK")
     assert d["roofline"]["bound"] == "alu" and 0 < d["roofline"]["frac"] and d["roofline"]["shares_the_chip"] == (schedule == "overlap")
     assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["cores"] == 1
+    # no entry runs faster than the chip can issue its instruction mix, nor than HBM can feed it
+    r = d["roofline"]
+    assert r["issue_bound"] > 0 and 0 < r["issue_frac"] <= 1 and 0 < r["whole_step"]["issue_frac"] <= 1
+    assert r["alone"]["issue_frac"] <= 1
+    assert set(r["issue_rates_TOP/s"]["this_run"]) == set(r["issue_rates_TOP/s"]["table"])
+    for name, e in d["per_config"].items():
+        assert 0 < e["issue_frac"] <= 1 and 0 < e["hbm_frac"] <= 1 and e["alu_frac"] <= e["issue_bound_TOP/s"] / 39.3, name
 
 
 def test_calls_can_be_captured_in_a_graph_and_replayed():
