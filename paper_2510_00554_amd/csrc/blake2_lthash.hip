@@ -507,9 +507,11 @@ lthash_order_place_kernel(const uint64_t *offsets, uint64_t n, const uint32_t *p
 
 // Lane l of every wave owns output block j = l & 31 and takes records 2*slot + (l >> 5),
 // slot = wave index, wave index + total waves, ...  part_out: one 2048-byte partial sum per
-// workgroup.
+// workgroup.  ONLY_SOURCE0: records whose source id is not 0 are left out (the one-source case of
+// the per-source sums).
+template <bool ONLY_SOURCE0>
 __global__ void __launch_bounds__(EXP_WG)
-lthash_expand_kernel(const uint64_t *h0, uint64_t n, uint32_t *part_out)
+lthash_expand_kernel(const uint64_t *h0, uint64_t n, uint32_t *part_out, const uint32_t *source_ids)
 {
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t j = lane & 31;
@@ -521,7 +523,7 @@ lthash_expand_kernel(const uint64_t *h0, uint64_t n, uint32_t *part_out)
     for (uint64_t slot = (uint64_t)blockIdx.x * EXP_WAVES + wave;; slot += total_waves) {
         if (2 * slot >= n) break;                      // wave-uniform
         const uint64_t rec = 2 * slot + (lane >> 5);
-        if (rec < n) {
+        if (rec < n && (!ONLY_SOURCE0 || source_ids[rec] == 0)) {
             uint64_t m[16];
 #pragma unroll
             for (int k = 0; k < 8; k++) { m[k] = h0[8 * rec + k]; m[8 + k] = 0; }
@@ -651,9 +653,10 @@ lthash_sum_kernel(const uint4 *rows, uint64_t n, uint4 *part_out)
 // out[g][c] = sum over the partial sums p of group g of part[p][c] (packed uint16 pairs), c < 512;
 // group g = rows [g * rows_per_group, (g + 1) * rows_per_group), g = blockIdx.y.  Each workgroup
 // owns FOLD_COLS columns; its lanes split the rows eight ways and keep eight loads in flight
-// (one at a time, 513 rows took 21 us: a load's latency per eight rows).
+// (one at a time, 513 rows took 21 us: a load's latency per eight rows).  add_to_out: the sums are
+// added to what out holds (a running sum) instead of replacing it.
 __global__ void __launch_bounds__(FOLD_WG)
-lthash_fold_kernel(const uint32_t *part, uint32_t n_part, uint32_t rows_per_group, uint16_t *out)
+lthash_fold_kernel(const uint32_t *part, uint32_t n_part, uint32_t rows_per_group, uint16_t *out, bool add_to_out)
 {
     constexpr int ROWS = FOLD_WG / FOLD_COLS;
     constexpr int AHEAD = 8;
@@ -683,6 +686,7 @@ lthash_fold_kernel(const uint32_t *part, uint32_t n_part, uint32_t rows_per_grou
             t += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
         }
         uint16_t *o = out + (uint64_t)blockIdx.y * SENTRY_LANES;
+        if (add_to_out) t += u16x2{o[2 * col], o[2 * col + 1]};
         o[2 * col] = t.x;            // 16-bit stores: out needs no more than 2-byte alignment
         o[2 * col + 1] = t.y;
     }
@@ -716,11 +720,20 @@ lthash_addsub_kernel(uint16_t *acc, const uint16_t *x)
 constexpr int SRC_WG = 256;
 constexpr uint32_t SRC_MAX_SOURCES = 4096;
 
-// tables (uint32): count[S] | start[S+1] | unit_start[S+1] | cursor[S]
+// tables (uint32), at fixed places whatever the number of sources:
+//   count[4096] | cursor[4096] | ticket (+ padding) | start[4097] | unit_start[4097]
+// count, cursor and ticket are zero between calls: the fill kernel clears them when the scratch is
+// allocated, and every call puts back to zero what it used (the last count workgroup the ticket,
+// the final fold the counts and cursors of its sources), which saves a launch per call.
+constexpr uint32_t SRC_TICKET_AT = 2 * SRC_MAX_SOURCES;
+constexpr uint32_t SRC_START_AT = SRC_TICKET_AT + 64;
+constexpr uint32_t SRC_UNIT_START_AT = SRC_START_AT + SRC_MAX_SOURCES + 1;
+constexpr uint32_t SRC_TABLE_WORDS = SRC_UNIT_START_AT + SRC_MAX_SOURCES + 1;
 __device__ __forceinline__ uint32_t *tab_count(uint32_t *t, uint32_t) { return t; }
-__device__ __forceinline__ uint32_t *tab_start(uint32_t *t, uint32_t S) { return t + S; }
-__device__ __forceinline__ uint32_t *tab_unit_start(uint32_t *t, uint32_t S) { return t + 2 * S + 1; }
-__device__ __forceinline__ uint32_t *tab_cursor(uint32_t *t, uint32_t S) { return t + 3 * S + 2; }
+__device__ __forceinline__ uint32_t *tab_cursor(uint32_t *t, uint32_t) { return t + SRC_MAX_SOURCES; }
+__device__ __forceinline__ uint32_t *tab_ticket(uint32_t *t) { return t + SRC_TICKET_AT; }
+__device__ __forceinline__ uint32_t *tab_start(uint32_t *t, uint32_t) { return t + SRC_START_AT; }
+__device__ __forceinline__ uint32_t *tab_unit_start(uint32_t *t, uint32_t) { return t + SRC_UNIT_START_AT; }
 
 __global__ void __launch_bounds__(SRC_WG)
 src_zero_kernel(uint32_t *tables, uint32_t n_words)
@@ -733,32 +746,10 @@ src_zero_kernel(uint32_t *tables, uint32_t n_words)
 constexpr int SRC_ITEMS = 8;                      // records per lane
 constexpr int SRC_TILE = SRC_WG * SRC_ITEMS;      // records per workgroup
 
-__global__ void __launch_bounds__(SRC_WG)
-src_count_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t *tables)
+// start[] = exclusive scan of count[], unit_start[] = exclusive scan of ceil(count/unit); both get a
+// closing total.  All lanes of one workgroup.
+__device__ __forceinline__ void src_plan(uint32_t S, uint32_t unit, uint32_t *tables, uint32_t *sum_c, uint32_t *sum_u)
 {
-    __shared__ uint32_t hist[SRC_MAX_SOURCES];
-    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG) hist[k] = 0;
-    __syncthreads();
-    const uint64_t tile = (uint64_t)blockIdx.x * SRC_TILE;
-#pragma unroll
-    for (int q = 0; q < SRC_ITEMS; q++) {
-        const uint64_t i = tile + (uint64_t)q * SRC_WG + threadIdx.x;
-        if (i < n) {
-            const uint32_t k = src[i];
-            if (k < S) atomicAdd(&hist[k], 1u);
-        }
-    }
-    __syncthreads();
-    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG)
-        if (hist[k]) atomicAdd(&tab_count(tables, S)[k], hist[k]);
-}
-
-// one workgroup: start[] = exclusive scan of count[], unit_start[] = exclusive scan of
-// ceil(count/unit); both get a closing total
-__global__ void __launch_bounds__(SRC_WG)
-src_plan_kernel(uint32_t S, uint32_t unit, uint32_t *tables)
-{
-    __shared__ uint32_t sum_c[SRC_WG], sum_u[SRC_WG];
     const uint32_t tid = threadIdx.x;
     const uint32_t per = (S + SRC_WG - 1) / SRC_WG;
     const uint32_t lo = tid * per, hi = lo + per < S ? lo + per : S;
@@ -791,6 +782,37 @@ src_plan_kernel(uint32_t S, uint32_t unit, uint32_t *tables)
         c += x;
         u += (x + unit - 1) / unit;
     }
+}
+
+// Counts per source; the workgroup that finishes last (a ticket counter, as in the one-launch Merkle
+// tree) turns them into the plan, so that no launch of its own is needed for that.
+__global__ void __launch_bounds__(SRC_WG)
+src_count_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t unit, uint32_t *tables)
+{
+    __shared__ uint32_t hist[SRC_MAX_SOURCES];
+    __shared__ uint32_t last;
+    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG) hist[k] = 0;
+    __syncthreads();
+    const uint64_t tile = (uint64_t)blockIdx.x * SRC_TILE;
+#pragma unroll
+    for (int q = 0; q < SRC_ITEMS; q++) {
+        const uint64_t i = tile + (uint64_t)q * SRC_WG + threadIdx.x;
+        if (i < n) {
+            const uint32_t k = src[i];
+            if (k < S) atomicAdd(&hist[k], 1u);
+        }
+    }
+    __syncthreads();
+    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG)
+        if (hist[k]) atomicAdd(&tab_count(tables, S)[k], hist[k]);
+    __threadfence();          // this workgroup's counts are visible to the device before its ticket
+    __syncthreads();
+    if (threadIdx.x == 0) last = atomicAdd(tab_ticket(tables), 1u) == gridDim.x - 1;
+    __syncthreads();
+    if (!last) return;
+    __threadfence();          // the counts of all other workgroups are read from memory, not from a stale line
+    src_plan(S, unit, tables, hist, hist + SRC_WG);
+    if (threadIdx.x == 0) *tab_ticket(tables) = 0;
 }
 
 __global__ void __launch_bounds__(SRC_WG)
@@ -883,6 +905,10 @@ lthash_fold_sources_kernel(const uint32_t *part, uint32_t S, uint32_t *tables, u
     const uint32_t row0 = threadIdx.x / FOLD_COLS;
     const uint32_t *unit_start = tab_unit_start(tables, S);
     const uint32_t u0 = unit_start[k], u1 = unit_start[k + 1];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {          // nothing reads them any more: zero for the next call
+        tab_count(tables, S)[k] = 0;
+        tab_cursor(tables, S)[k] = 0;
+    }
     if (u0 == u1) return;                               // no record of this source in the batch
     constexpr int AHEAD = 8;                            // loads in flight per lane, as in lthash_fold_kernel
     u16x2 s = u16x2{0, 0};
@@ -952,17 +978,18 @@ constexpr uint32_t FOLD_DIRECT = 640;     // up to here one launch (ten trips of
 
 static uint32_t fold_spare_rows(uint64_t n_rows) { return n_rows > FOLD_DIRECT ? (uint32_t)ceil_div(n_rows, FOLD_GROUP) : 0; }
 
-static int fold_rows(const uint32_t *rows, uint32_t n_rows, uint32_t *spare, uint16_t *out, hipStream_t s)
+static int fold_rows(const uint32_t *rows, uint32_t n_rows, uint32_t *spare, uint16_t *out, hipStream_t s,
+                     bool add_to_out = false)
 {
     if (n_rows > FOLD_DIRECT) {
         const uint32_t groups = fold_spare_rows(n_rows);
         hipLaunchKernelGGL(lthash_fold_kernel, dim3(LANE_WORDS / FOLD_COLS, groups), dim3(FOLD_WG), 0, s, rows, n_rows,
-                           FOLD_GROUP, reinterpret_cast<uint16_t *>(spare));
+                           FOLD_GROUP, reinterpret_cast<uint16_t *>(spare), false);
         rows = spare;
         n_rows = groups;
     }
     hipLaunchKernelGGL(lthash_fold_kernel, dim3(LANE_WORDS / FOLD_COLS, 1), dim3(FOLD_WG), 0, s, rows, n_rows,
-                       n_rows ? n_rows : 1u, out);
+                       n_rows ? n_rows : 1u, out, add_to_out);
     SENTRY_HIP_CHECK(hipGetLastError());
     return SENTRY_OK;
 }
@@ -977,7 +1004,7 @@ int lthash_sum_rows(const uint16_t *rows, uint32_t n_rows, uint16_t *out, hipStr
 }
 
 // Root hashes (64 bytes each) of n records at dev_records (offsets relative to offset_base).
-static int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
+int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
                         uint64_t *h0, hipStream_t s)
 {
     if (n == 0) return SENTRY_OK;
@@ -995,8 +1022,9 @@ static int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, ui
     hipLaunchKernelGGL(lthash_order_scan_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts), groups);
     hipLaunchKernelGGL(lthash_order_place_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n,
                        static_cast<const uint32_t *>(counts), static_cast<uint32_t *>(order));
-    hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
-                       static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, h0);
+    if (n > FEW_RECORDS)   // up to there the device always takes the four-lane path: nothing for this kernel to do
+        hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, h0);
     hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
                        static_cast<const uint32_t *>(order), h0);
@@ -1004,31 +1032,40 @@ static int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, ui
     return SENTRY_OK;
 }
 
-// Lattice hash of n records at dev_records (offsets relative to offset_base); result either
-// overwrites out (accumulate == false) or is added to it lane-wise.
-int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
-                uint16_t *out, bool accumulate, hipStream_t s)
+// Expansion of n root hashes and the lane sum over them, written to out or (accumulate) added to it.
+// only_source0: device array of n source ids, records with another id are left out; or NULL.
+int lthash_expand_and_fold(const uint64_t *h0, uint64_t n, const uint32_t *only_source0, uint16_t *out,
+                                  bool accumulate, hipStream_t s)
 {
-    void *h0, *part;
-    int rc = scratch_get(s, R_LT_H0, 64 * (n ? n : 1), &h0);
-    if (rc) return rc;
     // expansion grid: enough workgroups to give every SIMD two waves, no more than the work
     const uint64_t slots = ceil_div(n, 2);                        // one wave pass = two records
     uint64_t grid = ceil_div(slots, EXP_WAVES);
     const uint64_t cap = (uint64_t)cu_count() * 2;
     if (grid > cap) grid = cap;
     if (grid == 0) grid = 1;
-    const uint64_t n_part = grid + (accumulate ? 1 : 0);
-    rc = scratch_get(s, R_LT_PART, n_part * LANE_WORDS * 4, &part);
+    void *part;
+    int rc = scratch_get(s, R_LT_PART, grid * LANE_WORDS * 4, &part);
+    if (rc) return rc;
+    if (only_source0)
+        hipLaunchKernelGGL(lthash_expand_kernel<true>, dim3((uint32_t)grid), dim3(EXP_WG), 0, s, h0, n,
+                           static_cast<uint32_t *>(part), only_source0);
+    else
+        hipLaunchKernelGGL(lthash_expand_kernel<false>, dim3((uint32_t)grid), dim3(EXP_WG), 0, s, h0, n,
+                           static_cast<uint32_t *>(part), (const uint32_t *)nullptr);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return fold_rows(static_cast<const uint32_t *>(part), (uint32_t)grid, nullptr, out, s, accumulate);   // grid <= 512
+}
+
+// Lattice hash of n records at dev_records (offsets relative to offset_base); result either
+// overwrites out (accumulate == false) or is added to it lane-wise.
+int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
+                uint16_t *out, bool accumulate, hipStream_t s)
+{
+    void *h0;
+    int rc = scratch_get(s, R_LT_H0, 64 * (n ? n : 1), &h0);
     if (rc) return rc;
     if ((rc = lthash_roots(dev_records, dev_offsets, offset_base, n, static_cast<uint64_t *>(h0), s))) return rc;
-    hipLaunchKernelGGL(lthash_expand_kernel, dim3((uint32_t)grid), dim3(EXP_WG), 0, s,
-                       static_cast<const uint64_t *>(h0), n, static_cast<uint32_t *>(part));
-    SENTRY_HIP_CHECK(hipGetLastError());
-    if (accumulate)   // the running sum joins as one more partial row
-        SENTRY_HIP_CHECK(hipMemcpyAsync(static_cast<uint32_t *>(part) + grid * LANE_WORDS, out, XOF_BYTES,
-                                        hipMemcpyDefault, s));
-    return fold_rows(static_cast<const uint32_t *>(part), (uint32_t)n_part, nullptr, out, s);   // n_part <= 513
+    return lthash_expand_and_fold(static_cast<const uint64_t *>(h0), n, nullptr, out, accumulate, s);
 }
 
 }  // namespace sentry
@@ -1125,29 +1162,45 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
                    "sentry_lthash_sources: dev_source_ids must be non-NULL and 4-byte aligned");
     SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash_sources: too many records");
     const uint32_t S = (uint32_t)n_sources;
-    // records per unit: at least 32, and few enough units to keep the partial rows small
-    uint32_t unit = 32;
-    while (ceil_div(n, unit) > 8192) unit *= 2;
+    if (S == 1) {
+        // one source: nothing to sort; the plain launches, with records of other ids left out, and
+        // the lane sum added to the running sum
+        void *h0;
+        int rc1 = sentry::scratch_get(s, sentry::R_LT_H0, 64 * n, &h0);
+        if (rc1) return rc1;
+        if ((rc1 = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s))) return rc1;
+        return sentry::lthash_expand_and_fold(static_cast<const uint64_t *>(h0), n, dev_source_ids, acc_lanes, true, s);
+    }
+    // records per unit (one wave expands one unit): few enough that the launch has about four waves
+    // for every SIMD, whatever the sources' shares (with 32 and more, 50,000 records made 1563 waves
+    // for 1024 SIMDs, half of which then carried two waves and half one), and few enough units to
+    // keep the partial rows small
+    uint32_t unit = 8;
+    while (ceil_div(n, unit) > (uint64_t)cu_count() * 16) unit *= 2;
     const uint64_t max_units = ceil_div(n, unit) + S;          // every source may end in a short unit
     void *h0, *part, *tables, *perm;
     int rc;
     if ((rc = sentry::scratch_get(s, sentry::R_LT_H0, 64 * n, &h0))) return rc;
     if ((rc = sentry::scratch_get(s, sentry::R_LT_PART, max_units * LANE_WORDS * 4, &part))) return rc;
-    const uint32_t table_words = 4 * S + 2;
-    if ((rc = sentry::scratch_get(s, sentry::R_SRC_TABLES, 4 * (size_t)table_words, &tables))) return rc;
+    bool fresh_tables;
+    if ((rc = sentry::scratch_get_fresh(s, sentry::R_SRC_TABLES, 4 * (size_t)SRC_TABLE_WORDS, &tables, &fresh_tables))) return rc;
     if ((rc = sentry::scratch_get(s, sentry::R_SRC_PERM, 4 * n, &perm))) return rc;
     uint32_t *tab = static_cast<uint32_t *>(tables);
     const uint32_t *src = dev_source_ids;
     const uint32_t scan_grid = (uint32_t)ceil_div(n, SRC_TILE);
 
-    hipLaunchKernelGGL(src_zero_kernel, dim3(1), dim3(SRC_WG), 0, s, tab, table_words);
-    hipLaunchKernelGGL(src_count_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab);
-    hipLaunchKernelGGL(src_plan_kernel, dim3(1), dim3(SRC_WG), 0, s, S, unit, tab);
+    if (fresh_tables) hipLaunchKernelGGL(src_zero_kernel, dim3(1), dim3(SRC_WG), 0, s, tab, SRC_TABLE_WORDS);
+    hipLaunchKernelGGL(src_count_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, unit, tab);
     hipLaunchKernelGGL(src_scatter_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab,
                        static_cast<uint32_t *>(perm));
     SENTRY_HIP_CHECK(hipGetLastError());
     // the root hashes do not depend on the sources: the same launches as for one sum
-    if ((rc = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s))) return rc;
+    rc = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s);
+    if (rc) {   // the counts and cursors must not stay behind for the next call
+        hipLaunchKernelGGL(src_zero_kernel, dim3(1), dim3(SRC_WG), 0, s, tab, SRC_TABLE_WORDS);
+        (void)hipGetLastError();
+        return rc;
+    }
     hipLaunchKernelGGL(lthash_expand_units_kernel, dim3((uint32_t)ceil_div(max_units, EXP_WAVES)), dim3(EXP_WG), 0, s,
                        static_cast<const uint64_t *>(h0), static_cast<const uint32_t *>(perm), S, unit, tab,
                        static_cast<uint32_t *>(part));
