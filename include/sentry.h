@@ -192,9 +192,21 @@ SENTRY_API int sentry_merkle_reduce(const uint8_t *dev_nodes, size_t n, uint8_t 
  *         and releases the state after the stream has drained it.
  *         SENTRY_ERR_INVALID_ARG if fewer than total_len bytes were fed.
  * abort   releases a state without a result.
+ * update_h2d  the same as update for a chunk that still sits in host memory (section
+ *         4.4: the model is authenticated while it is loaded): the chunk is loaded
+ *         on a side stream into one of two staging buffers the library holds per
+ *         caller stream (each as large as the largest chunk fed so far) and hashed
+ *         on `stream` once it has landed, so that the load of one chunk overlaps
+ *         the hashing of the one before when the caller feeds chunks without
+ *         waiting in between.  host_chunk: host, 16-byte aligned; pinned memory is
+ *         read by a load kernel at the PCIe rate, pageable memory goes through
+ *         hipMemcpyAsync; it must stay unchanged until `stream` has passed the
+ *         update (record an event after the call to learn when).  Chunks of one
+ *         tree are fed on one stream; update and update_h2d may be mixed.
  */
 SENTRY_API int sentry_merkle_stream_begin(size_t total_len, size_t leaf_bytes, void **state);
 SENTRY_API int sentry_merkle_stream_update(void *state, const void *dev_chunk, size_t len, void *stream);
+SENTRY_API int sentry_merkle_stream_update_h2d(void *state, const void *host_chunk, size_t len, void *stream);
 SENTRY_API int sentry_merkle_stream_final(void *state, uint8_t *out_digest, void *stream);
 SENTRY_API int sentry_merkle_stream_abort(void *state);
 

@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     OK, MISMATCH, ERR_INVALID_ARG, ERR_HIP, ERR_NOMEM,
     sentry_merkle_root, sentry_merkle_root_noalloc, sentry_merkle_root_h, sentry_merkle_segments, sentry_merkle_inplace, sentry_merkle_segments_h, sentry_merkle_inplace_h,
     sentry_merkle_leaves, sentry_merkle_reduce,
-    sentry_merkle_stream_begin, sentry_merkle_stream_update, sentry_merkle_stream_final,
+    sentry_merkle_stream_begin, sentry_merkle_stream_update, sentry_merkle_stream_update_h2d, sentry_merkle_stream_final,
     sentry_merkle_stream_abort, sentry_merkle_root_h2d, sentry_verify,
     sentry_lthash, sentry_lthash_digests, sentry_lthash_sum, sentry_lthash_sources, sentry_lthash_model, sentry_lthash_combine, sentry_lthash_remove, sentry_lthash_h2d,
     sentry_last_error, sentry_release_scratch,

@@ -40,6 +40,7 @@ PROTOTYPES = {
     "sentry_merkle_reduce": (_int, [_vp, _sz, _vp, _vp]),
     "sentry_merkle_stream_begin": (_int, [_sz, _sz, ctypes.POINTER(_vp)]),
     "sentry_merkle_stream_update": (_int, [_vp, _vp, _sz, _vp]),
+    "sentry_merkle_stream_update_h2d": (_int, [_vp, _vp, _sz, _vp]),
     "sentry_merkle_stream_final": (_int, [_vp, _vp, _vp]),
     "sentry_merkle_stream_abort": (_int, [_vp]),
     "sentry_merkle_root_h2d": (_int, [_vp, _sz, _sz, _sz, _vp, _vp]),
@@ -163,6 +164,10 @@ def sentry_merkle_stream_begin(total_len, leaf_bytes):
 
 def sentry_merkle_stream_update(state, dev_chunk, length, stream=0):
     return _check(load().sentry_merkle_stream_update(state, dev_chunk, length, stream))
+
+
+def sentry_merkle_stream_update_h2d(state, host_chunk, length, stream=0):
+    return _check(load().sentry_merkle_stream_update_h2d(state, host_chunk, length, stream))
 
 
 def sentry_merkle_stream_final(state, out_digest, stream=0):

@@ -148,6 +148,16 @@ int copy_pipe_get(hipStream_t stream, bool with_hash_streams, CopyPipe **out)
     return SENTRY_OK;
 }
 
+void copy_pipe_drain(CopyPipe *pipe, bool with_hash_streams)
+{
+    if (!pipe) return;
+    (void)hipStreamSynchronize(pipe->copy_stream);
+    if (with_hash_streams)
+        for (int i = 0; i < PIPE_SLOTS - 1; i++)
+            if (pipe->hash_stream[i]) (void)hipStreamSynchronize(pipe->hash_stream[i]);
+    (void)hipGetLastError();
+}
+
 struct Retired {
     void *ptr;
     hipEvent_t done;

@@ -84,7 +84,11 @@ struct CopyPipe {
     hipEvent_t copied[PIPE_SLOTS];     // chunk k%slots has landed in its staging buffer
     hipEvent_t consumed[PIPE_SLOTS];   // the hash kernels have finished reading that staging buffer
     hipEvent_t start;                  // everything enqueued on the caller's stream before the call
+    uint64_t chunk_seq;                // chunks fed through sentry_merkle_stream_update_h2d (picks the staging slot)
 };
+// Error path of the host-streaming calls: wait (on the host) until the pipe's side streams have
+// drained, so that nothing still uses the caller stream's staging memory when the call returns.
+void copy_pipe_drain(CopyPipe *pipe, bool with_hash_streams);
 // with_hash_streams: also create the side hash streams (only the lattice call needs them;
 // streams that exist share the few hardware queues even when idle)
 int copy_pipe_get(hipStream_t stream, bool with_hash_streams, CopyPipe **out);

@@ -152,6 +152,53 @@ int sentry_merkle_stream_update(void *state, const void *dev_chunk, size_t len, 
     return SENTRY_OK;
 }
 
+int sentry_merkle_stream_update_h2d(void *state, const void *host_chunk, size_t len, void *stream)
+{
+    sentry::clear_error();
+    MerkleStream *st = static_cast<MerkleStream *>(state);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(st && st->magic == STREAM_MAGIC, "sentry_merkle_stream_update_h2d: bad state");
+    if (len == 0) return SENTRY_OK;
+    SENTRY_REQUIRE(host_chunk != nullptr && (reinterpret_cast<uintptr_t>(host_chunk) & 15) == 0,
+                   "sentry_merkle_stream_update_h2d: chunk must be non-NULL and 16-byte aligned");
+    SENTRY_REQUIRE(st->fed % st->leaf_bytes == 0,
+                   "sentry_merkle_stream_update_h2d: a chunk that is not a multiple of leaf_bytes must be the last");
+    SENTRY_REQUIRE(len <= st->total_len - st->fed, "sentry_merkle_stream_update_h2d: more than total_len bytes fed");
+    SENTRY_REQUIRE(len % st->leaf_bytes == 0 || st->fed + len == st->total_len,
+                   "sentry_merkle_stream_update_h2d: only the last chunk may end inside a leaf");
+    sentry::CopyPipe *pipe;
+    int rc = sentry::copy_pipe_get(s, false, &pipe);
+    if (rc) return rc;
+    // two staging buffers per caller stream, used in turn; growing one waits for the stream, whose
+    // hash kernels wait for the loads, so nothing is in flight on a buffer that is replaced
+    const int b = (int)(pipe->chunk_seq & 1);
+    void *stage;
+    if ((rc = sentry::scratch_get(s, b ? sentry::R_STAGE1 : sentry::R_STAGE0, len, &stage))) return rc;
+    if (st->fed == 0) {
+        // first chunk of this tree: the loads start after everything queued on the stream so far,
+        // whatever used the staging buffers before
+        SENTRY_HIP_CHECK(hipEventRecord(pipe->start, s));
+        SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->start, 0));
+    }
+    // the buffer is free once the hash of the chunk that used it last has read it
+    SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->consumed[b], 0));
+    const uint8_t *readable = kernel_readable(host_chunk, len);
+    rc = enqueue_load(static_cast<uint8_t *>(stage), static_cast<const uint8_t *>(host_chunk), readable, len, pipe->copy_stream);
+    if (rc) return rc;
+    pipe->chunk_seq++;
+    hipError_t e = hipEventRecord(pipe->copied[b], pipe->copy_stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(s, pipe->copied[b], 0);
+    if (e != hipSuccess) {   // the load is queued but the stream does not wait for it: drain it here
+        sentry::copy_pipe_drain(pipe, false);
+        SENTRY_HIP_CHECK(e);
+    }
+    uint8_t *dst = st->leaf_digests + 32 * (st->fed / st->leaf_bytes);
+    if ((rc = sentry::merkle_leaves_into(stage, len, st->leaf_bytes, dst, s))) return rc;
+    SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], s));
+    st->fed += len;
+    return SENTRY_OK;
+}
+
 int sentry_merkle_stream_final(void *state, uint8_t *out_digest, void *stream)
 {
     sentry::clear_error();
@@ -220,6 +267,9 @@ int sentry_merkle_root_h2d(const void *host_buf, size_t len, size_t leaf_bytes, 
 
     const uint8_t *src = static_cast<const uint8_t *>(host_buf);
     const uint8_t *readable = kernel_readable(host_buf, len);
+    // the enqueue loop; if it fails half way the side stream is drained before the call returns, so
+    // that no load still writes a staging buffer that a later call may replace
+    auto enqueue_all = [&]() -> int {
     size_t off = 0;
     uint64_t k = 0;
     do {
@@ -239,6 +289,12 @@ int sentry_merkle_root_h2d(const void *host_buf, size_t len, size_t leaf_bytes, 
         off += sz;
         k++;
     } while (off < len);
+    return SENTRY_OK;
+    };
+    if ((rc = enqueue_all())) {
+        sentry::copy_pipe_drain(pipe, false);
+        return rc;
+    }
     return sentry::merkle_reduce_into(static_cast<const uint8_t *>(digests), n_leaves, out_digest, s);
 }
 
@@ -307,6 +363,7 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
     const uint64_t lo = host_offsets[0], hi = host_offsets[n];
     const uint8_t *readable = hi > lo ? kernel_readable(src + lo, hi - lo) : nullptr;   // view of src + lo
     const uint8_t *off_readable = kernel_readable(host_offsets, 8 * (n + 1));
+    auto enqueue_all = [&]() -> int {
     for (size_t k = 0; k < batches.size(); k++) {
         const Batch &bt = batches[k];
         const int b = (int)(k % NS);
@@ -333,6 +390,14 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
         SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], hs));
     }
     for (int i = 1; i < used; i++) SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->consumed[i], 0));
+    return SENTRY_OK;
+    };
+    // a failure half way leaves loads and hashes queued on the side streams that the caller's stream
+    // does not wait for: drain them before returning, they use this stream's staging memory
+    if ((rc = enqueue_all())) {
+        sentry::copy_pipe_drain(pipe, true);
+        return rc;
+    }
     return sentry::lthash_sum_rows(static_cast<const uint16_t *>(sums), (uint32_t)used, out_lanes, s);
 }
 

@@ -121,35 +121,35 @@ def test_config5_70b_checkpoint_resident_and_streamed():
         torch.cuda.synchronize()
         assert bytes(d.cpu().numpy()) == dig, i
     print("config 5: resident root ok", flush=True)
-    # streamed: pinned host chunks copied on a side stream into two device buffers, each hashed
-    # on the main stream while the next one loads; compared with the stored root
+    # streamed through the library's own load path: 1 GiB chunks in two pinned host buffers, fed to
+    # sentry_merkle_stream_update_h2d, which loads chunk k on its side stream into its own staging
+    # buffers while chunk k - 1 is hashed; no host wait per chunk except the one a two-buffer
+    # reader needs anyway (buffer b is refilled once the update that read it has passed)
     chunk = 1 << 30
     host = [torch.empty(chunk, dtype=torch.uint8).pin_memory() for _ in range(2)]
-    stage = [torch.empty(chunk, dtype=torch.uint8, device="cuda") for _ in range(2)]
-    copy_stream = torch.cuda.Stream()
     main = torch.cuda.current_stream()
-    copied = [torch.cuda.Event() for _ in range(2)]
-    hashed = [torch.cuda.Event() for _ in range(2)]
+    fill = torch.cuda.Stream()                        # stands in for the reader that fills pinned memory
+    loaded = [torch.cuda.Event() for _ in range(2)]   # update k has passed: host[b] may be refilled
+    filled = [torch.cuda.Event() for _ in range(2)]
     st = sentry.sentry_merkle_stream_begin(total, leaf)
     pos, k = 0, 0
     while pos < total:
         n = min(chunk, total - pos)
         b = k & 1
-        hashed[b].synchronize()                        # host buffer b and stage b are free again
-        host[b][:n].copy_(buf[pos:pos + n])            # stands in for reading the file into pinned memory
-        torch.cuda.synchronize()
-        with torch.cuda.stream(copy_stream):
-            stage[b][:n].copy_(host[b][:n], non_blocking=True)
-            copied[b].record(copy_stream)
-        main.wait_event(copied[b])
-        sentry.sentry_merkle_stream_update(st, stage[b].data_ptr(), n, main.cuda_stream)
-        hashed[b].record(main)
+        with torch.cuda.stream(fill):
+            fill.wait_event(loaded[b])
+            host[b][:n].copy_(buf[pos:pos + n], non_blocking=True)
+            filled[b].record(fill)
+        filled[b].synchronize()                        # the chunk is in host memory: hand it to the library
+        sentry.sentry_merkle_stream_update_h2d(st, host[b].data_ptr(), n, main.cuda_stream)
+        loaded[b].record(main)
         pos += n
         k += 1
     sentry.sentry_merkle_stream_final(st, out.data_ptr(), main.cuda_stream)
     torch.cuda.synchronize()
-    assert sentry.sentry_verify(bytes(out.cpu().numpy()), want) == 0
-    del buf, host, stage
+    assert k == 129 and sentry.sentry_verify(bytes(out.cpu().numpy()), want) == 0
+    print("config 5: streamed root ok (%d chunks)" % k, flush=True)
+    del buf, host
     free_gpu()
 
 

@@ -35,6 +35,80 @@ def test_stream_api_equals_one_shot(total, leaf, chunks):
     assert bytes(out.cpu().numpy()) == want
 
 
+@pytest.mark.parametrize("total,leaf,chunks,pinned", [
+    (4096 * 10 + 100, 4096, [4096 * 4, 4096 * 6 + 100], True),
+    (4096 * 12, 4096, [4096] * 12, True),                       # both staging buffers reused many times
+    (64 * 1000 + 1, 64, [64 * 256, 64 * 300, 64 * 444 + 1], True),
+    ((3 << 20) + 77, 65536, [1 << 20, 1 << 16, 1 << 20, (1 << 20) - (1 << 16) + 77], True),   # growing and shrinking chunks
+    (4096 * 10 + 100, 4096, [4096 * 4, 4096 * 6 + 100], False),  # pageable host memory
+    (100, 4096, [100], True),
+])
+def test_stream_update_h2d_equals_one_shot(total, leaf, chunks, pinned):
+    buf = wl.uniform_bytes(2050 + total % 13, 0, total)
+    want = oracle.merkle_root(buf, leaf)
+    host = torch.from_numpy(buf.copy())
+    if pinned:
+        host = host.pin_memory()
+    s = torch.cuda.Stream()
+    st = sentry.sentry_merkle_stream_begin(total, leaf)
+    pos = 0
+    for c in chunks:      # fed back to back, no host wait in between: the chunks stay in place
+        sentry.sentry_merkle_stream_update_h2d(st, host.data_ptr() + pos, c, s.cuda_stream)
+        pos += c
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_stream_final(st, out.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    assert bytes(out.cpu().numpy()) == want
+
+
+def test_stream_update_h2d_mixed_with_device_chunks_and_two_trees_on_one_stream():
+    # two trees fed in turn on one stream share that stream's two staging buffers; one of them also
+    # takes a chunk that is already on the device
+    leaf = 4096
+    bufs = [wl.uniform_bytes(2060 + i, 0, leaf * 9 + 11 * i) for i in range(2)]
+    hosts = [torch.from_numpy(b.copy()).pin_memory() for b in bufs]
+    dev1 = to_dev(bufs[1][leaf * 3:leaf * 6])
+    sts = [sentry.sentry_merkle_stream_begin(b.size, leaf) for b in bufs]
+    for part in range(3):
+        lo = leaf * 3 * part
+        for i in range(2):
+            n = (bufs[i].size - lo) if part == 2 else leaf * 3
+            if i == 1 and part == 1:
+                sentry.sentry_merkle_stream_update(sts[i], dev1.data_ptr(), n)
+            else:
+                sentry.sentry_merkle_stream_update_h2d(sts[i], hosts[i].data_ptr() + lo, n)
+    outs = [torch.zeros(32, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    for i in range(2):
+        sentry.sentry_merkle_stream_final(sts[i], outs[i].data_ptr())
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert bytes(outs[i].cpu().numpy()) == oracle.merkle_root(bufs[i], leaf), i
+
+
+def test_merkle_root_h2d_in_the_shape_of_config_5():
+    # 64 KiB leaves, 1 GiB chunks, three chunks and a ragged fourth from pinned memory, so that both
+    # staging buffers are used twice; no host synchronisation while the call's pipeline runs
+    leaf, chunk = 64 << 10, 1 << 30
+    total = 3 * chunk + 5 * leaf + 12345
+    d = wl.uniform_bytes(2070, 0, total, device="cuda")
+    host = torch.empty(total, dtype=torch.uint8).pin_memory()
+    host.copy_(d)
+    a = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    b = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_root_h2d(host.data_ptr(), total, leaf, chunk, a.data_ptr())
+    sentry.sentry_merkle_root(d.data_ptr(), total, leaf, b.data_ptr())
+    torch.cuda.synchronize()
+    assert bytes(a.cpu().numpy()) == bytes(b.cpu().numpy())
+    # and against the oracle on the leaves it can afford: first, last (ragged) and one across a chunk seam
+    leaves = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    for i in (0, chunk // leaf, total // leaf):
+        n = min(leaf, total - i * leaf)
+        sentry.sentry_merkle_leaves(d.data_ptr() + i * leaf, n, leaf, leaves.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(leaves.cpu().numpy()) == oracle.sha256(d[i * leaf:i * leaf + n].cpu().numpy()), i
+    del d, host
+
+
 def test_stream_api_misuse():
     st = sentry.sentry_merkle_stream_begin(4096 * 4, 4096)
     d = torch.zeros(4096 * 4, dtype=torch.uint8, device="cuda")
@@ -48,6 +122,11 @@ def test_stream_api_misuse():
     st = sentry.sentry_merkle_stream_begin(4096, 4096)
     with pytest.raises(sentry.SentryError):
         sentry.sentry_merkle_stream_update(st, d.data_ptr(), 8192)        # more than announced
+    h = torch.zeros(8192, dtype=torch.uint8).pin_memory()
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_merkle_stream_update_h2d(st, h.data_ptr(), 8192)    # more than announced, host chunk
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_merkle_stream_update_h2d(st, h.data_ptr() + 8, 4096)    # misaligned host chunk
     sentry.sentry_merkle_stream_abort(st)
 
 
