@@ -323,6 +323,35 @@ SENTRY_API int sentry_lthash_h2d(const void *host_records, const uint64_t *host_
                       size_t batch_bytes, uint16_t *out_lanes, void *stream);
 
 /*
+ * The running sum over a dataset that arrives batch by batch from host memory
+ * (section 4.3: the digest of every batch is added to a running sum; section 4.4:
+ * while the data is loaded).  The same pipeline as sentry_lthash_h2d, fed one
+ * batch per call, so that the host needs to hold only the batches in flight:
+ * batch k is loaded on a side stream into one of three staging buffers (held per
+ * caller stream, each as large as the largest batch fed so far) and hashed on
+ * one of three streams while batches k+1 and k+2 load, each stream keeping its
+ * own running sum.
+ * begin       creates the state (an opaque handle owned by the library).
+ * update_h2d  feeds n records: record i = host_records[host_offsets[i],
+ *             host_offsets[i+1]), offsets as for sentry_lthash but in host memory
+ *             (n+1 of them, 8-byte aligned).  Pinned memory is read by the load
+ *             kernel at the PCIe rate; pageable memory goes through hipMemcpyAsync.
+ *             Both host arrays must stay unchanged until `stream` has passed the
+ *             call (it waits for the batch's load, not for its hash).  All batches
+ *             of one state are fed on one stream.  n == 0 does nothing.
+ * final       waits on `stream` for the hashes still running on the side streams,
+ *             writes the sum over all records fed to out_lanes (device-accessible,
+ *             1024 uint16; all zero if nothing was fed) and releases the state.
+ * abort       releases a state without a result (synchronises the device).
+ * The result equals sentry_lthash over all the records in any order.
+ */
+SENTRY_API int sentry_lthash_stream_begin(void **state);
+SENTRY_API int sentry_lthash_stream_update_h2d(void *state, const void *host_records, const uint64_t *host_offsets,
+                                               size_t n, void *stream);
+SENTRY_API int sentry_lthash_stream_final(void *state, uint16_t *out_lanes, void *stream);
+SENTRY_API int sentry_lthash_stream_abort(void *state);
+
+/*
  * Lattice hash of a model (section 4.2.2, Algorithm 4).  The blocks of all
  * tensors, in tensor order, are numbered 0, 1, 2, ... across the model; block k
  * (block_bytes bytes, the last block of a tensor may be short, a tensor of

@@ -53,6 +53,10 @@ PROTOTYPES = {
     "sentry_lthash_combine": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_remove": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_h2d": (_int, [_vp, _vp, _sz, _sz, _vp, _vp]),
+    "sentry_lthash_stream_begin": (_int, [ctypes.POINTER(_vp)]),
+    "sentry_lthash_stream_update_h2d": (_int, [_vp, _vp, _vp, _sz, _vp]),
+    "sentry_lthash_stream_final": (_int, [_vp, _vp, _vp]),
+    "sentry_lthash_stream_abort": (_int, [_vp]),
     "sentry_last_error": (ctypes.c_char_p, []),
     "sentry_release_scratch": (_int, []),
 }
@@ -226,3 +230,21 @@ def sentry_lthash_remove(acc, x, stream=0):
 
 def sentry_lthash_h2d(host_records, host_offsets, n, batch_bytes, out_lanes, stream=0):
     return _check(load().sentry_lthash_h2d(host_records, host_offsets, n, batch_bytes, out_lanes, stream))
+
+
+def sentry_lthash_stream_begin():
+    state = ctypes.c_void_p()
+    _check(load().sentry_lthash_stream_begin(ctypes.byref(state)))
+    return state
+
+
+def sentry_lthash_stream_update_h2d(state, host_records, host_offsets, n, stream=0):
+    return _check(load().sentry_lthash_stream_update_h2d(state, host_records, host_offsets, n, stream))
+
+
+def sentry_lthash_stream_final(state, out_lanes, stream=0):
+    return _check(load().sentry_lthash_stream_final(state, out_lanes, stream))
+
+
+def sentry_lthash_stream_abort(state):
+    return _check(load().sentry_lthash_stream_abort(state))

@@ -50,6 +50,15 @@ int scratch_get(hipStream_t stream, Region r, size_t bytes, void **out)
     return scratch_get_fresh(stream, r, bytes, out, &fresh);
 }
 
+size_t scratch_capacity(hipStream_t stream, Region r)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    auto it = g_ctx.find(std::make_pair(dev, stream));
+    return it == g_ctx.end() ? 0 : it->second.cap[r];
+}
+
 int scratch_get_fresh(hipStream_t stream, Region r, size_t bytes, void **out, bool *fresh)
 {
     std::lock_guard<std::mutex> lock(g_mu);

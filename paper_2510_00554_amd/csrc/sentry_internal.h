@@ -64,6 +64,8 @@ enum Region {
 // Returns a device pointer of at least `bytes` bytes for (current device, stream, region).
 // Growing a region frees the old allocation, which synchronises the device.
 int scratch_get(hipStream_t stream, Region r, size_t bytes, void **out);
+// Bytes the region holds now (0 if it was never allocated).
+size_t scratch_capacity(hipStream_t stream, Region r);
 // The same; *fresh is set when the memory was allocated by this call (its contents are undefined).
 int scratch_get_fresh(hipStream_t stream, Region r, size_t bytes, void **out, bool *fresh);
 

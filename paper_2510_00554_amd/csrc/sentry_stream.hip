@@ -99,6 +99,94 @@ constexpr uint64_t STREAM_MAGIC = 0x53454e5452594d53ull;
 
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
+// ---------------------------------------------------------------------------
+// Lattice hash of batches that arrive from host memory: the pipeline behind sentry_lthash_h2d and
+// sentry_lthash_stream_*.  Up to three batches are in flight: each has a staging buffer (held in
+// the caller stream's scratch) and a stream of its own (the caller's stream for slot 0, a side
+// stream for the others), so the hash of batch k (bound by its longest record, most of the chip
+// idle) overlaps the loads and hashes of batches k+1 and k+2.  Slot i keeps a running sum of its
+// batches; the caller's stream adds the sums at the end.
+// ---------------------------------------------------------------------------
+constexpr int LT_SLOTS = sentry::PIPE_SLOTS;
+static_assert(LT_SLOTS == 3, "three staging regions exist");
+const sentry::Region LT_STAGE_R[3] = {sentry::R_STAGE0, sentry::R_STAGE1, sentry::R_STAGE2};
+const sentry::Region LT_OFF_R[3] = {sentry::R_STAGE_OFF0, sentry::R_STAGE_OFF1, sentry::R_STAGE_OFF2};
+
+struct LtStream {
+    uint64_t magic;
+    uint64_t batches;              // batches fed so far: batch k goes to slot k % 3
+    uint16_t *sums;                // device, one row of 1024 lanes per slot
+    bool owns_sums;                // allocated by begin (else scratch of the one-call entry point)
+    hipStream_t stream;            // the caller's stream, fixed by the first update
+    sentry::CopyPipe *pipe;
+};
+constexpr uint64_t LT_STREAM_MAGIC = 0x53454e5452594c54ull;
+
+// Feed one batch: n records, record i = host_records[host_offsets[i] .. host_offsets[i+1]).
+int lt_stream_feed(LtStream *st, const uint8_t *host_records, const uint64_t *host_offsets, size_t n, hipStream_t s)
+{
+    if (n == 0) return SENTRY_OK;
+    int rc;
+    if (st->batches == 0) {
+        st->stream = s;
+        if ((rc = sentry::copy_pipe_get(s, true, &st->pipe))) return rc;
+    }
+    SENTRY_REQUIRE(st->stream == s, "lattice stream: all batches of one running sum are fed on one stream");
+    sentry::CopyPipe *pipe = st->pipe;
+    const int b = (int)(st->batches % LT_SLOTS);
+    hipStream_t hs = b == 0 ? s : pipe->hash_stream[b - 1];
+    const uint64_t beg = host_offsets[0], end = host_offsets[n];
+    // spare bytes: a batch sits at the same offset modulo 16 as in host memory, and the hash kernel
+    // reads the whole aligned word that holds a record's last byte
+    const size_t need = (end - beg) + 32, need_off = 8 * (n + 1) + 16;
+    if (sentry::scratch_capacity(s, LT_STAGE_R[b]) < need || sentry::scratch_capacity(s, LT_OFF_R[b]) < need_off)
+        sentry::copy_pipe_drain(pipe, true);   // a buffer is replaced: nothing on the side streams may still use it
+    void *stage, *stage_off;
+    if ((rc = sentry::scratch_get(s, LT_STAGE_R[b], need, &stage))) return rc;
+    if ((rc = sentry::scratch_get(s, LT_OFF_R[b], need_off, &stage_off))) return rc;
+    if ((rc = sentry::lthash_presize(n, hs))) return rc;
+    if (st->batches == 0) {
+        // nothing of this running sum may start before earlier work on the caller's stream is done
+        // with the staging buffers (a previous call ends on that stream)
+        SENTRY_HIP_CHECK(hipEventRecord(pipe->start, s));
+        SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->start, 0));
+        for (int i = 0; i < LT_SLOTS - 1; i++) SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->hash_stream[i], pipe->start, 0));
+    }
+    // the staging buffer is free once the last hash that read it is done (whichever running sum it
+    // belonged to; an event that was never recorded does not hold anything up)
+    SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->consumed[b], 0));
+    const uint8_t *readable = end > beg ? kernel_readable(host_records + beg, end - beg) : nullptr;
+    const uint8_t *off_readable = kernel_readable(host_offsets, 8 * (n + 1));
+    // the batch keeps its alignment modulo 16, so that the load moves whole aligned words
+    const uint8_t *from = readable ? readable : host_records + beg;
+    uint8_t *to = static_cast<uint8_t *>(stage) + (reinterpret_cast<uintptr_t>(from) & 15);
+    if ((rc = enqueue_load(to, host_records + beg, readable, end - beg, pipe->copy_stream))) return rc;
+    // the offsets of the batch, staged at the same offset modulo 16 as in host memory (0 or 8)
+    const uint8_t *off_from = off_readable ? off_readable : reinterpret_cast<const uint8_t *>(host_offsets);
+    uint8_t *off_to = static_cast<uint8_t *>(stage_off) + (reinterpret_cast<uintptr_t>(off_from) & 15);
+    if ((rc = enqueue_load(off_to, reinterpret_cast<const uint8_t *>(host_offsets), off_readable, 8 * (n + 1), pipe->copy_stream)))
+        return rc;
+    SENTRY_HIP_CHECK(hipEventRecord(pipe->copied[b], pipe->copy_stream));
+    SENTRY_HIP_CHECK(hipStreamWaitEvent(hs, pipe->copied[b], 0));
+    // the caller's stream passes this call once the batch has left host memory
+    if (hs != s) SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->copied[b], 0));
+    // record i of the batch sits at to + (offset[i] - beg); the kernel copes with any byte alignment
+    rc = sentry::lthash_into(to, reinterpret_cast<const uint64_t *>(off_to), beg, n,
+                             st->sums + (size_t)b * SENTRY_LANES, st->batches >= (uint64_t)LT_SLOTS, hs);
+    if (rc) return rc;
+    SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], hs));
+    st->batches++;
+    return SENTRY_OK;
+}
+
+// Join the side streams and write the sum over everything fed to out_lanes.
+int lt_stream_finish(LtStream *st, uint16_t *out_lanes, hipStream_t s)
+{
+    const int used = st->batches < (uint64_t)LT_SLOTS ? (int)st->batches : LT_SLOTS;
+    for (int i = 1; i < used; i++) SENTRY_HIP_CHECK(hipStreamWaitEvent(s, st->pipe->consumed[i], 0));
+    return sentry::lthash_sum_rows(st->sums, (uint32_t)used, out_lanes, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -329,76 +417,111 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
         i = j;
     }
 
-    // Up to three batches are in flight: each has a staging buffer and a stream of its own (the
-    // caller's stream for slot 0, a side stream for the others), so the hash of batch k (bound by
-    // its longest record, most of the chip idle) overlaps the copies and hashes of batches k+1
-    // and k+2.  Slot i keeps a running sum of its batches; the caller's stream adds the sums at
-    // the end.
-    constexpr int NS = sentry::PIPE_SLOTS;
-    static_assert(NS <= 3, "three staging regions exist");
-    static const sentry::Region stage_r[3] = {sentry::R_STAGE0, sentry::R_STAGE1, sentry::R_STAGE2};
-    static const sentry::Region off_r[3] = {sentry::R_STAGE_OFF0, sentry::R_STAGE_OFF1, sentry::R_STAGE_OFF2};
-    const int used = batches.size() < (size_t)NS ? (int)batches.size() : NS;
-    void *stage[NS], *stage_off[NS], *sums;
-    hipStream_t hstream[NS];
+    // pre-size everything for the largest batch, so that no buffer is replaced while the pipeline runs
+    void *p, *sums;
     int rc;
     sentry::CopyPipe *pipe;
     if ((rc = sentry::copy_pipe_get(s, true, &pipe))) return rc;
+    const int used = batches.size() < (size_t)LT_SLOTS ? (int)batches.size() : LT_SLOTS;
+    for (int i = 0; i < used; i++)
+        if (sentry::scratch_capacity(s, LT_STAGE_R[i]) < max_bytes + 32 ||
+            sentry::scratch_capacity(s, LT_OFF_R[i]) < 8 * (max_count + 1) + 16) {
+            sentry::copy_pipe_drain(pipe, true);   // a buffer will be replaced: the side streams must be done with it
+            break;
+        }
     for (int i = 0; i < used; i++) {
-        // spare bytes: a batch sits at the same offset modulo 16 as in host memory, and the hash
-        // kernel reads the whole aligned word that holds a record's last byte
-        if ((rc = sentry::scratch_get(s, stage_r[i], max_bytes + 32, &stage[i]))) return rc;
-        if ((rc = sentry::scratch_get(s, off_r[i], 8 * (max_count + 1) + 16, &stage_off[i]))) return rc;
-        hstream[i] = i == 0 ? s : pipe->hash_stream[i - 1];
-        if ((rc = sentry::lthash_presize(max_count, hstream[i]))) return rc;   // no regrowth in the pipeline
+        if ((rc = sentry::scratch_get(s, LT_STAGE_R[i], max_bytes + 32, &p))) return rc;
+        if ((rc = sentry::scratch_get(s, LT_OFF_R[i], 8 * (max_count + 1) + 16, &p))) return rc;
+        if ((rc = sentry::lthash_presize(max_count, i == 0 ? s : pipe->hash_stream[i - 1]))) return rc;
     }
-    if ((rc = sentry::scratch_get(s, sentry::R_LT_SUM, (size_t)NS * 2 * SENTRY_LANES, &sums))) return rc;
-    // nothing of this call may start before earlier work on the caller's stream is done with
-    // the staging buffers and the sums (a previous call ends on that stream)
-    SENTRY_HIP_CHECK(hipEventRecord(pipe->start, s));
-    SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->start, 0));
-    for (int i = 1; i < used; i++) SENTRY_HIP_CHECK(hipStreamWaitEvent(hstream[i], pipe->start, 0));
-
+    if ((rc = sentry::scratch_get(s, sentry::R_LT_SUM, (size_t)LT_SLOTS * 2 * SENTRY_LANES, &sums))) return rc;
+    LtStream st = {LT_STREAM_MAGIC, 0, static_cast<uint16_t *>(sums), false, s, nullptr};
     const uint8_t *src = static_cast<const uint8_t *>(host_records);
-    const uint64_t lo = host_offsets[0], hi = host_offsets[n];
-    const uint8_t *readable = hi > lo ? kernel_readable(src + lo, hi - lo) : nullptr;   // view of src + lo
-    const uint8_t *off_readable = kernel_readable(host_offsets, 8 * (n + 1));
-    auto enqueue_all = [&]() -> int {
-    for (size_t k = 0; k < batches.size(); k++) {
-        const Batch &bt = batches[k];
-        const int b = (int)(k % NS);
-        hipStream_t hs = hstream[b];
-        const uint64_t beg = host_offsets[bt.first], end = host_offsets[bt.first + bt.count];
-        if (k >= (size_t)NS) SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->consumed[b], 0));
-        // the batch keeps its alignment modulo 16, so that the load moves whole aligned words
-        const uint8_t *from = readable ? readable + (beg - lo) : src + beg;
-        uint8_t *to = static_cast<uint8_t *>(stage[b]) + (reinterpret_cast<uintptr_t>(from) & 15);
-        if ((rc = enqueue_load(to, src + beg, readable ? from : nullptr, end - beg, pipe->copy_stream))) return rc;
-        // the offsets of the batch, staged at the same offset modulo 16 as in host memory (0 or 8)
-        const uint8_t *off_from = off_readable ? off_readable + 8 * bt.first : reinterpret_cast<const uint8_t *>(host_offsets + bt.first);
-        uint8_t *off_to = static_cast<uint8_t *>(stage_off[b]) + (reinterpret_cast<uintptr_t>(off_from) & 15);
-        if ((rc = enqueue_load(off_to, reinterpret_cast<const uint8_t *>(host_offsets + bt.first),
-                               off_readable ? off_from : nullptr, 8 * (bt.count + 1), pipe->copy_stream)))
+    for (const Batch &bt : batches) {
+        // a failure half way leaves loads and hashes queued on the side streams that the caller's
+        // stream does not wait for: drain them before returning, they use this stream's staging memory
+        if ((rc = lt_stream_feed(&st, src, host_offsets + bt.first, bt.count, s))) {
+            sentry::copy_pipe_drain(pipe, true);
             return rc;
-        SENTRY_HIP_CHECK(hipEventRecord(pipe->copied[b], pipe->copy_stream));
-        SENTRY_HIP_CHECK(hipStreamWaitEvent(hs, pipe->copied[b], 0));
-        // record i of the batch sits at to + (offset[i] - beg); the kernel copes with any
-        // byte alignment of a record
-        rc = sentry::lthash_into(to, reinterpret_cast<const uint64_t *>(off_to), beg, bt.count,
-                                 static_cast<uint16_t *>(sums) + (size_t)b * SENTRY_LANES, k >= (size_t)NS, hs);
-        if (rc) return rc;
-        SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], hs));
+        }
     }
-    for (int i = 1; i < used; i++) SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->consumed[i], 0));
-    return SENTRY_OK;
-    };
-    // a failure half way leaves loads and hashes queued on the side streams that the caller's stream
-    // does not wait for: drain them before returning, they use this stream's staging memory
-    if ((rc = enqueue_all())) {
+    if ((rc = lt_stream_finish(&st, out_lanes, s))) {
         sentry::copy_pipe_drain(pipe, true);
         return rc;
     }
-    return sentry::lthash_sum_rows(static_cast<const uint16_t *>(sums), (uint32_t)used, out_lanes, s);
+    return SENTRY_OK;
+}
+
+int sentry_lthash_stream_begin(void **state)
+{
+    sentry::clear_error();
+    SENTRY_REQUIRE(state != nullptr, "sentry_lthash_stream_begin: NULL state");
+    LtStream *st = new (std::nothrow) LtStream();
+    if (!st) { sentry::set_error("sentry_lthash_stream_begin: out of host memory"); return SENTRY_ERR_NOMEM; }
+    (void)sentry::sweep_retired();
+    void *p = nullptr;
+    const hipError_t e = hipMalloc(&p, (size_t)LT_SLOTS * 2 * SENTRY_LANES);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        sentry::set_error("sentry_lthash_stream_begin: %s", hipGetErrorString(e));
+        delete st;
+        return SENTRY_ERR_NOMEM;
+    }
+    *st = LtStream{LT_STREAM_MAGIC, 0, static_cast<uint16_t *>(p), true, nullptr, nullptr};
+    *state = st;
+    return SENTRY_OK;
+}
+
+int sentry_lthash_stream_update_h2d(void *state, const void *host_records, const uint64_t *host_offsets, size_t n,
+                                    void *stream)
+{
+    sentry::clear_error();
+    LtStream *st = static_cast<LtStream *>(state);
+    SENTRY_REQUIRE(st && st->magic == LT_STREAM_MAGIC, "sentry_lthash_stream_update_h2d: bad state");
+    if (n == 0) return SENTRY_OK;
+    SENTRY_REQUIRE(host_offsets != nullptr && (reinterpret_cast<uintptr_t>(host_offsets) & 7) == 0,
+                   "sentry_lthash_stream_update_h2d: host_offsets must be non-NULL and 8-byte aligned");
+    SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash_stream_update_h2d: too many records");
+    SENTRY_REQUIRE(host_offsets[n] >= host_offsets[0], "sentry_lthash_stream_update_h2d: offsets decrease");
+    SENTRY_REQUIRE(host_records != nullptr || host_offsets[n] == host_offsets[0], "sentry_lthash_stream_update_h2d: NULL records");
+    const int rc = lt_stream_feed(st, static_cast<const uint8_t *>(host_records), host_offsets, n, static_cast<hipStream_t>(stream));
+    if (rc && st->pipe) sentry::copy_pipe_drain(st->pipe, true);
+    return rc;
+}
+
+int sentry_lthash_stream_final(void *state, uint16_t *out_lanes, void *stream)
+{
+    sentry::clear_error();
+    LtStream *st = static_cast<LtStream *>(state);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(st && st->magic == LT_STREAM_MAGIC, "sentry_lthash_stream_final: bad state");
+    SENTRY_REQUIRE(out_lanes != nullptr && (reinterpret_cast<uintptr_t>(out_lanes) & 1) == 0,
+                   "sentry_lthash_stream_final: out_lanes must be non-NULL and 2-byte aligned");
+    SENTRY_REQUIRE(st->batches == 0 || st->stream == s, "sentry_lthash_stream_final: not the stream the batches were fed on");
+    int rc;
+    if (st->batches == 0) {
+        rc = sentry::lthash_sum_rows(st->sums, 0, out_lanes, s);     // nothing fed: all-zero lanes
+    } else if ((rc = lt_stream_finish(st, out_lanes, s))) {
+        sentry::copy_pipe_drain(st->pipe, true);
+    }
+    if (rc) return rc;
+    // the sums are still read by the kernel just queued: freed once the stream has passed this point
+    rc = sentry::retire_device_memory(st->sums, s);
+    st->magic = 0;
+    delete st;
+    return rc;
+}
+
+int sentry_lthash_stream_abort(void *state)
+{
+    sentry::clear_error();
+    LtStream *st = static_cast<LtStream *>(state);
+    SENTRY_REQUIRE(st && st->magic == LT_STREAM_MAGIC, "sentry_lthash_stream_abort: bad state");
+    SENTRY_HIP_CHECK(hipDeviceSynchronize());
+    if (st->owns_sums) SENTRY_HIP_CHECK(hipFree(st->sums));
+    st->magic = 0;
+    delete st;
+    return SENTRY_OK;
 }
 
 }  // extern "C"

@@ -100,6 +100,10 @@ def test_stream_state_checks():
         sentry.sentry_merkle_stream_update(None, 0x1000, 64)
     with pytest.raises(sentry.SentryError):
         sentry.sentry_merkle_stream_update_h2d(None, 0x1000, 64)
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_lthash_stream_update_h2d(None, 0x1000, 0x2000, 4)
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_lthash_stream_final(None, 0x1000)
 
 
 def test_header_is_plain_c_and_a_c_program_can_use_the_library(tmp_path):

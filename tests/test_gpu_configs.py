@@ -80,6 +80,9 @@ def test_config4_streamed_lattice_hash_with_running_sum():
     host = [torch.empty(wl.C4_BATCH_BYTES, dtype=torch.uint8).pin_memory() for _ in range(2)]
     running = torch.zeros(1024, dtype=torch.int16, device="cuda")
     part = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    streamed = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    lt = sentry.sentry_lthash_stream_begin()          # the same 20 batches, fed whole to one running sum
+    offs_keep = []
     for k, (a, b) in enumerate(batches):
         assert (a, b) == want_batches[k][:2]
         nbytes = int(off[b] - off[a])
@@ -91,10 +94,15 @@ def test_config4_streamed_lattice_hash_with_running_sum():
         # loaded in 1 GB pieces on the side stream while the previous piece is hashed
         sentry.sentry_lthash_h2d(h.data_ptr(), h_off.data_ptr(), b - a, 1_000_000_000, part.data_ptr())
         sentry.sentry_lthash_combine(running.data_ptr(), part.data_ptr())
+        sentry.sentry_lthash_stream_update_h2d(lt, h.data_ptr(), h_off.data_ptr(), b - a)
+        offs_keep.append(h_off)
         torch.cuda.synchronize()
         assert (part.cpu().numpy().view(np.uint16) == want_batches[k][2]).all(), "batch %d" % k
         print("config 4: batch %d/%d ok" % (k + 1, len(batches)), flush=True)
     assert (running.cpu().numpy().view(np.uint16) == want_total).all()
+    sentry.sentry_lthash_stream_final(lt, streamed.data_ptr())
+    torch.cuda.synchronize()
+    assert (streamed.cpu().numpy().view(np.uint16) == want_total).all()
     del host
     free_gpu()
 

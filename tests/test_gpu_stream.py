@@ -180,6 +180,62 @@ def test_lthash_h2d_batches_and_running_sum():
     assert (acc.cpu().numpy().view(np.uint16) == want).all()
 
 
+@pytest.mark.parametrize("pinned", [True, False])
+def test_lthash_stream_running_sum_over_batches_fed_one_by_one(pinned):
+    # 13 batches of unequal sizes (one empty, one of a single empty record) fed back to back on a
+    # stream of their own with no host wait in between: every staging slot and every hash stream is
+    # reused several times and the staging buffers grow while batches are in flight
+    lens = wl.lognormal_record_lengths(1300, seed=101, median=9_000, lo=0, hi=300_000)
+    lens[700] = 0
+    off = wl.offsets_from_lengths(lens)
+    total = int(off[-1])
+    data = wl.uniform_bytes(2400, 0, total)
+    want = oracle.lthash(data, off)
+    host = torch.from_numpy(data.copy())
+    hoff = torch.from_numpy(off.view(np.int64).copy())
+    if pinned:
+        host, hoff = host.pin_memory(), hoff.pin_memory()
+    cuts = [0, 10, 11, 11, 300, 350, 700, 701, 900, 901, 1000, 1100, 1250, 1300]
+    s = torch.cuda.Stream()
+    st = sentry.sentry_lthash_stream_begin()
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr(), hoff.data_ptr() + 8 * a, b - a, s.cuda_stream)
+    out = torch.full((1024,), 0x2222, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy().view(np.uint16) == want).all()
+    # a second running sum on the same stream right after, two batches; and an empty one
+    st = sentry.sentry_lthash_stream_begin()
+    sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr(), hoff.data_ptr() + 8 * 300, 400, s.cuda_stream)
+    sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr(), hoff.data_ptr(), 300, s.cuda_stream)
+    sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy().view(np.uint16) == oracle.lthash(data[:int(off[700])], off[:701])).all()
+    st = sentry.sentry_lthash_stream_begin()
+    sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    assert (out.cpu() == 0).all()
+
+
+def test_lthash_stream_misuse():
+    st = sentry.sentry_lthash_stream_begin()
+    h = torch.zeros(4096, dtype=torch.uint8).pin_memory()
+    o = torch.tensor([0, 100, 50], dtype=torch.int64).pin_memory()
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_lthash_stream_update_h2d(st, h.data_ptr(), 0, 2)                 # NULL offsets
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_lthash_stream_update_h2d(st, h.data_ptr(), o.data_ptr() + 4, 2)  # misaligned offsets
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_lthash_stream_final(st, 0)                                       # NULL lanes
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    sentry.sentry_lthash_stream_update_h2d(st, h.data_ptr(), o.data_ptr(), 1, s1.cuda_stream)
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_lthash_stream_update_h2d(st, h.data_ptr(), o.data_ptr(), 1, s2.cuda_stream)   # another stream
+    sentry.sentry_lthash_stream_abort(st)
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_lthash_stream_update_h2d(None, h.data_ptr(), o.data_ptr(), 1)
+
+
 def test_h2d_from_pageable_pinned_and_device_memory():
     # pinned memory is read by the load kernel, pageable memory goes through hipMemcpyAsync,
     # and a device pointer in place of the host buffer is accepted as well
