@@ -203,8 +203,15 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
     // aligned words of this lane's 32-byte slice of the first block
     const uint32_t *q = reinterpret_cast<const uint32_t *>(records + beg - al) + 8 * j;
 
-    // per-lane LDS addresses of the message words of every round
+    // per-lane LDS addresses of the message words of every round.  The sixteen quads of a wave keep
+    // their blocks 128 bytes apart, which is the width of all LDS banks: unswizzled, the sixteen lanes
+    // that read the same message word of their quads would all hit one pair of banks.  So quad q keeps
+    // its eight 16-byte cells (two message words each) at cell number XOR (q & 7): the sixteen quads
+    // then spread over eight bank groups (two per group instead of sixteen), and a lane still stores
+    // its slice as two whole cells, at two addresses that are computed once.
     const uint32_t qbase = quad * 128;
+    const uint32_t cell_flip = quad & 7;
+    auto swizzled = [&](uint32_t word) -> uint32_t { return 16u * ((word >> 1) ^ cell_flip) + 8u * (word & 1); };
     uint32_t maddr[10][2];
 #pragma unroll
     for (int r = 0; r < 10; r++) {
@@ -212,12 +219,14 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
         for (int st = 0; st < 2; st++) {
             // column step: column j; diagonal step: the diagonal through b of column j, number j - 1
             const uint32_t g = st == 0 ? j : ((j + 3) & 3);
-            const uint32_t x = qbase + 8u * B2_SIGMA_TABLE[r][8 * st + 2 * g];
-            const uint32_t y = qbase + 8u * B2_SIGMA_TABLE[r][8 * st + 2 * g + 1];
+            const uint32_t x = qbase + swizzled(B2_SIGMA_TABLE[r][8 * st + 2 * g]);
+            const uint32_t y = qbase + swizzled(B2_SIGMA_TABLE[r][8 * st + 2 * g + 1]);
             maddr[r][st] = x | (y << 16);
         }
     }
-    unsigned char *my_slice = stage + qbase + 32 * j;
+    // this lane's 32-byte slice = message words 4j .. 4j+3 = the two 16-byte cells 2j and 2j+1
+    unsigned char *my_cell0 = stage + qbase + swizzled(4 * j);
+    unsigned char *my_cell1 = stage + qbase + swizzled(4 * j + 2);
 
     // column j of the chaining value and of the IV
     const uint64_t iv_lo = j == 0 ? b2_iv(0) : j == 1 ? b2_iv(1) : j == 2 ? b2_iv(2) : b2_iv(3);
@@ -283,8 +292,8 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
             t = len;
         }
         // stage the block: this lane's four message words
-        *reinterpret_cast<uint4 *>(my_slice) = make_uint4(w[0], w[1], w[2], w[3]);
-        *reinterpret_cast<uint4 *>(my_slice + 16) = make_uint4(w[4], w[5], w[6], w[7]);
+        *reinterpret_cast<uint4 *>(my_cell0) = make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4 *>(my_cell1) = make_uint4(w[4], w[5], w[6], w[7]);
 
         uint64_t a = h_lo, b = h_hi, c = iv_lo, dd = iv_hi;
         if (j == 0) dd ^= t;
