@@ -245,6 +245,48 @@ def probe_issue_rates(only=None, waves=(4,)):
     return out
 
 
+def run_only_config(args, sentry, wl, torch, np, dev, stream):
+    """Config 1 or config 2 alone, args.steps timed calls after args.warmup: one short JSON line."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if args.only_config == "c1":
+        buf = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20, device=dev)
+        out = torch.zeros(32, dtype=torch.uint8, device=dev)
+        nbytes, mix = buf.numel(), sha_tree_mix([buf.numel()], 4096, flat=True)
+
+        def call():
+            sentry.sentry_merkle_root(buf.data_ptr(), nbytes, 4096, out.data_ptr(), stream)
+    else:
+        img, ioff = wl.image_records(50_000, device=dev)
+        d_ioff = torch.from_numpy(ioff.view(np.int64).copy()).to(dev)
+        lanes, half_a, half_b = (torch.zeros(1024, dtype=torch.int16, device=dev) for _ in range(3))
+        nbytes, mix = img.numel(), lthash_mix([3072] * 50_000)
+
+        def call():
+            sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream)
+    for _ in range(max(args.warmup, 1)):
+        call()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(args.steps):
+        a.record()
+        call()
+        b.record()
+        b.synchronize()
+        ts.append(a.elapsed_time(b))
+    entry = rated({"ms": statistics.median(ts), "ms_min": min(ts), "ms_max": max(ts), "calls": len(ts), "bytes": nbytes,
+                   "GB/s": nbytes / statistics.median(ts) / 1e6}, mix)
+    if args.only_config == "c2":
+        # the two disjoint halves, combined, equal the whole (checked here as well as in tests/)
+        sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 25_000, half_a.data_ptr(), stream)
+        sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr() + 8 * 25_000, 25_000, half_b.data_ptr(), stream)
+        sentry.sentry_lthash_combine(half_a.data_ptr(), half_b.data_ptr(), stream)
+        torch.cuda.synchronize()
+        if not torch.equal(half_a, lanes):
+            sys.exit("bench.py: combine of the halves differs from the whole")
+        entry["samples/s"] = 50_000 / (entry["ms"] * 1e-3)
+    print(json.dumps({"config": args.only_config, **entry}))
+
+
 def print_valu_probe():
     """The table behind ISSUE_RATE_TOPS (profiles/valu_issue_rates.md is one run of this)."""
     rates = probe_issue_rates(waves=(1, 2, 4, 8))
@@ -272,6 +314,9 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip per-config and streaming side measurements")
     ap.add_argument("--merkle-prefix-gib", type=int, default=0,
                     help="hash only the first N GiB of the 70B stream (for counter runs; the workload name says so)")
+    ap.add_argument("--only-config", choices=("c1", "c2"), default=None,
+                    help="run only config 1 (16 MiB Merkle, 4 KiB leaves) or config 2 (50,000 images, lattice hash, and "
+                         "the two halves combined) --steps times and print its own short line (for kernel traces)")
     ap.add_argument("--valu-probe", action="store_true",
                     help="print the measured issue rate of every VALU opcode the hash kernels use, and exit")
     ap.add_argument("--copy-probe", action="store_true",
@@ -293,6 +338,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.valu_probe:
         print_valu_probe()
+        return
+    if args.only_config:
+        run_only_config(args, sentry, wl, torch, np, dev, torch.cuda.current_stream().cuda_stream)
         return
     # the issue rates of the opcodes in the hash kernels' mixes, measured now (a few ms each): printed
     # beside the table the fractions are computed against, as a check on that table
@@ -708,52 +756,90 @@ def main():
         two_l = sum(nb for _, _, nb in b_offs[:2])
         copy_rate_l = lt_bytes / ms_copy_l / 1e6       # GB/s of the plain copy
         steady = (ms_l_full - ms_l2) / max(len(b_offs) - 2, 1)      # ms per further batch once the pipeline runs
+        # top level of each leg: the full streamed pass of the configuration; beside it the short runs
+        copy_rate_m = m_bytes / ms_copy / 1e6
         streaming = {"pinned_bytes": hbytes,
-                     "merkle": {"bytes": m_bytes, "chunk_bytes": chunk, "copy_only_GB/s": m_bytes / ms_copy / 1e6,
-                                "h2d_GB/s": m_bytes / ms_m / 1e6, "overlap_efficiency": ms_copy / ms_m,
-                                "entry_point": "sentry_merkle_stream_update_h2d per chunk",
-                                "one_call_h2d_GB/s": m_bytes / ms_m_call / 1e6,
-                                "full_pass": {"bytes": full_m, "chunks": -(-full_m // chunk), "ms": float(ms_m_full),
-                                              "GB/s": full_m / ms_m_full / 1e6,
-                                              "overlap_efficiency": (full_m / ms_m_full) / (m_bytes / ms_copy)}},
-                     "lthash": {"bytes": lt_bytes, "batch_bytes": rec_bytes, "batches": 2,
-                                "copy_only_GB/s": copy_rate_l, "h2d_GB/s": lt_bytes / ms_l / 1e6,
-                                "overlap_efficiency": ms_copy_l / ms_l,
-                                "full_pass": {"entry_point": "sentry_lthash_stream_update_h2d per batch",
-                                              "bytes": full_l, "batches": len(b_offs), "records": int(sum(c for _, c, _ in b_offs)),
-                                              "ms": float(ms_l_full), "GB/s": full_l / ms_l_full / 1e6,
-                                              "overlap_efficiency": (full_l / ms_l_full / 1e6) / copy_rate_l,
-                                              "first_two_batches_ms": float(ms_l2),
-                                              "steady_state_ms_per_batch": steady,
-                                              "steady_state_efficiency": ((full_l - two_l) / max(len(b_offs) - 2, 1) / steady / 1e6) / copy_rate_l
-                                              if steady > 0 else None,
-                                              "tail_ms": float(ms_l2) - two_l / 1e6 / copy_rate_l}}}
+                     "merkle": {"entry_point": "sentry_merkle_stream_update_h2d per chunk", "bytes": full_m,
+                                "chunk_bytes": chunk, "chunks": -(-full_m // chunk), "ms": float(ms_m_full),
+                                "copy_only_GB/s": copy_rate_m, "h2d_GB/s": full_m / ms_m_full / 1e6,
+                                "overlap_efficiency": (full_m / ms_m_full / 1e6) / copy_rate_m,
+                                "sixteen_chunks": {"bytes": m_bytes, "h2d_GB/s": m_bytes / ms_m / 1e6,
+                                                   "overlap_efficiency": ms_copy / ms_m,
+                                                   "one_call_sentry_merkle_root_h2d_GB/s": m_bytes / ms_m_call / 1e6}},
+                     "lthash": {"entry_point": "sentry_lthash_stream_update_h2d per batch", "bytes": full_l,
+                                "batch_bytes": batch_bytes, "batches": len(b_offs), "records": int(sum(c for _, c, _ in b_offs)),
+                                "ms": float(ms_l_full), "copy_only_GB/s": copy_rate_l, "h2d_GB/s": full_l / ms_l_full / 1e6,
+                                "overlap_efficiency": (full_l / ms_l_full / 1e6) / copy_rate_l,
+                                "first_two_batches_ms": float(ms_l2), "steady_state_ms_per_batch": steady,
+                                "steady_state_efficiency": ((full_l - two_l) / max(len(b_offs) - 2, 1) / steady / 1e6) / copy_rate_l
+                                if steady > 0 else None,
+                                "tail_ms": float(ms_l2) - two_l / 1e6 / copy_rate_l,
+                                "two_batches_one_call_sentry_lthash_h2d": {"bytes": lt_bytes, "h2d_GB/s": lt_bytes / ms_l / 1e6,
+                                                                           "overlap_efficiency": ms_copy_l / ms_l}}}
         del host, stage
 
     # ---------------- CPU baseline: the oracle, one thread, on a bounded sample ----------------
+    # Configs 1 and 2 in full; of the three big configurations the first 4 GiB of the 70B stream (config 5),
+    # the first 2 GB of the 7B checkpoint's tensors (config 3, per-tensor roots) and the first 2 GB of the
+    # batch (config 4): about 20 s of single-thread work.  More is not run: the default bench run has to
+    # finish within minutes, and the oracle's rate does not depend on how much it is given.
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         log("CPU baseline (oracle, 1 thread)")
-        m_bytes = (64 << 20) if args.quick else (2 << 30)
-        l_bytes = (32 << 20) if args.quick else (1 << 30)
+        m_bytes = (64 << 20) if args.quick else (4 << 30)
+        l_bytes = (32 << 20) if args.quick else 2_000_000_000
+        s_bytes = (32 << 20) if args.quick else 2_000_000_000
+        parts = {}
+
+        def cpu_leg(name, nbytes, cpu_fn, gpu_fn):
+            t = time.perf_counter()
+            want = cpu_fn()
+            sec = time.perf_counter() - t
+            got = gpu_fn()
+            if got != want:
+                sys.exit("bench.py: GPU result differs from the oracle on the CPU-baseline sample (%s)" % name)
+            parts[name] = {"bytes": nbytes, "s": sec, "GB/s": nbytes / sec / 1e9}
+
+        def gpu_root(ptr, n, leaf):
+            sentry.sentry_merkle_root(ptr, n, leaf, root7.data_ptr(), stream)
+            torch.cuda.synchronize()
+            return bytes(root7.cpu().numpy())
+
+        def gpu_lanes(d, o, n):
+            sentry.sentry_lthash(d.data_ptr(), o.data_ptr(), n, lanes.data_ptr(), stream)
+            torch.cuda.synchronize()
+            return lanes.cpu().numpy().view(np.uint16).tobytes()
+
         sample_m = ckpt70[:m_bytes].cpu().numpy()
+        cpu_leg("c5_prefix", m_bytes, lambda: oracle.merkle_root(sample_m, LEAF70), lambda: gpu_root(ckpt70.data_ptr(), m_bytes, LEAF70))
         nb = int(np.searchsorted(rec_off - rec_off[0], np.uint64(l_bytes), side="right")) - 1
         lt_b = int(rec_off[nb] - rec_off[0])
         sample_l = records[:lt_b].cpu().numpy()
         sample_off = (rec_off[:nb + 1] - rec_off[0]).copy()
-        t = time.perf_counter()
-        r_cpu = oracle.merkle_root(sample_m, LEAF70)
-        t_m = time.perf_counter() - t
-        t = time.perf_counter()
-        l_cpu = oracle.lthash(sample_l, sample_off)
-        t_l = time.perf_counter() - t
-        # the same sample on the GPU must agree
-        sentry.sentry_merkle_root(ckpt70.data_ptr(), m_bytes, LEAF70, root7.data_ptr(), stream)
-        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), nb, lanes.data_ptr(), stream)
-        torch.cuda.synchronize()
-        if bytes(root7.cpu().numpy()) != r_cpu or (lanes.cpu().numpy().view(np.uint16) != l_cpu).any():
-            sys.exit("bench.py: GPU result differs from the oracle on the CPU-baseline sample")
+        cpu_leg("c4_prefix", lt_b, lambda: oracle.lthash(sample_l, sample_off).tobytes(), lambda: gpu_lanes(records, d_off, nb))
+        # config 3: the tensors of the 7B checkpoint in order until the sample is full
+        n_t, acc_b = 0, 0
+        while n_t < len(t7) and (n_t == 0 or acc_b + t7_lens[n_t] <= s_bytes):
+            acc_b += t7_lens[n_t]
+            n_t += 1
+        segs = [t7[i].view(torch.uint8).reshape(-1).cpu().numpy() for i in range(n_t)]
+
+        def gpu_segments():
+            sentry.sentry_merkle_segments(t7_ptrs[:n_t], t7_lens[:n_t], LEAF7, 0, root7.data_ptr(), stream)
+            torch.cuda.synchronize()
+            return bytes(root7.cpu().numpy())
+
+        cpu_leg("c3_first_%d_tensors" % n_t, acc_b, lambda: oracle.merkle_segments(segs, LEAF7)[1], gpu_segments)
+        if not args.quick:
+            c1_np = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20)
+            c1_d = torch.from_numpy(c1_np).to(dev)
+            cpu_leg("c1_full", c1_np.size, lambda: oracle.merkle_root(c1_np, 4096), lambda: gpu_root(c1_d.data_ptr(), c1_np.size, 4096))
+            img_np, ioff_np = wl.image_records(50_000)
+            img_d = torch.from_numpy(img_np).to(dev)
+            ioff_d = torch.from_numpy(ioff_np.view(np.int64).copy()).to(dev)
+            cpu_leg("c2_full", img_np.size, lambda: oracle.lthash(img_np, ioff_np).tobytes(), lambda: gpu_lanes(img_d, ioff_d, 50_000))
+        t_m, t_l = parts["c5_prefix"]["s"], parts["c4_prefix"]["s"]
         # context, not baselines: the same oracle on every host core at once (leaves and records are
         # independent: one slice per thread, the C oracle runs outside the interpreter lock), and the
         # host's hashing library on one core (the paper's CPU baseline is that library)
@@ -781,11 +867,14 @@ def main():
         context = {"oracle_all_cores_GB/s": (m_bytes + lt_b) / t_all / 1e9, "threads": n_thr,
                    "hashlib_sha256_1_core_GB/s": min(m_bytes, 1 << 29) / t_hs / 1e9,
                    "hashlib_blake2b_1_core_GB/s": min(lt_b, 1 << 29) / t_hb / 1e9}
-        cpu = {"value": (m_bytes + lt_b) / (t_m + t_l) / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-               "sample": "Merkle over the first %d bytes of the 70B stream (64 KiB leaves) + lattice hash of the "
-                         "first %d records (%d bytes) of the batch; GPU results on the same sample match"
-                         % (m_bytes, nb, lt_b),
-               "merkle_GB/s": m_bytes / t_m / 1e9, "lthash_GB/s": lt_b / t_l / 1e9,
+        all_b, all_s = sum(v["bytes"] for v in parts.values()), sum(v["s"] for v in parts.values())
+        cpu = {"value": all_b / all_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "configs 1 and 2 in full; Merkle over the first %d bytes of the 70B stream (64 KiB leaves); "
+                         "per-tensor roots and model root of the first %d tensors (%d bytes) of the 7B checkpoint; lattice "
+                         "hash of the first %d records (%d bytes) of the batch; %.0f s of oracle time in all, bounded so "
+                         "that the default run ends within minutes; GPU results on every sample match"
+                         % (m_bytes, n_t, acc_b, nb, lt_b, all_s),
+               "merkle_GB/s": m_bytes / t_m / 1e9, "lthash_GB/s": lt_b / t_l / 1e9, "parts": parts,
                "host_cpus": os.cpu_count(), "context": context}
 
     out = {
