@@ -312,6 +312,7 @@ def main():
                     help="overlap: the 70B root on one stream, the other two parts one after the other on a second; "
                          "pair: the 70B root alone, then the other two side by side; serial: one stream")
     ap.add_argument("--no-extras", action="store_true", help="skip per-config and streaming side measurements")
+    ap.add_argument("--no-streaming", action="store_true", help="skip the host-to-device streaming legs (for counter runs)")
     ap.add_argument("--merkle-prefix-gib", type=int, default=0,
                     help="hash only the first N GiB of the 70B stream (for counter runs; the workload name says so)")
     ap.add_argument("--only-config", choices=("c1", "c2"), default=None,
@@ -367,10 +368,10 @@ def main():
             if acc >= args.merkle_prefix_gib << 30:
                 break
         lay70 = cut
-    # resident inputs, plus (side measurements) a 16 GB copy target and two 8 GB staging buffers
+    # resident inputs, plus (side measurements) a 16 GB copy target, three staging buffers of one batch and two of one chunk
     need = 2 * sum(n for _, n in lay70) + 2 * sum(n for _, n in lay7) + batch_bytes + (2 << 30)
-    if not args.no_extras and not args.quick:
-        need += (16 << 30) + 2 * batch_bytes + (2 << 30)
+    if not args.no_extras and not args.no_streaming and not args.quick:
+        need += (16 << 30) + 3 * batch_bytes + (4 << 30)
     free, _ = torch.cuda.mem_get_info()
     if free < need:
         sys.exit("bench.py: needs %.1f GB of free HBM, %.1f GB available" % (need / 1e9, free / 1e9))
@@ -679,104 +680,105 @@ def main():
             {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
             lthash_mix([3072] * 50_000), hbm_bytes=img.numel() + rows.numel())
         del rows
-        # host-to-device streaming in the shape of configs 5 and 4, from a pinned host buffer of 16 GB:
-        # Merkle while loading in 1 GiB chunks, and the lattice hash of 8 GB batches, each against the
-        # plain copy of the same bytes; then one full streamed pass of each configuration (137.95 GB in
-        # 129 chunks; 159.64 GB in the 20 batches of config 4, with their true record boundaries), fed
-        # chunk by chunk from the same pinned buffer used round-robin (the bytes repeat, which the time
-        # does not see; the full-size digests are checked against the oracle's in tests/).
-        if args.quick:
-            hbytes, chunk = 1 << 28, 1 << 26
-        else:
-            hbytes, chunk = 16 << 30, 1 << 30
-        hbytes = max(hbytes, 2 * rec_bytes)
-        host = torch.empty(hbytes, dtype=torch.uint8).pin_memory()
-        stage = torch.empty(hbytes, dtype=torch.uint8, device=dev)
-        m_bytes = min(hbytes, bytes70) // LEAF70 * LEAF70
-        host[:m_bytes].copy_(ckpt70[:m_bytes])
-        ms_copy = timed_call(lambda: stage[:m_bytes].copy_(host[:m_bytes], non_blocking=True), 3)
+        if not args.no_streaming:
+            # host-to-device streaming in the shape of configs 5 and 4, from a pinned host buffer of 16 GB:
+            # Merkle while loading in 1 GiB chunks, and the lattice hash of 8 GB batches, each against the
+            # plain copy of the same bytes; then one full streamed pass of each configuration (137.95 GB in
+            # 129 chunks; 159.64 GB in the 20 batches of config 4, with their true record boundaries), fed
+            # chunk by chunk from the same pinned buffer used round-robin (the bytes repeat, which the time
+            # does not see; the full-size digests are checked against the oracle's in tests/).
+            if args.quick:
+                hbytes, chunk = 1 << 28, 1 << 26
+            else:
+                hbytes, chunk = 16 << 30, 1 << 30
+            hbytes = max(hbytes, 2 * rec_bytes)
+            host = torch.empty(hbytes, dtype=torch.uint8).pin_memory()
+            stage = torch.empty(hbytes, dtype=torch.uint8, device=dev)
+            m_bytes = min(hbytes, bytes70) // LEAF70 * LEAF70
+            host[:m_bytes].copy_(ckpt70[:m_bytes])
+            ms_copy = timed_call(lambda: stage[:m_bytes].copy_(host[:m_bytes], non_blocking=True), 3)
 
-        def merkle_fed(total):
-            """`total` bytes fed in chunks to one tree through the library's load path."""
-            state = sentry.sentry_merkle_stream_begin(total, LEAF70)
-            pos = 0
-            while pos < total:
-                n = min(chunk, total - pos)
-                at = pos % m_bytes
-                if at + n > m_bytes:
-                    at = 0
-                sentry.sentry_merkle_stream_update_h2d(state, host.data_ptr() + at, n, stream)
-                pos += n
-            sentry.sentry_merkle_stream_final(state, root7.data_ptr(), stream)
+            def merkle_fed(total):
+                """`total` bytes fed in chunks to one tree through the library's load path."""
+                state = sentry.sentry_merkle_stream_begin(total, LEAF70)
+                pos = 0
+                while pos < total:
+                    n = min(chunk, total - pos)
+                    at = pos % m_bytes
+                    if at + n > m_bytes:
+                        at = 0
+                    sentry.sentry_merkle_stream_update_h2d(state, host.data_ptr() + at, n, stream)
+                    pos += n
+                sentry.sentry_merkle_stream_final(state, root7.data_ptr(), stream)
 
-        ms_m = timed_call(lambda: merkle_fed(m_bytes), 3)
-        sentry.sentry_merkle_root(ckpt70.data_ptr(), m_bytes, LEAF70, root70.data_ptr(), stream)
-        torch.cuda.synchronize()
-        if bytes(root7.cpu().numpy()) != bytes(root70.cpu().numpy()):
-            sys.exit("bench.py: Merkle root while loading differs from the root of the resident bytes")
-        ms_m_call = timed_call(lambda: sentry.sentry_merkle_root_h2d(host.data_ptr(), m_bytes, LEAF70, chunk,
-                                                                     root7.data_ptr(), stream), 3)
-        full_m = bytes70 if not args.merkle_prefix_gib else m_bytes
-        ms_m_full = timed_call(lambda: merkle_fed(full_m), 1, warm=0)
-        # lattice: the resident batch twice in pinned memory
-        lt_bytes = 2 * rec_bytes
-        host[:rec_bytes].copy_(records)
-        host[rec_bytes:lt_bytes].copy_(records)
-        rel = rec_off - rec_off[0]
-        h_off = torch.from_numpy(np.concatenate([rel, rel[1:] + np.uint64(rec_bytes)]).view(np.int64).copy()).pin_memory()
-        ms_copy_l = timed_call(lambda: stage[:lt_bytes].copy_(host[:lt_bytes], non_blocking=True), 3)
-        lanes2 = torch.zeros(1024, dtype=torch.int16, device=dev)
-        ms_l = timed_call(lambda: sentry.sentry_lthash_h2d(host.data_ptr(), h_off.data_ptr(), 2 * n_rec, rec_bytes,
-                                                           lanes2.data_ptr(), stream), 3)
-        sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), stream)
-        sentry.sentry_lthash_combine(lanes.data_ptr(), lanes.data_ptr(), stream)      # the batch twice
-        torch.cuda.synchronize()
-        if (lanes.cpu() != lanes2.cpu()).any():
-            sys.exit("bench.py: lattice hash while loading differs from the hash of the resident batch")
-        # the full pass: every batch of the configuration with its own record boundaries, batch k read from
-        # half k % 2 of the pinned buffer
-        all_batches = wl.cut_batches(offsets, batch_bytes)
-        half = hbytes // 2
-        b_offs = []
-        for k, (a0, a1) in enumerate(all_batches):
-            o = offsets[a0:a1 + 1] - offsets[a0] + np.uint64((k & 1) * half)
-            b_offs.append((torch.from_numpy(o.view(np.int64).copy()).pin_memory(), a1 - a0, int(offsets[a1] - offsets[a0])))
+            ms_m = timed_call(lambda: merkle_fed(m_bytes), 3)
+            sentry.sentry_merkle_root(ckpt70.data_ptr(), m_bytes, LEAF70, root70.data_ptr(), stream)
+            torch.cuda.synchronize()
+            if bytes(root7.cpu().numpy()) != bytes(root70.cpu().numpy()):
+                sys.exit("bench.py: Merkle root while loading differs from the root of the resident bytes")
+            ms_m_call = timed_call(lambda: sentry.sentry_merkle_root_h2d(host.data_ptr(), m_bytes, LEAF70, chunk,
+                                                                         root7.data_ptr(), stream), 3)
+            full_m = bytes70 if not args.merkle_prefix_gib else m_bytes
+            ms_m_full = timed_call(lambda: merkle_fed(full_m), 1, warm=0)
+            # lattice: the resident batch twice in pinned memory
+            lt_bytes = 2 * rec_bytes
+            host[:rec_bytes].copy_(records)
+            host[rec_bytes:lt_bytes].copy_(records)
+            rel = rec_off - rec_off[0]
+            h_off = torch.from_numpy(np.concatenate([rel, rel[1:] + np.uint64(rec_bytes)]).view(np.int64).copy()).pin_memory()
+            ms_copy_l = timed_call(lambda: stage[:lt_bytes].copy_(host[:lt_bytes], non_blocking=True), 3)
+            lanes2 = torch.zeros(1024, dtype=torch.int16, device=dev)
+            ms_l = timed_call(lambda: sentry.sentry_lthash_h2d(host.data_ptr(), h_off.data_ptr(), 2 * n_rec, rec_bytes,
+                                                               lanes2.data_ptr(), stream), 3)
+            sentry.sentry_lthash(records.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), stream)
+            sentry.sentry_lthash_combine(lanes.data_ptr(), lanes.data_ptr(), stream)      # the batch twice
+            torch.cuda.synchronize()
+            if (lanes.cpu() != lanes2.cpu()).any():
+                sys.exit("bench.py: lattice hash while loading differs from the hash of the resident batch")
+            # the full pass: every batch of the configuration with its own record boundaries, batch k read from
+            # half k % 2 of the pinned buffer
+            all_batches = wl.cut_batches(offsets, batch_bytes)
+            half = hbytes // 2
+            b_offs = []
+            for k, (a0, a1) in enumerate(all_batches):
+                o = offsets[a0:a1 + 1] - offsets[a0] + np.uint64((k & 1) * half)
+                b_offs.append((torch.from_numpy(o.view(np.int64).copy()).pin_memory(), a1 - a0, int(offsets[a1] - offsets[a0])))
 
-        def lattice_fed(n_batches):
-            state = sentry.sentry_lthash_stream_begin()
-            for o, cnt, _ in b_offs[:n_batches]:
-                sentry.sentry_lthash_stream_update_h2d(state, host.data_ptr(), o.data_ptr(), cnt, stream)
-            sentry.sentry_lthash_stream_final(state, lanes2.data_ptr(), stream)
+            def lattice_fed(n_batches):
+                state = sentry.sentry_lthash_stream_begin()
+                for o, cnt, _ in b_offs[:n_batches]:
+                    sentry.sentry_lthash_stream_update_h2d(state, host.data_ptr(), o.data_ptr(), cnt, stream)
+                sentry.sentry_lthash_stream_final(state, lanes2.data_ptr(), stream)
 
-        lattice_fed(min(3, len(b_offs)))      # sizes the staging buffers
-        torch.cuda.synchronize()
-        ms_l2 = timed_call(lambda: lattice_fed(2), 3, warm=1)
-        ms_l_full = timed_call(lambda: lattice_fed(len(b_offs)), 1, warm=0)
-        full_l = sum(nb for _, _, nb in b_offs)
-        two_l = sum(nb for _, _, nb in b_offs[:2])
-        copy_rate_l = lt_bytes / ms_copy_l / 1e6       # GB/s of the plain copy
-        steady = (ms_l_full - ms_l2) / max(len(b_offs) - 2, 1)      # ms per further batch once the pipeline runs
-        # top level of each leg: the full streamed pass of the configuration; beside it the short runs
-        copy_rate_m = m_bytes / ms_copy / 1e6
-        streaming = {"pinned_bytes": hbytes,
-                     "merkle": {"entry_point": "sentry_merkle_stream_update_h2d per chunk", "bytes": full_m,
-                                "chunk_bytes": chunk, "chunks": -(-full_m // chunk), "ms": float(ms_m_full),
-                                "copy_only_GB/s": copy_rate_m, "h2d_GB/s": full_m / ms_m_full / 1e6,
-                                "overlap_efficiency": (full_m / ms_m_full / 1e6) / copy_rate_m,
-                                "sixteen_chunks": {"bytes": m_bytes, "h2d_GB/s": m_bytes / ms_m / 1e6,
-                                                   "overlap_efficiency": ms_copy / ms_m,
-                                                   "one_call_sentry_merkle_root_h2d_GB/s": m_bytes / ms_m_call / 1e6}},
-                     "lthash": {"entry_point": "sentry_lthash_stream_update_h2d per batch", "bytes": full_l,
-                                "batch_bytes": batch_bytes, "batches": len(b_offs), "records": int(sum(c for _, c, _ in b_offs)),
-                                "ms": float(ms_l_full), "copy_only_GB/s": copy_rate_l, "h2d_GB/s": full_l / ms_l_full / 1e6,
-                                "overlap_efficiency": (full_l / ms_l_full / 1e6) / copy_rate_l,
-                                "first_two_batches_ms": float(ms_l2), "steady_state_ms_per_batch": steady,
-                                "steady_state_efficiency": ((full_l - two_l) / max(len(b_offs) - 2, 1) / steady / 1e6) / copy_rate_l
-                                if steady > 0 else None,
-                                "tail_ms": float(ms_l2) - two_l / 1e6 / copy_rate_l,
-                                "two_batches_one_call_sentry_lthash_h2d": {"bytes": lt_bytes, "h2d_GB/s": lt_bytes / ms_l / 1e6,
-                                                                           "overlap_efficiency": ms_copy_l / ms_l}}}
-        del host, stage
+            lattice_fed(min(3, len(b_offs)))      # sizes the staging buffers
+            torch.cuda.synchronize()
+            ms_l2 = timed_call(lambda: lattice_fed(2), 3, warm=1)
+            ms_l_full = timed_call(lambda: lattice_fed(len(b_offs)), 1, warm=0)
+            full_l = sum(nb for _, _, nb in b_offs)
+            two_l = sum(nb for _, _, nb in b_offs[:2])
+            copy_rate_l = lt_bytes / ms_copy_l / 1e6       # GB/s of the plain copy
+            steady = (ms_l_full - ms_l2) / max(len(b_offs) - 2, 1)      # ms per further batch once the pipeline runs
+            # top level of each leg: the full streamed pass of the configuration; beside it the short runs
+            copy_rate_m = m_bytes / ms_copy / 1e6
+            streaming = {"pinned_bytes": hbytes,
+                         "merkle": {"entry_point": "sentry_merkle_stream_update_h2d per chunk", "bytes": full_m,
+                                    "chunk_bytes": chunk, "chunks": -(-full_m // chunk), "ms": float(ms_m_full),
+                                    "copy_only_GB/s": copy_rate_m, "h2d_GB/s": full_m / ms_m_full / 1e6,
+                                    "overlap_efficiency": (full_m / ms_m_full / 1e6) / copy_rate_m,
+                                    "sixteen_chunks": {"bytes": m_bytes, "h2d_GB/s": m_bytes / ms_m / 1e6,
+                                                       "overlap_efficiency": ms_copy / ms_m,
+                                                       "one_call_sentry_merkle_root_h2d_GB/s": m_bytes / ms_m_call / 1e6}},
+                         "lthash": {"entry_point": "sentry_lthash_stream_update_h2d per batch", "bytes": full_l,
+                                    "batch_bytes": batch_bytes, "batches": len(b_offs), "records": int(sum(c for _, c, _ in b_offs)),
+                                    "ms": float(ms_l_full), "copy_only_GB/s": copy_rate_l, "h2d_GB/s": full_l / ms_l_full / 1e6,
+                                    "overlap_efficiency": (full_l / ms_l_full / 1e6) / copy_rate_l,
+                                    "first_two_batches_ms": float(ms_l2), "steady_state_ms_per_batch": steady,
+                                    "steady_state_efficiency": ((full_l - two_l) / max(len(b_offs) - 2, 1) / steady / 1e6) / copy_rate_l
+                                    if steady > 0 else None,
+                                    "tail_ms": float(ms_l2) - two_l / 1e6 / copy_rate_l,
+                                    "two_batches_one_call_sentry_lthash_h2d": {"bytes": lt_bytes, "h2d_GB/s": lt_bytes / ms_l / 1e6,
+                                                                               "overlap_efficiency": ms_copy_l / ms_l}}}
+            del host, stage
 
     # ---------------- CPU baseline: the oracle, one thread, on a bounded sample ----------------
     # Configs 1 and 2 in full; of the three big configurations the first 4 GiB of the 70B stream (config 5),
