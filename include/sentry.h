@@ -228,8 +228,8 @@ SENTRY_API int sentry_merkle_stream_abort(void *state);
 SENTRY_API int sentry_merkle_root_h2d(const void *host_buf, size_t len, size_t leaf_bytes,
                            size_t chunk_bytes, uint8_t *out_digest, void *stream);
 
-/* Constant-time comparison of two host digests ("recompute model digests and
- * verify", section 4.1.1).  SENTRY_OK if equal, SENTRY_MISMATCH if not,
+/* Constant-time comparison of two host digests: the check of a recomputed model
+ * digest against the expected one (section 4.1.1).  SENTRY_OK if equal, SENTRY_MISMATCH if not,
  * SENTRY_ERR_INVALID_ARG for NULL. */
 SENTRY_API int sentry_verify(const uint8_t *root, const uint8_t *expected);
 

@@ -1,6 +1,6 @@
 // Merkle trees over the paper's other two leaf functions, BLAKE2b-512 and SHA3-256 (section
-// 4.2.1: "supports SHA256, BLAKE2B, and SHA3 as compression functions for Merkle tree
-// hashing").  Same tree rules as the SHA-256 path: one leaf per lane, node = H(left || right)
+// 4.2.1 names three hash functions for the tree: SHA-256, BLAKE2b and SHA-3).  Same tree rules
+// as the SHA-256 path: one leaf per lane, node = H(left || right)
 // with the full hash, a lone last node moves up unchanged, a short last leaf is hashed at its
 // true length.  These kernels are the plain version of the scheme (leaf digests to memory,
 // then 512 nodes folded per workgroup in LDS); the tuned path is the SHA-256 one.
