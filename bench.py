@@ -170,10 +170,11 @@ def model_lthash_ops(lens, block_bytes):
 # whatever the instruction (measured: 5.0 with the rest of its CU idle, 5.3 - 5.4 with the other SIMDs
 # of the CU busy), so chain_floor = instructions on the longest chain x 5.0 cycles /
 # 2.4 GHz.  Instructions per block on the critical wave: 930 for the SHA-256 rounds-only
-# consumer wave, 2304 for one tree level (two compressions by one lane), 700 for one BLAKE2b
-# compression spread over four lanes.
+# consumer wave, 2304 for one tree level (two compressions by one lane; 1850 where a second wave
+# expands the node's message schedule, as the one-launch tree of small inputs does), 700 for one
+# BLAKE2b compression spread over four lanes.
 LONE_WAVE_CYCLES_PER_INSTR, CLOCK_HZ = 5.0, 2.4e9
-SHA_CONSUMER_INSTRS, SHA_NODE_INSTRS, B2_FOUR_LANE_INSTRS = 930, 2304, 700
+SHA_CONSUMER_INSTRS, SHA_NODE_INSTRS, SHA_NODE_SPLIT_INSTRS, B2_FOUR_LANE_INSTRS = 930, 2304, 1850, 700
 
 
 def chain_bound(entry, instrs):
@@ -619,7 +620,7 @@ def main():
         ms = timed_call(lambda: sentry.sentry_merkle_root(c1.data_ptr(), c1.numel(), 4096, root7.data_ptr(), stream), 50)
         per_config["C1_merkle_16MiB_4KiB"] = chain_bound(
             rated({"GB/s": c1.numel() / ms / 1e6, "ms": ms, "bytes": c1.numel()}, sha_tree_mix([c1.numel()], 4096, flat=True)),
-            (4096 // 64 + 1) * SHA_CONSUMER_INSTRS + tree_levels(c1.numel() // 4096) * SHA_NODE_INSTRS)
+            (4096 // 64 + 1) * SHA_CONSUMER_INSTRS + tree_levels(c1.numel() // 4096) * SHA_NODE_SPLIT_INSTRS)
         img, ioff = wl.image_records(50_000, device=dev)
         d_ioff = torch.from_numpy(ioff.view(np.int64).copy()).to(dev)
         ms = timed_call(lambda: sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream), 50)

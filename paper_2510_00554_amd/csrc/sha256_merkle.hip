@@ -532,6 +532,152 @@ __device__ __forceinline__ void sha256_rounds_from_lds(uint32_t (&st)[8], const 
     }
 }
 
+// A tree level of a launch that has more SIMDs than nodes is one node hash on a lone wave:
+// two compressions, 2304 instructions, one after the other.  The message schedule of the first
+// compression (480 of them) does not depend on the chaining value, so a second wave can expand it
+// while the first runs the rounds, as for the leaves: the producer writes W[16..63] to LDS in six
+// chunks of eight words, one barrier after each; the consumer starts with the sixteen words it holds
+// (the two child digests), passes barrier k before the eight rounds that precede the use of chunk
+// k, and requests chunk k right behind the barrier, so that the read's latency hides behind those
+// rounds.  The producer needs 80 instructions per chunk, the consumer 112 per eight rounds, so the
+// consumer never waits.  Its chain per node: 64 + 64 rounds and the reads, about 1850 instructions.
+constexpr int TREE_LANE_WORDS = 52;                         // 48 schedule words + 4: 16-byte accesses stay conflict-free
+constexpr int TREE_SLOT_WORDS = 64 * TREE_LANE_WORDS;       // one pair of waves
+enum TreeRole { TREE_PRODUCER = 0, TREE_CONSUMER = 1, TREE_BYSTANDER = 2 };
+
+__device__ __forceinline__ void sha256_eight_rounds(uint32_t (&v)[8], const uint32_t (&w8)[8], int t0)
+{
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+        const int t = t0 + k;
+#define V(i) v[((i) - t) & 7]
+        uint32_t t1 = V(7) + bsig1(V(4)) + ch(V(4), V(5), V(6)) + k256(t) + w8[k];
+        V(3) += t1;
+        V(7) = t1 + bsig0(V(0)) + maj(V(0), V(1), V(2));
+#undef V
+    }
+}
+
+// out = SHA-256(l || r), computed by the consumer wave with the producer wave's help.  Every wave of
+// the workgroup calls this at the same point; the six barriers stand outside the role-dependent
+// parts, so that every wave executes exactly six whatever its role.  The lanes of producer and
+// consumer with the same lane number hold the same l, r and the same slot (LDS, TREE_LANE_WORDS
+// words).  Only the consumer's out is defined.
+__device__ __forceinline__ void node_hash_split(int role, const uint32_t (&l)[8], const uint32_t (&r)[8], uint32_t *slot,
+                                                uint32_t (&out)[8])
+{
+    const bool producer = role == TREE_PRODUCER, consumer = role == TREE_CONSUMER;
+    const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>(slot);   // LDS byte address of this lane's slot
+    uint4 *s4 = reinterpret_cast<uint4 *>(slot);
+    uint32_t w[16] = {};
+    uint32_t v[8] = SENTRY_H0;
+    u32x4 c0 = {}, c1 = {}, n0 = {}, n1 = {};
+    // producer: chunk g = W[16 + 8g .. 23 + 8g] into the slot
+    auto chunk = [&](int g) {
+#pragma unroll
+        for (int t = 16 + 8 * g; t < 24 + 8 * g; t++)
+            w[t & 15] = w[t & 15] + ssig0(w[(t + 1) & 15]) + w[(t + 9) & 15] + ssig1(w[(t + 14) & 15]);
+        const int b = (8 * g) & 15;                     // W[16 + 8g + k] sits in w[(8g + k) & 15]
+        s4[2 * g] = make_uint4(w[b], w[b + 1], w[b + 2], w[b + 3]);
+        s4[2 * g + 1] = make_uint4(w[b + 4], w[b + 5], w[b + 6], w[b + 7]);
+    };
+    if (producer) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) { w[i] = l[i]; w[8 + i] = r[i]; }
+        chunk(0);
+    }
+    if (consumer) sha256_eight_rounds(v, l, 0);
+    __syncthreads();                                    // chunk 0 is in LDS
+    if (producer) chunk(1);
+    if (consumer) {
+        lds_request_8_words(base, slot, c0, c1, v[0]);
+        sha256_eight_rounds(v, r, 8);
+        lds_wait_8_words(c0, c1);
+    }
+    __syncthreads();                                    // chunk 1
+#pragma unroll
+    for (int g = 1; g < 5; g++) {
+        if (producer) chunk(g + 1);
+        if (consumer) {
+            lds_request_8_words(base + 32u * (uint32_t)g, slot, n0, n1, v[0]);
+            const uint32_t w8[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+            sha256_eight_rounds(v, w8, 8 + 8 * g);
+            lds_wait_8_words(n0, n1);
+            c0 = n0;
+            c1 = n1;
+        }
+        __syncthreads();                                // chunk g + 1
+    }
+    if (consumer) {
+        lds_request_8_words(base + 32u * 5u, slot, n0, n1, v[0]);
+        const uint32_t w8[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        sha256_eight_rounds(v, w8, 48);
+        lds_wait_8_words(n0, n1);
+        const uint32_t x8[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
+        sha256_eight_rounds(v, x8, 56);
+        uint32_t st[8] = SENTRY_H0;
+#pragma unroll
+        for (int i = 0; i < 8; i++) st[i] += v[i];
+        sha256_compress_pad64(st);
+#pragma unroll
+        for (int i = 0; i < 8; i++) out[i] = st[i];
+    }
+}
+
+// tail_fold for workgroups of two or four waves: wave 0 is the producer and wave 1 the consumer of
+// every node hash, 64 nodes of a level per trip.  t = LDS, 2 x 8 x 512 words; slots = LDS,
+// TREE_SLOT_WORDS words.
+template <int NT>
+__device__ __forceinline__ void tail_fold_split(const uint8_t *nodes, uint32_t cnt, uint8_t *out, uint32_t *ticket,
+                                                uint32_t tid, uint32_t (*t)[8][RED_IN], uint32_t *slots)
+{
+    for (uint32_t i = tid; i < cnt; i += NT) {
+        uint32_t d[8];
+        load_digest(nodes + 32 * (uint64_t)i, d);
+#pragma unroll
+        for (int k = 0; k < 8; k++) t[0][k][i] = d[k];
+    }
+    __syncthreads();
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    const int role = wave == 0 ? TREE_PRODUCER : wave == 1 ? TREE_CONSUMER : TREE_BYSTANDER;
+    uint32_t *slot = slots + lane * TREE_LANE_WORDS;
+    int cur = 0;
+#pragma unroll 1
+    while (cnt > 1) {
+        const uint32_t pairs = cnt >> 1;
+#pragma unroll 1
+        for (uint32_t first = 0; first < pairs; first += 64) {
+            const uint32_t i = first + lane;
+            const bool act = i < pairs;
+            const uint32_t at = act ? i : 0;
+            uint32_t l[8], r[8], d[8];
+            if (role != TREE_BYSTANDER) {
+#pragma unroll
+                for (int k = 0; k < 8; k++) { l[k] = t[cur][k][2 * at]; r[k] = t[cur][k][2 * at + 1]; }
+            }
+            node_hash_split(role, l, r, slot, d);
+            if (role == TREE_CONSUMER && act) {
+#pragma unroll
+                for (int k = 0; k < 8; k++) t[cur ^ 1][k][i] = d[k];
+            }
+        }
+        if (tid == 0 && (cnt & 1)) {
+#pragma unroll
+            for (int k = 0; k < 8; k++) t[cur ^ 1][k][pairs] = t[cur][k][cnt - 1];
+        }
+        __syncthreads();
+        cnt = pairs + (cnt & 1);
+        cur ^= 1;
+    }
+    if (tid == 0) {
+        uint32_t root[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) root[k] = t[cur][k][0];
+        store_digest(out, root);
+        *ticket = 0;          // ready for the next launch
+    }
+}
+
 // Workgroup = 256 lanes = two producer/consumer pairs (waves P0, C0, P1, C1), each pair with
 // its own group of 64 leaves.  Four waves of one workgroup land on the four SIMDs of a CU,
 // one each, which single- or two-wave workgroups do not guarantee once a CU holds two of
@@ -548,7 +694,7 @@ merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
 {
     static_assert(!PACKED || (SEGMENTED && !FUSE), "the packed leaf stage writes leaf digests");
     static_assert(!TAIL || (FUSE && !SEGMENTED && !PACKED), "the one-launch tree is for one buffer");
-    static_assert(2 * SPLIT_SLOT_WORDS >= 2 * 8 * RED_IN, "the tail folds in the schedule slots of pair 0");
+    static_assert(2 * SPLIT_SLOT_WORDS >= TREE_SLOT_WORDS, "the tree levels use the schedule slots of their pair");
     __shared__ __attribute__((aligned(16))) uint32_t sched[PAIRS][2 * SPLIT_SLOT_WORDS];
     __shared__ uint32_t lds[PAIRS][2][8][SPLIT_LEAVES];
     __shared__ unsigned long long trip_share[2 * PAIRS];
@@ -660,17 +806,25 @@ merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
         for (int i = 0; i < 8; i++) lds[pr][0][i][lane] = st[i];
     }
     __syncthreads();
+    // the schedule slots are free now: the producer wave of each pair expands the message schedules of
+    // the node hashes there while the consumer wave runs their rounds (node_hash_split)
+    uint32_t *tree_slot = &sched[pr][lane * TREE_LANE_WORDS];
     uint32_t cnt = count;
     int cur = 0;
 #pragma unroll 1
     for (int level = 0; level < 6; level++) {
         const uint32_t pairs = cnt >> 1;
-        if (consumer && cnt > 1) {
-            if (lane < pairs) {
-                uint32_t l[8], rr[8], d[8];
+        const bool work = cnt > 1;                       // the same for both waves of a pair
+        const bool act = work && lane < pairs;
+        const uint32_t at = act ? lane : 0;
+        uint32_t l[8], rr[8], d[8];
+        if (work) {
 #pragma unroll
-                for (int i = 0; i < 8; i++) { l[i] = lds[pr][cur][i][2 * lane]; rr[i] = lds[pr][cur][i][2 * lane + 1]; }
-                node_hash(l, rr, d);
+            for (int i = 0; i < 8; i++) { l[i] = lds[pr][cur][i][2 * at]; rr[i] = lds[pr][cur][i][2 * at + 1]; }
+        }
+        node_hash_split(work ? (consumer ? TREE_CONSUMER : TREE_PRODUCER) : TREE_BYSTANDER, l, rr, tree_slot, d);
+        if (consumer && work) {
+            if (act) {
 #pragma unroll
                 for (int i = 0; i < 8; i++) lds[pr][cur ^ 1][i][lane] = d[i];
             } else if (lane == pairs && (cnt & 1)) {
@@ -689,11 +843,11 @@ merkle_leaf_split_kernel(const uint8_t *base0, uint64_t len0, uint64_t nleaves0,
         if constexpr (TAIL) __threadfence();   // released by the lane that stored it
     }
     if constexpr (TAIL) {
-        // the schedule slots are free now (tail_ticket starts with a barrier)
+        // the schedule slots of pair 0 are free now (tail_ticket starts with a barrier)
         __shared__ uint32_t last;
+        __shared__ uint32_t tail_nodes[2][8][RED_IN];
         if (tail_ticket(ticket, threadIdx.x, &last))
-            tail_fold<SPLIT_PAIR_LANES * PAIRS>(out, n_groups, final_out, ticket, threadIdx.x,
-                                                reinterpret_cast<uint32_t (*)[8][RED_IN]>(&sched[0][0]));
+            tail_fold_split<SPLIT_PAIR_LANES * PAIRS>(out, n_groups, final_out, ticket, threadIdx.x, tail_nodes, &sched[0][0]);
     }
 }
 
