@@ -93,6 +93,10 @@ def _bind(L):
         L.oracle_lthash_model_from.restype = None
         L.oracle_lanes_add.argtypes = [vp, vp, sz]
         L.oracle_lanes_add.restype = None
+        L.oracle_lanes_sub.argtypes = [vp, vp, sz]
+        L.oracle_lanes_sub.restype = None
+        L.oracle_lthash32.argtypes = [vp, vp, sz, vp]
+        L.oracle_lthash32.restype = None
         L.oracle_lthash_combine.argtypes = [vp, vp]
         L.oracle_lthash_combine.restype = None
         L.oracle_lthash_remove.argtypes = [vp, vp]
@@ -346,6 +350,26 @@ def lanes_add(acc, x):
     assert r.shape == xx.shape
     lib().oracle_lanes_add(r.ctypes.data, xx.ctypes.data, r.size)
     return r
+
+
+def lanes_sub(acc, x):
+    r = np.array(acc, dtype=np.uint16, copy=True)
+    xx = np.ascontiguousarray(x, dtype=np.uint16)
+    assert r.shape == xx.shape
+    lib().oracle_lanes_sub(r.ctypes.data, xx.ctypes.data, r.size)
+    return r
+
+
+def lthash32(records, offsets):
+    """Dataset lattice hash at the paper's digest width: 32 uint16 partitions (section 4.2.2)."""
+    rec = _u8(records)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    n = max(off.size - 1, 0)
+    out = np.full(32, 0xAAAA, np.uint16)          # the C function must overwrite every partition
+    if n:
+        assert int(off[-1]) <= rec.size
+    lib().oracle_lthash32(_ptr(rec), _ptr(off), n, out.ctypes.data)
+    return out
 
 
 def lthash_model(segments, block_bytes, first_index=0):

@@ -21,8 +21,10 @@
  *   - batches that mix data sources, one running sum per source: section 4.1.2, 4.3.
  *   - lattice hash of a model, block index mixed into each block digest: section 4.2.2,
  *     Algorithm 4.
- *   - Merkle trees with BLAKE2b and SHA-3 as the leaf function: section 4.2.1 ("supports
- *     SHA256, BLAKE2B, and SHA3").
+ *   - Merkle trees with BLAKE2b and SHA-3 as the leaf function: section 4.2.1 (which names
+ *     the three hash functions).
+ *   - the dataset lattice hash at the paper's own digest width, one 64-byte BLAKE2b digest per
+ *     sample = 32 partitions of 16 bits: section 4.2.2 (oracle_lthash32).
  *
  * Readings fixed where the paper leaves the point open (the build's target
  * configurations fix them):
@@ -686,6 +688,33 @@ void oracle_lthash_model_from(const uint8_t *const *ptrs, const size_t *lens, si
         }
     }
     free(msg);
+}
+
+/* The dataset lattice hash at the paper's own digest width (section 4.2.2: a 64-byte BLAKE2b
+ * digest per item, its 64-bit words split into four 16-bit partitions): h(M) = the plain,
+ * unkeyed BLAKE2b-512 of the sample (digest 64, fanout 1, depth 1, nothing else set), read as
+ * 32 little-endian uint16; acc[l] = sum over the records of h(record)[l] mod 2^16.  No index
+ * is mixed in (samples are a multiset, section 4.1.2). */
+void oracle_lthash32(const uint8_t *records, const uint64_t *offsets, size_t n, uint16_t acc[ORACLE_MODEL_LANES])
+{
+    uint8_t param[64];
+    memset(param, 0, sizeof param);
+    param[0] = 64; param[2] = 1; param[3] = 1;
+    memset(acc, 0, ORACLE_MODEL_LANES * sizeof(uint16_t));
+    for (size_t i = 0; i < n; i++) {
+        uint8_t dig[64];
+        oracle_blake2b_param(param, records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), dig, 64);
+        for (int l = 0; l < ORACLE_MODEL_LANES; l++) {
+            uint16_t v = (uint16_t)(dig[2 * l] | ((uint16_t)dig[2 * l + 1] << 8));
+            acc[l] = (uint16_t)((acc[l] + v) & 0xFFFFu);
+        }
+    }
+}
+
+/* acc[l] = (acc[l] - x[l]) mod 2^16 for n partitions */
+void oracle_lanes_sub(uint16_t *acc, const uint16_t *x, size_t n)
+{
+    for (size_t l = 0; l < n; l++) acc[l] = (uint16_t)((acc[l] + 0x10000u - x[l]) & 0xFFFFu);
 }
 
 void oracle_lthash_combine(uint16_t acc[ORACLE_LANES], const uint16_t x[ORACLE_LANES])

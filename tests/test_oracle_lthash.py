@@ -198,3 +198,57 @@ def test_sum_of_given_digests_in_python_integers():
     assert not oracle.lthash_sum(np.tile(row, (65536, 1))).any()
     d = rng.integers(0, 65536, size=(50, 1024)).astype(np.uint16)
     assert (oracle.lthash_sum(d) == oracle.lthash_sum(d[::-1].copy())).all()
+
+
+# ---------------------------------------------------------------------------
+# the dataset lattice hash at the paper's own digest width: one plain BLAKE2b-512 digest per
+# sample = 32 partitions of 16 bits (section 4.2.2).  Pinned by hashlib all the way: no XOF.
+# ---------------------------------------------------------------------------
+
+def lanes32_via_hashlib(rec):
+    return np.frombuffer(hashlib.blake2b(rec).digest(), dtype="<u2").astype(np.int64)
+
+
+def test_lthash32_is_the_sum_of_hashlib_digests():
+    rng = random.Random(31)
+    assert not oracle.lthash32(b"", np.zeros(1, np.uint64)).any()       # the empty set
+    assert not oracle.lthash32(b"", np.zeros(0, np.uint64)).any()
+    for n in (1, 2, 3, 17, 200):
+        recs = [rng.randbytes(rng.choice([0, 1, 127, 128, 129, 255, 256, 3072, rng.randrange(0, 700)])) for _ in range(n)]
+        data, off = pack(recs)
+        want = sum(lanes32_via_hashlib(r) for r in recs) % 65536
+        got = oracle.lthash32(data, off)
+        assert got.dtype == np.uint16 and got.shape == (32,)
+        assert (got.astype(np.int64) == want).all(), n
+    # one record: the 32 partitions are the digest's bytes, little endian, in order
+    rec = rng.randbytes(3072)
+    d = hashlib.blake2b(rec).digest()
+    got = oracle.lthash32(*pack([rec]))
+    assert int(got[0]) == d[0] | (d[1] << 8) and int(got[31]) == d[62] | (d[63] << 8)
+    # the empty record counts: its digest is that of the empty message, not zero
+    assert (oracle.lthash32(*pack([b""])).astype(np.int64) == lanes32_via_hashlib(b"")).all()
+
+
+def test_lthash32_set_identities_and_modulus():
+    rng = random.Random(32)
+    recs = [rng.randbytes(rng.randrange(0, 500)) for _ in range(60)]
+    a, b = recs[:23], recs[23:]
+    ha, hb, hab = (oracle.lthash32(*pack(x)) for x in (a, b, recs))
+    assert (oracle.lanes_add(ha, hb) == hab).all()                  # union of disjoint sets = sum
+    assert (oracle.lanes_sub(hab, ha) == hb).all()                  # removal = subtraction
+    shuffled = recs[:]
+    rng.shuffle(shuffled)
+    assert (oracle.lthash32(*pack(shuffled)) == hab).all()          # order does not matter
+    twice = oracle.lthash32(*pack(recs + recs[:5]))                  # a multiset: duplicates count
+    assert (twice == oracle.lanes_add(hab, oracle.lthash32(*pack(recs[:5])))).all()
+    # offsets need not start at zero
+    data, off = pack(recs)
+    shifted = b"\xee" * 13 + data
+    assert (oracle.lthash32(shifted, off + np.uint64(13)) == hab).all()
+    # 65,536 copies of one record sum to zero in every partition; 65,537 to the record itself
+    rec = rng.randbytes(40)
+    many = np.arange(65537, dtype=np.uint64) * np.uint64(0)
+    off1 = np.concatenate([many, np.array([40], np.uint64)])       # 65,536 empty records and then the record once
+    base = oracle.lthash32(rec, off1)
+    want = (65536 * lanes32_via_hashlib(b"") + lanes32_via_hashlib(rec)) % 65536
+    assert (base.astype(np.int64) == want).all()

@@ -39,6 +39,7 @@ PINS = [
     t_lt.test_per_source_sums_are_the_hashes_of_the_sub_multisets, t_lt.test_model_lattice_hash_against_hashlib,
     t_lt.test_model_hash_of_slices_adds_up, t_lt.test_digests_one_by_one_and_their_sum,
     t_lt.test_sum_of_given_digests_in_python_integers, t_lt.test_modulus_is_2_to_16,
+    t_lt.test_lthash32_is_the_sum_of_hashlib_digests, t_lt.test_lthash32_set_identities_and_modulus,
     t_oh.test_keccak_constants_match_fips202_definitions, t_oh.test_sha3_fips202_examples, t_oh.test_sha3_against_hashlib,
 ] + [(lambda h=h, f=f: t_oh.test_merkle_trees_over_each_leaf_function(h, f)) for h, f in t_oh.HASHES] \
   + [(lambda h=h, f=f: t_oh.test_per_tensor_and_flat_trees_over_each_leaf_function(h, f)) for h, f in t_oh.HASHES]
@@ -80,12 +81,18 @@ MUTANTS = [
      "            acc[l] = (uint16_t)((acc[l] + lanes[l]) > 0xFFFFu ? 0xFFFFu : (acc[l] + lanes[l]));\n    }\n}\n\n/* The digests of Eq. (1)"),
     ("lattice: the last record is left out", "    for (size_t i = 0; i < n; i++) {\n        uint16_t lanes[ORACLE_LANES];\n        oracle_lthash_one(records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), lanes);\n        for (int l = 0; l < ORACLE_LANES; l++)\n            acc[l]",
      "    for (size_t i = 0; i + 1 < n; i++) {\n        uint16_t lanes[ORACLE_LANES];\n        oracle_lthash_one(records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), lanes);\n        for (int l = 0; l < ORACLE_LANES; l++)\n            acc[l]"),
-    ("lattice: remove adds", "acc[l] = (uint16_t)((acc[l] + 0x10000u - x[l]) & 0xFFFFu);", "acc[l] = (uint16_t)((acc[l] + x[l]) & 0xFFFFu);"),
+    ("lattice: remove adds", "    for (int l = 0; l < ORACLE_LANES; l++)\n        acc[l] = (uint16_t)((acc[l] + 0x10000u - x[l]) & 0xFFFFu);",
+     "    for (int l = 0; l < ORACLE_LANES; l++)\n        acc[l] = (uint16_t)((acc[l] + x[l]) & 0xFFFFu);"),
     ("lattice: the sum of given digests skips row 0", "    for (size_t i = 0; i < n; i++)\n        for (int l = 0; l < ORACLE_LANES; l++)\n            acc[l] = (uint16_t)((acc[l] + digests[i * ORACLE_LANES + l]) & 0xFFFFu);",
      "    for (size_t i = 1; i < n; i++)\n        for (int l = 0; l < ORACLE_LANES; l++)\n            acc[l] = (uint16_t)((acc[l] + digests[i * ORACLE_LANES + l]) & 0xFFFFu);"),
     ("per source: records go to the next source", "uint16_t *row = acc + (size_t)src[i] * ORACLE_LANES;", "uint16_t *row = acc + (size_t)((src[i] + 1) % n_sources) * ORACLE_LANES;"),
     ("model lattice: the index restarts in every tensor", "        for (size_t start = 0; start < lens[t]; start += block_bytes, k++) {", "        k = first_index;\n        for (size_t start = 0; start < lens[t]; start += block_bytes, k++) {"),
     ("model lattice: big-endian index", "for (int i = 0; i < 8; i++) msg[i] = (uint8_t)(k >> (8 * i));", "for (int i = 0; i < 8; i++) msg[7 - i] = (uint8_t)(k >> (8 * i));"),
+    ("32-partition lattice: big-endian partitions", "            uint16_t v = (uint16_t)(dig[2 * l] | ((uint16_t)dig[2 * l + 1] << 8));\n            acc[l] = (uint16_t)((acc[l] + v) & 0xFFFFu);",
+     "            uint16_t v = (uint16_t)(dig[2 * l + 1] | ((uint16_t)dig[2 * l] << 8));\n            acc[l] = (uint16_t)((acc[l] + v) & 0xFFFFu);"),
+    ("32-partition lattice: the XOF root's parameter block instead of the plain hash", "    param[0] = 64; param[2] = 1; param[3] = 1;\n    memset(acc, 0, ORACLE_MODEL_LANES * sizeof(uint16_t));",
+     "    param[0] = 64; param[2] = 1; param[3] = 1; param[13] = 8;\n    memset(acc, 0, ORACLE_MODEL_LANES * sizeof(uint16_t));"),
+    ("32-partition lattice: subtraction adds", "acc[l] = (uint16_t)((acc[l] + 0x10000u - x[l]) & 0xFFFFu);\n}\n\nvoid oracle_lthash_combine", "acc[l] = (uint16_t)((acc[l] + x[l]) & 0xFFFFu);\n}\n\nvoid oracle_lthash_combine"),
     ("SHA-3: SHAKE's domain byte", "last[len] ^= 0x06;", "last[len] ^= 0x1f;"),
     ("SHA-3: theta rotates by two", "D[x] = C[(x + 4) % 5] ^ rotl64(C[(x + 1) % 5], 1);", "D[x] = C[(x + 4) % 5] ^ rotl64(C[(x + 1) % 5], 2);"),
     ("SHA-3: chi without the complement", "B[x + 5 * y] ^ (~B[(x + 1) % 5 + 5 * y] & B[(x + 2) % 5 + 5 * y]);", "B[x + 5 * y] ^ (B[(x + 1) % 5 + 5 * y] & B[(x + 2) % 5 + 5 * y]);"),
