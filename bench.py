@@ -153,6 +153,13 @@ def lthash_ops(record_lengths):
     return lthash_mix(record_lengths).total()
 
 
+def lthash32_mix(record_lengths):
+    """The 32-partition hash: the root compressions alone, and one packed add per digest word."""
+    import numpy as np
+    blocks = np.maximum(1, -(-np.asarray(record_lengths, dtype=np.int64) // 128))
+    return int(blocks.sum()) * B2_BLOCK_MIX + Mix({"v_pk_add_u16": 16 * len(record_lengths)})
+
+
 def model_lthash_mix(lens, block_bytes):
     blocks = 0
     for ln in lens:
@@ -667,6 +674,12 @@ def main():
             per_config["F1_lthash_50k_images_%d_sources" % n_src] = rated(
                 {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
                 lthash_mix([3072] * 50_000))
+        # the same 50,000 samples at the paper's own digest width: plain BLAKE2b-512, 32 partitions (section 4.2.2)
+        lanes32 = torch.zeros(32, dtype=torch.int16, device=dev)
+        ms = timed_call(lambda: sentry.sentry_lthash32(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes32.data_ptr(), stream), 50)
+        per_config["F2_lthash32_50k_images"] = rated(
+            {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
+            lthash32_mix([3072] * 50_000))
         # the lane sum taken alone, over digests that are already in memory (any 2048 bytes are a valid
         # digest row: the first 2 GiB of the 70B stream stand in for 2^20 of them): bound by HBM
         n_rows = min(1 << 20, bytes70 // 2048)

@@ -62,6 +62,7 @@ enum {
 #define SENTRY_HASH_BLAKE2B 1      /* BLAKE2b-512, 64-byte nodes */
 #define SENTRY_HASH_SHA3_256 2     /* 32-byte nodes */
 #define SENTRY_LANES 1024
+#define SENTRY_LANES32 32   /* lanes of the 32-partition lattice hash (section 4.2.2) */
 #define SENTRY_MODEL_LANES 32
 
 /* ------------------------------------------------------------------------ */
@@ -302,6 +303,29 @@ SENTRY_API int sentry_lthash_sum(const uint16_t *dev_digests, size_t n, uint16_t
  * 1024 uint16, 2-byte aligned; x is not modified; acc == x is allowed. */
 SENTRY_API int sentry_lthash_combine(uint16_t *acc, const uint16_t *x, void *stream);
 SENTRY_API int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stream);
+
+/*
+ * The lattice hash at the digest width section 4.2.2 describes: every sample is
+ * hashed by plain unkeyed BLAKE2b with a 64-byte digest, the digest is cut into
+ * 32 partitions of 16 bits (little-endian, in digest order), and partition l of
+ * all samples is summed mod 2^16:
+ *   out_lanes[l] = sum_i BLAKE2b-512(record_i)[2l .. 2l+1] mod 2^16, l < 32.
+ * (sentry_lthash is the same sum over 1024 lanes of the extended-output hash;
+ * this one is the 64-byte form.)  Records, offsets and n as for sentry_lthash
+ * (same alignment rules, same over-read of up to 3 bytes, n == 0 gives zeros).
+ * out_lanes    device-accessible, 32 uint16 (2-byte aligned), overwritten.
+ * sentry_lthash32_combine / _remove are the lattice addition and subtraction on
+ * such 32-lane values (acc and x device-accessible, 32 uint16 each, 2-byte
+ * aligned; x is not modified; acc == x is allowed).
+ * Errors: SENTRY_ERR_INVALID_ARG for NULL or misaligned pointers or n > 2^30 - 65;
+ * SENTRY_ERR_NOMEM / SENTRY_ERR_HIP from the scratch allocation or a launch.
+ * Like sentry_lthash, the calls only launch kernels once the stream's scratch
+ * is large enough.
+ */
+SENTRY_API int sentry_lthash32(const void *dev_records, const uint64_t *dev_offsets, size_t n,
+                               uint16_t *out_lanes, void *stream);
+SENTRY_API int sentry_lthash32_combine(uint16_t *acc, const uint16_t *x, void *stream);
+SENTRY_API int sentry_lthash32_remove(uint16_t *acc, const uint16_t *x, void *stream);
 
 /*
  * Lattice hash of records that sit in host memory, loaded in batches on a side

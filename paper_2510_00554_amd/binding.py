@@ -52,6 +52,9 @@ PROTOTYPES = {
     "sentry_lthash_model": (_int, [_vp, _vp, _sz, _sz, _vp, _vp, _vp]),
     "sentry_lthash_combine": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_remove": (_int, [_vp, _vp, _vp]),
+    "sentry_lthash32": (_int, [_vp, _vp, _sz, _vp, _vp]),
+    "sentry_lthash32_combine": (_int, [_vp, _vp, _vp]),
+    "sentry_lthash32_remove": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_h2d": (_int, [_vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_lthash_stream_begin": (_int, [ctypes.POINTER(_vp)]),
     "sentry_lthash_stream_update_h2d": (_int, [_vp, _vp, _vp, _sz, _vp]),
@@ -226,6 +229,18 @@ def sentry_lthash_combine(acc, x, stream=0):
 
 def sentry_lthash_remove(acc, x, stream=0):
     return _check(load().sentry_lthash_remove(acc, x, stream))
+
+
+def sentry_lthash32(dev_records, dev_offsets, n, out_lanes, stream=0):
+    return _check(load().sentry_lthash32(dev_records, dev_offsets, n, out_lanes, stream))
+
+
+def sentry_lthash32_combine(acc, x, stream=0):
+    return _check(load().sentry_lthash32_combine(acc, x, stream))
+
+
+def sentry_lthash32_remove(acc, x, stream=0):
+    return _check(load().sentry_lthash32_remove(acc, x, stream))
 
 
 def sentry_lthash_h2d(host_records, host_offsets, n, batch_bytes, out_lanes, stream=0):

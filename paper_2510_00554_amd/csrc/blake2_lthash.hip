@@ -35,6 +35,10 @@ typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 // Root hash: digest 64, fanout 1, depth 1, XOF length 2048.
 constexpr uint64_t ROOT_P0 = 0x0000000001010040ull;
 constexpr uint64_t ROOT_P1 = (uint64_t)XOF_BYTES << 32;
+// The plain unkeyed BLAKE2b-512 (digest 64, fanout 1, depth 1), whose 64-byte digest is the paper's own
+// per-sample digest (section 4.2.2): the 32-partition hash sentry_lthash32.
+constexpr uint64_t PLAIN_P0 = 0x0000000001010040ull;
+constexpr uint64_t PLAIN_P1 = 0;
 // Expansion node j: digest 64, fanout 0, depth 0, leaf length 64, node offset j, XOF
 // length 2048, inner length 64.
 constexpr uint64_t EXP_P0 = 0x0000004000000040ull;
@@ -49,8 +53,9 @@ constexpr uint64_t EXP_P2 = 0x0000000000004000ull;
 #define M32(k) __builtin_amdgcn_alignbit(d[(k) + 1], d[k], sh)
 
 // One record per lane: record i of n.
+// p0, p1: the first two words of the parameter block (the others are zero for both hashes used).
 __device__ __forceinline__ void root_one_lane(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base,
-                                              uint64_t n, uint64_t *h0_out, uint64_t i)
+                                              uint64_t n, uint64_t *h0_out, uint64_t i, uint64_t p0, uint64_t p1)
 {
     if (i >= n) return;
     const uint64_t beg = offsets[i] - offset_base;
@@ -62,8 +67,8 @@ __device__ __forceinline__ void root_one_lane(const uint8_t *records, const uint
     uint64_t h[8];
 #pragma unroll
     for (int k = 0; k < 8; k++) h[k] = b2_iv(k);
-    h[0] ^= ROOT_P0;
-    h[1] ^= ROOT_P1;
+    h[0] ^= p0;
+    h[1] ^= p1;
 
     uint32_t d[33];
     uint64_t done = 0;
@@ -176,7 +181,7 @@ __device__ __forceinline__ uint64_t add64(uint64_t a, uint64_t b) { return a + b
 // Sixteen records per wave, four lanes each: the wave's records are first_rec .. first_rec + 15.
 __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base,
                                                 uint64_t n, const uint32_t *order, uint64_t *h0_out, uint64_t first_rec,
-                                                unsigned char *stage)
+                                                unsigned char *stage, uint64_t p0, uint64_t p1)
 {
     const uint32_t lane = threadIdx.x, quad = lane >> 2, j = lane & 3;
     const uint64_t slot = first_rec + quad;
@@ -231,7 +236,7 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
     // column j of the chaining value and of the IV
     const uint64_t iv_lo = j == 0 ? b2_iv(0) : j == 1 ? b2_iv(1) : j == 2 ? b2_iv(2) : b2_iv(3);
     const uint64_t iv_hi = j == 0 ? b2_iv(4) : j == 1 ? b2_iv(5) : j == 2 ? b2_iv(6) : b2_iv(7);
-    uint64_t h_lo = iv_lo ^ (j == 0 ? ROOT_P0 : j == 1 ? ROOT_P1 : 0ull);
+    uint64_t h_lo = iv_lo ^ (j == 0 ? p0 : j == 1 ? p1 : 0ull);
     uint64_t h_hi = iv_hi;
 
     // Four blocks of this lane's slice are in flight: a global load takes about as long as one
@@ -376,20 +381,21 @@ __device__ __forceinline__ bool four_lane_mode(const uint64_t *offsets, uint64_t
 // kernel that slowed the one-lane path down by a third).  Both are launched when the choice
 // launched; the one whose mode is not taken returns at once.
 __global__ void __launch_bounds__(ROOT1_WG)
-lthash_root1_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n, uint64_t *h0_out)
+lthash_root1_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n, uint64_t *h0_out,
+                    uint64_t p0, uint64_t p1)
 {
     if (four_lane_mode(offsets, n)) return;
-    root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT1_WG + threadIdx.x);
+    root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT1_WG + threadIdx.x, p0, p1);
 }
 
 __global__ void __launch_bounds__(ROOT4_WG)
 lthash_root4_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
-                    const uint32_t *order, uint64_t *h0_out)
+                    const uint32_t *order, uint64_t *h0_out, uint64_t p0, uint64_t p1)
 {
     __shared__ __attribute__((aligned(16))) unsigned char stage[ROOT4_RECORDS * 128];
     if (!four_lane_mode(offsets, n)) return;
     root_four_lanes(records, offsets, offset_base, n, ordered_mode(offsets, n) ? order : nullptr, h0_out,
-                    (uint64_t)blockIdx.x * ROOT4_RECORDS, stage);
+                    (uint64_t)blockIdx.x * ROOT4_RECORDS, stage, p0, p1);
 }
 
 // Order of the records for the four-lane path: longest first (a counting sort by length in
@@ -716,6 +722,61 @@ lthash_addsub_kernel(uint16_t *acc, const uint16_t *x)
 }
 
 // ---------------------------------------------------------------------------
+// the 32-partition hash: the 64-byte digest itself cut into 32 lanes (section 4.2.2)
+// ---------------------------------------------------------------------------
+//
+// The rows are the plain BLAKE2b-512 digests the root kernels leave: 16 packed words of two
+// lanes each.  A workgroup takes a contiguous run of rows; thread t adds word t % 16 of every
+// 16th row of the run, starting at row t / 16, so a wave reads four whole rows (256 adjacent
+// bytes) at a time; the 16 partial sums of a word meet in LDS.  The first launch leaves one
+// packed row per workgroup, the second (one workgroup, over those rows) writes the 32 lanes.
+
+constexpr int SUM32_WG = 256;
+constexpr int SUM32_WORDS = SENTRY_LANES32 / 2;      // 16 packed words = one 64-byte digest
+constexpr int SUM32_SLICES = SUM32_WG / SUM32_WORDS; // 16 rows in flight per trip
+constexpr int SUM32_AHEAD = 4;                       // loads issued before the first add
+
+__global__ void __launch_bounds__(SUM32_WG)
+lthash32_sum_kernel(const uint32_t *rows, uint64_t n_rows, uint32_t *packed_out, uint16_t *lanes_out)
+{
+    __shared__ uint32_t lds[SUM32_SLICES][SUM32_WORDS];
+    const uint32_t col = threadIdx.x % SUM32_WORDS;
+    const uint32_t slice = threadIdx.x / SUM32_WORDS;
+    const uint64_t per = (n_rows + gridDim.x - 1) / gridDim.x;
+    const uint64_t lo = per * blockIdx.x < n_rows ? per * blockIdx.x : n_rows;
+    const uint64_t hi = lo + per < n_rows ? lo + per : n_rows;
+    u16x2 t = {0, 0};
+    uint64_t r = lo + slice;
+    for (; r + (uint64_t)(SUM32_AHEAD - 1) * SUM32_SLICES < hi; r += (uint64_t)SUM32_AHEAD * SUM32_SLICES) {
+        uint32_t x[SUM32_AHEAD];
+#pragma unroll
+        for (int a = 0; a < SUM32_AHEAD; a++) x[a] = rows[(r + (uint64_t)a * SUM32_SLICES) * SUM32_WORDS + col];
+#pragma unroll
+        for (int a = 0; a < SUM32_AHEAD; a++) t += u16x2{(unsigned short)x[a], (unsigned short)(x[a] >> 16)};
+    }
+    for (; r < hi; r += SUM32_SLICES) {
+        const uint32_t x = rows[r * SUM32_WORDS + col];
+        t += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+    }
+    lds[slice][col] = (uint32_t)t.x | ((uint32_t)t.y << 16);
+    __syncthreads();
+    if (threadIdx.x < SUM32_WORDS) {
+        u16x2 sum = {0, 0};
+#pragma unroll
+        for (int k = 0; k < SUM32_SLICES; k++) {
+            const uint32_t x = lds[k][threadIdx.x];
+            sum += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
+        }
+        if (lanes_out) {
+            lanes_out[2 * threadIdx.x] = sum.x;       // 16-bit stores: 2-byte alignment is enough
+            lanes_out[2 * threadIdx.x + 1] = sum.y;
+        } else {
+            packed_out[(uint64_t)blockIdx.x * SUM32_WORDS + threadIdx.x] = (uint32_t)sum.x | ((uint32_t)sum.y << 16);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // mixed-source batches: one running sum per data source (section 4.1.2, section 4.3)
 // ---------------------------------------------------------------------------
 //
@@ -1014,7 +1075,7 @@ int lthash_sum_rows(const uint16_t *rows, uint32_t n_rows, uint16_t *out, hipStr
 
 // Root hashes (64 bytes each) of n records at dev_records (offsets relative to offset_base).
 int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
-                        uint64_t *h0, hipStream_t s)
+                 uint64_t *h0, hipStream_t s, uint64_t p0 = ROOT_P0, uint64_t p1 = ROOT_P1)
 {
     if (n == 0) return SENTRY_OK;
     // Both root kernels are launched; the device takes one path (see four_lane_mode).  The
@@ -1033,10 +1094,10 @@ int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t 
                        static_cast<const uint32_t *>(counts), static_cast<uint32_t *>(order));
     if (n > FEW_RECORDS)   // up to there the device always takes the four-lane path: nothing for this kernel to do
         hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
-                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, h0);
+                           static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, h0, p0, p1);
     hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n,
-                       static_cast<const uint32_t *>(order), h0);
+                       static_cast<const uint32_t *>(order), h0, p0, p1);
     SENTRY_HIP_CHECK(hipGetLastError());
     return SENTRY_OK;
 }
@@ -1140,7 +1201,7 @@ int sentry_lthash_sum(const uint16_t *dev_digests, size_t n, uint16_t *out_lanes
                              static_cast<uint32_t *>(part) + grid * LANE_WORDS, out_lanes, s);
 }
 
-static int addsub(const char *fn, uint16_t *acc, const uint16_t *x, void *stream, bool sub)
+static int addsub(const char *fn, uint16_t *acc, const uint16_t *x, void *stream, bool sub, int lane_words = LANE_WORDS)
 {
     sentry::clear_error();
     SENTRY_REQUIRE(acc != nullptr && x != nullptr, "%s: NULL argument", fn);
@@ -1148,9 +1209,9 @@ static int addsub(const char *fn, uint16_t *acc, const uint16_t *x, void *stream
                    "%s: lanes must be 2-byte aligned", fn);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (sub)
-        hipLaunchKernelGGL(lthash_addsub_kernel<true>, dim3(1), dim3(LANE_WORDS), 0, s, acc, x);
+        hipLaunchKernelGGL(lthash_addsub_kernel<true>, dim3(1), dim3(lane_words), 0, s, acc, x);
     else
-        hipLaunchKernelGGL(lthash_addsub_kernel<false>, dim3(1), dim3(LANE_WORDS), 0, s, acc, x);
+        hipLaunchKernelGGL(lthash_addsub_kernel<false>, dim3(1), dim3(lane_words), 0, s, acc, x);
     SENTRY_HIP_CHECK(hipGetLastError());
     return SENTRY_OK;
 }
@@ -1227,6 +1288,50 @@ int sentry_lthash_combine(uint16_t *acc, const uint16_t *x, void *stream)
 int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stream)
 {
     return addsub("sentry_lthash_remove", acc, x, stream, true);
+}
+
+int sentry_lthash32(const void *dev_records, const uint64_t *dev_offsets, size_t n, uint16_t *out_lanes, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(out_lanes != nullptr && (reinterpret_cast<uintptr_t>(out_lanes) & 1) == 0,
+                   "sentry_lthash32: out_lanes must be non-NULL and 2-byte aligned");
+    SENTRY_REQUIRE(n == 0 || (dev_offsets != nullptr && (reinterpret_cast<uintptr_t>(dev_offsets) & 7) == 0),
+                   "sentry_lthash32: dev_offsets must be non-NULL and 8-byte aligned when n > 0");
+    SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash32: too many records");
+    // one partial row per workgroup; a workgroup's run is at least one full trip of its 16 slices
+    uint64_t grid = ceil_div(n, (uint64_t)SUM32_SLICES * SUM32_AHEAD * 4);
+    const uint64_t cap = (uint64_t)cu_count() * 4;
+    if (grid > cap) grid = cap;
+    if (grid == 0) grid = 1;
+    void *h0, *part;
+    int rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_LT_H0, 64 * n, &h0))) return rc;
+    if ((rc = sentry::scratch_get(s, sentry::R_LT_PART, grid * SUM32_WORDS * 4, &part))) return rc;
+    if ((rc = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s, PLAIN_P0, PLAIN_P1)))
+        return rc;
+    if (grid == 1) {
+        hipLaunchKernelGGL(lthash32_sum_kernel, dim3(1), dim3(SUM32_WG), 0, s, static_cast<const uint32_t *>(h0),
+                           (uint64_t)n, static_cast<uint32_t *>(nullptr), out_lanes);
+    } else {
+        hipLaunchKernelGGL(lthash32_sum_kernel, dim3((uint32_t)grid), dim3(SUM32_WG), 0, s,
+                           static_cast<const uint32_t *>(h0), (uint64_t)n, static_cast<uint32_t *>(part),
+                           static_cast<uint16_t *>(nullptr));
+        hipLaunchKernelGGL(lthash32_sum_kernel, dim3(1), dim3(SUM32_WG), 0, s, static_cast<const uint32_t *>(part),
+                           grid, static_cast<uint32_t *>(nullptr), out_lanes);
+    }
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
+int sentry_lthash32_combine(uint16_t *acc, const uint16_t *x, void *stream)
+{
+    return addsub("sentry_lthash32_combine", acc, x, stream, false, SUM32_WORDS);
+}
+
+int sentry_lthash32_remove(uint16_t *acc, const uint16_t *x, void *stream)
+{
+    return addsub("sentry_lthash32_remove", acc, x, stream, true, SUM32_WORDS);
 }
 
 }  // extern "C"

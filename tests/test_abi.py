@@ -84,6 +84,13 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_lthash_model([0x1000], [64], 8192, 0, 0),                   # NULL output
     lambda: sentry.sentry_lthash_combine(0, 0x2000),
     lambda: sentry.sentry_lthash_remove(0x2001, 0x2000),
+    lambda: sentry.sentry_lthash32(0x1000, 0x3000, 5, 0),                # NULL output
+    lambda: sentry.sentry_lthash32(0x1000, 0x3000, 5, 0x2001),           # misaligned output
+    lambda: sentry.sentry_lthash32(0x1000, 0x3004, 5, 0x2000),           # misaligned offsets
+    lambda: sentry.sentry_lthash32(0x1000, 0, 5, 0x2000),                # NULL offsets with n > 0
+    lambda: sentry.sentry_lthash32(0x1000, 0x3000, 1 << 30, 0x2000),     # too many records
+    lambda: sentry.sentry_lthash32_combine(0x2000, 0),
+    lambda: sentry.sentry_lthash32_remove(0x2000, 0x2003),
     lambda: sentry.sentry_lthash_h2d(0x1000, 0x3000, 5, 0, 0x2000),      # batch_bytes == 0
 ])
 def test_bad_arguments_are_rejected_on_the_host(call):

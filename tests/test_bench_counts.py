@@ -86,6 +86,8 @@ def test_blake2b_and_keccak_counts():
     lens = [rng.randrange(0, 5000) for _ in range(50)] + [0, 1, 127, 128, 129, 256]
     want = sum(max(1, -(-n // 128)) for n in lens) * bench.B2_BLOCK_OPS + len(lens) * 32 * bench.B2_EXPAND_OPS
     assert bench.lthash_ops(lens) == want
+    # the 32-partition hash: the same root blocks, no expansion, 16 packed adds per digest
+    assert bench.lthash32_mix(lens).total() == want - len(lens) * 32 * bench.B2_EXPAND_OPS + 16 * len(lens)
     # model lattice hash: 8 index bytes in front of every block
     for n, blk in ((0, 8192), (1, 8192), (8192, 8192), (8193, 8192), (3 * 112 + 5, 112), (120, 120), (121, 120)):
         blocks = leaves_of(n, blk, empty_has_leaf=False)

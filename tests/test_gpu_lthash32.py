@@ -1,0 +1,137 @@
+"""GPU parity: the 32-partition lattice hash (plain BLAKE2b-512 digests, section 4.2.2)
+against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_00554_amd as sentry
+from paper_2510_00554_amd import workloads as wl
+from conftest import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_lthash32(data_np, off_np, base_shift=0):
+    """base_shift moves the record bytes inside the device buffer to vary their alignment."""
+    n = len(off_np) - 1
+    buf = torch.zeros(data_np.size + base_shift + 16, dtype=torch.uint8, device="cuda")
+    if data_np.size:
+        buf[base_shift:base_shift + data_np.size] = to_dev(data_np)
+    off = to_dev(np.asarray(off_np, dtype=np.uint64))
+    out = torch.full((32,), 0x5555, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash32(buf.data_ptr() + base_shift, off.data_ptr(), n, out.data_ptr())
+    torch.cuda.synchronize()
+    return out.cpu().numpy().view(np.uint16)
+
+
+def test_empty_set():
+    out = torch.full((32,), 0x5555, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash32(0, 0, 0, out.data_ptr())
+    torch.cuda.synchronize()
+    assert not out.cpu().numpy().any()
+
+
+@pytest.mark.parametrize("length", [0, 1, 2, 3, 4, 5, 63, 64, 127, 128, 129, 130, 131, 132, 255, 256, 257,
+                                    383, 384, 385, 3072, 8000, 100_003])
+def test_single_record_every_alignment(length):
+    data = wl.uniform_bytes(4000 + length, 0, length)
+    off = np.array([0, length], np.uint64)
+    want = oracle.lthash32(data, off)
+    for shift in (0, 1, 2, 3):
+        assert (gpu_lthash32(data, off, shift) == want).all(), (length, shift)
+
+
+def test_many_small_variable_records_one_lane_each():
+    rng = np.random.default_rng(131)
+    lens = rng.integers(0, 700, 3000).astype(np.uint64)
+    lens[:20] = [0, 1, 127, 128, 129, 255, 256, 257, 0, 0, 5, 640, 128, 128, 1, 2, 3, 4, 384, 512]
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4100, 0, int(off[-1]))
+    assert (gpu_lthash32(data, off) == oracle.lthash32(data, off)).all()
+    # offsets need not start at zero
+    assert (gpu_lthash32(data, off[7:]) == oracle.lthash32(data, off[7:])).all()
+
+
+def test_equal_long_records_four_lanes_each():
+    # equal lengths of 384 bytes and more go four lanes to a record, unordered
+    for length, n, shift in ((3072, 300, 0), (385, 257, 1), (150_528, 9, 2)):
+        off = wl.offsets_from_lengths(np.full(n, length, np.uint64))
+        data = wl.uniform_bytes(4200 + n, 0, int(off[-1]))
+        assert (gpu_lthash32(data, off, shift) == oracle.lthash32(data, off)).all(), (length, n)
+
+
+def test_unequal_long_records_in_length_order():
+    lens = wl.lognormal_record_lengths(400, seed=177)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4300, 0, int(off[-1]))
+    assert (gpu_lthash32(data, off, 3) == oracle.lthash32(data, off)).all()
+
+
+def test_few_records():
+    lens = np.array([5, 0, 1000, 129, 128], np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4400, 0, int(off[-1]))
+    assert (gpu_lthash32(data, off) == oracle.lthash32(data, off)).all()
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 255, 256, 257, 4095, 4097, 70_001, 300_000])
+def test_row_sum_over_one_and_many_workgroups(n):
+    """Short records, so that the count decides how the digest rows are cut among the
+    workgroups of the sum: one workgroup, a ragged last trip, runs of unequal length."""
+    rng = np.random.default_rng(n)
+    lens = rng.integers(0, 24, n).astype(np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4500 + n, 0, max(int(off[-1]), 1))[:int(off[-1])]
+    assert (gpu_lthash32(data, off) == oracle.lthash32(data, off)).all()
+
+
+def test_same_record_65536_times_is_zero_and_order_does_not_matter():
+    rec = wl.uniform_bytes(4600, 0, 40)
+    data = np.tile(rec, 65536)
+    off = wl.offsets_from_lengths(np.full(65536, 40, np.uint64))
+    assert not gpu_lthash32(data, off).any()
+    lens = np.array([40, 3, 200, 7, 90], np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4601, 0, int(off[-1]))
+    parts = [data[int(off[i]):int(off[i + 1])] for i in range(5)]
+    perm = [3, 0, 4, 2, 1]
+    data2 = np.concatenate([parts[i] for i in perm])
+    off2 = wl.offsets_from_lengths(lens[perm])
+    assert (gpu_lthash32(data, off) == gpu_lthash32(data2, off2)).all()
+
+
+def test_combine_and_remove_against_the_oracle_with_wraparound():
+    lens = np.array([100, 400, 3, 0, 129, 77, 5000, 64], np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4700, 0, int(off[-1]))
+    a = oracle.lthash32(data, off[:4])          # records 0..2
+    b = oracle.lthash32(data, off[3:])          # records 3..7
+    whole = oracle.lthash32(data, off)
+    da = to_dev(a.view(np.int16).copy())
+    db = to_dev(b.view(np.int16).copy())
+    sentry.sentry_lthash32_combine(da.data_ptr(), db.data_ptr())
+    torch.cuda.synchronize()
+    assert (da.cpu().numpy().view(np.uint16) == whole).all()
+    sentry.sentry_lthash32_remove(da.data_ptr(), db.data_ptr())
+    torch.cuda.synchronize()
+    assert (da.cpu().numpy().view(np.uint16) == a).all()
+    # lanes that wrap: 0xffff + 2 = 1, 1 - 2 = 0xffff
+    x = to_dev(np.full(32, -1, np.int16))
+    y = to_dev(np.full(32, 2, np.int16))
+    sentry.sentry_lthash32_combine(x.data_ptr(), y.data_ptr())
+    torch.cuda.synchronize()
+    assert (x.cpu().numpy().view(np.uint16) == 1).all()
+    sentry.sentry_lthash32_remove(x.data_ptr(), y.data_ptr())
+    torch.cuda.synchronize()
+    assert (x.cpu().numpy().view(np.uint16) == 0xffff).all()
+    want = oracle.lanes_sub(whole.copy(), b)
+    assert (want == a).all()
+    # the 1024-lane calls and the 32-lane calls do not disturb each other on one stream
+    big = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    d_data, d_off = to_dev(data), to_dev(off)
+    sentry.sentry_lthash(d_data.data_ptr(), d_off.data_ptr(), len(lens), big.data_ptr())
+    small = gpu_lthash32(data, off)
+    torch.cuda.synchronize()
+    assert (big.cpu().numpy().view(np.uint16) == oracle.lthash(data, off)).all()
+    assert (small == whole).all()
