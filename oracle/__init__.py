@@ -67,6 +67,8 @@ def _bind(L):
         L.oracle_merkle_segments_h.restype = ctypes.c_int
         L.oracle_merkle_inplace_h.argtypes = [ctypes.c_int, vp, vp, sz, sz, vp]
         L.oracle_merkle_inplace_h.restype = ctypes.c_int
+        L.oracle_merkle_coalesced_h.argtypes = [ctypes.c_int, vp, vp, sz, sz, vp]
+        L.oracle_merkle_coalesced_h.restype = ctypes.c_int
         L.oracle_verify.argtypes = [vp, vp]
         L.oracle_verify.restype = ctypes.c_int
         L.oracle_blake2b_constants.argtypes = [vp, vp]
@@ -253,6 +255,19 @@ def merkle_inplace_h(hash_id, segments, leaf_bytes):
     dl = lib().oracle_merkle_inplace_h(hash_id, ptrs, lens, n, leaf_bytes, out.ctypes.data)
     if dl < 0:
         raise ValueError("oracle_merkle_inplace_h rc=%d" % dl)
+    return out[:dl].tobytes()
+
+
+def merkle_coalesced_h(hash_id, segments, leaf_bytes):
+    """Algorithm 1 under hash ``hash_id``: the root of the tree over the zero-padded concatenation."""
+    arrs = [_u8(s) for s in segments]
+    n = len(arrs)
+    ptrs = (ctypes.c_void_p * max(n, 1))(*[_ptr(a) for a in arrs])
+    lens = (ctypes.c_size_t * max(n, 1))(*[a.size for a in arrs])
+    out = np.empty(64, np.uint8)
+    dl = lib().oracle_merkle_coalesced_h(hash_id, ptrs, lens, n, leaf_bytes, out.ctypes.data)
+    if dl < 0:
+        raise ValueError("oracle_merkle_coalesced_h rc=%d" % dl)
     return out[:dl].tobytes()
 
 

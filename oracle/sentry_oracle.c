@@ -15,6 +15,7 @@
  *   - per-tensor digests, then one reduction over the list of per-tensor
  *     digests:                         Algorithm 2 (per-layer hashing).
  *   - one flat tree over the blocks of all fragmented tensors: Algorithm 3.
+ *   - all tensors copied into one buffer padded to whole blocks, one tree over it: Algorithm 1.
  *   - lattice hash = component-wise sum of per-item digests mod 2^d, d = 16:
  *                                      section 2.2 Eq. (1), section 4.2.2.
  *   - one digest per dataset sample, running sum over batches: section 4.3.
@@ -35,7 +36,8 @@
  *   - the per-sample digest h(M) is BLAKE2Xb(M) with 2048 output bytes, read as
  *     1024 little-endian uint16 lanes (the paper's own h is one 64-byte BLAKE2b
  *     digest = 32 lanes; the target configurations ask for 1024 lanes);
- *   - no index is mixed into a dataset sample's digest.
+ *   - no index is mixed into a dataset sample's digest;
+ *   - the padding behind the last tensor in Algorithm 1's buffer is zero bytes.
  *
  * Pins (tests/test_oracle_*.py): FIPS 180-4 vectors, RFC 7693 vector, hashlib
  * on random inputs and on every parameter block hashlib accepts, brute-force
@@ -568,6 +570,31 @@ int oracle_merkle_inplace_h(int hash, const uint8_t *const *ptrs, const size_t *
     reduce_h(hash, nodes, total, out);
     free(nodes);
     return (int)dl;
+}
+
+/* Algorithm 1 (coalesced hashing) under hash h: the tensors are copied one behind the other
+ * into one buffer; the buffer's size is the total rounded up to a whole number of blocks and
+ * the bytes after the last tensor are filled (section 4.2.1, "Coalesced Hashing"; the fill value
+ * is not given there: zero bytes here); then the Merkle tree over that buffer.  No byte at all
+ * = the single empty leaf, as everywhere else. */
+int oracle_merkle_coalesced_h(int hash, const uint8_t *const *ptrs, const size_t *lens, size_t n_seg,
+                              size_t leaf_bytes, uint8_t *out)
+{
+    if (leaf_bytes == 0 || hash < 0 || hash > 2) return -1;
+    size_t total = 0;
+    for (size_t t = 0; t < n_seg; t++) total += lens[t];
+    const size_t padded = (total + leaf_bytes - 1) / leaf_bytes * leaf_bytes;
+    uint8_t *buffer = (uint8_t *)malloc(padded ? padded : 1);
+    if (!buffer) return -3;
+    size_t at = 0;
+    for (size_t t = 0; t < n_seg; t++) {
+        if (lens[t]) memcpy(buffer + at, ptrs[t], lens[t]);
+        at += lens[t];
+    }
+    memset(buffer + at, 0, padded - at);
+    int rc = oracle_merkle_root_h(hash, buffer, padded, leaf_bytes, out);
+    free(buffer);
+    return rc;
 }
 
 /* ------------------------------------------------------------------------ */

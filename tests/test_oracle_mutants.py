@@ -42,7 +42,8 @@ PINS = [
     t_lt.test_lthash32_is_the_sum_of_hashlib_digests, t_lt.test_lthash32_set_identities_and_modulus,
     t_oh.test_keccak_constants_match_fips202_definitions, t_oh.test_sha3_fips202_examples, t_oh.test_sha3_against_hashlib,
 ] + [(lambda h=h, f=f: t_oh.test_merkle_trees_over_each_leaf_function(h, f)) for h, f in t_oh.HASHES] \
-  + [(lambda h=h, f=f: t_oh.test_per_tensor_and_flat_trees_over_each_leaf_function(h, f)) for h, f in t_oh.HASHES]
+  + [(lambda h=h, f=f: t_oh.test_per_tensor_and_flat_trees_over_each_leaf_function(h, f)) for h, f in t_oh.HASHES] \
+  + [(lambda h=h, f=f: t_oh.test_coalesced_tree_is_the_tree_over_the_zero_padded_concatenation(h, f)) for h, f in t_oh.HASHES]
 
 # (what is planted, text in the source, replacement); every text occurs exactly once
 MUTANTS = [
@@ -67,6 +68,13 @@ MUTANTS = [
      "for (size_t t = 0; t < n_seg; t++) oracle_sha256(seg_roots + 32 * t, 32, nodes + 32 * t);"),
     ("Merkle (flat): an empty tensor contributes an empty leaf", "for (size_t t = 0; t < n_seg; t++) total += (lens[t] + leaf_bytes - 1) / leaf_bytes;\n    if (total == 0) { oracle_sha256(NULL, 0, out); return 0; }",
      "for (size_t t = 0; t < n_seg; t++) total += lens[t] ? (lens[t] + leaf_bytes - 1) / leaf_bytes : 1;\n    if (total == 0) { oracle_sha256(NULL, 0, out); return 0; }"),
+    ("Merkle (coalesced): no padding behind the last tensor", "int rc = oracle_merkle_root_h(hash, buffer, padded, leaf_bytes, out);\n    free(buffer);",
+     "int rc = oracle_merkle_root_h(hash, buffer, at, leaf_bytes, out);\n    free(buffer);"),
+    ("Merkle (coalesced): the padding is not zero", "memset(buffer + at, 0, padded - at);", "memset(buffer + at, 0x80, padded - at);"),
+    ("Merkle (coalesced): a whole extra block when the total is a multiple of the block size",
+     "const size_t padded = (total + leaf_bytes - 1) / leaf_bytes * leaf_bytes;", "const size_t padded = (total / leaf_bytes + 1) * leaf_bytes;"),
+    ("Merkle (coalesced): the tensors are laid down last to first", "for (size_t t = 0; t < n_seg; t++) {\n        if (lens[t]) memcpy(buffer + at, ptrs[t], lens[t]);",
+     "for (size_t t = n_seg; t-- > 0;) {\n        if (lens[t]) memcpy(buffer + at, ptrs[t], lens[t]);"),
     ("verify: the last byte is not looked at", "for (int i = 0; i < 32; i++) diff |= (unsigned)(a[i] ^ b[i]);", "for (int i = 0; i < 31; i++) diff |= (unsigned)(a[i] ^ b[i]);"),
     ("BLAKE2b: a rotation of G off by one", "v[b] = rotr64(v[b] ^ v[c], 24);", "v[b] = rotr64(v[b] ^ v[c], 25);"),
     ("BLAKE2b: G adds x twice", "v[a] = v[a] + v[b] + y;", "v[a] = v[a] + v[b] + x;"),

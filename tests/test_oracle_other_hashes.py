@@ -101,3 +101,34 @@ def test_per_tensor_and_flat_trees_over_each_leaf_function(hid, hfun):
         if hid == oracle.HASH_SHA256:
             assert (roots, root) == oracle.merkle_segments(segs, L)
             assert want_flat == oracle.merkle_inplace(segs, L)
+
+
+@pytest.mark.parametrize("hid,hfun", HASHES)
+def test_coalesced_tree_is_the_tree_over_the_zero_padded_concatenation(hid, hfun):
+    # Algorithm 1: tensors copied one behind the other, the buffer a whole number of blocks long
+    # (zero bytes behind the last tensor), one tree over it; rebuilt here with bytes.join, hashlib
+    # and a Python list of nodes
+    rng = random.Random(70 + hid)
+    L = 128
+    for sizes in ([1], [0], [], [L], [L - 1, 1], [L + 1, 0, 3 * L, 5], [0, 0], [3, 5, 7, 11, 13],
+                  [7 * L - 1, L, 2 * L + 9, 0, 64, 33 * L], [rng.randrange(0, 6 * L) for _ in range(13)]):
+        segs = [rng.randbytes(n) for n in sizes]
+        cat = b"".join(segs)
+        cat += bytes(-len(cat) % L)
+        want = brute(hfun, cat, L)
+        assert oracle.merkle_coalesced_h(hid, segs, L) == want, (hid, sizes)
+        assert len(cat) % L == 0
+    # blocks run across tensor boundaries: the same bytes cut differently give the same root ...
+    buf = rng.randbytes(5 * L + 17)
+    a = oracle.merkle_coalesced_h(hid, [buf[:100], buf[100:101], buf[101:]], L)
+    b = oracle.merkle_coalesced_h(hid, [buf], L)
+    assert a == b
+    # ... which is not the in-place root of the same tensors (short last blocks, Algorithm 3),
+    # and the padding is part of what is hashed: a buffer of whole blocks has none
+    assert a != oracle.merkle_inplace_h(hid, [buf[:100], buf[100:101], buf[101:]], L)
+    assert b != oracle.merkle_root_h(hid, buf, L)
+    whole = rng.randbytes(4 * L)
+    assert oracle.merkle_coalesced_h(hid, [whole[:L + 5], whole[L + 5:]], L) == oracle.merkle_root_h(hid, whole, L)
+    # one short tensor: the hash of its bytes and the zeros up to the block size
+    assert oracle.merkle_coalesced_h(hid, [b"abc"], L) == hfun(b"abc" + bytes(L - 3))
+    assert oracle.merkle_coalesced_h(hid, [], L) == hfun(b"")
