@@ -640,6 +640,23 @@ def main():
         ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, 8192, root7.data_ptr(), stream), 5)
         per_config["F3_merkle_7b_inplace_flat_8KiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
                                                              sha_tree_mix(t7_lens, 8192, flat=True))
+        # the same checkpoint as one zero-padded byte stream (Algorithm 1, coalesced hashing), 8 KiB blocks:
+        # hashed where the tensors lie (only blocks that span tensors are gathered), and the scheme as
+        # stated, through a coalesced copy in a second buffer (the copy reads and writes every byte once more)
+        pad7 = -(-bytes7 // 8192) * 8192
+        ms = timed_call(lambda: sentry.sentry_merkle_coalesced(t7_ptrs, t7_lens, 8192, 0, 0, root7.data_ptr(), stream), 5)
+        per_config["A1_merkle_7b_coalesced_in_place_8KiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
+                                                                    sha_tree_mix([pad7], 8192, flat=True))
+        cbuf = torch.empty(pad7, dtype=torch.uint8, device=dev)
+        ms_c = timed_call(lambda: sentry.sentry_merkle_coalesced(t7_ptrs, t7_lens, 8192, cbuf.data_ptr(), pad7,
+                                                                 root7.data_ptr(), stream), 5)
+        ms_r = timed_call(lambda: sentry.sentry_merkle_root(cbuf.data_ptr(), pad7, 8192, root7.data_ptr(), stream), 5)
+        e = rated({"GB/s": bytes7 / ms_c / 1e6, "ms": ms_c, "bytes": bytes7}, sha_tree_mix([pad7], 8192, flat=True),
+                  hbm_bytes=3 * bytes7)
+        e["copy_ms"] = ms_c - ms_r            # the gather kernel: the call less the tree over the filled buffer
+        e["copy_TB/s_read_plus_write"] = 2 * bytes7 / (ms_c - ms_r) / 1e9
+        per_config["A1_merkle_7b_coalesced_with_copy_8KiB"] = e
+        del cbuf
         # the three leaf functions of section 4.2.1 on the first 16 GiB of the 70B stream, 8 KiB leaves
         f4_bytes = min(bytes70, 16 << 30)
         big_root = torch.zeros(64, dtype=torch.uint8, device=dev)

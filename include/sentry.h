@@ -167,6 +167,47 @@ SENTRY_API int sentry_merkle_inplace_h(int hash, const void *const *dev_ptrs, co
                                        size_t leaf_bytes, uint8_t *out_root, void *stream);
 
 /*
+ * Coalesced hashing (Algorithm 1; section 4.2.1, "Coalesced Hashing"): the root
+ * of the Merkle tree over ONE buffer that holds the tensors one behind the
+ * other, in order, without gaps; the buffer is a whole number of blocks long
+ * and the bytes behind the last tensor are zero (the paper does not give the
+ * fill value).  Blocks run across tensor boundaries, so the root depends on the
+ * concatenated bytes only, not on where one tensor ends: it equals
+ * sentry_merkle_root_h over the zero-padded concatenation.
+ * dev_ptrs, lens, n_seg  host arrays (read before the call returns) of n_seg >= 1
+ *              device pointers and byte lengths; ANY alignment and length; a
+ *              pointer may be NULL where its length is 0.  Not modified.
+ * leaf_bytes   block size, a positive multiple of 64.
+ * dev_buffer   device, 16-byte aligned, at least ceil(total / leaf_bytes) *
+ *              leaf_bytes bytes (buffer_bytes says how many it has), disjoint
+ *              from every tensor: the scheme as stated.  A copy kernel lays the
+ *              tensors into it and clears the padding, then the tree runs over
+ *              it; on return (once the stream has been synchronised) it holds
+ *              the coalesced model.  Bytes behind the padded size are not
+ *              touched.
+ *              NULL (buffer_bytes ignored): the same root without the second
+ *              copy of the model.  Only blocks that hold bytes of more than one
+ *              tensor, the padded last block, and blocks whose bytes are not
+ *              16-byte aligned in their tensor are put together in library
+ *              scratch (at most one block per tensor when all tensors are
+ *              16-byte aligned and their lengths multiples of 16); all other
+ *              blocks are hashed where they lie.
+ * out_root     device-accessible, one digest (32 bytes, 64 for BLAKE2b).
+ * hash         as for sentry_merkle_root_h; sentry_merkle_coalesced is SHA-256.
+ * No byte at all (every length 0) gives the root of the single empty leaf.
+ * Errors: SENTRY_ERR_INVALID_ARG for a NULL argument, an unknown hash, a bad
+ * leaf_bytes, a buffer that is too small, misaligned or overlaps a tensor;
+ * SENTRY_ERR_NOMEM / SENTRY_ERR_HIP from scratch or a launch.  Uploads a table:
+ * not meant for graph capture.
+ */
+SENTRY_API int sentry_merkle_coalesced(const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                                       size_t leaf_bytes, void *dev_buffer, size_t buffer_bytes,
+                                       uint8_t *out_root, void *stream);
+SENTRY_API int sentry_merkle_coalesced_h(int hash, const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                                         size_t leaf_bytes, void *dev_buffer, size_t buffer_bytes,
+                                         uint8_t *out_root, void *stream);
+
+/*
  * The block hashing kernel alone: the max(1, ceil(len/leaf_bytes)) leaf digests
  * of a buffer, 32 bytes each, in leaf order (section 4.2.1).
  * out_leaf_digests  device, 16-byte aligned, 32 bytes per leaf.

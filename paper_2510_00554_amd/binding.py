@@ -36,6 +36,8 @@ PROTOTYPES = {
     "sentry_merkle_inplace": (_int, [_vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_segments_h": (_int, [_int, _vp, _vp, _sz, _sz, _vp, _vp, _vp]),
     "sentry_merkle_inplace_h": (_int, [_int, _vp, _vp, _sz, _sz, _vp, _vp]),
+    "sentry_merkle_coalesced": (_int, [_vp, _vp, _sz, _sz, _vp, _sz, _vp, _vp]),
+    "sentry_merkle_coalesced_h": (_int, [_int, _vp, _vp, _sz, _sz, _vp, _sz, _vp, _vp]),
     "sentry_merkle_leaves": (_int, [_vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_reduce": (_int, [_vp, _sz, _vp, _vp]),
     "sentry_merkle_stream_begin": (_int, [_sz, _sz, ctypes.POINTER(_vp)]),
@@ -153,6 +155,18 @@ def sentry_merkle_inplace_h(hash_id, dev_ptrs, lens, leaf_bytes, out_root, strea
     """dev_ptrs, lens: Python sequences of ints (device addresses, byte lengths)."""
     ptrs, ls, n = _segment_arrays(dev_ptrs, lens)
     return _check(load().sentry_merkle_inplace_h(hash_id, ptrs, ls, n, leaf_bytes, out_root, stream))
+
+
+def sentry_merkle_coalesced(dev_ptrs, lens, leaf_bytes, dev_buffer, buffer_bytes, out_root, stream=0):
+    """dev_ptrs, lens: Python sequences of ints; dev_buffer 0 = no coalesced copy is made."""
+    ptrs, ls, n = _segment_arrays(dev_ptrs, lens)
+    return _check(load().sentry_merkle_coalesced(ptrs, ls, n, leaf_bytes, dev_buffer, buffer_bytes, out_root, stream))
+
+
+def sentry_merkle_coalesced_h(hash_id, dev_ptrs, lens, leaf_bytes, dev_buffer, buffer_bytes, out_root, stream=0):
+    ptrs, ls, n = _segment_arrays(dev_ptrs, lens)
+    return _check(load().sentry_merkle_coalesced_h(hash_id, ptrs, ls, n, leaf_bytes, dev_buffer, buffer_bytes, out_root,
+                                                   stream))
 
 
 def sentry_merkle_leaves(dev_buf, length, leaf_bytes, out_leaf_digests, stream=0):

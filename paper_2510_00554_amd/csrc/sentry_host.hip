@@ -24,10 +24,10 @@ void clear_error() { g_err[0] = '\0'; }
 struct StreamCtx {
     void *region[R_COUNT] = {};
     size_t cap[R_COUNT] = {};
-    void *tab_host = nullptr;      // pinned
-    size_t tab_cap = 0;
-    hipEvent_t tab_event = nullptr;
-    bool tab_pending = false;
+    void *tab_host[TABLE_SLOTS] = {};      // pinned
+    size_t tab_cap[TABLE_SLOTS] = {};
+    hipEvent_t tab_event[TABLE_SLOTS] = {};
+    bool tab_pending[TABLE_SLOTS] = {};
     CopyPipe pipe = {};
     bool pipe_ready = false;
     bool hash_streams_ready = false;
@@ -91,20 +91,20 @@ int scratch_get_fresh(hipStream_t stream, Region r, size_t bytes, void **out, bo
     return SENTRY_OK;
 }
 
-int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr)
+int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr, int slot)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     StreamCtx *c;
     int rc = ctx_for(stream, &c);
     if (rc) return rc;
-    if (c->tab_pending) {   // the previous upload must have left the pinned memory
-        SENTRY_HIP_CHECK(hipEventSynchronize(c->tab_event));
-        c->tab_pending = false;
+    if (c->tab_pending[slot]) {   // the previous upload must have left the pinned memory
+        SENTRY_HIP_CHECK(hipEventSynchronize(c->tab_event[slot]));
+        c->tab_pending[slot] = false;
     }
-    if (c->tab_cap < bytes) {
-        if (c->tab_host) SENTRY_HIP_CHECK(hipHostFree(c->tab_host));
-        c->tab_host = nullptr;
-        c->tab_cap = 0;
+    if (c->tab_cap[slot] < bytes) {
+        if (c->tab_host[slot]) SENTRY_HIP_CHECK(hipHostFree(c->tab_host[slot]));
+        c->tab_host[slot] = nullptr;
+        c->tab_cap[slot] = 0;
         size_t want = (bytes + 4095) & ~(size_t)4095;
         void *p = nullptr;
         hipError_t e = hipHostMalloc(&p, want, hipHostMallocDefault);
@@ -113,22 +113,22 @@ int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr)
             set_error("pinned table allocation of %zu bytes failed: %s", want, hipGetErrorString(e));
             return SENTRY_ERR_NOMEM;
         }
-        c->tab_host = p;
-        c->tab_cap = want;
+        c->tab_host[slot] = p;
+        c->tab_cap[slot] = want;
     }
-    if (!c->tab_event) SENTRY_HIP_CHECK(hipEventCreateWithFlags(&c->tab_event, hipEventDisableTiming));
-    *host_ptr = c->tab_host;
+    if (!c->tab_event[slot]) SENTRY_HIP_CHECK(hipEventCreateWithFlags(&c->tab_event[slot], hipEventDisableTiming));
+    *host_ptr = c->tab_host[slot];
     return SENTRY_OK;
 }
 
-int table_staging_mark(hipStream_t stream)
+int table_staging_mark(hipStream_t stream, int slot)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     StreamCtx *c;
     int rc = ctx_for(stream, &c);
     if (rc) return rc;
-    SENTRY_HIP_CHECK(hipEventRecord(c->tab_event, stream));
-    c->tab_pending = true;
+    SENTRY_HIP_CHECK(hipEventRecord(c->tab_event[slot], stream));
+    c->tab_pending[slot] = true;
     return SENTRY_OK;
 }
 
@@ -218,8 +218,10 @@ int release_all_scratch()
         StreamCtx &c = it->second;
         for (int r = 0; r < R_COUNT; r++)
             if (c.region[r]) SENTRY_HIP_CHECK(hipFree(c.region[r]));
-        if (c.tab_host) SENTRY_HIP_CHECK(hipHostFree(c.tab_host));
-        if (c.tab_event) SENTRY_HIP_CHECK(hipEventDestroy(c.tab_event));
+        for (int t = 0; t < TABLE_SLOTS; t++) {
+            if (c.tab_host[t]) SENTRY_HIP_CHECK(hipHostFree(c.tab_host[t]));
+            if (c.tab_event[t]) SENTRY_HIP_CHECK(hipEventDestroy(c.tab_event[t]));
+        }
         if (c.pipe_ready) {
             SENTRY_HIP_CHECK(hipStreamDestroy(c.pipe.copy_stream));
             SENTRY_HIP_CHECK(hipEventDestroy(c.pipe.start));

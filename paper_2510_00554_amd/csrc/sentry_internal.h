@@ -58,6 +58,8 @@ enum Region {
     R_STAGE_OFF1,
     R_STAGE_OFF2,
     R_TICKET,        // "last workgroup" counter of the one-launch Merkle tree (zero between launches)
+    R_GATHER,        // blocks of the coalesced scheme that are put together from several tensors
+    R_GATHER_TAB,    // copy table of the gather kernel
     R_COUNT
 };
 
@@ -71,9 +73,12 @@ int scratch_get_fresh(hipStream_t stream, Region r, size_t bytes, void **out, bo
 
 // Pinned host staging for tables (per stream): returns a host pointer of >= bytes.  Before
 // the memory is reused the previous upload from it has completed (tracked by an event).
-int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr);
+// Two independent slots, so that a call which uploads a table of its own and then runs an
+// entry point that uploads another does not wait for its first upload.
+constexpr int TABLE_SLOTS = 2;
+int table_staging_get(hipStream_t stream, size_t bytes, void **host_ptr, int slot = 0);
 // Record that an upload from the staging memory was enqueued on `stream`.
-int table_staging_mark(hipStream_t stream);
+int table_staging_mark(hipStream_t stream, int slot = 0);
 
 // Side stream and events for the host-streaming entry points (per stream).
 // PIPE_SLOTS = batches in flight in the lattice host-streaming call.  Slot 0 hashes on the

@@ -7,7 +7,7 @@ touches the GPU library.  Leaves and records are independent, so the work is fan
 over processes, each running the single-threaded oracle on its slice; the reductions are
 done by the oracle in the parent.  Run from the repository root:
 
-    python tests/golden/make_golden.py [c1 c2 c3 c4 c5] [--procs N]
+    python tests/golden/make_golden.py [c1 c2 c3 c3model c3coalesced c4 c5] [--procs N]
 """
 import argparse
 import multiprocessing as mp
@@ -149,6 +149,53 @@ def c3model(pool):
           [lanes_hex(total)] + ["%s %s" % (lay[i][0], lanes_hex(layers[i])) for i in range(len(lay))])
 
 
+def _c3co_task(args):
+    start, nbytes, leaf, h = args
+    lay = wl.layout_7b()
+    data = wl.checkpoint_stream_np(lay, start, nbytes, base_seed=wl.SEED_C3)
+    if nbytes % leaf:                      # Algorithm 1: zero bytes up to a whole block
+        data = np.concatenate([data, np.zeros(leaf - nbytes % leaf, np.uint8)])
+    if h == oracle.HASH_SHA256:
+        return start, oracle.merkle_leaves(data, leaf).tobytes()
+    return start, b"".join(oracle.merkle_root_h(h, data[i:i + leaf], leaf) for i in range(0, data.size, leaf))
+
+
+def c3coalesced(pool):
+    """Algorithm 1 over the 7B checkpoint: the tensors as one byte stream, zero-padded to whole blocks;
+    SHA-256 at 1 MiB blocks, and SHA-256 and BLAKE2b-512 at the paper's default 8 KiB."""
+    lay = wl.layout_7b()
+    total = wl.checkpoint_offsets(lay)[-1]
+    lines = []
+    for name, h, dl, leaf in (("sha256", oracle.HASH_SHA256, 32, 1 << 20), ("sha256", oracle.HASH_SHA256, 32, 8192),
+                              ("blake2b", oracle.HASH_BLAKE2B, 64, 8192)):
+        span = 64 << 20
+        tasks = [(s, min(span, total - s), leaf, h) for s in range(0, total, span)]
+        n_leaves = -(-total // leaf)
+        digests = np.empty((n_leaves, dl), np.uint8)
+        for start, blob in pool.imap_unordered(_c3co_task, tasks, chunksize=1):
+            d = np.frombuffer(blob, np.uint8).reshape(-1, dl)
+            digests[start // leaf:start // leaf + d.shape[0]] = d
+        # the tree over ready-made nodes: the hash of the 2-node concatenation, level by level,
+        # is what merkle_root_h does to a buffer of digests cut into leaves of two digests' size
+        root = oracle.merkle_reduce(digests) if h == oracle.HASH_SHA256 else _reduce_h(h, digests)
+        lines.append("%s %d %s" % (name, leaf, root.hex()))
+        print("c3coalesced", name, leaf, flush=True)
+    write("config3_coalesced_root.txt",
+          ["Root (oracle) of the tree over the 291 tensors of config 3 laid one behind the other in one buffer,",
+           "zero bytes up to a whole block (Algorithm 1, coalesced hashing); %d bytes.  '<hash> <block bytes> <root>'" % total],
+          lines)
+
+
+def _reduce_h(h, digests):
+    level = [bytes(d) for d in digests]
+    while len(level) > 1:
+        nxt = [oracle.merkle_root_h(h, level[i] + level[i + 1], 2 * len(level[i])) for i in range(0, len(level) - 1, 2)]
+        if len(level) % 2:
+            nxt.append(level[-1])
+        level = nxt
+    return level[0]
+
+
 # ---- config 4: lattice hash of record ranges ---------------------------------------------
 
 _C4_OFF = None
@@ -197,12 +244,12 @@ def c4(pool):
 
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
-    ap.add_argument("configs", nargs="*", default=["c1", "c2", "c3", "c3model", "c4", "c5"])
+    ap.add_argument("configs", nargs="*", default=["c1", "c2", "c3", "c3model", "c3coalesced", "c4", "c5"])
     ap.add_argument("--procs", type=int, default=os.cpu_count())
     a = ap.parse_args()
     oracle.build()
     with mp.Pool(a.procs) as pool:
         for c in a.configs:
             t = time.time()
-            {"c1": c1, "c2": c2}.get(c, lambda: {"c3": c3, "c3model": c3model, "c4": c4, "c5": c5}[c](pool))()
+            {"c1": c1, "c2": c2}.get(c, lambda: {"c3": c3, "c3model": c3model, "c3coalesced": c3coalesced, "c4": c4, "c5": c5}[c](pool))()
             print("%s done in %.0fs" % (c, time.time() - t), flush=True)

@@ -82,6 +82,14 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_lthash_model([0x1000], [64], 100, 0, 0x2000),               # block not a multiple of 16
     lambda: sentry.sentry_lthash_model([0x1008], [64], 8192, 0, 0x2000),              # misaligned tensor
     lambda: sentry.sentry_lthash_model([0x1000], [64], 8192, 0, 0),                   # NULL output
+    lambda: sentry.sentry_merkle_coalesced([0x1000], [64], 100, 0, 0, 0x2000),         # leaf_bytes not a multiple of 64
+    lambda: sentry.sentry_merkle_coalesced([], [], 64, 0, 0, 0x2000),                  # no tensors
+    lambda: sentry.sentry_merkle_coalesced([0], [64], 64, 0, 0, 0x2000),               # NULL tensor with bytes
+    lambda: sentry.sentry_merkle_coalesced([0x1000], [64], 64, 0, 0, 0),               # NULL output
+    lambda: sentry.sentry_merkle_coalesced([0x1000], [65], 64, 0x4000, 64, 0x2000),    # buffer too small for the padding
+    lambda: sentry.sentry_merkle_coalesced([0x1000], [64], 64, 0x4004, 64, 0x2000),    # misaligned buffer
+    lambda: sentry.sentry_merkle_coalesced([0x1000], [64], 64, 0x1020, 64, 0x2000),    # buffer inside the tensor
+    lambda: sentry.sentry_merkle_coalesced_h(7, [0x1000], [64], 64, 0, 0, 0x2000),     # unknown hash
     lambda: sentry.sentry_lthash_combine(0, 0x2000),
     lambda: sentry.sentry_lthash_remove(0x2001, 0x2000),
     lambda: sentry.sentry_lthash32(0x1000, 0x3000, 5, 0),                # NULL output

@@ -173,3 +173,36 @@ def test_config3_checkpoint_inplace_flat_tree():
     assert bytes(top.cpu().numpy()) == want
     del tensors
     free_gpu()
+
+
+def test_config3_checkpoint_coalesced_tree():
+    # the same 291 fragmented tensors as ONE zero-padded byte stream (Algorithm 1): hashed where they lie
+    # (only the blocks that span tensors are gathered), and through a coalesced copy in a second buffer
+    want = {}
+    for ln in golden_lines("config3_coalesced_root.txt"):
+        name, leaf, root = ln.split()
+        want[(name, int(leaf))] = bytes.fromhex(root)
+    lay = wl.layout_7b()
+    tensors = [wl.checkpoint_tensor(lay, i, base_seed=wl.SEED_C3, device="cuda") for i in range(len(lay))]
+    ptrs, lens = [t.data_ptr() for t in tensors], [2 * t.numel() for t in tensors]
+    total = sum(lens)
+    top = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    for (name, leaf), root in want.items():
+        hid = {"sha256": sentry.HASH_SHA256, "blake2b": sentry.HASH_BLAKE2B}[name]
+        top.zero_()
+        sentry.sentry_merkle_coalesced_h(hid, ptrs, lens, leaf, 0, 0, top.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(top.cpu().numpy()[:len(root)]) == root, (name, leaf)
+    padded = -(-total // (1 << 20)) * (1 << 20)
+    buf = torch.empty(padded, dtype=torch.uint8, device="cuda")
+    top.zero_()
+    sentry.sentry_merkle_coalesced(ptrs, lens, 1 << 20, buf.data_ptr(), padded, top.data_ptr())
+    torch.cuda.synchronize()
+    assert bytes(top.cpu().numpy()[:32]) == want[("sha256", 1 << 20)]
+    # the buffer now holds the stream: its plain root at another block size is the coalesced root at that size
+    if padded == total:
+        sentry.sentry_merkle_root(buf.data_ptr(), total, 8192, top.data_ptr())
+        torch.cuda.synchronize()
+        assert bytes(top.cpu().numpy()[:32]) == want[("sha256", 8192)]
+    del tensors, buf
+    free_gpu()
