@@ -254,9 +254,28 @@ def probe_issue_rates(only=None, waves=(4,)):
 
 
 def run_only_config(args, sentry, wl, torch, np, dev, stream):
-    """Config 1 or config 2 alone, args.steps timed calls after args.warmup: one short JSON line."""
+    """One configuration alone, args.steps timed calls after args.warmup: one short JSON line."""
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    if args.only_config == "c1":
+    if args.only_config == "a1":
+        # coalesced hashing with the copy (Algorithm 1) of the 7B checkpoint, 8 KiB blocks
+        lay7 = wl.layout_7b()
+        t7 = [wl.checkpoint_tensor(lay7, i, base_seed=wl.SEED_C3, device=dev) for i in range(len(lay7))]
+        ptrs, lens = [t.data_ptr() for t in t7], [t.numel() * 2 for t in t7]
+        nbytes = sum(lens)
+        padded = -(-nbytes // 8192) * 8192
+        cbuf = torch.empty(padded, dtype=torch.uint8, device=dev)
+        out = torch.zeros(32, dtype=torch.uint8, device=dev)
+        mix = sha_tree_mix([padded], 8192, flat=True)
+        if args.copy_probe:
+            src = torch.ones(1 << 30, dtype=torch.int32, device=dev)
+            dst = torch.empty_like(src)
+            torch.add(src, 1, out=dst)
+            torch.cuda.synchronize()
+            del src, dst
+
+        def call():
+            sentry.sentry_merkle_coalesced(ptrs, lens, 8192, cbuf.data_ptr(), padded, out.data_ptr(), stream)
+    elif args.only_config == "c1":
         buf = wl.uniform_bytes(wl.SEED_C1, 0, 16 << 20, device=dev)
         out = torch.zeros(32, dtype=torch.uint8, device=dev)
         nbytes, mix = buf.numel(), sha_tree_mix([buf.numel()], 4096, flat=True)
@@ -323,9 +342,10 @@ def main():
     ap.add_argument("--no-streaming", action="store_true", help="skip the host-to-device streaming legs (for counter runs)")
     ap.add_argument("--merkle-prefix-gib", type=int, default=0,
                     help="hash only the first N GiB of the 70B stream (for counter runs; the workload name says so)")
-    ap.add_argument("--only-config", choices=("c1", "c2"), default=None,
-                    help="run only config 1 (16 MiB Merkle, 4 KiB leaves) or config 2 (50,000 images, lattice hash, and "
-                         "the two halves combined) --steps times and print its own short line (for kernel traces)")
+    ap.add_argument("--only-config", choices=("c1", "c2", "a1"), default=None,
+                    help="run only config 1 (16 MiB Merkle, 4 KiB leaves), config 2 (50,000 images, lattice hash, and "
+                         "the two halves combined) or a1 (coalesced hashing of the 7B checkpoint with the copy, 8 KiB "
+                         "blocks) --steps times and print its own short line (for kernel traces)")
     ap.add_argument("--valu-probe", action="store_true",
                     help="print the measured issue rate of every VALU opcode the hash kernels use, and exit")
     ap.add_argument("--copy-probe", action="store_true",
