@@ -146,9 +146,15 @@ Plan plan_in_place(const void *const *ptrs, const size_t *lens, size_t n_seg, ui
         uint64_t left = lens[t];
         while (left) {
             const uint64_t in_block = pos % leaf;
-            if (in_block == 0 && left >= leaf && (reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+            if (in_block == 0 && left >= leaf) {            // whole blocks of this tensor, in one step
                 const uint64_t whole = left / leaf * leaf;
-                pl.run(false, reinterpret_cast<uintptr_t>(p), whole);
+                if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+                    pl.run(false, reinterpret_cast<uintptr_t>(p), whole);
+                } else {
+                    pl.run(true, (uintptr_t)pl.gathered_bytes, whole);
+                    pl.piece(p, pl.gathered_bytes, whole);
+                    pl.gathered_bytes += whole;
+                }
                 p += whole; left -= whole; pos += whole;
                 continue;
             }
