@@ -203,6 +203,19 @@ SENTRY_API int sentry_merkle_inplace_h(int hash, const void *const *dev_ptrs, co
 SENTRY_API int sentry_merkle_coalesced(const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
                                        size_t leaf_bytes, void *dev_buffer, size_t buffer_bytes,
                                        uint8_t *out_root, void *stream);
+/*
+ * What the call above would do with dev_buffer == NULL, without doing it (host
+ * only, no GPU work; the pointers are looked at, never followed):
+ * out_gathered_bytes  bytes of library scratch the gathered blocks take (a
+ *                     multiple of leaf_bytes);
+ * out_copied_bytes    bytes of the tensors that are copied into them (the rest
+ *                     of the scratch is the zero padding of the last block);
+ * out_runs            runs of whole blocks the leaf stage is given.
+ * Each may be NULL.  Errors: SENTRY_ERR_INVALID_ARG as above.
+ */
+SENTRY_API int sentry_merkle_coalesced_plan(const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                                            size_t leaf_bytes, size_t *out_gathered_bytes,
+                                            size_t *out_copied_bytes, size_t *out_runs);
 SENTRY_API int sentry_merkle_coalesced_h(int hash, const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
                                          size_t leaf_bytes, void *dev_buffer, size_t buffer_bytes,
                                          uint8_t *out_root, void *stream);

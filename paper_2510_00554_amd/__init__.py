@@ -6,7 +6,7 @@ C ABI in ``include/sentry.h``); this package only marshals arguments.
 from .binding import (  # noqa: F401
     LANES, HASH_SHA256, HASH_BLAKE2B, HASH_SHA3_256, SentryError, lib_path, load,
     OK, MISMATCH, ERR_INVALID_ARG, ERR_HIP, ERR_NOMEM,
-    sentry_merkle_root, sentry_merkle_root_noalloc, sentry_merkle_root_h, sentry_merkle_segments, sentry_merkle_inplace, sentry_merkle_segments_h, sentry_merkle_inplace_h, sentry_merkle_coalesced, sentry_merkle_coalesced_h,
+    sentry_merkle_root, sentry_merkle_root_noalloc, sentry_merkle_root_h, sentry_merkle_segments, sentry_merkle_inplace, sentry_merkle_segments_h, sentry_merkle_inplace_h, sentry_merkle_coalesced, sentry_merkle_coalesced_h, sentry_merkle_coalesced_plan,
     sentry_merkle_leaves, sentry_merkle_reduce,
     sentry_merkle_stream_begin, sentry_merkle_stream_update, sentry_merkle_stream_update_h2d, sentry_merkle_stream_final,
     sentry_merkle_stream_abort, sentry_merkle_root_h2d, sentry_verify,

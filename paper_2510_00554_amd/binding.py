@@ -37,6 +37,7 @@ PROTOTYPES = {
     "sentry_merkle_segments_h": (_int, [_int, _vp, _vp, _sz, _sz, _vp, _vp, _vp]),
     "sentry_merkle_inplace_h": (_int, [_int, _vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_coalesced": (_int, [_vp, _vp, _sz, _sz, _vp, _sz, _vp, _vp]),
+    "sentry_merkle_coalesced_plan": (_int, [_vp, _vp, _sz, _sz, _vp, _vp, _vp]),
     "sentry_merkle_coalesced_h": (_int, [_int, _vp, _vp, _sz, _sz, _vp, _sz, _vp, _vp]),
     "sentry_merkle_leaves": (_int, [_vp, _sz, _sz, _vp, _vp]),
     "sentry_merkle_reduce": (_int, [_vp, _sz, _vp, _vp]),
@@ -161,6 +162,14 @@ def sentry_merkle_coalesced(dev_ptrs, lens, leaf_bytes, dev_buffer, buffer_bytes
     """dev_ptrs, lens: Python sequences of ints; dev_buffer 0 = no coalesced copy is made."""
     ptrs, ls, n = _segment_arrays(dev_ptrs, lens)
     return _check(load().sentry_merkle_coalesced(ptrs, ls, n, leaf_bytes, dev_buffer, buffer_bytes, out_root, stream))
+
+
+def sentry_merkle_coalesced_plan(dev_ptrs, lens, leaf_bytes):
+    """(gathered bytes, copied bytes, runs) of the call without a buffer; no GPU work."""
+    ptrs, ls, n = _segment_arrays(dev_ptrs, lens)
+    g, c, r = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load().sentry_merkle_coalesced_plan(ptrs, ls, n, leaf_bytes, ctypes.byref(g), ctypes.byref(c), ctypes.byref(r)))
+    return g.value, c.value, r.value
 
 
 def sentry_merkle_coalesced_h(hash_id, dev_ptrs, lens, leaf_bytes, dev_buffer, buffer_bytes, out_root, stream=0):

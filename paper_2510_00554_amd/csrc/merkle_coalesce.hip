@@ -256,6 +256,30 @@ int sentry_merkle_coalesced_h(int hash, const void *const *dev_ptrs, const size_
     return sentry_merkle_inplace_h(hash, run_ptrs.data(), run_lens.data(), run_ptrs.size(), leaf_bytes, out_root, stream);
 }
 
+int sentry_merkle_coalesced_plan(const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes,
+                                 size_t *out_gathered_bytes, size_t *out_copied_bytes, size_t *out_runs)
+{
+    sentry::clear_error();
+    SENTRY_REQUIRE(n_seg >= 1, "sentry_merkle_coalesced_plan: n_seg must be at least 1");
+    SENTRY_REQUIRE(dev_ptrs && lens, "sentry_merkle_coalesced_plan: NULL argument");
+    SENTRY_REQUIRE(leaf_bytes > 0 && leaf_bytes % 64 == 0,
+                   "sentry_merkle_coalesced_plan: leaf_bytes must be a positive multiple of 64 (got %zu)", leaf_bytes);
+    uint64_t total = 0;
+    for (size_t t = 0; t < n_seg; t++) {
+        SENTRY_REQUIRE(dev_ptrs[t] != nullptr || lens[t] == 0, "sentry_merkle_coalesced_plan: segment %zu is NULL", t);
+        SENTRY_REQUIRE(total + lens[t] >= total, "sentry_merkle_coalesced_plan: the lengths overflow");
+        total += lens[t];
+    }
+    const Plan pl = plan_in_place(dev_ptrs, lens, n_seg, leaf_bytes);
+    uint64_t copied = 0;
+    for (const Piece &p : pl.pieces)
+        if (p.src) copied += p.bytes;
+    if (out_gathered_bytes) *out_gathered_bytes = pl.gathered_bytes;
+    if (out_copied_bytes) *out_copied_bytes = copied;
+    if (out_runs) *out_runs = pl.runs.size();
+    return SENTRY_OK;
+}
+
 int sentry_merkle_coalesced(const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t leaf_bytes,
                             void *dev_buffer, size_t buffer_bytes, uint8_t *out_root, void *stream)
 {

@@ -131,3 +131,52 @@ def test_header_is_plain_c_and_a_c_program_can_use_the_library(tmp_path):
                    check=True, capture_output=True, text=True)
     r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and "abi smoke ok" in r.stdout, r.stdout + r.stderr
+
+
+def test_coalesced_plan_against_a_block_by_block_model():
+    """Host logic of the coalesced scheme without a buffer (no GPU work): which blocks are put
+    together in scratch.  Model, block by block: a block of the zero-padded concatenation is
+    gathered when it holds bytes of more than one tensor, when it is the padded last block, or when
+    its first byte is not 16-byte aligned where it lies."""
+    import random
+    rng = random.Random(11)
+    for trial in range(300):
+        leaf = rng.choice([64, 128, 1024])
+        n = rng.randrange(1, 12)
+        aligned = trial % 3 != 0
+        lens, ptrs, at = [], [], 0x10000
+        for _ in range(n):
+            ln = rng.choice([0, 1, 16, leaf, leaf - 16, 3 * leaf, rng.randrange(0, 5 * leaf), 16 * rng.randrange(0, 300)])
+            ptr = at if aligned else at + rng.randrange(0, 16)
+            lens.append(ln)
+            ptrs.append(ptr if ln else 0)
+            at += (ln + 0x1000) // 0x1000 * 0x1000 + 0x1000
+        total = sum(lens)
+        # owner[i] = (tensor, offset in it) of byte i of the concatenation
+        gathered = copied = runs = 0
+        kinds = []
+        starts = [sum(lens[:t]) for t in range(n)]
+        for b0 in range(0, total, leaf):
+            b1 = b0 + leaf
+            owners = [t for t in range(n) if lens[t] and starts[t] < b1 and starts[t] + lens[t] > b0]
+            where = None
+            if len(owners) == 1 and b1 <= total:
+                t = owners[0]
+                addr = ptrs[t] + (b0 - starts[t])
+                if addr % 16 == 0:
+                    where = ("tensor", addr)
+            if where is None:
+                where = ("scratch", gathered)
+                gathered += leaf
+                copied += min(b1, total) - b0
+            kinds.append(where)
+        for k, (kind, addr) in enumerate(kinds):
+            if k == 0 or kinds[k - 1][0] != kind or kinds[k - 1][1] + leaf != addr:
+                runs += 1
+        assert sentry.sentry_merkle_coalesced_plan(ptrs, lens, leaf) == (gathered, copied, runs), (trial, leaf, lens, ptrs)
+    # aligned tensors whose lengths are multiples of the block size: nothing is gathered
+    assert sentry.sentry_merkle_coalesced_plan([0x1000, 0x9000], [4096, 8192], 1024) == (0, 0, 2)
+    # tensors that touch in memory are one run
+    assert sentry.sentry_merkle_coalesced_plan([0x1000, 0x2000], [4096, 8192], 1024) == (0, 0, 1)
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_merkle_coalesced_plan([0x1000], [64], 100)
