@@ -422,8 +422,12 @@ SENTRY_API int sentry_lthash_h2d(const void *host_records, const uint64_t *host_
  *             1024 uint16; all zero if nothing was fed) and releases the state.
  * abort       releases a state without a result (synchronises the device).
  * The result equals sentry_lthash over all the records in any order.
+ * sentry_lthash32_stream_begin creates a state for the 32-partition hash
+ * instead: update_h2d and abort are the same calls, final writes 32 uint16 to
+ * out_lanes, and the result equals sentry_lthash32 over all the records.
  */
 SENTRY_API int sentry_lthash_stream_begin(void **state);
+SENTRY_API int sentry_lthash32_stream_begin(void **state);
 SENTRY_API int sentry_lthash_stream_update_h2d(void *state, const void *host_records, const uint64_t *host_offsets,
                                                size_t n, void *stream);
 SENTRY_API int sentry_lthash_stream_final(void *state, uint16_t *out_lanes, void *stream);

@@ -60,6 +60,7 @@ PROTOTYPES = {
     "sentry_lthash32_remove": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_h2d": (_int, [_vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_lthash_stream_begin": (_int, [ctypes.POINTER(_vp)]),
+    "sentry_lthash32_stream_begin": (_int, [ctypes.POINTER(_vp)]),
     "sentry_lthash_stream_update_h2d": (_int, [_vp, _vp, _vp, _sz, _vp]),
     "sentry_lthash_stream_final": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_stream_abort": (_int, [_vp]),
@@ -273,6 +274,12 @@ def sentry_lthash_h2d(host_records, host_offsets, n, batch_bytes, out_lanes, str
 def sentry_lthash_stream_begin():
     state = ctypes.c_void_p()
     _check(load().sentry_lthash_stream_begin(ctypes.byref(state)))
+    return state
+
+
+def sentry_lthash32_stream_begin():
+    state = ctypes.c_void_p()
+    _check(load().sentry_lthash32_stream_begin(ctypes.byref(state)))
     return state
 
 

@@ -730,6 +730,7 @@ lthash_addsub_kernel(uint16_t *acc, const uint16_t *x)
 // 16th row of the run, starting at row t / 16, so a wave reads four whole rows (256 adjacent
 // bytes) at a time; the 16 partial sums of a word meet in LDS.  The first launch leaves one
 // packed row per workgroup, the second (one workgroup, over those rows) writes the 32 lanes.
+// Rows are row_words 32-bit words apart (16 for digests and partial rows).
 
 constexpr int SUM32_WG = 256;
 constexpr int SUM32_WORDS = SENTRY_LANES32 / 2;      // 16 packed words = one 64-byte digest
@@ -737,7 +738,8 @@ constexpr int SUM32_SLICES = SUM32_WG / SUM32_WORDS; // 16 rows in flight per tr
 constexpr int SUM32_AHEAD = 4;                       // loads issued before the first add
 
 __global__ void __launch_bounds__(SUM32_WG)
-lthash32_sum_kernel(const uint32_t *rows, uint64_t n_rows, uint32_t *packed_out, uint16_t *lanes_out)
+lthash32_sum_kernel(const uint32_t *rows, uint64_t n_rows, uint64_t row_words, uint32_t *packed_out, uint16_t *lanes_out,
+                    bool add_to_out)
 {
     __shared__ uint32_t lds[SUM32_SLICES][SUM32_WORDS];
     const uint32_t col = threadIdx.x % SUM32_WORDS;
@@ -750,12 +752,12 @@ lthash32_sum_kernel(const uint32_t *rows, uint64_t n_rows, uint32_t *packed_out,
     for (; r + (uint64_t)(SUM32_AHEAD - 1) * SUM32_SLICES < hi; r += (uint64_t)SUM32_AHEAD * SUM32_SLICES) {
         uint32_t x[SUM32_AHEAD];
 #pragma unroll
-        for (int a = 0; a < SUM32_AHEAD; a++) x[a] = rows[(r + (uint64_t)a * SUM32_SLICES) * SUM32_WORDS + col];
+        for (int a = 0; a < SUM32_AHEAD; a++) x[a] = rows[(r + (uint64_t)a * SUM32_SLICES) * row_words + col];
 #pragma unroll
         for (int a = 0; a < SUM32_AHEAD; a++) t += u16x2{(unsigned short)x[a], (unsigned short)(x[a] >> 16)};
     }
     for (; r < hi; r += SUM32_SLICES) {
-        const uint32_t x = rows[r * SUM32_WORDS + col];
+        const uint32_t x = rows[r * row_words + col];
         t += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
     }
     lds[slice][col] = (uint32_t)t.x | ((uint32_t)t.y << 16);
@@ -768,6 +770,7 @@ lthash32_sum_kernel(const uint32_t *rows, uint64_t n_rows, uint32_t *packed_out,
             sum += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
         }
         if (lanes_out) {
+            if (add_to_out) sum += u16x2{lanes_out[2 * threadIdx.x], lanes_out[2 * threadIdx.x + 1]};
             lanes_out[2 * threadIdx.x] = sum.x;       // 16-bit stores: 2-byte alignment is enough
             lanes_out[2 * threadIdx.x + 1] = sum.y;
         } else {
@@ -1138,6 +1141,46 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
     return lthash_expand_and_fold(static_cast<const uint64_t *>(h0), n, nullptr, out, accumulate, s);
 }
 
+// The 32-partition hash of n records (offsets relative to offset_base): overwrites the 32 lanes at
+// out or, with accumulate, is added to them.
+int lthash32_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
+                  uint16_t *out, bool accumulate, hipStream_t s)
+{
+    // one partial row per workgroup; a workgroup's run is at least one full trip of its 16 slices
+    uint64_t grid = ceil_div(n, (uint64_t)SUM32_SLICES * SUM32_AHEAD * 4);
+    const uint64_t cap = (uint64_t)cu_count() * 4;
+    if (grid > cap) grid = cap;
+    if (grid == 0) grid = 1;
+    void *h0, *part;
+    int rc;
+    if ((rc = scratch_get(s, R_LT_H0, 64 * (n ? n : 1), &h0))) return rc;
+    if ((rc = scratch_get(s, R_LT_PART, grid * SUM32_WORDS * 4, &part))) return rc;
+    if ((rc = lthash_roots(dev_records, dev_offsets, offset_base, n, static_cast<uint64_t *>(h0), s, PLAIN_P0, PLAIN_P1)))
+        return rc;
+    if (grid == 1) {
+        hipLaunchKernelGGL(lthash32_sum_kernel, dim3(1), dim3(SUM32_WG), 0, s, static_cast<const uint32_t *>(h0),
+                           (uint64_t)n, (uint64_t)SUM32_WORDS, static_cast<uint32_t *>(nullptr), out, accumulate);
+    } else {
+        hipLaunchKernelGGL(lthash32_sum_kernel, dim3((uint32_t)grid), dim3(SUM32_WG), 0, s,
+                           static_cast<const uint32_t *>(h0), (uint64_t)n, (uint64_t)SUM32_WORDS,
+                           static_cast<uint32_t *>(part), static_cast<uint16_t *>(nullptr), false);
+        hipLaunchKernelGGL(lthash32_sum_kernel, dim3(1), dim3(SUM32_WG), 0, s, static_cast<const uint32_t *>(part),
+                           grid, (uint64_t)SUM32_WORDS, static_cast<uint32_t *>(nullptr), out, accumulate);
+    }
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
+// out (32 lanes) = sum of the first 32 lanes of n_rows rows that lie row_lanes uint16 apart
+// (4-byte aligned rows: the slots of a running sum).
+int lthash32_sum_rows(const uint16_t *rows, uint32_t n_rows, uint32_t row_lanes, uint16_t *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(lthash32_sum_kernel, dim3(1), dim3(SUM32_WG), 0, s, reinterpret_cast<const uint32_t *>(rows),
+                       (uint64_t)n_rows, (uint64_t)(row_lanes / 2), static_cast<uint32_t *>(nullptr), out, false);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
 }  // namespace sentry
 
 extern "C" {
@@ -1299,29 +1342,7 @@ int sentry_lthash32(const void *dev_records, const uint64_t *dev_offsets, size_t
     SENTRY_REQUIRE(n == 0 || (dev_offsets != nullptr && (reinterpret_cast<uintptr_t>(dev_offsets) & 7) == 0),
                    "sentry_lthash32: dev_offsets must be non-NULL and 8-byte aligned when n > 0");
     SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash32: too many records");
-    // one partial row per workgroup; a workgroup's run is at least one full trip of its 16 slices
-    uint64_t grid = ceil_div(n, (uint64_t)SUM32_SLICES * SUM32_AHEAD * 4);
-    const uint64_t cap = (uint64_t)cu_count() * 4;
-    if (grid > cap) grid = cap;
-    if (grid == 0) grid = 1;
-    void *h0, *part;
-    int rc;
-    if ((rc = sentry::scratch_get(s, sentry::R_LT_H0, 64 * n, &h0))) return rc;
-    if ((rc = sentry::scratch_get(s, sentry::R_LT_PART, grid * SUM32_WORDS * 4, &part))) return rc;
-    if ((rc = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s, PLAIN_P0, PLAIN_P1)))
-        return rc;
-    if (grid == 1) {
-        hipLaunchKernelGGL(lthash32_sum_kernel, dim3(1), dim3(SUM32_WG), 0, s, static_cast<const uint32_t *>(h0),
-                           (uint64_t)n, static_cast<uint32_t *>(nullptr), out_lanes);
-    } else {
-        hipLaunchKernelGGL(lthash32_sum_kernel, dim3((uint32_t)grid), dim3(SUM32_WG), 0, s,
-                           static_cast<const uint32_t *>(h0), (uint64_t)n, static_cast<uint32_t *>(part),
-                           static_cast<uint16_t *>(nullptr));
-        hipLaunchKernelGGL(lthash32_sum_kernel, dim3(1), dim3(SUM32_WG), 0, s, static_cast<const uint32_t *>(part),
-                           grid, static_cast<uint32_t *>(nullptr), out_lanes);
-    }
-    SENTRY_HIP_CHECK(hipGetLastError());
-    return SENTRY_OK;
+    return sentry::lthash32_into(dev_records, dev_offsets, 0, n, out_lanes, false, s);
 }
 
 int sentry_lthash32_combine(uint16_t *acc, const uint16_t *x, void *stream)

@@ -26,6 +26,9 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
                 uint16_t *out, bool accumulate, hipStream_t s);
 int lthash_presize(uint64_t max_records, hipStream_t s);
 int lthash_sum_rows(const uint16_t *rows, uint32_t n_rows, uint16_t *out, hipStream_t s);
+int lthash32_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
+                  uint16_t *out, bool accumulate, hipStream_t s);
+int lthash32_sum_rows(const uint16_t *rows, uint32_t n_rows, uint32_t row_lanes, uint16_t *out, hipStream_t s);
 }  // namespace sentry
 
 namespace {
@@ -119,6 +122,7 @@ struct LtStream {
     bool owns_sums;                // allocated by begin (else scratch of the one-call entry point)
     hipStream_t stream;            // the caller's stream, fixed by the first update
     sentry::CopyPipe *pipe;
+    bool narrow;                   // the 32-partition hash: only the first 32 lanes of each row are used
 };
 constexpr uint64_t LT_STREAM_MAGIC = 0x53454e5452594c54ull;
 
@@ -171,8 +175,9 @@ int lt_stream_feed(LtStream *st, const uint8_t *host_records, const uint64_t *ho
     // the caller's stream passes this call once the batch has left host memory
     if (hs != s) SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->copied[b], 0));
     // record i of the batch sits at to + (offset[i] - beg); the kernel copes with any byte alignment
-    rc = sentry::lthash_into(to, reinterpret_cast<const uint64_t *>(off_to), beg, n,
-                             st->sums + (size_t)b * SENTRY_LANES, st->batches >= (uint64_t)LT_SLOTS, hs);
+    rc = (st->narrow ? sentry::lthash32_into : sentry::lthash_into)(
+        to, reinterpret_cast<const uint64_t *>(off_to), beg, n, st->sums + (size_t)b * SENTRY_LANES,
+        st->batches >= (uint64_t)LT_SLOTS, hs);
     if (rc) return rc;
     SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], hs));
     st->batches++;
@@ -184,6 +189,7 @@ int lt_stream_finish(LtStream *st, uint16_t *out_lanes, hipStream_t s)
 {
     const int used = st->batches < (uint64_t)LT_SLOTS ? (int)st->batches : LT_SLOTS;
     for (int i = 1; i < used; i++) SENTRY_HIP_CHECK(hipStreamWaitEvent(s, st->pipe->consumed[i], 0));
+    if (st->narrow) return sentry::lthash32_sum_rows(st->sums, (uint32_t)used, SENTRY_LANES, out_lanes, s);
     return sentry::lthash_sum_rows(st->sums, (uint32_t)used, out_lanes, s);
 }
 
@@ -435,7 +441,7 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
         if ((rc = sentry::lthash_presize(max_count, i == 0 ? s : pipe->hash_stream[i - 1]))) return rc;
     }
     if ((rc = sentry::scratch_get(s, sentry::R_LT_SUM, (size_t)LT_SLOTS * 2 * SENTRY_LANES, &sums))) return rc;
-    LtStream st = {LT_STREAM_MAGIC, 0, static_cast<uint16_t *>(sums), false, s, nullptr};
+    LtStream st = {LT_STREAM_MAGIC, 0, static_cast<uint16_t *>(sums), false, s, nullptr, false};
     const uint8_t *src = static_cast<const uint8_t *>(host_records);
     for (const Batch &bt : batches) {
         // a failure half way leaves loads and hashes queued on the side streams that the caller's
@@ -452,25 +458,29 @@ int sentry_lthash_h2d(const void *host_records, const uint64_t *host_offsets, si
     return SENTRY_OK;
 }
 
-int sentry_lthash_stream_begin(void **state)
+static int lt_stream_begin(const char *fn, void **state, bool narrow)
 {
     sentry::clear_error();
-    SENTRY_REQUIRE(state != nullptr, "sentry_lthash_stream_begin: NULL state");
+    SENTRY_REQUIRE(state != nullptr, "%s: NULL state", fn);
     LtStream *st = new (std::nothrow) LtStream();
-    if (!st) { sentry::set_error("sentry_lthash_stream_begin: out of host memory"); return SENTRY_ERR_NOMEM; }
+    if (!st) { sentry::set_error("%s: out of host memory", fn); return SENTRY_ERR_NOMEM; }
     (void)sentry::sweep_retired();
     void *p = nullptr;
     const hipError_t e = hipMalloc(&p, (size_t)LT_SLOTS * 2 * SENTRY_LANES);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        sentry::set_error("sentry_lthash_stream_begin: %s", hipGetErrorString(e));
+        sentry::set_error("%s: %s", fn, hipGetErrorString(e));
         delete st;
         return SENTRY_ERR_NOMEM;
     }
-    *st = LtStream{LT_STREAM_MAGIC, 0, static_cast<uint16_t *>(p), true, nullptr, nullptr};
+    *st = LtStream{LT_STREAM_MAGIC, 0, static_cast<uint16_t *>(p), true, nullptr, nullptr, narrow};
     *state = st;
     return SENTRY_OK;
 }
+
+int sentry_lthash_stream_begin(void **state) { return lt_stream_begin("sentry_lthash_stream_begin", state, false); }
+
+int sentry_lthash32_stream_begin(void **state) { return lt_stream_begin("sentry_lthash32_stream_begin", state, true); }
 
 int sentry_lthash_stream_update_h2d(void *state, const void *host_records, const uint64_t *host_offsets, size_t n,
                                     void *stream)
@@ -499,8 +509,9 @@ int sentry_lthash_stream_final(void *state, uint16_t *out_lanes, void *stream)
                    "sentry_lthash_stream_final: out_lanes must be non-NULL and 2-byte aligned");
     SENTRY_REQUIRE(st->batches == 0 || st->stream == s, "sentry_lthash_stream_final: not the stream the batches were fed on");
     int rc;
-    if (st->batches == 0) {
-        rc = sentry::lthash_sum_rows(st->sums, 0, out_lanes, s);     // nothing fed: all-zero lanes
+    if (st->batches == 0) {                                          // nothing fed: all-zero lanes
+        rc = st->narrow ? sentry::lthash32_sum_rows(st->sums, 0, SENTRY_LANES, out_lanes, s)
+                        : sentry::lthash_sum_rows(st->sums, 0, out_lanes, s);
     } else if ((rc = lt_stream_finish(st, out_lanes, s))) {
         sentry::copy_pipe_drain(st->pipe, true);
     }

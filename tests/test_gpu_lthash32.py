@@ -135,3 +135,48 @@ def test_combine_and_remove_against_the_oracle_with_wraparound():
     torch.cuda.synchronize()
     assert (big.cpu().numpy().view(np.uint16) == oracle.lthash(data, off)).all()
     assert (small == whole).all()
+
+
+@pytest.mark.parametrize("pinned", [True, False])
+def test_running_sum_over_batches_fed_from_host_memory(pinned):
+    # 13 batches of unequal sizes (one empty, one of a single empty record) fed back to back on a
+    # stream of their own: every staging slot and hash stream is used several times, and a 1024-lane
+    # running sum is fed in between on the same stream (they share staging buffers and scratch)
+    lens = wl.lognormal_record_lengths(1300, seed=151, median=9_000, lo=0, hi=300_000)
+    lens[700] = 0
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4800, 0, int(off[-1]))
+    want = oracle.lthash32(data, off)
+    host = torch.from_numpy(data.copy())
+    hoff = torch.from_numpy(off.view(np.int64).copy())
+    if pinned:
+        host, hoff = host.pin_memory(), hoff.pin_memory()
+    cuts = [0, 10, 11, 11, 300, 350, 700, 701, 900, 901, 1000, 1100, 1250, 1300]
+    s = torch.cuda.Stream()
+    st = sentry.sentry_lthash32_stream_begin()
+    wide = sentry.sentry_lthash_stream_begin()
+    for k, (a, b) in enumerate(zip(cuts[:-1], cuts[1:])):
+        sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr(), hoff.data_ptr() + 8 * a, b - a, s.cuda_stream)
+        if k in (3, 4):
+            sentry.sentry_lthash_stream_update_h2d(wide, host.data_ptr(), hoff.data_ptr() + 8 * a, b - a, s.cuda_stream)
+    out = torch.full((48,), 0x2222, dtype=torch.int16, device="cuda")
+    out_wide = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
+    sentry.sentry_lthash_stream_final(wide, out_wide.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint16)
+    assert (got[:32] == want).all() and (got[32:] == 0x2222).all()
+    assert (out_wide.cpu().numpy().view(np.uint16) == oracle.lthash(data[:int(off[350])], off[11:351])).all()
+    # two batches; and nothing at all
+    st = sentry.sentry_lthash32_stream_begin()
+    sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr(), hoff.data_ptr() + 8 * 300, 400, s.cuda_stream)
+    sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr(), hoff.data_ptr(), 300, s.cuda_stream)
+    sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy().view(np.uint16)[:32] == oracle.lthash32(data[:int(off[700])], off[:701])).all()
+    st = sentry.sentry_lthash32_stream_begin()
+    sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    assert (out.cpu()[:32] == 0).all()
+    st = sentry.sentry_lthash32_stream_begin()
+    sentry.sentry_lthash_stream_abort(st)
