@@ -24,8 +24,8 @@
  *     calls on one stream from several host threads are not supported.
  *     sentry_release_scratch() frees it.
  *   - Graph capture: sentry_merkle_root, sentry_merkle_root_h, sentry_merkle_leaves,
- *     sentry_merkle_reduce, sentry_lthash, sentry_lthash_digests, sentry_lthash_sum,
- *     sentry_lthash_combine and sentry_lthash_remove only launch kernels once the
+ *     sentry_merkle_reduce, sentry_lthash, sentry_lthash32, sentry_lthash_digests,
+ *     sentry_lthash_sum and the combine and remove calls only launch kernels once the
  *     stream's scratch is large enough, so a caller may capture them into a HIP
  *     graph after one plain call with the same sizes on the same stream; the graph
  *     then refers to that stream's scratch, which must not be released, or grown

@@ -218,11 +218,14 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
     d_off = to_dev(off)
     root = torch.zeros(32, dtype=torch.uint8, device="cuda")
     lanes = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    lanes32 = torch.zeros(32, dtype=torch.int16, device="cuda")
 
     def calls():
         sentry.sentry_merkle_root(buf.data_ptr(), n_bytes, leaf, root.data_ptr(), s.cuda_stream)
         sentry.sentry_lthash(rec.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), s.cuda_stream)
         sentry.sentry_lthash_combine(lanes.data_ptr(), lanes.data_ptr(), s.cuda_stream)    # lanes doubled
+        sentry.sentry_lthash32(rec.data_ptr(), d_off.data_ptr(), n_rec, lanes32.data_ptr(), s.cuda_stream)
+        sentry.sentry_lthash32_combine(lanes32.data_ptr(), lanes32.data_ptr(), s.cuda_stream)
 
     with torch.cuda.stream(s):
         calls()
@@ -239,12 +242,15 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
         rec.copy_(torch.from_numpy(r))
         root.zero_()
         lanes.zero_()
+        lanes32.zero_()
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
         assert bytes(root.cpu().numpy()) == oracle.merkle_root(b, leaf), k
         one = oracle.lthash(r, off)
         assert (lanes.cpu().numpy().view(np.uint16) == oracle.lthash_combine(one, one)).all(), k
+        one32 = oracle.lthash32(r, off)
+        assert (lanes32.cpu().numpy().view(np.uint16) == oracle.lanes_add(one32, one32)).all(), k
         # eager work of the library between the replays, on another stream
         sentry.sentry_merkle_root(d_other.data_ptr(), other.size, 64, out_other.data_ptr())
         torch.cuda.synchronize()
