@@ -1,11 +1,13 @@
 """The five target configurations at full size on the GPU, against expected values that
-tests/golden/make_golden.py computed with the CPU oracle on the same synthetic inputs."""
+tests/golden/make_golden.py computed with the CPU oracle on the same synthetic inputs (the
+32-partition hash of config 2 is small enough for the oracle to run inside its test)."""
 import gc
 
 import numpy as np
 import pytest
 import torch
 
+import oracle
 import paper_2510_00554_amd as sentry
 from paper_2510_00554_amd import workloads as wl
 from conftest import golden_lines, to_dev
@@ -45,6 +47,29 @@ def test_config2_lanes_and_halves():
     sentry.sentry_lthash_combine(out[1].data_ptr(), out[2].data_ptr())
     torch.cuda.synchronize()
     assert (out[1].cpu().numpy().view(np.uint16) == full).all()
+
+
+def test_config2_at_the_32_partition_width():
+    # the same 50,000 images under the 64-byte digest of section 4.2.2; the oracle hashes them here
+    # (0.15 GB of BLAKE2b on one core), whole and in two halves
+    data, off = wl.image_records(50_000, device="cuda")
+    host = data.cpu().numpy()
+    d_off = to_dev(off)
+    out = [torch.zeros(32, dtype=torch.int16, device="cuda") for _ in range(3)]
+    sentry.sentry_lthash32(data.data_ptr(), d_off.data_ptr(), 50_000, out[0].data_ptr())
+    sentry.sentry_lthash32(data.data_ptr(), d_off.data_ptr(), 25_000, out[1].data_ptr())
+    sentry.sentry_lthash32(data.data_ptr(), d_off.data_ptr() + 8 * 25_000, 25_000, out[2].data_ptr())
+    torch.cuda.synchronize()
+    got = [o.cpu().numpy().view(np.uint16) for o in out]
+    assert (got[0] == oracle.lthash32(host, off)).all()
+    assert (got[1] == oracle.lthash32(host, off[:25_001])).all()
+    assert (got[2] == oracle.lthash32(host, off[25_000:])).all()
+    sentry.sentry_lthash32_combine(out[1].data_ptr(), out[2].data_ptr())
+    torch.cuda.synchronize()
+    assert (out[1].cpu().numpy().view(np.uint16) == got[0]).all()
+    sentry.sentry_lthash32_remove(out[1].data_ptr(), out[2].data_ptr())
+    torch.cuda.synchronize()
+    assert (out[1].cpu().numpy().view(np.uint16) == oracle.lthash32(host, off[:25_001])).all()
 
 
 def test_config3_7b_checkpoint_per_tensor_roots():
