@@ -99,6 +99,8 @@ def _bind(L):
         L.oracle_lanes_sub.restype = None
         L.oracle_lthash32.argtypes = [vp, vp, sz, vp]
         L.oracle_lthash32.restype = None
+        L.oracle_lthash32_sources.argtypes = [vp, vp, vp, sz, sz, vp]
+        L.oracle_lthash32_sources.restype = None
         L.oracle_lthash_combine.argtypes = [vp, vp]
         L.oracle_lthash_combine.restype = None
         L.oracle_lthash_remove.argtypes = [vp, vp]
@@ -384,6 +386,19 @@ def lthash32(records, offsets):
     if n:
         assert int(off[-1]) <= rec.size
     lib().oracle_lthash32(_ptr(rec), _ptr(off), n, out.ctypes.data)
+    return out
+
+
+def lthash32_sources(records, offsets, sources, n_sources, acc=None):
+    """Per-source running sums at the 32-partition width: acc (n_sources x 32 uint16) updated with this batch."""
+    a = _u8(records)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    src = np.ascontiguousarray(sources, dtype=np.uint32)
+    n = max(off.size - 1, 0)
+    assert src.size == n
+    out = np.zeros((n_sources, 32), np.uint16) if acc is None else np.array(acc, dtype=np.uint16, copy=True)
+    assert out.shape == (n_sources, 32)
+    lib().oracle_lthash32_sources(_ptr(a), _ptr(off), _ptr(src), n, n_sources, out.ctypes.data)
     return out
 
 

@@ -738,6 +738,27 @@ void oracle_lthash32(const uint8_t *records, const uint64_t *offsets, size_t n, 
     }
 }
 
+/* Mixed-source batch at the 32-partition width (section 4.1.2, section 4.3 with the digest of
+ * section 4.2.2): acc holds n_sources rows of 32 partitions; the digest of record i is added to
+ * row src[i]; records whose source id is not below n_sources are left out. */
+void oracle_lthash32_sources(const uint8_t *records, const uint64_t *offsets, const uint32_t *src,
+                             size_t n, size_t n_sources, uint16_t *acc)
+{
+    uint8_t param[64];
+    memset(param, 0, sizeof param);
+    param[0] = 64; param[2] = 1; param[3] = 1;
+    for (size_t i = 0; i < n; i++) {
+        if (src[i] >= n_sources) continue;
+        uint8_t dig[64];
+        oracle_blake2b_param(param, records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), dig, 64);
+        uint16_t *mine = acc + (size_t)src[i] * ORACLE_MODEL_LANES;
+        for (int l = 0; l < ORACLE_MODEL_LANES; l++) {
+            uint16_t v = (uint16_t)(dig[2 * l] | ((uint16_t)dig[2 * l + 1] << 8));
+            mine[l] = (uint16_t)((mine[l] + v) & 0xFFFFu);
+        }
+    }
+}
+
 /* acc[l] = (acc[l] - x[l]) mod 2^16 for n partitions */
 void oracle_lanes_sub(uint16_t *acc, const uint16_t *x, size_t n)
 {

@@ -252,3 +252,36 @@ def test_lthash32_set_identities_and_modulus():
     base = oracle.lthash32(rec, off1)
     want = (65536 * lanes32_via_hashlib(b"") + lanes32_via_hashlib(rec)) % 65536
     assert (base.astype(np.int64) == want).all()
+
+
+def test_lthash32_per_source_sums_against_hashlib():
+    # every provider's row is the sum of hashlib's BLAKE2b-512 digests of exactly its samples,
+    # partition by partition in Python integers; a second batch adds on top
+    import hashlib
+    rng = random.Random(36)
+    nprng = np.random.default_rng(36)
+    recs = [rng.randbytes(rng.randrange(0, 300)) for _ in range(70)]
+    src = nprng.integers(0, 6, 70).astype(np.uint32)
+    src[11] = 6                                  # an id outside the table is left out
+    src[12] = 0xFFFFFFFF
+    data, off = pack(recs)
+    acc = oracle.lthash32_sources(data, off, src, 6)
+    want = [[0] * 32 for _ in range(6)]
+    for r, k in zip(recs, src):
+        if k < 6:
+            d = hashlib.blake2b(r).digest()
+            for l in range(32):
+                want[k][l] = (want[k][l] + d[2 * l] + 256 * d[2 * l + 1]) % 65536
+    assert acc.tolist() == want
+    acc2 = oracle.lthash32_sources(data, off, src, 6, acc=acc)
+    assert (acc2 == (2 * acc.astype(np.int64)) % 65536).all()
+    one = oracle.lthash32_sources(data, off, np.zeros(70, np.uint32), 1)
+    assert (one[0] == oracle.lthash32(data, off)).all()
+    # rows that wrap: 65,536 copies of one record in one source give zero, one fewer gives minus its digest
+    rec = rng.randbytes(33)
+    data, off = pack([rec] * 65536)
+    src = np.ones(65536, np.uint32)
+    acc = oracle.lthash32_sources(data, off, src, 2)
+    assert not acc.any()
+    acc = oracle.lthash32_sources(data, off[:-1], src[:-1], 2)
+    assert (acc[1] == oracle.lanes_sub(np.zeros(32, np.uint16), oracle.lthash32(*pack([rec])))).all() and not acc[0].any()

@@ -40,6 +40,7 @@ PINS = [
     t_lt.test_model_hash_of_slices_adds_up, t_lt.test_digests_one_by_one_and_their_sum,
     t_lt.test_sum_of_given_digests_in_python_integers, t_lt.test_modulus_is_2_to_16,
     t_lt.test_lthash32_is_the_sum_of_hashlib_digests, t_lt.test_lthash32_set_identities_and_modulus,
+    t_lt.test_lthash32_per_source_sums_against_hashlib,
     t_oh.test_keccak_constants_match_fips202_definitions, t_oh.test_sha3_fips202_examples, t_oh.test_sha3_against_hashlib,
 ] + [(lambda h=h, f=f: t_oh.test_merkle_trees_over_each_leaf_function(h, f)) for h, f in t_oh.HASHES] \
   + [(lambda h=h, f=f: t_oh.test_per_tensor_and_flat_trees_over_each_leaf_function(h, f)) for h, f in t_oh.HASHES] \
@@ -75,6 +76,11 @@ MUTANTS = [
      "const size_t padded = (total + leaf_bytes - 1) / leaf_bytes * leaf_bytes;", "const size_t padded = (total / leaf_bytes + 1) * leaf_bytes;"),
     ("Merkle (coalesced): the tensors are laid down last to first", "for (size_t t = 0; t < n_seg; t++) {\n        if (lens[t]) memcpy(buffer + at, ptrs[t], lens[t]);",
      "for (size_t t = n_seg; t-- > 0;) {\n        if (lens[t]) memcpy(buffer + at, ptrs[t], lens[t]);"),
+    ("lattice, 32 partitions per source: ids outside the table are counted for source 0",
+     "if (src[i] >= n_sources) continue;\n        uint8_t dig[64];\n        oracle_blake2b_param(param, records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), dig, 64);\n        uint16_t *mine = acc + (size_t)src[i] * ORACLE_MODEL_LANES;",
+     "uint8_t dig[64];\n        oracle_blake2b_param(param, records + offsets[i], (size_t)(offsets[i + 1] - offsets[i]), dig, 64);\n        uint16_t *mine = acc + (size_t)(src[i] >= n_sources ? 0 : src[i]) * ORACLE_MODEL_LANES;"),
+    ("lattice, 32 partitions per source: rows saturate", "mine[l] = (uint16_t)((mine[l] + v) & 0xFFFFu);", "mine[l] = (uint16_t)(mine[l] + v > 0xFFFF ? 0xFFFF : mine[l] + v);"),
+    ("lattice, 32 partitions per source: rows 16 partitions apart", "acc + (size_t)src[i] * ORACLE_MODEL_LANES;", "acc + (size_t)src[i] * 16;"),
     ("verify: the last byte is not looked at", "for (int i = 0; i < 32; i++) diff |= (unsigned)(a[i] ^ b[i]);", "for (int i = 0; i < 31; i++) diff |= (unsigned)(a[i] ^ b[i]);"),
     ("BLAKE2b: a rotation of G off by one", "v[b] = rotr64(v[b] ^ v[c], 24);", "v[b] = rotr64(v[b] ^ v[c], 25);"),
     ("BLAKE2b: G adds x twice", "v[a] = v[a] + v[b] + y;", "v[a] = v[a] + v[b] + x;"),
