@@ -371,6 +371,11 @@ SENTRY_API int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stre
  * sentry_lthash32_combine / _remove are the lattice addition and subtraction on
  * such 32-lane values (acc and x device-accessible, 32 uint16 each, 2-byte
  * aligned; x is not modified; acc == x is allowed).
+ * sentry_lthash32_sources is sentry_lthash_sources at this width (section 4.3:
+ * one running sum per data source): acc_lanes holds n_sources (1 .. 4096) rows
+ * of 32 uint16, row k is increased by the digests of the records whose
+ * dev_source_ids entry is k; ids not below n_sources are left out; arguments
+ * otherwise as for sentry_lthash_sources.
  * Errors: SENTRY_ERR_INVALID_ARG for NULL or misaligned pointers or n > 2^30 - 65;
  * SENTRY_ERR_NOMEM / SENTRY_ERR_HIP from the scratch allocation or a launch.
  * Like sentry_lthash, the calls only launch kernels once the stream's scratch
@@ -378,6 +383,9 @@ SENTRY_API int sentry_lthash_remove(uint16_t *acc, const uint16_t *x, void *stre
  */
 SENTRY_API int sentry_lthash32(const void *dev_records, const uint64_t *dev_offsets, size_t n,
                                uint16_t *out_lanes, void *stream);
+SENTRY_API int sentry_lthash32_sources(const void *dev_records, const uint64_t *dev_offsets,
+                                       const uint32_t *dev_source_ids, size_t n, size_t n_sources,
+                                       uint16_t *acc_lanes, void *stream);
 SENTRY_API int sentry_lthash32_combine(uint16_t *acc, const uint16_t *x, void *stream);
 SENTRY_API int sentry_lthash32_remove(uint16_t *acc, const uint16_t *x, void *stream);
 

@@ -779,6 +779,74 @@ lthash32_sum_kernel(const uint32_t *rows, uint64_t n_rows, uint64_t row_words, u
     }
 }
 
+// Per-source sums of the 64-byte digests (section 4.3 at the width of section 4.2.2).  A sum
+// mod 2^16 can be kept in a 32-bit counter whatever it overflows (2^16 divides 2^32), so every
+// partition of every source gets a 32-bit counter and the digests are added with atomics:
+// first in LDS, one set of counters per workgroup, for up to SRC32_LDS_SOURCES sources (a
+// workgroup takes a long run of records, so most additions stay in LDS), then the non-zero
+// counters go to the global ones; with more sources than that, where few records meet in a
+// counter, straight to the global ones.  A last kernel adds the counters to the running sums.
+constexpr int SRC32_WG = 256;
+constexpr uint32_t SRC32_LDS_SOURCES = 256;       // 256 x 32 counters of 4 bytes = 32 KiB of LDS
+
+template <bool IN_LDS>
+__global__ void __launch_bounds__(SRC32_WG)
+lthash32_src_sum_kernel(const uint32_t *rows, const uint32_t *src, uint64_t n, uint32_t n_sources, uint32_t *counters)
+{
+    extern __shared__ uint32_t lds_counters[];
+    const uint32_t col = threadIdx.x % SUM32_WORDS;
+    const uint32_t slice = threadIdx.x / SUM32_WORDS;
+    const uint32_t words = n_sources * SENTRY_LANES32;
+    if (IN_LDS) {
+        for (uint32_t i = threadIdx.x; i < words; i += SRC32_WG) lds_counters[i] = 0;
+        __syncthreads();
+    }
+    const uint64_t per = (n + gridDim.x - 1) / gridDim.x;
+    const uint64_t lo = per * blockIdx.x < n ? per * blockIdx.x : n;
+    const uint64_t hi = lo + per < n ? lo + per : n;
+    uint32_t *to = IN_LDS ? lds_counters : counters;
+    uint64_t r = lo + slice;
+    for (; r + (uint64_t)(SUM32_AHEAD - 1) * SUM32_SLICES < hi; r += (uint64_t)SUM32_AHEAD * SUM32_SLICES) {
+        uint32_t k[SUM32_AHEAD], x[SUM32_AHEAD];          // the loads of four records before their additions
+#pragma unroll
+        for (int a = 0; a < SUM32_AHEAD; a++) {
+            k[a] = src[r + (uint64_t)a * SUM32_SLICES];
+            x[a] = rows[(r + (uint64_t)a * SUM32_SLICES) * SUM32_WORDS + col];
+        }
+#pragma unroll
+        for (int a = 0; a < SUM32_AHEAD; a++) {
+            if (k[a] >= n_sources) continue;              // not a source of this call: left out
+            atomicAdd(&to[k[a] * SENTRY_LANES32 + 2 * col], x[a] & 0xffffu);
+            atomicAdd(&to[k[a] * SENTRY_LANES32 + 2 * col + 1], x[a] >> 16);
+        }
+    }
+    for (; r < hi; r += SUM32_SLICES) {
+        const uint32_t k = src[r];
+        if (k >= n_sources) continue;
+        const uint32_t x = rows[r * SUM32_WORDS + col];
+        atomicAdd(&to[k * SENTRY_LANES32 + 2 * col], x & 0xffffu);
+        atomicAdd(&to[k * SENTRY_LANES32 + 2 * col + 1], x >> 16);
+    }
+    if (IN_LDS) {
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < words; i += SRC32_WG) {
+            const uint32_t v = lds_counters[i];
+            if (v) atomicAdd(&counters[i], v);
+        }
+    }
+}
+
+// adds the counters to the running sums and leaves them zero for the next call
+__global__ void __launch_bounds__(SRC32_WG)
+lthash32_src_add_kernel(uint32_t *counters, uint32_t n_words, uint16_t *acc)
+{
+    const uint32_t i = blockIdx.x * SRC32_WG + threadIdx.x;
+    if (i < n_words) {
+        acc[i] = (uint16_t)(acc[i] + counters[i]);
+        counters[i] = 0;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // mixed-source batches: one running sum per data source (section 4.1.2, section 4.3)
 // ---------------------------------------------------------------------------
@@ -1343,6 +1411,65 @@ int sentry_lthash32(const void *dev_records, const uint64_t *dev_offsets, size_t
                    "sentry_lthash32: dev_offsets must be non-NULL and 8-byte aligned when n > 0");
     SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash32: too many records");
     return sentry::lthash32_into(dev_records, dev_offsets, 0, n, out_lanes, false, s);
+}
+
+int sentry_lthash32_sources(const void *dev_records, const uint64_t *dev_offsets, const uint32_t *dev_source_ids,
+                            size_t n, size_t n_sources, uint16_t *acc_lanes, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(n_sources >= 1 && n_sources <= SRC_MAX_SOURCES, "sentry_lthash32_sources: n_sources must be 1..%u",
+                   SRC_MAX_SOURCES);
+    SENTRY_REQUIRE(acc_lanes != nullptr && (reinterpret_cast<uintptr_t>(acc_lanes) & 1) == 0,
+                   "sentry_lthash32_sources: acc_lanes must be non-NULL and 2-byte aligned");
+    if (n == 0) return SENTRY_OK;
+    SENTRY_REQUIRE(dev_offsets != nullptr && (reinterpret_cast<uintptr_t>(dev_offsets) & 7) == 0,
+                   "sentry_lthash32_sources: dev_offsets must be non-NULL and 8-byte aligned");
+    SENTRY_REQUIRE(dev_source_ids != nullptr && (reinterpret_cast<uintptr_t>(dev_source_ids) & 3) == 0,
+                   "sentry_lthash32_sources: dev_source_ids must be non-NULL and 4-byte aligned");
+    SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash32_sources: too many records");
+    const uint32_t S = (uint32_t)n_sources;
+    const uint32_t words = S * SENTRY_LANES32;
+    void *h0, *counters;
+    int rc;
+    bool fresh;
+    if ((rc = sentry::scratch_get(s, sentry::R_LT_H0, 64 * n, &h0))) return rc;
+    // the counters of every possible source, so that the region never grows and what the last call
+    // left zero stays zero: cleared by a launch only when newly allocated (or after a failure)
+    const uint32_t all_words = SRC_MAX_SOURCES * SENTRY_LANES32;
+    if ((rc = sentry::scratch_get_fresh(s, sentry::R_SRC32, 4 * (size_t)all_words, &counters, &fresh))) return rc;
+    uint32_t *cnt = static_cast<uint32_t *>(counters);
+    if (fresh) hipLaunchKernelGGL(src_zero_kernel, dim3(all_words / (16 * SRC_WG)), dim3(SRC_WG), 0, s, cnt, all_words);
+    auto launches = [&]() -> int {
+        int rc2 = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s, PLAIN_P0, PLAIN_P1);
+        if (rc2) return rc2;
+        if (S <= SRC32_LDS_SOURCES) {
+            // a workgroup's counters are worth their flush when its run of records is several times as
+            // long as the table: 4 records per source, 256 at least; at most four workgroups per CU
+            const uint64_t run = 4 * (uint64_t)S > 256 ? 4 * (uint64_t)S : 256;
+            uint64_t grid = ceil_div(n, run);
+            const uint64_t cap = (uint64_t)cu_count() * 4;
+            if (grid > cap) grid = cap;
+            hipLaunchKernelGGL(lthash32_src_sum_kernel<true>, dim3((uint32_t)grid), dim3(SRC32_WG), 4 * (size_t)words, s,
+                               static_cast<const uint32_t *>(h0), dev_source_ids, (uint64_t)n, S, cnt);
+        } else {
+            uint64_t grid = ceil_div(n, 256);
+            const uint64_t cap = (uint64_t)cu_count() * 8;
+            if (grid > cap) grid = cap;
+            hipLaunchKernelGGL(lthash32_src_sum_kernel<false>, dim3((uint32_t)grid), dim3(SRC32_WG), 0, s,
+                               static_cast<const uint32_t *>(h0), dev_source_ids, (uint64_t)n, S, cnt);
+        }
+        hipLaunchKernelGGL(lthash32_src_add_kernel, dim3((uint32_t)ceil_div(words, SRC32_WG)), dim3(SRC32_WG), 0, s, cnt, words,
+                           acc_lanes);
+        SENTRY_HIP_CHECK(hipGetLastError());
+        return SENTRY_OK;
+    };
+    if ((rc = launches())) {
+        // whatever was queued may have left counters behind: clear them for the next call
+        hipLaunchKernelGGL(src_zero_kernel, dim3(all_words / (16 * SRC_WG)), dim3(SRC_WG), 0, s, cnt, all_words);
+        (void)hipGetLastError();
+    }
+    return rc;
 }
 
 int sentry_lthash32_combine(uint16_t *acc, const uint16_t *x, void *stream)

@@ -58,6 +58,7 @@ enum Region {
     R_STAGE_OFF1,
     R_STAGE_OFF2,
     R_TICKET,        // "last workgroup" counter of the one-launch Merkle tree (zero between launches)
+    R_SRC32,         // per-source 32-bit counters of the 32-partition hash (zero between calls)
     R_GATHER,        // blocks of the coalesced scheme that are put together from several tensors
     R_GATHER_TAB,    // copy table of the gather kernel
     R_COUNT

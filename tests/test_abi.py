@@ -97,6 +97,11 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_lthash32(0x1000, 0x3004, 5, 0x2000),           # misaligned offsets
     lambda: sentry.sentry_lthash32(0x1000, 0, 5, 0x2000),                # NULL offsets with n > 0
     lambda: sentry.sentry_lthash32(0x1000, 0x3000, 1 << 30, 0x2000),     # too many records
+    lambda: sentry.sentry_lthash32_sources(0x1000, 0x3000, 0x4000, 5, 0, 0x2000),     # no sources
+    lambda: sentry.sentry_lthash32_sources(0x1000, 0x3000, 0x4000, 5, 4097, 0x2000),  # too many sources
+    lambda: sentry.sentry_lthash32_sources(0x1000, 0x3000, 0x4002, 5, 4, 0x2000),     # misaligned ids
+    lambda: sentry.sentry_lthash32_sources(0x1000, 0x3000, 0, 5, 4, 0x2000),          # NULL ids
+    lambda: sentry.sentry_lthash32_sources(0x1000, 0x3000, 0x4000, 5, 4, 0),          # NULL sums
     lambda: sentry.sentry_lthash32_combine(0x2000, 0),
     lambda: sentry.sentry_lthash32_remove(0x2000, 0x2003),
     lambda: sentry.sentry_lthash_h2d(0x1000, 0x3000, 5, 0, 0x2000),      # batch_bytes == 0

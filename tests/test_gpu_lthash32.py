@@ -180,3 +180,63 @@ def test_running_sum_over_batches_fed_from_host_memory(pinned):
     assert (out.cpu()[:32] == 0).all()
     st = sentry.sentry_lthash32_stream_begin()
     sentry.sentry_lthash_stream_abort(st)
+
+
+def gpu_sources32(data_np, off_np, src_np, n_sources, acc=None):
+    n = len(off_np) - 1
+    buf = torch.zeros(max(data_np.size, 1) + 16, dtype=torch.uint8, device="cuda")
+    if data_np.size:
+        buf[:data_np.size] = to_dev(data_np)
+    off = to_dev(np.asarray(off_np, dtype=np.uint64))
+    src = to_dev(np.asarray(src_np, dtype=np.uint32).view(np.int32))
+    if acc is None:
+        acc = torch.zeros(n_sources * 32 + 8, dtype=torch.int16, device="cuda")
+        acc[n_sources * 32:] = 0x1111
+    sentry.sentry_lthash32_sources(buf.data_ptr(), off.data_ptr(), src.data_ptr(), n, n_sources, acc.data_ptr())
+    torch.cuda.synchronize()
+    return acc
+
+
+def rows32(acc, n_sources):
+    a = acc.cpu().numpy().view(np.uint16)
+    assert (a[n_sources * 32:] == 0x1111).all()
+    return a[:n_sources * 32].reshape(n_sources, 32)
+
+
+@pytest.mark.parametrize("n,n_sources", [(1, 1), (60, 5), (1000, 16), (5000, 128), (9000, 256), (9000, 257), (333, 4096),
+                                         (300_000, 16), (300_000, 1000)])
+def test_per_source_running_sums(n, n_sources):
+    # counters in LDS up to 256 sources and in memory beyond; one and many workgroups; ids outside the table
+    rng = np.random.default_rng(171 + n + n_sources)
+    lens = rng.integers(0, 600 if n < 100_000 else 24, n).astype(np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4900 + n, 0, int(off[-1]))
+    src = rng.integers(0, n_sources, n).astype(np.uint32)
+    if n > 10:
+        src[3] = n_sources
+        src[7] = 0xFFFFFFFF
+    want = oracle.lthash32_sources(data, off, src, n_sources)
+    acc = gpu_sources32(data, off, src, n_sources)
+    assert (rows32(acc, n_sources) == want).all()
+    # a second batch lands on top of the running sums
+    want2 = oracle.lthash32_sources(data, off, src, n_sources, acc=want)
+    acc = gpu_sources32(data, off, src, n_sources, acc=acc)
+    assert (rows32(acc, n_sources) == want2).all()
+
+
+def test_per_source_one_owner_of_nearly_everything_and_one_source_is_the_plain_hash():
+    n = 70_000                                        # more than 65,536 records meet in one counter
+    rng = np.random.default_rng(181)
+    lens = rng.integers(1, 40, n).astype(np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(4950, 0, int(off[-1]))
+    src = np.zeros(n, np.uint32)
+    src[rng.choice(n, 40, replace=False)] = rng.integers(1, 8, 40)
+    assert (rows32(gpu_sources32(data, off, src, 8), 8) == oracle.lthash32_sources(data, off, src, 8)).all()
+    one = rows32(gpu_sources32(data, off, np.zeros(n, np.uint32), 1), 1)
+    assert (one[0] == gpu_lthash32(data, off)).all() and (one[0] == oracle.lthash32(data, off)).all()
+    # no record at all: the running sums stay as they are
+    acc = torch.full((8 * 32 + 8,), 0x1111, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash32_sources(0, 0, 0, 0, 8, acc.data_ptr())
+    torch.cuda.synchronize()
+    assert (acc.cpu() == 0x1111).all()
