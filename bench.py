@@ -717,8 +717,18 @@ def main():
             per_config["F1_lthash32_50k_images_%d_sources" % n_src] = rated(
                 {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
                 lthash32_mix([3072] * 50_000))
+        # the same 50,000 samples through the call for samples of one size (no offsets array: the host knows
+        # the batch and launches only the kernels that have work)
+        ms = timed_call(lambda: sentry.sentry_lthash_fixed(img.data_ptr(), 3072, 50_000, lanes.data_ptr(), stream), 50)
+        per_config["C2_lthash_50k_images_fixed_size_call"] = rated(
+            {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
+            lthash_mix([3072] * 50_000))
         # the same 50,000 samples at the paper's own digest width: plain BLAKE2b-512, 32 partitions (section 4.2.2)
         lanes32 = torch.zeros(32, dtype=torch.int16, device=dev)
+        ms = timed_call(lambda: sentry.sentry_lthash32_fixed(img.data_ptr(), 3072, 50_000, lanes32.data_ptr(), stream), 50)
+        per_config["F2_lthash32_50k_images_fixed_size_call"] = rated(
+            {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
+            lthash32_mix([3072] * 50_000))
         ms = timed_call(lambda: sentry.sentry_lthash32(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes32.data_ptr(), stream), 50)
         per_config["F2_lthash32_50k_images"] = rated(
             {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},

@@ -24,7 +24,7 @@
  *     calls on one stream from several host threads are not supported.
  *     sentry_release_scratch() frees it.
  *   - Graph capture: sentry_merkle_root, sentry_merkle_root_h, sentry_merkle_leaves,
- *     sentry_merkle_reduce, sentry_lthash, sentry_lthash32, sentry_lthash_digests,
+ *     sentry_merkle_reduce, sentry_lthash, sentry_lthash32, their _fixed forms, sentry_lthash_digests,
  *     sentry_lthash_sum and the combine and remove calls only launch kernels once the
  *     stream's scratch is large enough, so a caller may capture them into a HIP
  *     graph after one plain call with the same sizes on the same stream; the graph
@@ -312,6 +312,25 @@ SENTRY_API int sentry_verify(const uint8_t *root, const uint8_t *expected);
  */
 SENTRY_API int sentry_lthash(const void *dev_records, const uint64_t *dev_offsets, size_t n,
                   uint16_t *out_lanes, void *stream);
+
+/*
+ * The same for samples of one size laid back to back, which is how section 4.3
+ * runs the dataset kernel (its block size is the size of one sample: 32x32x3
+ * bytes for images, the padded length for text): record i = bytes
+ * [i * record_bytes, (i + 1) * record_bytes) of dev_records, no offsets array.
+ * The host then knows all about the batch and launches only the kernels that
+ * have work.  out_lanes equals sentry_lthash (sentry_lthash32 for the second
+ * call, 32 uint16) over the same records.
+ * dev_records   device, any alignment; may be NULL when n or record_bytes is 0.
+ * record_bytes  any size; 0 makes n empty records.
+ * n             number of records (0 gives all-zero lanes).
+ * Errors: SENTRY_ERR_INVALID_ARG for NULL or misaligned out_lanes, NULL records
+ * with bytes to read, n > 2^30 - 65 or n * record_bytes beyond 2^64.
+ */
+SENTRY_API int sentry_lthash_fixed(const void *dev_records, size_t record_bytes, size_t n,
+                                   uint16_t *out_lanes, void *stream);
+SENTRY_API int sentry_lthash32_fixed(const void *dev_records, size_t record_bytes, size_t n,
+                                     uint16_t *out_lanes, void *stream);
 
 /*
  * Batches that mix data sources (section 4.1.2: shuffled batches hold samples of

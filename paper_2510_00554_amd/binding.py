@@ -56,6 +56,8 @@ PROTOTYPES = {
     "sentry_lthash_combine": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_remove": (_int, [_vp, _vp, _vp]),
     "sentry_lthash32": (_int, [_vp, _vp, _sz, _vp, _vp]),
+    "sentry_lthash_fixed": (_int, [_vp, _sz, _sz, _vp, _vp]),
+    "sentry_lthash32_fixed": (_int, [_vp, _sz, _sz, _vp, _vp]),
     "sentry_lthash32_sources": (_int, [_vp, _vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_lthash32_combine": (_int, [_vp, _vp, _vp]),
     "sentry_lthash32_remove": (_int, [_vp, _vp, _vp]),
@@ -258,6 +260,14 @@ def sentry_lthash_remove(acc, x, stream=0):
 
 def sentry_lthash32(dev_records, dev_offsets, n, out_lanes, stream=0):
     return _check(load().sentry_lthash32(dev_records, dev_offsets, n, out_lanes, stream))
+
+
+def sentry_lthash_fixed(dev_records, record_bytes, n, out_lanes, stream=0):
+    return _check(load().sentry_lthash_fixed(dev_records, record_bytes, n, out_lanes, stream))
+
+
+def sentry_lthash32_fixed(dev_records, record_bytes, n, out_lanes, stream=0):
+    return _check(load().sentry_lthash32_fixed(dev_records, record_bytes, n, out_lanes, stream))
 
 
 def sentry_lthash32_sources(dev_records, dev_offsets, dev_source_ids, n, n_sources, acc_lanes, stream=0):

@@ -52,14 +52,28 @@ constexpr uint64_t EXP_P2 = 0x0000000000004000ull;
 // 32-bit word k of a 128-byte block that starts `sh`/8 bytes into the aligned word d[0]
 #define M32(k) __builtin_amdgcn_alignbit(d[(k) + 1], d[k], sh)
 
+// Where record i lies: bytes [offsets[i], offsets[i + 1]) less offset_base, or, for records of one
+// size laid back to back (offsets == nullptr), i times that size, which offset_base then holds.
+__device__ __forceinline__ void record_span(const uint64_t *offsets, uint64_t offset_base, uint64_t i, uint64_t &beg,
+                                            uint64_t &len)
+{
+    if (offsets) {
+        beg = offsets[i] - offset_base;
+        len = offsets[i + 1] - offsets[i];
+    } else {
+        beg = i * offset_base;
+        len = offset_base;
+    }
+}
+
 // One record per lane: record i of n.
 // p0, p1: the first two words of the parameter block (the others are zero for both hashes used).
 __device__ __forceinline__ void root_one_lane(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base,
                                               uint64_t n, uint64_t *h0_out, uint64_t i, uint64_t p0, uint64_t p1)
 {
     if (i >= n) return;
-    const uint64_t beg = offsets[i] - offset_base;
-    const uint64_t len = offsets[i + 1] - offsets[i];
+    uint64_t beg, len;
+    record_span(offsets, offset_base, i, beg, len);
     const uint32_t a = (uint32_t)((reinterpret_cast<uintptr_t>(records) + beg) & 3);
     const uint32_t sh = 8 * a;
     const uint32_t *q = reinterpret_cast<const uint32_t *>(records + beg - a);
@@ -188,10 +202,7 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
     const bool active = slot < n;
     const uint64_t rec = (active && order) ? order[slot] : slot;   // longest records first when ordered
     uint64_t beg = 0, len = 0;
-    if (active) {
-        beg = offsets[rec] - offset_base;
-        len = offsets[rec + 1] - offsets[rec];
-    }
+    if (active) record_span(offsets, offset_base, rec, beg, len);
     // blocks of this lane's record (the empty record has one)
     const uint32_t my_blocks = (uint32_t)(((len + 127) >> 7) > 0xffffffffull ? 0xffffffffull : (len ? (len + 127) >> 7 : 1));
     uint32_t wave_blocks = active ? my_blocks : 0u;   // the longest record of the wave
@@ -384,7 +395,7 @@ __global__ void __launch_bounds__(ROOT1_WG)
 lthash_root1_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n, uint64_t *h0_out,
                     uint64_t p0, uint64_t p1)
 {
-    if (four_lane_mode(offsets, n)) return;
+    if (offsets && four_lane_mode(offsets, n)) return;    // without offsets the host launches the one kernel it wants
     root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)blockIdx.x * ROOT1_WG + threadIdx.x, p0, p1);
 }
 
@@ -393,8 +404,8 @@ lthash_root4_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t of
                     const uint32_t *order, uint64_t *h0_out, uint64_t p0, uint64_t p1)
 {
     __shared__ __attribute__((aligned(16))) unsigned char stage[ROOT4_RECORDS * 128];
-    if (!four_lane_mode(offsets, n)) return;
-    root_four_lanes(records, offsets, offset_base, n, ordered_mode(offsets, n) ? order : nullptr, h0_out,
+    if (offsets && !four_lane_mode(offsets, n)) return;
+    root_four_lanes(records, offsets, offset_base, n, offsets && ordered_mode(offsets, n) ? order : nullptr, h0_out,
                     (uint64_t)blockIdx.x * ROOT4_RECORDS, stage, p0, p1);
 }
 
@@ -1173,6 +1184,24 @@ int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t 
     return SENTRY_OK;
 }
 
+// Root hashes of n records of record_bytes bytes each, back to back at dev_records.  The host
+// knows all there is to know about such a batch, so only the kernel that the rules above pick is
+// launched (four lanes for few records or long ones), and nothing is ordered: the records are equal.
+int lthash_roots_fixed(const void *dev_records, uint64_t record_bytes, uint64_t n, uint64_t *h0, hipStream_t s,
+                       uint64_t p0 = ROOT_P0, uint64_t p1 = ROOT_P1)
+{
+    if (n == 0) return SENTRY_OK;
+    if (n <= FEW_RECORDS || record_bytes >= FOUR_LANE_MEAN_BYTES)
+        hipLaunchKernelGGL(lthash_root4_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS)), dim3(ROOT4_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_records), (const uint64_t *)nullptr, record_bytes, n,
+                           (const uint32_t *)nullptr, h0, p0, p1);
+    else
+        hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_records), (const uint64_t *)nullptr, record_bytes, n, h0, p0, p1);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
 // Expansion of n root hashes and the lane sum over them, written to out or (accumulate) added to it.
 // only_source0: device array of n source ids, records with another id are left out; or NULL.
 int lthash_expand_and_fold(const uint64_t *h0, uint64_t n, const uint32_t *only_source0, uint16_t *out,
@@ -1197,7 +1226,8 @@ int lthash_expand_and_fold(const uint64_t *h0, uint64_t n, const uint32_t *only_
     return fold_rows(static_cast<const uint32_t *>(part), (uint32_t)grid, nullptr, out, s, accumulate);   // grid <= 512
 }
 
-// Lattice hash of n records at dev_records (offsets relative to offset_base); result either
+// Lattice hash of n records at dev_records (offsets relative to offset_base; or, with
+// dev_offsets == nullptr, records of offset_base bytes each, back to back); result either
 // overwrites out (accumulate == false) or is added to it lane-wise.
 int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
                 uint16_t *out, bool accumulate, hipStream_t s)
@@ -1205,11 +1235,13 @@ int lthash_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t o
     void *h0;
     int rc = scratch_get(s, R_LT_H0, 64 * (n ? n : 1), &h0);
     if (rc) return rc;
-    if ((rc = lthash_roots(dev_records, dev_offsets, offset_base, n, static_cast<uint64_t *>(h0), s))) return rc;
+    rc = dev_offsets ? lthash_roots(dev_records, dev_offsets, offset_base, n, static_cast<uint64_t *>(h0), s)
+                     : lthash_roots_fixed(dev_records, offset_base, n, static_cast<uint64_t *>(h0), s);
+    if (rc) return rc;
     return lthash_expand_and_fold(static_cast<const uint64_t *>(h0), n, nullptr, out, accumulate, s);
 }
 
-// The 32-partition hash of n records (offsets relative to offset_base): overwrites the 32 lanes at
+// The 32-partition hash of n records (offsets as for lthash_into): overwrites the 32 lanes at
 // out or, with accumulate, is added to them.
 int lthash32_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
                   uint16_t *out, bool accumulate, hipStream_t s)
@@ -1223,8 +1255,9 @@ int lthash32_into(const void *dev_records, const uint64_t *dev_offsets, uint64_t
     int rc;
     if ((rc = scratch_get(s, R_LT_H0, 64 * (n ? n : 1), &h0))) return rc;
     if ((rc = scratch_get(s, R_LT_PART, grid * SUM32_WORDS * 4, &part))) return rc;
-    if ((rc = lthash_roots(dev_records, dev_offsets, offset_base, n, static_cast<uint64_t *>(h0), s, PLAIN_P0, PLAIN_P1)))
-        return rc;
+    rc = dev_offsets ? lthash_roots(dev_records, dev_offsets, offset_base, n, static_cast<uint64_t *>(h0), s, PLAIN_P0, PLAIN_P1)
+                     : lthash_roots_fixed(dev_records, offset_base, n, static_cast<uint64_t *>(h0), s, PLAIN_P0, PLAIN_P1);
+    if (rc) return rc;
     if (grid == 1) {
         hipLaunchKernelGGL(lthash32_sum_kernel, dim3(1), dim3(SUM32_WG), 0, s, static_cast<const uint32_t *>(h0),
                            (uint64_t)n, (uint64_t)SUM32_WORDS, static_cast<uint32_t *>(nullptr), out, accumulate);
@@ -1411,6 +1444,32 @@ int sentry_lthash32(const void *dev_records, const uint64_t *dev_offsets, size_t
                    "sentry_lthash32: dev_offsets must be non-NULL and 8-byte aligned when n > 0");
     SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "sentry_lthash32: too many records");
     return sentry::lthash32_into(dev_records, dev_offsets, 0, n, out_lanes, false, s);
+}
+
+static int check_fixed(const char *fn, const void *dev_records, size_t record_bytes, size_t n, const uint16_t *out_lanes)
+{
+    SENTRY_REQUIRE(out_lanes != nullptr && (reinterpret_cast<uintptr_t>(out_lanes) & 1) == 0,
+                   "%s: out_lanes must be non-NULL and 2-byte aligned", fn);
+    SENTRY_REQUIRE(n <= 0xffffffffull / 4 - 64, "%s: too many records", fn);
+    SENTRY_REQUIRE(n == 0 || record_bytes <= 0xffffffffffffffffull / n, "%s: n * record_bytes overflows", fn);
+    SENTRY_REQUIRE(dev_records != nullptr || n == 0 || record_bytes == 0, "%s: NULL records", fn);
+    return SENTRY_OK;
+}
+
+int sentry_lthash_fixed(const void *dev_records, size_t record_bytes, size_t n, uint16_t *out_lanes, void *stream)
+{
+    sentry::clear_error();
+    const int rc = check_fixed("sentry_lthash_fixed", dev_records, record_bytes, n, out_lanes);
+    if (rc) return rc;
+    return sentry::lthash_into(dev_records, nullptr, record_bytes, n, out_lanes, false, static_cast<hipStream_t>(stream));
+}
+
+int sentry_lthash32_fixed(const void *dev_records, size_t record_bytes, size_t n, uint16_t *out_lanes, void *stream)
+{
+    sentry::clear_error();
+    const int rc = check_fixed("sentry_lthash32_fixed", dev_records, record_bytes, n, out_lanes);
+    if (rc) return rc;
+    return sentry::lthash32_into(dev_records, nullptr, record_bytes, n, out_lanes, false, static_cast<hipStream_t>(stream));
 }
 
 int sentry_lthash32_sources(const void *dev_records, const uint64_t *dev_offsets, const uint32_t *dev_source_ids,

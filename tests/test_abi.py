@@ -97,6 +97,10 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_lthash32(0x1000, 0x3004, 5, 0x2000),           # misaligned offsets
     lambda: sentry.sentry_lthash32(0x1000, 0, 5, 0x2000),                # NULL offsets with n > 0
     lambda: sentry.sentry_lthash32(0x1000, 0x3000, 1 << 30, 0x2000),     # too many records
+    lambda: sentry.sentry_lthash_fixed(0, 100, 5, 0x2000),                            # NULL records with bytes to read
+    lambda: sentry.sentry_lthash_fixed(0x1000, 100, 5, 0x2001),                       # misaligned output
+    lambda: sentry.sentry_lthash32_fixed(0x1000, 1 << 62, 8, 0x2000),                 # n * record_bytes overflows
+    lambda: sentry.sentry_lthash32_fixed(0x1000, 1, 1 << 30, 0x2000),                 # too many records
     lambda: sentry.sentry_lthash32_sources(0x1000, 0x3000, 0x4000, 5, 0, 0x2000),     # no sources
     lambda: sentry.sentry_lthash32_sources(0x1000, 0x3000, 0x4000, 5, 4097, 0x2000),  # too many sources
     lambda: sentry.sentry_lthash32_sources(0x1000, 0x3000, 0x4002, 5, 4, 0x2000),     # misaligned ids
