@@ -153,14 +153,15 @@ def test_running_sum_over_batches_fed_from_host_memory(pinned):
         host, hoff = host.pin_memory(), hoff.pin_memory()
     cuts = [0, 10, 11, 11, 300, 350, 700, 701, 900, 901, 1000, 1100, 1250, 1300]
     s = torch.cuda.Stream()
+    out = torch.full((48,), 0x2222, dtype=torch.int16, device="cuda")
+    out_wide = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()     # torch fills the outputs on its own stream, which s does not wait for
     st = sentry.sentry_lthash32_stream_begin()
     wide = sentry.sentry_lthash_stream_begin()
     for k, (a, b) in enumerate(zip(cuts[:-1], cuts[1:])):
         sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr(), hoff.data_ptr() + 8 * a, b - a, s.cuda_stream)
         if k in (3, 4):
             sentry.sentry_lthash_stream_update_h2d(wide, host.data_ptr(), hoff.data_ptr() + 8 * a, b - a, s.cuda_stream)
-    out = torch.full((48,), 0x2222, dtype=torch.int16, device="cuda")
-    out_wide = torch.zeros(1024, dtype=torch.int16, device="cuda")
     sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
     sentry.sentry_lthash_stream_final(wide, out_wide.data_ptr(), s.cuda_stream)
     torch.cuda.synchronize()

@@ -114,6 +114,7 @@ def test_output_to_pinned_host_unaligned_and_on_a_side_stream():
     assert bytes(pinned[3:35].numpy()) == want
     assert not pinned[:3].any() and not pinned[35:].any()
     dev_out = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()     # torch fills dev_out on its own stream, which s does not wait for
     sentry.sentry_merkle_root(d.data_ptr(), buf.size, 8192, dev_out.data_ptr() + 5, s.cuda_stream)
     s.synchronize()
     assert bytes(dev_out[5:37].cpu().numpy()) == want

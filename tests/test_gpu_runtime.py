@@ -219,6 +219,7 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
     root = torch.zeros(32, dtype=torch.uint8, device="cuda")
     lanes = torch.zeros(1024, dtype=torch.int16, device="cuda")
     lanes32 = torch.zeros(32, dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()     # torch fills these on its own stream, which s does not wait for
 
     def calls():
         sentry.sentry_merkle_root(buf.data_ptr(), n_bytes, leaf, root.data_ptr(), s.cuda_stream)

@@ -50,12 +50,13 @@ def test_stream_update_h2d_equals_one_shot(total, leaf, chunks, pinned):
     if pinned:
         host = host.pin_memory()
     s = torch.cuda.Stream()
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()     # torch fills `out` on its own stream, which s does not wait for
     st = sentry.sentry_merkle_stream_begin(total, leaf)
     pos = 0
     for c in chunks:      # fed back to back, no host wait in between: the chunks stay in place
         sentry.sentry_merkle_stream_update_h2d(st, host.data_ptr() + pos, c, s.cuda_stream)
         pos += c
-    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
     sentry.sentry_merkle_stream_final(st, out.data_ptr(), s.cuda_stream)
     torch.cuda.synchronize()
     assert bytes(out.cpu().numpy()) == want
@@ -197,10 +198,11 @@ def test_lthash_stream_running_sum_over_batches_fed_one_by_one(pinned):
         host, hoff = host.pin_memory(), hoff.pin_memory()
     cuts = [0, 10, 11, 11, 300, 350, 700, 701, 900, 901, 1000, 1100, 1250, 1300]
     s = torch.cuda.Stream()
+    out = torch.full((1024,), 0x2222, dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()     # torch fills `out` on its own stream, which s does not wait for
     st = sentry.sentry_lthash_stream_begin()
     for a, b in zip(cuts[:-1], cuts[1:]):
         sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr(), hoff.data_ptr() + 8 * a, b - a, s.cuda_stream)
-    out = torch.full((1024,), 0x2222, dtype=torch.int16, device="cuda")
     sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
     torch.cuda.synchronize()
     assert (out.cpu().numpy().view(np.uint16) == want).all()

@@ -18,6 +18,7 @@ pytestmark = pytest.mark.gpu
 def both_roots(d, size, leaf, stream=0):
     a = torch.zeros(32, dtype=torch.uint8, device="cuda")
     b = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()     # torch fills the outputs on its own stream, which `stream` does not wait for
     sentry.sentry_merkle_root_noalloc(d.data_ptr() if size else 0, size, leaf, a.data_ptr(), stream)
     sentry.sentry_merkle_root(d.data_ptr() if size else 0, size, leaf, b.data_ptr(), stream)
     torch.cuda.synchronize()
