@@ -485,6 +485,24 @@ SENTRY_API int sentry_lthash_model(const void *const *dev_ptrs, const size_t *le
 /* Text for the calling thread's last failing call ("" if none). */
 SENTRY_API const char *sentry_last_error(void);
 
+/*
+ * Take the scratch memory of later calls now (for callers that want those calls
+ * to return without waiting and to be fit for graph capture from the first one;
+ * not a step of the paper).  Grows, on `stream`, the scratch of
+ *   - sentry_merkle_root, sentry_merkle_leaves and sentry_merkle_reduce for inputs
+ *     of up to merkle_max_len bytes in leaves of merkle_leaf_bytes (0 = leave the
+ *     Merkle scratch alone), and
+ *   - sentry_lthash, sentry_lthash32, their _fixed forms, sentry_lthash_digests and
+ *     sentry_lthash_sum for up to lthash_max_records records or digests (0 = leave
+ *     it alone),
+ * to what the largest such call needs; calls within those limits then only
+ * launch kernels.  Growing a region waits for the stream (once, here).
+ * Errors: SENTRY_ERR_INVALID_ARG for a leaf size that is not a multiple of 64 or
+ * more than 2^30 - 65 records; SENTRY_ERR_NOMEM / SENTRY_ERR_HIP.
+ */
+SENTRY_API int sentry_reserve_scratch(size_t merkle_max_len, size_t merkle_leaf_bytes,
+                                      size_t lthash_max_records, void *stream);
+
 /* Free all cached scratch memory of the current device (synchronises it). */
 SENTRY_API int sentry_release_scratch(void);
 

@@ -68,6 +68,7 @@ PROTOTYPES = {
     "sentry_lthash_stream_final": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_stream_abort": (_int, [_vp]),
     "sentry_last_error": (ctypes.c_char_p, []),
+    "sentry_reserve_scratch": (_int, [_sz, _sz, _sz, _vp]),
     "sentry_release_scratch": (_int, []),
 }
 
@@ -102,6 +103,10 @@ def _check(rc):
 
 def sentry_last_error():
     return load().sentry_last_error().decode("utf-8", "replace")
+
+
+def sentry_reserve_scratch(merkle_max_len, merkle_leaf_bytes, lthash_max_records, stream=0):
+    return _check(load().sentry_reserve_scratch(merkle_max_len, merkle_leaf_bytes, lthash_max_records, stream))
 
 
 def sentry_release_scratch():

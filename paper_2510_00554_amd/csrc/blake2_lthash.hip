@@ -1122,6 +1122,18 @@ int lthash_presize(uint64_t max_records, hipStream_t s)
     return scratch_get(s, R_LT_PART, ((size_t)cu_count() * 2 + 1) * LANE_WORDS * 4, &p);
 }
 
+// The same, and the partial rows of the lane sum over stored digests (four workgroups per CU and
+// their group sums): everything the lattice calls on device-resident records of up to max_records
+// take from the stream's scratch.
+int lthash_reserve(uint64_t max_records, hipStream_t s)
+{
+    int rc = lthash_presize(max_records, s);
+    if (rc) return rc;
+    void *p;
+    const uint64_t rows = (uint64_t)cu_count() * 4;
+    return scratch_get(s, R_LT_PART, (rows + ceil_div(rows, 64) + 1) * LANE_WORDS * 4, &p);
+}
+
 // out = lane-wise sum of n_rows rows of 1024 lanes (rows are 2048 bytes apart, 4-byte aligned).
 // Many rows are folded in two steps, groups of FOLD_GROUP rows first; `spare` then holds the group
 // sums (ceil(n_rows / FOLD_GROUP) rows) and is not used otherwise.

@@ -9,6 +9,9 @@
 
 namespace sentry {
 
+int merkle_reserve(uint64_t max_len, uint64_t leaf_bytes, hipStream_t s);   // sha256_merkle.hip
+int lthash_reserve(uint64_t max_records, hipStream_t s);                     // blake2_lthash.hip
+
 static thread_local char g_err[512] = "";
 
 void set_error(const char *fmt, ...)
@@ -247,6 +250,19 @@ int sentry_release_scratch(void)
 {
     sentry::clear_error();
     return sentry::release_all_scratch();
+}
+
+int sentry_reserve_scratch(size_t merkle_max_len, size_t merkle_leaf_bytes, size_t lthash_max_records, void *stream)
+{
+    sentry::clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SENTRY_REQUIRE(merkle_leaf_bytes == 0 || merkle_leaf_bytes % 64 == 0,
+                   "sentry_reserve_scratch: merkle_leaf_bytes must be 0 or a multiple of 64 (got %zu)", merkle_leaf_bytes);
+    SENTRY_REQUIRE(lthash_max_records <= 0xffffffffull / 4 - 64, "sentry_reserve_scratch: too many records");
+    int rc;
+    if (merkle_leaf_bytes && (rc = sentry::merkle_reserve(merkle_max_len, merkle_leaf_bytes, s))) return rc;
+    if (lthash_max_records && (rc = sentry::lthash_reserve(lthash_max_records, s))) return rc;
+    return SENTRY_OK;
 }
 
 int sentry_verify(const uint8_t *root, const uint8_t *expected)

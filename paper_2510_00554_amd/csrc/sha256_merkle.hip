@@ -1073,6 +1073,29 @@ int noalloc_scratch(unsigned char **out)
 namespace sentry {
 
 // Leaf digests of a device chunk into dst (32 bytes per leaf), used by the streaming paths.
+// Scratch for every sentry_merkle_root, sentry_merkle_leaves and sentry_merkle_reduce call on s whose
+// input has at most max_len bytes in leaves of leaf_bytes: the node buffer for the smallest
+// workgroups any such input gets (64 leaves), the level buffers of the reduction over that many
+// nodes, and the ticket counter of the one-launch tree, cleared.
+int merkle_reserve(uint64_t max_len, uint64_t leaf_bytes, hipStream_t s)
+{
+    const uint64_t leaves = leaf_count(max_len, leaf_bytes);
+    const uint64_t groups = ceil_div(leaves, LEAF_WG_SMALL);
+    void *p;
+    int rc;
+    bool fresh;
+    if ((rc = scratch_get(s, R_NODES_A, 32 * groups, &p))) return rc;
+    // sentry_merkle_reduce may be given all the leaf digests: its first level has leaves / 512 nodes
+    if ((rc = scratch_get(s, R_RED_0, 32 * ceil_div(leaves, RED_IN), &p))) return rc;
+    if ((rc = scratch_get(s, R_RED_1, 32 * ceil_div(leaves, RED_IN), &p))) return rc;
+    if ((rc = scratch_get_fresh(s, R_TICKET, 256, &p, &fresh))) return rc;
+    if (fresh) {
+        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, static_cast<uint32_t *>(p), 64u);
+        SENTRY_HIP_CHECK(hipGetLastError());
+    }
+    return SENTRY_OK;
+}
+
 int merkle_leaves_into(const void *dev_buf, size_t len, size_t leaf_bytes, uint8_t *dst, hipStream_t s)
 {
     const uint64_t n = leaf_count(len, leaf_bytes);

@@ -97,6 +97,8 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_lthash32(0x1000, 0x3004, 5, 0x2000),           # misaligned offsets
     lambda: sentry.sentry_lthash32(0x1000, 0, 5, 0x2000),                # NULL offsets with n > 0
     lambda: sentry.sentry_lthash32(0x1000, 0x3000, 1 << 30, 0x2000),     # too many records
+    lambda: sentry.sentry_reserve_scratch(1000, 100, 0),                              # leaf size not a multiple of 64
+    lambda: sentry.sentry_reserve_scratch(0, 0, 1 << 30),                             # too many records
     lambda: sentry.sentry_lthash_fixed(0, 100, 5, 0x2000),                            # NULL records with bytes to read
     lambda: sentry.sentry_lthash_fixed(0x1000, 100, 5, 0x2001),                       # misaligned output
     lambda: sentry.sentry_lthash32_fixed(0x1000, 1 << 62, 8, 0x2000),                 # n * record_bytes overflows

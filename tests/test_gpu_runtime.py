@@ -256,3 +256,60 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
         sentry.sentry_merkle_root(d_other.data_ptr(), other.size, 64, out_other.data_ptr())
         torch.cuda.synchronize()
         assert bytes(out_other.cpu().numpy()) == oracle.merkle_root(other, 64)
+
+
+def test_reserved_scratch_makes_the_first_calls_on_a_stream_fit_for_capture():
+    # a fresh stream has no scratch: without the reservation the first call would allocate, which a
+    # capturing stream does not allow; with it the very first calls on the stream are captured
+    n_bytes, leaf, n_rec = 64 * 70_000 + 9, 64, 5000
+    buf_np = wl.uniform_bytes(1200, 0, n_bytes)
+    data, off = _records(1201, n_rec, 0, 900)
+    buf, rec, d_off = to_dev(buf_np), to_dev(data), to_dev(off)
+    root = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    leaves = torch.zeros(32 * 70_001, dtype=torch.uint8, device="cuda")
+    root2 = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    lanes = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    lanes32 = torch.zeros(32, dtype=torch.int16, device="cuda")
+    rows = torch.zeros(n_rec * 1024, dtype=torch.int16, device="cuda")
+    summed = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    fixed = torch.zeros(1024, dtype=torch.int16, device="cuda")
+    # code objects are loaded by a first launch: make those on the default stream, with tiny inputs
+    sentry.sentry_merkle_root(buf.data_ptr(), 64 * 700, leaf, root.data_ptr())
+    sentry.sentry_merkle_root(buf.data_ptr(), 64 * 70_000, leaf, root.data_ptr())
+    sentry.sentry_merkle_leaves(buf.data_ptr(), 640, leaf, leaves.data_ptr())
+    sentry.sentry_merkle_reduce(leaves.data_ptr(), 10, root2.data_ptr())
+    sentry.sentry_lthash(rec.data_ptr(), d_off.data_ptr(), 40_000 if n_rec > 40_000 else n_rec, lanes.data_ptr())
+    sentry.sentry_lthash32(rec.data_ptr(), d_off.data_ptr(), 10, lanes32.data_ptr())
+    sentry.sentry_lthash_digests(rec.data_ptr(), d_off.data_ptr(), 10, rows.data_ptr())
+    sentry.sentry_lthash_sum(rows.data_ptr(), 10, summed.data_ptr())
+    sentry.sentry_lthash_fixed(rec.data_ptr(), 100, 10, fixed.data_ptr())
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    sentry.sentry_reserve_scratch(n_bytes, leaf, n_rec, s.cuda_stream)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        sentry.sentry_merkle_root(buf.data_ptr(), n_bytes, leaf, root.data_ptr(), s.cuda_stream)
+        sentry.sentry_merkle_leaves(buf.data_ptr(), n_bytes, leaf, leaves.data_ptr(), s.cuda_stream)
+        sentry.sentry_merkle_reduce(leaves.data_ptr(), 70_001, root2.data_ptr(), s.cuda_stream)
+        sentry.sentry_lthash(rec.data_ptr(), d_off.data_ptr(), n_rec, lanes.data_ptr(), s.cuda_stream)
+        sentry.sentry_lthash32(rec.data_ptr(), d_off.data_ptr(), n_rec, lanes32.data_ptr(), s.cuda_stream)
+        sentry.sentry_lthash_digests(rec.data_ptr(), d_off.data_ptr(), n_rec, rows.data_ptr(), s.cuda_stream)
+        sentry.sentry_lthash_sum(rows.data_ptr(), n_rec, summed.data_ptr(), s.cuda_stream)
+        sentry.sentry_lthash_fixed(rec.data_ptr(), 100, n_rec, fixed.data_ptr(), s.cuda_stream)
+    want_root = oracle.merkle_root(buf_np, leaf)
+    want_lanes = oracle.lthash(data, off)
+    want_fixed = oracle.lthash(data[:100 * n_rec], np.arange(n_rec + 1, dtype=np.uint64) * np.uint64(100))
+    for k in range(2):
+        for t in (root, root2, lanes, lanes32, summed, fixed):
+            t.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert bytes(root.cpu().numpy()) == want_root and bytes(root2.cpu().numpy()) == want_root, k
+        assert (lanes.cpu().numpy().view(np.uint16) == want_lanes).all(), k
+        assert (summed.cpu().numpy().view(np.uint16) == want_lanes).all(), k
+        assert (lanes32.cpu().numpy().view(np.uint16) == oracle.lthash32(data, off)).all(), k
+        assert (fixed.cpu().numpy().view(np.uint16) == want_fixed).all(), k
+    with pytest.raises(sentry.SentryError):
+        sentry.sentry_reserve_scratch(1000, 100, 0)
