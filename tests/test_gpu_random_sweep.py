@@ -112,3 +112,68 @@ def test_lattice_hash_over_random_record_mixes(seed):
     sentry.sentry_lthash_h2d(host.data_ptr(), hoff.ctypes.data, n, max(longest, int(off[-1]) // 5 + 1), lanes.data_ptr())
     torch.cuda.synchronize()
     assert (lanes.cpu().numpy().view(np.uint16) == want).all(), (seed, style, n)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_coalesced_trees_over_random_tensor_lists(seed):
+    # both ways of Algorithm 1, tensors at random alignments
+    rng = np.random.default_rng(7300 + seed)
+    hid, dl = HASHES[seed % 3]
+    leaf = int(rng.choice([64, 192, 1024, 4096, 65_536]))
+    n_seg = int(rng.integers(1, 30))
+    sizes = random_lengths(rng, n_seg, leaf)
+    shifts = [int(rng.integers(0, 16)) if rng.integers(0, 2) else 0 for _ in sizes]
+    segs = [wl.uniform_bytes(7310 + 40 * seed + i, 0, n) for i, n in enumerate(sizes)]
+    devs, ptrs = [], []
+    for s, sh in zip(segs, shifts):
+        d = torch.zeros(s.size + sh + 16, dtype=torch.uint8, device="cuda")
+        if s.size:
+            d[sh:sh + s.size] = to_dev(s)
+        devs.append(d)
+        ptrs.append(d.data_ptr() + sh if s.size else 0)
+    total = sum(sizes)
+    padded = -(-total // leaf) * leaf
+    buf = torch.zeros(padded + 16, dtype=torch.uint8, device="cuda")
+    a = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    b = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_coalesced_h(hid, ptrs, sizes, leaf, buf.data_ptr(), padded, a.data_ptr())
+    sentry.sentry_merkle_coalesced_h(hid, ptrs, sizes, leaf, 0, 0, b.data_ptr())
+    torch.cuda.synchronize()
+    want = oracle.merkle_coalesced_h(hid, segs, leaf)
+    assert bytes(a.cpu().numpy()[:dl]) == want, (hid, leaf, sizes, shifts)
+    assert bytes(b.cpu().numpy()[:dl]) == want, (hid, leaf, sizes, shifts)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_32_partition_hash_over_random_record_mixes(seed):
+    # plain, per source (counters in LDS and in memory) and for samples of one size
+    rng = np.random.default_rng(7400 + seed)
+    n = int(rng.choice([1, 7, 100, 3000, 40_000]))
+    hi = int(rng.choice([40, 700, 5000])) if n <= 3000 else 60
+    lens = rng.integers(0, hi, n).astype(np.uint64)
+    if n <= 100:
+        lens[int(rng.integers(0, n))] = int(rng.integers(5000, 200_000))      # one long record among short ones
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(7410 + seed, 0, max(int(off[-1]), 1))[:int(off[-1])]
+    sh = int(rng.integers(0, 4))
+    buf = torch.zeros(data.size + sh + 16, dtype=torch.uint8, device="cuda")
+    if data.size:
+        buf[sh:sh + data.size] = to_dev(data)
+    d_off = to_dev(off)
+    out = torch.zeros(32, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash32(buf.data_ptr() + sh, d_off.data_ptr(), n, out.data_ptr())
+    n_src = int(rng.choice([1, 3, 16, 255, 256, 257, 1000, 4096]))
+    src = rng.integers(0, n_src + 1, n).astype(np.uint32)                       # some ids outside the table
+    acc0 = rng.integers(0, 65536, (n_src, 32)).astype(np.uint16)
+    acc, d_src = to_dev(acc0.reshape(-1)), to_dev(src.view(np.int32))
+    sentry.sentry_lthash32_sources(buf.data_ptr() + sh, d_off.data_ptr(), d_src.data_ptr(), n, n_src, acc.data_ptr())
+    rb = int(rng.choice([0, 1, 100, 129, 3072]))
+    m = min(n, data.size // rb) if rb else n
+    fixed = torch.zeros(32, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash32_fixed(buf.data_ptr() + sh, rb, m, fixed.data_ptr())
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy().view(np.uint16) == oracle.lthash32(data, off)).all(), (n, hi, sh)
+    want = oracle.lthash32_sources(data, off, src, n_src, acc=acc0)
+    assert (acc.cpu().numpy().view(np.uint16).reshape(n_src, 32) == want).all(), (n, n_src, sh)
+    o2 = np.arange(m + 1, dtype=np.uint64) * np.uint64(rb)
+    assert (fixed.cpu().numpy().view(np.uint16) == oracle.lthash32(data[:rb * m], o2)).all(), (rb, m, sh)
