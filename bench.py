@@ -653,6 +653,16 @@ def main():
         ms = timed_call(lambda: sentry.sentry_lthash(img.data_ptr(), d_ioff.data_ptr(), 50_000, lanes.data_ptr(), stream), 50)
         per_config["C2_lthash_50k_images"] = rated({"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(),
                                                     "samples/s": 50_000 / (ms * 1e-3)}, lthash_mix([3072] * 50_000))
+        # config 5 per tensor as well (Algorithm 2 over the 723 tensors of the 70B checkpoint where they lie
+        # in the resident buffer, 64 KiB leaves): per-tensor roots and the root over them
+        if not args.merkle_prefix_gib:
+            offs70 = wl.checkpoint_offsets(lay70)
+            p70 = [ckpt70.data_ptr() + offs70[i] for i in range(len(lay70))]
+            l70 = [offs70[i + 1] - offs70[i] for i in range(len(lay70))]
+            roots70 = torch.zeros(32 * len(lay70), dtype=torch.uint8, device=dev)
+            ms = timed_call(lambda: sentry.sentry_merkle_segments(p70, l70, LEAF70, roots70.data_ptr(), root7.data_ptr(), stream), 3)
+            per_config["C5_merkle_70b_per_tensor_64KiB"] = rated({"GB/s": bytes70 / ms / 1e6, "ms": ms, "bytes": bytes70,
+                                                                  "tensors": len(lay70)}, sha_tree_mix(l70, LEAF70))
         # the 7B checkpoint as one flat tree over all blocks of all tensors (Algorithm 3)
         ms = timed_call(lambda: sentry.sentry_merkle_inplace(t7_ptrs, t7_lens, LEAF7, root7.data_ptr(), stream), 5)
         per_config["F3_merkle_7b_inplace_flat_1MiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},

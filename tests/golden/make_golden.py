@@ -7,7 +7,7 @@ touches the GPU library.  Leaves and records are independent, so the work is fan
 over processes, each running the single-threaded oracle on its slice; the reductions are
 done by the oracle in the parent.  Run from the repository root:
 
-    python tests/golden/make_golden.py [c1 c2 c3 c3model c3coalesced c4 c5] [--procs N]
+    python tests/golden/make_golden.py [c1 c2 c3 c3model c3coalesced c4 c5 c5pertensor] [--procs N]
 """
 import argparse
 import multiprocessing as mp
@@ -85,6 +85,37 @@ def c5(pool):
           ["Merkle root (oracle) of config 5: 70B checkpoint (workloads.layout_70b, SEED_C5) as one byte stream,",
            "%d bytes, 64 KiB leaves, %d leaves.  line 1: root; then 'leaf <index> <digest>' samples" % (total, n_leaves)],
           [root.hex()] + ["leaf %d %s" % (i, bytes(digests[i]).hex()) for i in sample])
+
+
+def _c5pt_task(args):
+    idx, e0, e1, leaf = args
+    data = wl.normal_bf16_bits(wl.tensor_seed(wl.SEED_C5, idx), e0, e1 - e0).view(np.uint8)
+    return idx, e0, oracle.merkle_leaves(data, leaf).tobytes()
+
+
+def c5pertensor(pool):
+    """Config 5 per tensor (Algorithm 2): the 723 tensor roots at 64 KiB leaves and the root over them."""
+    lay = wl.layout_70b()
+    leaf = 64 << 10
+    per = 1024 * (leaf // 2)    # elements per task: 1024 leaves = 64 MiB
+    tasks = []
+    for i, (_, numel) in enumerate(lay):
+        for e0 in range(0, numel, per):
+            tasks.append((i, e0, min(numel, e0 + per), leaf))
+    leaves = [np.empty((max(1, -(-2 * numel // leaf)), 32), np.uint8) for _, numel in lay]
+    t0 = time.time()
+    for k, (idx, e0, blob) in enumerate(pool.imap_unordered(_c5pt_task, tasks, chunksize=1)):
+        d = np.frombuffer(blob, np.uint8).reshape(-1, 32)
+        l0 = (2 * e0) // leaf
+        leaves[idx][l0:l0 + d.shape[0]] = d
+        if k % 200 == 0:
+            print("c5pertensor %d/%d tasks %.0fs" % (k, len(tasks), time.time() - t0), flush=True)
+    roots = [oracle.merkle_reduce(lv) for lv in leaves]
+    top = oracle.merkle_reduce(np.frombuffer(b"".join(roots), np.uint8).reshape(-1, 32))
+    write("config5_per_tensor_roots.txt",
+          ["Per-tensor Merkle roots and the root over them (oracle) of config 5's checkpoint (workloads.layout_70b,",
+           "SEED_C5), 64 KiB leaves.  line 1: root over the 723 tensor roots; then one tensor root per line"],
+          [top.hex()] + ["%s %s" % (lay[i][0], roots[i].hex()) for i in range(len(lay))])
 
 
 def _c3_task(args):
@@ -244,12 +275,12 @@ def c4(pool):
 
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
-    ap.add_argument("configs", nargs="*", default=["c1", "c2", "c3", "c3model", "c3coalesced", "c4", "c5"])
+    ap.add_argument("configs", nargs="*", default=["c1", "c2", "c3", "c3model", "c3coalesced", "c4", "c5", "c5pertensor"])
     ap.add_argument("--procs", type=int, default=os.cpu_count())
     a = ap.parse_args()
     oracle.build()
     with mp.Pool(a.procs) as pool:
         for c in a.configs:
             t = time.time()
-            {"c1": c1, "c2": c2}.get(c, lambda: {"c3": c3, "c3model": c3model, "c3coalesced": c3coalesced, "c4": c4, "c5": c5}[c](pool))()
+            {"c1": c1, "c2": c2}.get(c, lambda: {"c3": c3, "c3model": c3model, "c3coalesced": c3coalesced, "c4": c4, "c5": c5, "c5pertensor": c5pertensor}[c](pool))()
             print("%s done in %.0fs" % (c, time.time() - t), flush=True)

@@ -154,6 +154,19 @@ def test_config5_70b_checkpoint_resident_and_streamed():
         torch.cuda.synchronize()
         assert bytes(d.cpu().numpy()) == dig, i
     print("config 5: resident root ok", flush=True)
+    # the same checkpoint per tensor (Algorithm 2): 723 roots and the root over them, where the tensors lie
+    pt = golden_lines("config5_per_tensor_roots.txt")
+    want_top, want_roots = bytes.fromhex(pt[0]), [bytes.fromhex(ln.split()[1]) for ln in pt[1:]]
+    assert len(want_roots) == len(lay) == 723
+    roots = torch.zeros(32 * len(lay), dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_segments([buf.data_ptr() + offs[i] for i in range(len(lay))],
+                                  [offs[i + 1] - offs[i] for i in range(len(lay))], leaf, roots.data_ptr(), out.data_ptr())
+    torch.cuda.synchronize()
+    got = roots.cpu().numpy().reshape(len(lay), 32)
+    bad = [lay[i][0] for i in range(len(lay)) if bytes(got[i]) != want_roots[i]]
+    assert not bad, bad[:5]
+    assert bytes(out.cpu().numpy()) == want_top
+    print("config 5: per-tensor roots ok", flush=True)
     # streamed through the library's own load path: 1 GiB chunks in two pinned host buffers, fed to
     # sentry_merkle_stream_update_h2d, which loads chunk k on its side stream into its own staging
     # buffers while chunk k - 1 is hashed; no host wait per chunk except the one a two-buffer
