@@ -7,7 +7,7 @@ touches the GPU library.  Leaves and records are independent, so the work is fan
 over processes, each running the single-threaded oracle on its slice; the reductions are
 done by the oracle in the parent.  Run from the repository root:
 
-    python tests/golden/make_golden.py [c1 c2 c3 c3model c3coalesced c4 c5 c5pertensor] [--procs N]
+    python tests/golden/make_golden.py [c1 c2 c3 c3model c3coalesced c4 c4narrow c5 c5pertensor] [--procs N]
 """
 import argparse
 import multiprocessing as mp
@@ -273,14 +273,47 @@ def c4(pool):
                                 for k, (a, b) in enumerate(batches)])
 
 
+def _c4n_task(args):
+    a, b = args
+    off = _c4_offsets()
+    data = wl.uniform_bytes(wl.SEED_C4_BYTES, int(off[a]), int(off[b] - off[a]))
+    return a, oracle.lthash32(data, off[a:b + 1] - off[a]).tobytes()
+
+
+def c4narrow(pool):
+    """Config 4 at the 32-partition width (section 4.2.2): the same records and batches."""
+    off = _c4_offsets()
+    batches = wl.cut_batches(off, wl.C4_BATCH_BYTES)
+    tasks, owner = [], {}
+    for bi, (a, b) in enumerate(batches):
+        for (x, y) in [(a + p, a + q) for p, q in wl.cut_batches(off[a:b + 1] - off[a], 64_000_000)]:
+            tasks.append((x, y))
+            owner[x] = bi
+    per_batch = [np.zeros(32, np.uint16) for _ in batches]
+    t0 = time.time()
+    for k, (a, blob) in enumerate(pool.imap_unordered(_c4n_task, tasks, chunksize=1)):
+        per_batch[owner[a]] = oracle.lanes_add(per_batch[owner[a]], np.frombuffer(blob, np.uint16))
+        if k % 200 == 0:
+            print("c4narrow %d/%d tasks %.0fs" % (k, len(tasks), time.time() - t0), flush=True)
+    total = np.zeros(32, np.uint16)
+    for lanes in per_batch:
+        total = oracle.lanes_add(total, lanes)
+    write("config4_lanes32.txt",
+          ["32-partition lattice hash (oracle: plain BLAKE2b-512 per record) of config 4's records, %d bytes in %d batches."
+           % (int(off[-1]), len(batches)),
+           "line 1: all records; then 'batch <k> <first> <last_exclusive> <32 hex uint16>'"],
+          [lanes_hex(total)] + ["batch %d %d %d %s" % (k, a, b, lanes_hex(per_batch[k]))
+                                for k, (a, b) in enumerate(batches)])
+
+
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
-    ap.add_argument("configs", nargs="*", default=["c1", "c2", "c3", "c3model", "c3coalesced", "c4", "c5", "c5pertensor"])
+    ap.add_argument("configs", nargs="*", default=["c1", "c2", "c3", "c3model", "c3coalesced", "c4", "c4narrow", "c5", "c5pertensor"])
     ap.add_argument("--procs", type=int, default=os.cpu_count())
     a = ap.parse_args()
     oracle.build()
     with mp.Pool(a.procs) as pool:
         for c in a.configs:
             t = time.time()
-            {"c1": c1, "c2": c2}.get(c, lambda: {"c3": c3, "c3model": c3model, "c3coalesced": c3coalesced, "c4": c4, "c5": c5, "c5pertensor": c5pertensor}[c](pool))()
+            {"c1": c1, "c2": c2}.get(c, lambda: {"c3": c3, "c3model": c3model, "c3coalesced": c3coalesced, "c4": c4, "c4narrow": c4narrow, "c5": c5, "c5pertensor": c5pertensor}[c](pool))()
             print("%s done in %.0fs" % (c, time.time() - t), flush=True)

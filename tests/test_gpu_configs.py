@@ -107,6 +107,12 @@ def test_config4_streamed_lattice_hash_with_running_sum():
     part = torch.zeros(1024, dtype=torch.int16, device="cuda")
     streamed = torch.zeros(1024, dtype=torch.int16, device="cuda")
     lt = sentry.sentry_lthash_stream_begin()          # the same 20 batches, fed whole to one running sum
+    narrow = golden_lines("config4_lanes32.txt")      # and to one at the 32-partition width
+    want_total32 = lanes_from_hex(narrow[0])
+    want_batches32 = [lanes_from_hex(ln.split(" ", 4)[4]) for ln in narrow[1:]]
+    lt32 = sentry.sentry_lthash32_stream_begin()
+    part32 = torch.zeros(32, dtype=torch.int16, device="cuda")
+    streamed32 = torch.zeros(32, dtype=torch.int16, device="cuda")
     offs_keep = []
     for k, (a, b) in enumerate(batches):
         assert (a, b) == want_batches[k][:2]
@@ -120,14 +126,25 @@ def test_config4_streamed_lattice_hash_with_running_sum():
         sentry.sentry_lthash_h2d(h.data_ptr(), h_off.data_ptr(), b - a, 1_000_000_000, part.data_ptr())
         sentry.sentry_lthash_combine(running.data_ptr(), part.data_ptr())
         sentry.sentry_lthash_stream_update_h2d(lt, h.data_ptr(), h_off.data_ptr(), b - a)
+        sentry.sentry_lthash_stream_update_h2d(lt32, h.data_ptr(), h_off.data_ptr(), b - a)
         offs_keep.append(h_off)
         torch.cuda.synchronize()
         assert (part.cpu().numpy().view(np.uint16) == want_batches[k][2]).all(), "batch %d" % k
+        if k in (0, 7, len(batches) - 1):          # three batches on their own at the narrow width, resident
+            d_off = h_off.cuda()
+            dev = h[:nbytes].cuda()
+            sentry.sentry_lthash32(dev.data_ptr(), d_off.data_ptr(), b - a, part32.data_ptr())
+            torch.cuda.synchronize()
+            assert (part32.cpu().numpy().view(np.uint16) == want_batches32[k]).all(), "batch %d, 32 partitions" % k
+            del dev
         print("config 4: batch %d/%d ok" % (k + 1, len(batches)), flush=True)
     assert (running.cpu().numpy().view(np.uint16) == want_total).all()
     sentry.sentry_lthash_stream_final(lt, streamed.data_ptr())
     torch.cuda.synchronize()
     assert (streamed.cpu().numpy().view(np.uint16) == want_total).all()
+    sentry.sentry_lthash_stream_final(lt32, streamed32.data_ptr())
+    torch.cuda.synchronize()
+    assert (streamed32.cpu().numpy().view(np.uint16) == want_total32).all()
     del host
     free_gpu()
 
