@@ -41,6 +41,17 @@ int main(void)
     EXPECT(sentry_lthash((const void *)0x1000, NULL, 5, lanes, NULL) == SENTRY_ERR_INVALID_ARG);
     EXPECT(sentry_lthash_model(ptrs, lens, 1, 100, NULL, lanes, NULL) == SENTRY_ERR_INVALID_ARG);
     EXPECT(sentry_lthash_combine(NULL, lanes, NULL) == SENTRY_ERR_INVALID_ARG);
+    EXPECT(sentry_lthash32((const void *)0x1000, NULL, 5, lanes, NULL) == SENTRY_ERR_INVALID_ARG);
+    EXPECT(sentry_lthash_fixed(NULL, 100, 5, lanes, NULL) == SENTRY_ERR_INVALID_ARG);
+    EXPECT(sentry_merkle_coalesced(ptrs, lens, 1, 100, NULL, 0, a, NULL) == SENTRY_ERR_INVALID_ARG);
+    EXPECT(sentry_reserve_scratch(1000, 100, 0, NULL) == SENTRY_ERR_INVALID_ARG);
+    {   /* a host-only call with a result: one 64-byte tensor in 128-byte blocks is one gathered block */
+        size_t gathered = 1, copied = 1, runs = 0;
+        EXPECT(sentry_merkle_coalesced_plan(ptrs, lens, 1, 128, &gathered, &copied, &runs) == SENTRY_OK);
+        EXPECT(gathered == 128 && copied == 64 && runs == 1);
+        EXPECT(sentry_merkle_coalesced_plan(ptrs, lens, 1, 64, &gathered, &copied, &runs) == SENTRY_OK);
+        EXPECT(gathered == 0 && copied == 0 && runs == 1);
+    }
     /* a successful host-only call clears the text */
     EXPECT(sentry_verify(a, a) == SENTRY_OK);
     EXPECT(strcmp(sentry_last_error(), "") == 0);
