@@ -479,6 +479,20 @@ SENTRY_API int sentry_lthash_stream_abort(void *state);
 SENTRY_API int sentry_lthash_model(const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
                                    size_t block_bytes, uint16_t *out_layer_lanes, uint16_t *out_lanes,
                                    void *stream);
+/*
+ * The same for a run of tensors out of a model: their blocks are numbered from
+ * first_index (the number of blocks of the tensors in front of them) instead of
+ * 0.  The digests of disjoint runs add up to the model's (section 2.2: the sum
+ * over a union is the sum of the sums), so after a change to some tensors the
+ * model digest is brought up to date from their digests alone:
+ *   model' = model - digest(old tensor) + digest(new tensor)
+ * with sentry_lthash32_remove and sentry_lthash32_combine on the 32 partitions.
+ * Other arguments and errors as for sentry_lthash_model (which is this call with
+ * first_index 0).
+ */
+SENTRY_API int sentry_lthash_model_from(const void *const *dev_ptrs, const size_t *lens, size_t n_seg,
+                                        size_t block_bytes, uint64_t first_index,
+                                        uint16_t *out_layer_lanes, uint16_t *out_lanes, void *stream);
 
 /* ------------------------------------------------------------------------ */
 

@@ -53,6 +53,7 @@ PROTOTYPES = {
     "sentry_lthash_sum": (_int, [_vp, _sz, _vp, _vp]),
     "sentry_lthash_sources": (_int, [_vp, _vp, _vp, _sz, _sz, _vp, _vp]),
     "sentry_lthash_model": (_int, [_vp, _vp, _sz, _sz, _vp, _vp, _vp]),
+    "sentry_lthash_model_from": (_int, [_vp, _vp, _sz, _sz, ctypes.c_uint64, _vp, _vp, _vp]),
     "sentry_lthash_combine": (_int, [_vp, _vp, _vp]),
     "sentry_lthash_remove": (_int, [_vp, _vp, _vp]),
     "sentry_lthash32": (_int, [_vp, _vp, _sz, _vp, _vp]),
@@ -253,6 +254,11 @@ def sentry_lthash_model(dev_ptrs, lens, block_bytes, out_layer_lanes, out_lanes,
     ptrs = (ctypes.c_void_p * max(n, 1))(*dev_ptrs)
     ls = (ctypes.c_size_t * max(n, 1))(*lens)
     return _check(load().sentry_lthash_model(ptrs, ls, n, block_bytes, out_layer_lanes, out_lanes, stream))
+
+
+def sentry_lthash_model_from(dev_ptrs, lens, block_bytes, first_index, out_layer_lanes, out_lanes, stream=0):
+    ptrs, ls, n = _segment_arrays(dev_ptrs, lens)
+    return _check(load().sentry_lthash_model_from(ptrs, ls, n, block_bytes, first_index, out_layer_lanes, out_lanes, stream))
 
 
 def sentry_lthash_combine(acc, x, stream=0):

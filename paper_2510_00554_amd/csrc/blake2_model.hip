@@ -172,6 +172,12 @@ extern "C" {
 int sentry_lthash_model(const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t block_bytes,
                         uint16_t *out_layer_lanes, uint16_t *out_lanes, void *stream)
 {
+    return sentry_lthash_model_from(dev_ptrs, lens, n_seg, block_bytes, 0, out_layer_lanes, out_lanes, stream);
+}
+
+int sentry_lthash_model_from(const void *const *dev_ptrs, const size_t *lens, size_t n_seg, size_t block_bytes,
+                             uint64_t first_index, uint16_t *out_layer_lanes, uint16_t *out_lanes, void *stream)
+{
     sentry::clear_error();
     hipStream_t s = static_cast<hipStream_t>(stream);
     SENTRY_REQUIRE(n_seg >= 1 && n_seg <= 0x7fffffffull, "sentry_lthash_model: n_seg must be at least 1");
@@ -183,7 +189,7 @@ int sentry_lthash_model(const void *const *dev_ptrs, const size_t *lens, size_t 
     // the lookup table: one row per workgroup, groups of up to 256 blocks of one tensor
     std::vector<MGroup> groups;
     std::vector<uint32_t> row_start(n_seg + 1);
-    uint64_t index = 0;
+    uint64_t index = first_index;
     for (size_t t = 0; t < n_seg; t++) {
         SENTRY_REQUIRE(dev_ptrs[t] != nullptr || lens[t] == 0, "sentry_lthash_model: segment %zu is NULL", t);
         SENTRY_REQUIRE((reinterpret_cast<uintptr_t>(dev_ptrs[t]) & 15) == 0,

@@ -61,6 +61,47 @@ def test_block_order_matters():
     assert (ta != tb).any() and (tb == oracle.lthash_model([b], 8192)[1]).all()
 
 
+def test_a_run_of_tensors_with_its_first_block_index_and_an_update_of_one_tensor():
+    # section 2.2 / 4.2.2: the digests of disjoint runs of tensors add up to the model's, so a model
+    # digest is brought up to date from the digests of the changed tensor alone
+    block = 256
+    sizes = [256 * 5 + 3, 0, 256 * 300, 77, 256 * 40, 256 * 257 + 1]
+    segs = [wl.uniform_bytes(3300 + i, 0, s) for i, s in enumerate(sizes)]
+    blocks = [-(-s // block) for s in sizes]
+    want_layers, want_total = oracle.lthash_model(segs, block)
+    devs = [to_dev(s) if s.size else torch.empty(16, dtype=torch.uint8, device="cuda") for s in segs]
+    ptrs = [d.data_ptr() for d in devs]
+    total = torch.zeros(32, dtype=torch.int16, device="cuda")
+    part = torch.zeros(32, dtype=torch.int16, device="cuda")
+    layers = torch.zeros(6 * 32, dtype=torch.int16, device="cuda")
+    for lo, hi in ((0, 2), (2, 3), (3, 6)):                        # three runs, each numbered from its first block
+        first = sum(blocks[:lo])
+        sentry.sentry_lthash_model_from(ptrs[lo:hi], sizes[lo:hi], block, first, layers.data_ptr() + 64 * lo, part.data_ptr())
+        sentry.sentry_lthash32_combine(total.data_ptr(), part.data_ptr())
+        torch.cuda.synchronize()
+        w_layers, w_part = oracle.lthash_model(segs[lo:hi], block, first_index=first)
+        assert (part.cpu().numpy().view(np.uint16) == w_part).all(), (lo, hi)
+    assert (total.cpu().numpy().view(np.uint16) == want_total).all()
+    assert (layers.cpu().numpy().view(np.uint16).reshape(6, 32) == want_layers).all()
+    # tensor 4 changes: model' = model - digest(old tensor 4) + digest(new tensor 4)
+    new4 = wl.uniform_bytes(3399, 0, sizes[4])
+    d_new = to_dev(new4)
+    first = sum(blocks[:4])
+    old_digest = torch.zeros(32, dtype=torch.int16, device="cuda")
+    new_digest = torch.zeros(32, dtype=torch.int16, device="cuda")
+    sentry.sentry_lthash_model_from([ptrs[4]], [sizes[4]], block, first, 0, old_digest.data_ptr())
+    sentry.sentry_lthash_model_from([d_new.data_ptr()], [sizes[4]], block, first, 0, new_digest.data_ptr())
+    sentry.sentry_lthash32_remove(total.data_ptr(), old_digest.data_ptr())
+    sentry.sentry_lthash32_combine(total.data_ptr(), new_digest.data_ptr())
+    torch.cuda.synchronize()
+    changed = segs[:4] + [new4] + segs[5:]
+    assert (total.cpu().numpy().view(np.uint16) == oracle.lthash_model(changed, block)[1]).all()
+    # with the wrong first index the digest is another one: the index is part of what is hashed
+    sentry.sentry_lthash_model_from([ptrs[4]], [sizes[4]], block, first + 1, 0, part.data_ptr())
+    torch.cuda.synchronize()
+    assert (part.cpu() != old_digest.cpu()).any()
+
+
 def test_config3_checkpoint_model_lattice_hash():
     # the 7B checkpoint (291 fragmented tensors), 8 KiB blocks, against the stored oracle digests
     lines = golden_lines("config3_model_lthash.txt")
