@@ -757,6 +757,35 @@ def main():
             {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3)},
             lthash_mix([3072] * 50_000), hbm_bytes=img.numel() + rows.numel())
         del rows
+        # the 50,000 images as a data pipeline hands them over (batches of 128 samples from 16 sources, as in the
+        # paper's pipeline runs): one per-source call per batch into running sums, 391 calls back to back on one
+        # stream, and dealt over four streams (each with running sums of its own, which add up); host time included
+        ids16 = torch.from_numpy((wl._words_np(wl.SEED_C2 + 9, 0, 50_000) % np.uint64(16)).astype(np.int32)).to(dev)
+        for n_streams in (1, 4):
+            pipe_streams = [torch.cuda.Stream() for _ in range(n_streams)]
+            for name, call, lanes_per in (("lthash", sentry.sentry_lthash_sources, 1024), ("lthash32", sentry.sentry_lthash32_sources, 32)):
+                accs = [torch.zeros(16 * lanes_per, dtype=torch.int16, device=dev) for _ in range(n_streams)]
+                torch.cuda.synchronize()
+
+                def whole_dataset():
+                    for k, a in enumerate(range(0, 50_000, 128)):
+                        n = min(128, 50_000 - a)
+                        call(img.data_ptr() + 3072 * a, d_ioff.data_ptr(), ids16.data_ptr() + 4 * a, n, 16,
+                             accs[k % n_streams].data_ptr(), pipe_streams[k % n_streams].cuda_stream)
+                    torch.cuda.synchronize()
+
+                whole_dataset()
+                ts = []
+                for _ in range(3):
+                    t0 = time.perf_counter()
+                    whole_dataset()
+                    ts.append((time.perf_counter() - t0) * 1e3)
+                ms = statistics.median(ts)
+                per_config["E4_%s_50k_images_batches_of_128_16_sources_%d_stream%s" % (name, n_streams, "s" if n_streams > 1 else "")] = rated(
+                    {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3), "calls": 391,
+                     "us_per_call": ms * 1e3 / 391, "clock": "host wall time around all calls and the final synchronisation"},
+                    (lthash_mix if name == "lthash" else lthash32_mix)([3072] * 50_000))
+        del ids16
         if not args.no_streaming:
             # host-to-device streaming in the shape of configs 5 and 4, from a pinned host buffer of 16 GB:
             # Merkle while loading in 1 GiB chunks, and the lattice hash of 8 GB batches, each against the
