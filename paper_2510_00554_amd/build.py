@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsentry_hip.so")
-SOURCES = ["sentry_host.hip", "sha256_merkle.hip", "blake2_lthash.hip", "blake2_model.hip", "merkle_other.hip", "merkle_coalesce.hip", "sentry_stream.hip"]
+SOURCES = ["sentry_host.hip", "sha256_merkle.hip", "blake2_lthash.hip", "blake2_lthash32.hip", "blake2_model.hip", "merkle_other.hip", "merkle_coalesce.hip", "sentry_stream.hip"]
 # synthetic-input fill kernels for tests and bench.py: a library of its own, not part of the product
 WORKLOADS_LIB = os.path.join(HERE, "libsentry_workloads.so")
 WORKLOADS_SOURCE = "workloads_fill.hip"
