@@ -1237,7 +1237,9 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
     // for every SIMD, whatever the sources' shares (with 32 and more, 50,000 records made 1563 waves
     // for 1024 SIMDs, half of which then carried two waves and half one), and few enough units to
     // keep the partial rows small
-    uint32_t unit = 8;
+    // (a small batch gets units of two records, one pass of a wave: with eight, 128 records made 16
+    // waves of four compressions per lane each, 19 us where 5 us do)
+    uint32_t unit = 2;
     while (ceil_div(n, unit) > (uint64_t)cu_count() * 16) unit *= 2;
     const uint64_t max_units = ceil_div(n, unit) + S;          // every source may end in a short unit
     void *h0, *part, *tables, *perm;
