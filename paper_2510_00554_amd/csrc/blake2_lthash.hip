@@ -362,6 +362,7 @@ __device__ __forceinline__ void root_four_lanes(const uint8_t *records, const ui
 constexpr uint64_t FOUR_LANE_MEAN_BYTES = 16384;
 constexpr uint64_t UNEQUAL_MIN_BYTES = 4096;
 constexpr uint64_t FEW_RECORDS = 32768;
+constexpr uint64_t ORDER_MIN_RECORDS = 16384;   // batches up to this size are not ordered (host side: see lthash_roots)
 
 __device__ __forceinline__ bool ordered_mode(const uint64_t *offsets, uint64_t n)
 {
@@ -1053,16 +1054,21 @@ int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t 
     // four-lane path is kept for any number of long records: in length order it sustains
     // 1.7 TB/s, while one lane per record, which issues fewer instructions, has chains three
     // times as long and reaches that rate only with millions of records.
-    void *order, *counts;
-    int rc = scratch_get(s, R_LT_ORDER, 4 * n, &order);
-    if (rc) return rc;
-    uint32_t groups = (uint32_t)ceil_div(n, SORT_MIN_RUN);
-    if (groups > SORT_MAX_GROUPS) groups = SORT_MAX_GROUPS;
-    if ((rc = scratch_get(s, R_LT_COUNTS, 4 * (size_t)SORT_MAX_GROUPS * SORT_BINS, &counts))) return rc;
-    hipLaunchKernelGGL(lthash_order_count_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts));
-    hipLaunchKernelGGL(lthash_order_scan_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts), groups);
-    hipLaunchKernelGGL(lthash_order_place_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n,
-                       static_cast<const uint32_t *>(counts), static_cast<uint32_t *>(order));
+    void *order = nullptr, *counts;
+    int rc;
+    // Up to one wave per SIMD (16 records a wave) every wave has a SIMD to itself and the launch lasts as
+    // long as its longest record whatever the order: no ordering then, which takes three launches
+    // out of the way of a small batch.
+    if (n > ORDER_MIN_RECORDS) {
+        if ((rc = scratch_get(s, R_LT_ORDER, 4 * n, &order))) return rc;
+        uint32_t groups = (uint32_t)ceil_div(n, SORT_MIN_RUN);
+        if (groups > SORT_MAX_GROUPS) groups = SORT_MAX_GROUPS;
+        if ((rc = scratch_get(s, R_LT_COUNTS, 4 * (size_t)SORT_MAX_GROUPS * SORT_BINS, &counts))) return rc;
+        hipLaunchKernelGGL(lthash_order_count_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts));
+        hipLaunchKernelGGL(lthash_order_scan_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts), groups);
+        hipLaunchKernelGGL(lthash_order_place_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n,
+                           static_cast<const uint32_t *>(counts), static_cast<uint32_t *>(order));
+    }
     if (n > FEW_RECORDS)   // up to there the device always takes the four-lane path: nothing for this kernel to do
         hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
                            static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, h0, p0, p1);
