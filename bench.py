@@ -687,6 +687,29 @@ def main():
         e["copy_TB/s_read_plus_write"] = 2 * bytes7 / (ms_c - ms_r) / 1e9
         per_config["A1_merkle_7b_coalesced_with_copy_8KiB"] = e
         del cbuf
+        # small models in the shapes of the paper's own model runs (transformer stacks of BERT-base and GPT2-XL size,
+        # synthetic bf16 weights, one allocation per tensor), the paper's default 8 KiB blocks, the four schemes.
+        # Launches with fewer leaves than lanes: one 8 KiB leaf is a serial chain of 129 compressions (0.25 ms).
+        for shape, lay_s in (("bert_base_like_12x768", wl.llama_layout(12, 768, 3072, 30522)),
+                             ("gpt2_xl_like_48x1600", wl.llama_layout(48, 1600, 6400, 50257))):
+            ts = [wl.checkpoint_tensor(lay_s, i, base_seed=wl.SEED_C3 + 5, device=dev) for i in range(len(lay_s))]
+            ps, ls = [t.data_ptr() for t in ts], [t.numel() * 2 for t in ts]
+            nb = sum(ls)
+            roots_s = torch.zeros(32 * len(ls), dtype=torch.uint8, device=dev)
+            lanes_s = torch.zeros(32, dtype=torch.int16, device=dev)
+            for scheme, call, mix in (
+                    ("coalesced_alg1", lambda: sentry.sentry_merkle_coalesced(ps, ls, 8192, 0, 0, root7.data_ptr(), stream),
+                     sha_tree_mix([-(-nb // 8192) * 8192], 8192, flat=True)),
+                    ("per_layer_alg2", lambda: sentry.sentry_merkle_segments(ps, ls, 8192, roots_s.data_ptr(), root7.data_ptr(), stream),
+                     sha_tree_mix(ls, 8192)),
+                    ("in_place_alg3", lambda: sentry.sentry_merkle_inplace(ps, ls, 8192, root7.data_ptr(), stream),
+                     sha_tree_mix(ls, 8192, flat=True)),
+                    ("lattice_alg4", lambda: sentry.sentry_lthash_model(ps, ls, 8192, 0, lanes_s.data_ptr(), stream),
+                     model_lthash_mix(ls, 8192))):
+                ms = timed_call(call, 20)
+                per_config["E1_%s_%s_8KiB" % (shape, scheme)] = rated(
+                    {"GB/s": nb / ms / 1e6, "ms": ms, "bytes": nb, "tensors": len(ls)}, mix)
+            del ts, roots_s
         # the three leaf functions of section 4.2.1 on the first 16 GiB of the 70B stream, 8 KiB leaves
         f4_bytes = min(bytes70, 16 << 30)
         big_root = torch.zeros(64, dtype=torch.uint8, device=dev)
