@@ -91,22 +91,27 @@ __device__ __forceinline__ void blake2b_index_block(uint64_t k, const uint8_t *p
     }
 }
 
+// One wave per group of up to 64 blocks of one tensor (a workgroup holds four such waves, each with a
+// group of its own, so that a model of many small tensors still keeps all four SIMDs of a compute
+// unit busy: with one group of up to 256 blocks per workgroup a tensor of nine blocks left three of
+// its four waves empty, and the busy waves of the workgroups of a compute unit met on one SIMD).
 __global__ void __launch_bounds__(MODEL_WG)
-lthash_model_kernel(const MSeg *segs, const MGroup *groups, uint64_t block_bytes, uint32_t *rows_out)
+lthash_model_kernel(const MSeg *segs, const MGroup *groups, uint32_t n_groups, uint64_t block_bytes, uint32_t *rows_out)
 {
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const MGroup gr = groups[blockIdx.x];
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t g = blockIdx.x * (MODEL_WG / 64) + (threadIdx.x >> 6);
+    if (g >= n_groups) return;                       // wave-uniform; no barrier below
+    const MGroup gr = groups[g];
     const MSeg sg = segs[gr.seg];
     uint64_t h[8];
 #pragma unroll
     for (int i = 0; i < 8; i++) h[i] = 0;
-    if (tid < gr.count) {
-        const uint64_t start = (gr.first + tid) * block_bytes;
+    if (lane < gr.count) {
+        const uint64_t start = (gr.first + lane) * block_bytes;
         const uint64_t left = sg.len - start;
-        blake2b_index_block(gr.index + tid, sg.base + start, left < block_bytes ? left : block_bytes, h);
+        blake2b_index_block(gr.index + lane, sg.base + start, left < block_bytes ? left : block_bytes, h);
     }
     // add the 64 digests of the wave: 16 packed words, butterfly over the lanes
-    __shared__ uint32_t lds[MODEL_WG / 64][MODEL_WORDS];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
 #pragma unroll
@@ -119,18 +124,8 @@ lthash_model_kernel(const MSeg *segs, const MGroup *groups, uint64_t block_bytes
                 const uint32_t y = (uint32_t)__shfl_xor((int)x, sft, 64);
                 s += u16x2{(unsigned short)y, (unsigned short)(y >> 16)};
             }
-            if (lane == 0) lds[wave][2 * i + half] = (uint32_t)s.x | ((uint32_t)s.y << 16);
+            if (lane == 0) rows_out[(uint64_t)g * MODEL_WORDS + 2 * i + half] = (uint32_t)s.x | ((uint32_t)s.y << 16);
         }
-    }
-    __syncthreads();
-    if (tid < MODEL_WORDS) {
-        u16x2 s = u16x2{0, 0};
-#pragma unroll
-        for (int w = 0; w < MODEL_WG / 64; w++) {
-            const uint32_t x = lds[w][tid];
-            s += u16x2{(unsigned short)x, (unsigned short)(x >> 16)};
-        }
-        rows_out[(uint64_t)blockIdx.x * MODEL_WORDS + tid] = (uint32_t)s.x | ((uint32_t)s.y << 16);
     }
 }
 
@@ -186,7 +181,7 @@ int sentry_lthash_model_from(const void *const *dev_ptrs, const size_t *lens, si
                    "sentry_lthash_model: block_bytes must be a positive multiple of 16 (got %zu)", block_bytes);
     SENTRY_REQUIRE(((reinterpret_cast<uintptr_t>(out_lanes) | reinterpret_cast<uintptr_t>(out_layer_lanes)) & 1) == 0,
                    "sentry_lthash_model: lanes must be 2-byte aligned");
-    // the lookup table: one row per workgroup, groups of up to 256 blocks of one tensor
+    // the lookup table: one row per wave, groups of up to 64 blocks of one tensor
     std::vector<MGroup> groups;
     std::vector<uint32_t> row_start(n_seg + 1);
     uint64_t index = first_index;
@@ -196,10 +191,10 @@ int sentry_lthash_model_from(const void *const *dev_ptrs, const size_t *lens, si
                        "sentry_lthash_model: segment %zu is not 16-byte aligned", t);
         row_start[t] = (uint32_t)groups.size();
         const uint64_t nb = ceil_div(lens[t], block_bytes);
-        for (uint64_t f = 0; f < nb; f += MODEL_WG)
-            groups.push_back(MGroup{f, index + f, (uint32_t)(nb - f < MODEL_WG ? nb - f : MODEL_WG), (uint32_t)t});
+        for (uint64_t f = 0; f < nb; f += 64)
+            groups.push_back(MGroup{f, index + f, (uint32_t)(nb - f < 64 ? nb - f : 64), (uint32_t)t});
         index += nb;
-        SENTRY_REQUIRE(groups.size() <= 0xffffffffull / MODEL_WG, "sentry_lthash_model: too many blocks");
+        SENTRY_REQUIRE(groups.size() <= 0xffffffffull / 64, "sentry_lthash_model: too many blocks");
     }
     row_start[n_seg] = (uint32_t)groups.size();
     const size_t n_groups = groups.size();
@@ -221,9 +216,9 @@ int sentry_lthash_model_from(const void *const *dev_ptrs, const size_t *lens, si
     if ((rc = sentry::table_staging_mark(s))) return rc;
     char *dp = static_cast<char *>(dev_tab);
     if (n_groups) {
-        hipLaunchKernelGGL(lthash_model_kernel, dim3((uint32_t)n_groups), dim3(MODEL_WG), 0, s,
+        hipLaunchKernelGGL(lthash_model_kernel, dim3((uint32_t)ceil_div(n_groups, MODEL_WG / 64)), dim3(MODEL_WG), 0, s,
                            reinterpret_cast<const MSeg *>(dp), reinterpret_cast<const MGroup *>(dp + seg_bytes),
-                           (uint64_t)block_bytes, static_cast<uint32_t *>(rows));
+                           (uint32_t)n_groups, (uint64_t)block_bytes, static_cast<uint32_t *>(rows));
         SENTRY_HIP_CHECK(hipGetLastError());
     }
     // per-tensor digests, then the model digest over them
