@@ -443,7 +443,10 @@ SENTRY_API int sentry_lthash_h2d(const void *host_records, const uint64_t *host_
  *             kernel at the PCIe rate; pageable memory goes through hipMemcpyAsync.
  *             Both host arrays must stay unchanged until `stream` has passed the
  *             call (it waits for the batch's load, not for its hash).  All batches
- *             of one state are fed on one stream.  n == 0 does nothing.
+ *             of one state are fed on one stream.  n == 0 does nothing.  The call
+ *             reads the offsets on the host: a batch whose records all have one
+ *             size is hashed as sentry_lthash_fixed hashes it, and its offsets
+ *             are not loaded to the device.
  * final       waits on `stream` for the hashes still running on the side streams,
  *             writes the sum over all records fed to out_lanes (device-accessible,
  *             1024 uint16; all zero if nothing was fed) and releases the state.

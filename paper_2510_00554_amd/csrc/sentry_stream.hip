@@ -140,14 +140,19 @@ int lt_stream_feed(LtStream *st, const uint8_t *host_records, const uint64_t *ho
     const int b = (int)(st->batches % LT_SLOTS);
     hipStream_t hs = b == 0 ? s : pipe->hash_stream[b - 1];
     const uint64_t beg = host_offsets[0], end = host_offsets[n];
+    // A batch whose records all have one size needs no offsets on the device, and the host, which
+    // sees that here, picks the kernel itself (the scan ends at the first record of another size).
+    const uint64_t rec = host_offsets[1] - beg;
+    bool one_size = host_offsets[1] >= beg;
+    for (size_t i = 1; i < n && one_size; i++) one_size = host_offsets[i + 1] - host_offsets[i] == rec;
     // spare bytes: a batch sits at the same offset modulo 16 as in host memory, and the hash kernel
     // reads the whole aligned word that holds a record's last byte
     const size_t need = (end - beg) + 32, need_off = 8 * (n + 1) + 16;
-    if (sentry::scratch_capacity(s, LT_STAGE_R[b]) < need || sentry::scratch_capacity(s, LT_OFF_R[b]) < need_off)
+    if (sentry::scratch_capacity(s, LT_STAGE_R[b]) < need || (!one_size && sentry::scratch_capacity(s, LT_OFF_R[b]) < need_off))
         sentry::copy_pipe_drain(pipe, true);   // a buffer is replaced: nothing on the side streams may still use it
-    void *stage, *stage_off;
+    void *stage, *stage_off = nullptr;
     if ((rc = sentry::scratch_get(s, LT_STAGE_R[b], need, &stage))) return rc;
-    if ((rc = sentry::scratch_get(s, LT_OFF_R[b], need_off, &stage_off))) return rc;
+    if (!one_size && (rc = sentry::scratch_get(s, LT_OFF_R[b], need_off, &stage_off))) return rc;
     if ((rc = sentry::lthash_presize(n, hs))) return rc;
     if (st->batches == 0) {
         // nothing of this running sum may start before earlier work on the caller's stream is done
@@ -160,23 +165,28 @@ int lt_stream_feed(LtStream *st, const uint8_t *host_records, const uint64_t *ho
     // belonged to; an event that was never recorded does not hold anything up)
     SENTRY_HIP_CHECK(hipStreamWaitEvent(pipe->copy_stream, pipe->consumed[b], 0));
     const uint8_t *readable = end > beg ? kernel_readable(host_records + beg, end - beg) : nullptr;
-    const uint8_t *off_readable = kernel_readable(host_offsets, 8 * (n + 1));
     // the batch keeps its alignment modulo 16, so that the load moves whole aligned words
     const uint8_t *from = readable ? readable : host_records + beg;
     uint8_t *to = static_cast<uint8_t *>(stage) + (reinterpret_cast<uintptr_t>(from) & 15);
     if ((rc = enqueue_load(to, host_records + beg, readable, end - beg, pipe->copy_stream))) return rc;
-    // the offsets of the batch, staged at the same offset modulo 16 as in host memory (0 or 8)
-    const uint8_t *off_from = off_readable ? off_readable : reinterpret_cast<const uint8_t *>(host_offsets);
-    uint8_t *off_to = static_cast<uint8_t *>(stage_off) + (reinterpret_cast<uintptr_t>(off_from) & 15);
-    if ((rc = enqueue_load(off_to, reinterpret_cast<const uint8_t *>(host_offsets), off_readable, 8 * (n + 1), pipe->copy_stream)))
-        return rc;
+    const uint64_t *dev_offsets = nullptr;
+    if (!one_size) {
+        // the offsets of the batch, staged at the same offset modulo 16 as in host memory (0 or 8)
+        const uint8_t *off_readable = kernel_readable(host_offsets, 8 * (n + 1));
+        const uint8_t *off_from = off_readable ? off_readable : reinterpret_cast<const uint8_t *>(host_offsets);
+        uint8_t *off_to = static_cast<uint8_t *>(stage_off) + (reinterpret_cast<uintptr_t>(off_from) & 15);
+        if ((rc = enqueue_load(off_to, reinterpret_cast<const uint8_t *>(host_offsets), off_readable, 8 * (n + 1), pipe->copy_stream)))
+            return rc;
+        dev_offsets = reinterpret_cast<const uint64_t *>(off_to);
+    }
     SENTRY_HIP_CHECK(hipEventRecord(pipe->copied[b], pipe->copy_stream));
     SENTRY_HIP_CHECK(hipStreamWaitEvent(hs, pipe->copied[b], 0));
     // the caller's stream passes this call once the batch has left host memory
     if (hs != s) SENTRY_HIP_CHECK(hipStreamWaitEvent(s, pipe->copied[b], 0));
     // record i of the batch sits at to + (offset[i] - beg); the kernel copes with any byte alignment
+    // (without offsets the third argument is the size of a record)
     rc = (st->narrow ? sentry::lthash32_into : sentry::lthash_into)(
-        to, reinterpret_cast<const uint64_t *>(off_to), beg, n, st->sums + (size_t)b * SENTRY_LANES,
+        to, dev_offsets, one_size ? rec : beg, n, st->sums + (size_t)b * SENTRY_LANES,
         st->batches >= (uint64_t)LT_SLOTS, hs);
     if (rc) return rc;
     SENTRY_HIP_CHECK(hipEventRecord(pipe->consumed[b], hs));

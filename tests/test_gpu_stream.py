@@ -219,6 +219,38 @@ def test_lthash_stream_running_sum_over_batches_fed_one_by_one(pinned):
     assert (out.cpu() == 0).all()
 
 
+@pytest.mark.parametrize("narrow", [False, True])
+def test_lthash_stream_batches_of_one_record_size_need_no_offsets_on_the_device(narrow):
+    # batches in which every record has one size take the call without offsets (the host sees it);
+    # here they alternate with batches of mixed sizes inside one running sum: 3072-byte samples
+    # (one lane per record), 70 records of 40,000 bytes (four lanes), a batch of empty records, a
+    # batch of one record, and a batch that is equal but for its last record (the ordinary path)
+    lens = np.concatenate([
+        np.full(500, 3072), wl.lognormal_record_lengths(200, seed=5, median=5000, lo=0, hi=60_000),
+        np.full(70, 40_000), np.zeros(9, dtype=np.int64), [777], np.full(40, 1000), [1001], np.full(64, 129)]).astype(np.int64)
+    cuts = np.cumsum([0, 500, 200, 70, 9, 1, 41, 64])
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(2500, 0, int(off[-1]))
+    want = (oracle.lthash32 if narrow else oracle.lthash)(data, off)
+    # the records start 3 bytes into the host buffer: staging keeps that alignment modulo 16
+    host = torch.zeros(int(off[-1]) + 3, dtype=torch.uint8).pin_memory()
+    host[3:] = torch.from_numpy(data.copy())
+    hoff = torch.from_numpy(off.view(np.int64).copy())
+    s = torch.cuda.Stream()
+    out = torch.full((1024,), 0x3333, dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(2):      # the second running sum finds the staging buffers as the first left them
+        st = (sentry.sentry_lthash32_stream_begin if narrow else sentry.sentry_lthash_stream_begin)()
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            sentry.sentry_lthash_stream_update_h2d(st, host.data_ptr() + 3, hoff.data_ptr() + 8 * int(a), int(b - a), s.cuda_stream)
+        sentry.sentry_lthash_stream_final(st, out.data_ptr(), s.cuda_stream)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().view(np.uint16)
+        assert (got[:len(want)] == want).all()
+        out.fill_(0x3333)
+        torch.cuda.synchronize()
+
+
 def test_lthash_stream_misuse():
     st = sentry.sentry_lthash_stream_begin()
     h = torch.zeros(4096, dtype=torch.uint8).pin_memory()
