@@ -808,6 +808,49 @@ def main():
                     {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3), "calls": 391,
                      "us_per_call": ms * 1e3 / 391, "clock": "host wall time around all calls and the final synchronisation"},
                     (lthash_mix if name == "lthash" else lthash32_mix)([3072] * 50_000))
+        # what a HIP graph buys such a pipeline: the per-source call on a batch buffer (a pipeline hands every batch
+        # over in the same buffer) captured once and replayed 391 times, against the same 391 calls issued one by one;
+        # both running sums must come out equal
+        gs = torch.cuda.Stream()
+        for name, call, lanes_per in (("lthash", sentry.sentry_lthash_sources, 1024), ("lthash32", sentry.sentry_lthash32_sources, 32)):
+            acc_e = torch.zeros(16 * lanes_per, dtype=torch.int16, device=dev)
+            acc_g = torch.zeros(16 * lanes_per, dtype=torch.int16, device=dev)
+            torch.cuda.synchronize()
+
+            def one_batch(acc):
+                call(img.data_ptr(), d_ioff.data_ptr(), ids16.data_ptr(), 128, 16, acc.data_ptr(), gs.cuda_stream)
+
+            one_batch(acc_e)                      # the stream's scratch has its size before the capture
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=gs):
+                one_batch(acc_g)
+            ms_by = {}
+            acc_e.zero_()
+            acc_g.zero_()
+            torch.cuda.synchronize()
+            for kind in ("calls", "graph_replays"):
+                ts = []
+                for _ in range(4):                # the first pass warms up
+                    t0 = time.perf_counter()
+                    for _k in range(391):
+                        if kind == "calls":
+                            one_batch(acc_e)
+                        else:
+                            graph.replay()
+                    torch.cuda.synchronize()
+                    ts.append((time.perf_counter() - t0) * 1e3)
+                ms_by[kind] = statistics.median(ts[1:])
+            torch.cuda.synchronize()
+            if not torch.equal(acc_e, acc_g):
+                raise SystemExit("bench: the replayed graph and the eager calls disagree (%s)" % name)
+            ms = ms_by["graph_replays"]
+            per_config["E4_%s_batch_of_128_16_sources_graph_replayed_391_times" % name] = rated(
+                {"GB/s": 391 * 128 * 3072 / ms / 1e6, "ms": ms, "bytes": 391 * 128 * 3072, "samples/s": 391 * 128 / (ms * 1e-3),
+                 "calls": 391, "us_per_call": ms * 1e3 / 391, "us_per_call_without_graph": ms_by["calls"] * 1e3 / 391,
+                 "clock": "host wall time around all replays and the final synchronisation"},
+                (lthash_mix if name == "lthash" else lthash32_mix)([3072] * (391 * 128)))
+            del graph
         del ids16
         if not args.no_streaming:
             # host-to-device streaming in the shape of configs 5 and 4, from a pinned host buffer of 16 GB:
