@@ -340,6 +340,7 @@ def main():
                          "pair: the 70B root alone, then the other two side by side; serial: one stream")
     ap.add_argument("--no-extras", action="store_true", help="skip per-config and streaming side measurements")
     ap.add_argument("--no-streaming", action="store_true", help="skip the host-to-device streaming legs (for counter runs)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the entry that captures and replays a HIP graph (for profiler runs)")
     ap.add_argument("--merkle-prefix-gib", type=int, default=0,
                     help="hash only the first N GiB of the 70B stream (for counter runs; the workload name says so)")
     ap.add_argument("--only-config", choices=("c1", "c2", "a1"), default=None,
@@ -812,7 +813,8 @@ def main():
         # over in the same buffer) captured once and replayed 391 times, against the same 391 calls issued one by one;
         # both running sums must come out equal
         gs = torch.cuda.Stream()
-        for name, call, lanes_per in (("lthash", sentry.sentry_lthash_sources, 1024), ("lthash32", sentry.sentry_lthash32_sources, 32)):
+        for name, call, lanes_per in (() if args.no_graph else
+                                      (("lthash", sentry.sentry_lthash_sources, 1024), ("lthash32", sentry.sentry_lthash32_sources, 32))):
             acc_e = torch.zeros(16 * lanes_per, dtype=torch.int16, device=dev)
             acc_g = torch.zeros(16 * lanes_per, dtype=torch.int16, device=dev)
             torch.cuda.synchronize()

@@ -17,7 +17,8 @@
 //   lthash_digests_kernel, lthash_sum_kernel   the digests written out one by one, and the
 //                         lane sum over digests that are in memory;
 //   src_count/scatter_kernel, lthash_expand_units_kernel, lthash_fold_sources_kernel   one
-//                         running sum per data source (section 4.3).
+//                         running sum per data source (section 4.3); lthash_root4_rider_kernel
+//                         for small batches: root hashes and the sort by source in one launch.
 // The root kernels take the first two words of the parameter block as arguments: with those of
 // the plain BLAKE2b-512 they also serve the 32-partition hash of blake2_lthash32.hip.
 #include "blake2b_device.h"
@@ -872,6 +873,96 @@ src_scatter_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t *tables
     }
 }
 
+// A small batch over few sources: the whole sort is the work of one wave, and it does not depend
+// on the root hashes, so it rides along in their launch as one more workgroup (the root hashes of
+// such a batch are one wave per SIMD at most and last as long as one record's chain: 37 us for a
+// 3 KiB sample, behind which the sort's 5 us disappear, and with them two launches of 6 us each).
+constexpr uint32_t RIDER_MAX_RECORDS = 8192;          // one wave sorts them in 20 us, and their root hashes are still one wave per SIMD
+constexpr uint32_t RIDER_MAX_SOURCES = ROOT4_RECORDS * 128 / 8;       // two tables of words in the root kernel's LDS
+static_assert(RIDER_MAX_RECORDS <= FEW_RECORDS, "the batch of a rider always takes the four-lane path");
+
+struct SourceSort {
+    const uint32_t *src;      // source id per record
+    uint32_t n, S, unit;
+    uint32_t *tables;         // start[] and unit_start[] are written; count[], cursor[] and the ticket stay zero
+    uint32_t *perm;
+};
+
+// All 64 lanes of a one-wave workgroup; lds holds 2 * RIDER_MAX_SOURCES words.
+__device__ __forceinline__ void src_sort_one_wave(const SourceSort &j, uint32_t *lds)
+{
+    uint32_t *hist = lds, *cur = lds + RIDER_MAX_SOURCES;
+    const uint32_t lane = threadIdx.x, S = j.S;
+    constexpr int AHEAD = 8;                                        // ids in flight per lane
+    for (uint32_t k = lane; k < S; k += 64) hist[k] = 0;
+    __syncthreads();
+    for (uint32_t i0 = lane; i0 < j.n; i0 += 64 * AHEAD) {
+        uint32_t k[AHEAD];
+#pragma unroll
+        for (int a = 0; a < AHEAD; a++) k[a] = i0 + 64 * a < j.n ? j.src[i0 + 64 * a] : 0xffffffffu;
+#pragma unroll
+        for (int a = 0; a < AHEAD; a++)
+            if (k[a] < S) atomicAdd(&hist[k[a]], 1u);
+    }
+    __syncthreads();
+    // exclusive scans of the counts and of the units they make; lane l owns sources 4l .. 4l+3
+    constexpr int OWN = RIDER_MAX_SOURCES / 64;
+    uint32_t c[OWN], sum_c = 0, sum_u = 0;
+#pragma unroll
+    for (int q = 0; q < OWN; q++) {
+        const uint32_t k = OWN * lane + q;
+        c[q] = k < S ? hist[k] : 0;
+        sum_c += c[q];
+        sum_u += (c[q] + j.unit - 1) / j.unit;
+    }
+    uint32_t inc_c = sum_c, inc_u = sum_u;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t tc = (uint32_t)__shfl_up((int)inc_c, d, 64), tu = (uint32_t)__shfl_up((int)inc_u, d, 64);
+        if (lane >= (uint32_t)d) { inc_c += tc; inc_u += tu; }
+    }
+    uint32_t at_c = inc_c - sum_c, at_u = inc_u - sum_u;
+#pragma unroll
+    for (int q = 0; q < OWN; q++) {
+        const uint32_t k = OWN * lane + q;
+        if (k < S) {
+            tab_start(j.tables, S)[k] = at_c;
+            tab_unit_start(j.tables, S)[k] = at_u;
+            cur[k] = at_c;
+        }
+        at_c += c[q];
+        at_u += (c[q] + j.unit - 1) / j.unit;
+    }
+    if (lane == 63) {
+        tab_start(j.tables, S)[S] = inc_c;
+        tab_unit_start(j.tables, S)[S] = inc_u;
+    }
+    __syncthreads();
+    for (uint32_t i0 = lane; i0 < j.n; i0 += 64 * AHEAD) {
+        uint32_t k[AHEAD];
+#pragma unroll
+        for (int a = 0; a < AHEAD; a++) k[a] = i0 + 64 * a < j.n ? j.src[i0 + 64 * a] : 0xffffffffu;
+#pragma unroll
+        for (int a = 0; a < AHEAD; a++)
+            if (k[a] < S) j.perm[atomicAdd(&cur[k[a]], 1u)] = i0 + 64 * a;
+    }
+}
+
+// The four-lane root hashes of a batch of at most RIDER_MAX_RECORDS records, and in the last
+// workgroup the sort of the batch by source.
+__global__ void __launch_bounds__(ROOT4_WG)
+lthash_root4_rider_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
+                          uint64_t *h0_out, uint64_t p0, uint64_t p1, SourceSort sort)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char stage[ROOT4_RECORDS * 128];
+    static_assert(ROOT4_WG == 64, "the rider is written for a workgroup of one wave");
+    if (blockIdx.x == gridDim.x - 1) {
+        src_sort_one_wave(sort, reinterpret_cast<uint32_t *>(stage));
+        return;
+    }
+    root_four_lanes(records, offsets, offset_base, n, nullptr, h0_out, (uint64_t)blockIdx.x * ROOT4_RECORDS, stage, p0, p1);
+}
+
 // One wave per unit.  Lane l owns output block l & 31 and takes every second record of the
 // unit; the order of the records inside a source does not matter for the sum.
 __global__ void __launch_bounds__(EXP_WG)
@@ -1260,12 +1351,21 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
     const uint32_t scan_grid = (uint32_t)ceil_div(n, SRC_TILE);
 
     if (fresh_tables) hipLaunchKernelGGL(src_zero_kernel, dim3(1), dim3(SRC_WG), 0, s, tab, SRC_TABLE_WORDS);
-    hipLaunchKernelGGL(src_count_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, unit, tab);
-    hipLaunchKernelGGL(src_scatter_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab,
-                       static_cast<uint32_t *>(perm));
-    SENTRY_HIP_CHECK(hipGetLastError());
-    // the root hashes do not depend on the sources: the same launches as for one sum
-    rc = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s);
+    if (n <= RIDER_MAX_RECORDS && S <= RIDER_MAX_SOURCES) {
+        // a small batch: root hashes and sort in one launch
+        const SourceSort sort{src, (uint32_t)n, S, unit, tab, static_cast<uint32_t *>(perm)};
+        hipLaunchKernelGGL(lthash_root4_rider_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS) + 1), dim3(ROOT4_WG), 0, s,
+                           static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
+                           static_cast<uint64_t *>(h0), sentry::LT_ROOT_P0, sentry::LT_ROOT_P1, sort);
+        rc = SENTRY_OK;
+    } else {
+        hipLaunchKernelGGL(src_count_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, unit, tab);
+        hipLaunchKernelGGL(src_scatter_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab,
+                           static_cast<uint32_t *>(perm));
+        SENTRY_HIP_CHECK(hipGetLastError());
+        // the root hashes do not depend on the sources: the same launches as for one sum
+        rc = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s);
+    }
     if (rc) {   // the counts and cursors must not stay behind for the next call
         hipLaunchKernelGGL(src_zero_kernel, dim3(1), dim3(SRC_WG), 0, s, tab, SRC_TABLE_WORDS);
         (void)hipGetLastError();

@@ -322,6 +322,44 @@ def test_per_source_running_sums(n, n_sources):
     assert (as_u16(acc, n_sources) == want2).all()
 
 
+@pytest.mark.parametrize("n,n_sources", [(2, 2), (63, 3), (64, 255), (65, 256), (128, 16), (129, 257), (2048, 200),
+                                         (8191, 7), (8192, 256), (8193, 256), (8192, 257), (1500, 2)])
+def test_per_source_small_batches_sorted_inside_the_root_hash_launch(n, n_sources):
+    # up to 8192 records over up to 256 sources the sort by source is one more workgroup of the
+    # root-hash launch; one step beyond either limit it is the two sort kernels: both sides of
+    # both limits, sources without records, ids outside the table, and the same call twice over
+    # (the second finds the tables as the first left them) and then the other path on top
+    rng = np.random.default_rng(7100 + 31 * n + n_sources)
+    lens = rng.integers(0, 300, n).astype(np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(7200 + n, 0, int(off[-1]))
+    src = rng.integers(0, n_sources, n).astype(np.uint32)
+    if n_sources > 4:
+        src[src == 1] = 0                      # a source with no record
+        src[src == n_sources - 2] = n_sources - 1
+    if n > 10:
+        src[5] = n_sources
+        src[9] = 0xFFFFFFFF
+    want = oracle.lthash_sources(data, off, src, n_sources)
+    acc = gpu_sources(data, off, src, n_sources)
+    assert (as_u16(acc, n_sources) == want).all()
+    want = oracle.lthash_sources(data, off, src, n_sources, acc=want)
+    acc = gpu_sources(data, off, src, n_sources, acc=acc)
+    assert (as_u16(acc, n_sources) == want).all()
+    # a larger batch (the two sort kernels) and the small one again, into the same sums
+    big = 9000
+    lens_b = rng.integers(0, 100, big).astype(np.uint64)
+    off_b = wl.offsets_from_lengths(lens_b)
+    data_b = wl.uniform_bytes(7300 + n, 0, int(off_b[-1]))
+    src_b = rng.integers(0, n_sources, big).astype(np.uint32)
+    want = oracle.lthash_sources(data_b, off_b, src_b, n_sources, acc=want)
+    acc = gpu_sources(data_b, off_b, src_b, n_sources, acc=acc)
+    assert (as_u16(acc, n_sources) == want).all()
+    want = oracle.lthash_sources(data, off, src, n_sources, acc=want)
+    acc = gpu_sources(data, off, src, n_sources, acc=acc)
+    assert (as_u16(acc, n_sources) == want).all()
+
+
 def test_per_source_skewed_and_single_source_equals_plain_hash():
     n = 3000
     rng = np.random.default_rng(81)
