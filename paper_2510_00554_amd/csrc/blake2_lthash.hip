@@ -973,13 +973,18 @@ lthash_expand_units_kernel(const uint64_t *h0, const uint32_t *perm, uint32_t S,
     const uint32_t u = blockIdx.x * EXP_WAVES + (threadIdx.x >> 6);
     const uint32_t *unit_start = tab_unit_start(tables, S);
     if (u >= unit_start[S]) return;                     // wave-uniform
-    // the source whose unit range holds u: last k with unit_start[k] <= u
-    uint32_t lo = 0, hi = S;
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (unit_start[mid] <= u) lo = mid; else hi = mid;
+    // the source whose unit range holds u: the last k with unit_start[k] <= u.  The whole wave looks
+    // for it: every lane reads the first entry of one of 64 stretches of the table, then the lanes
+    // read the stretch that holds it (two loads one behind the other where a bisection has twelve).
+    const uint32_t stretch = (S + 63) / 64;
+    const uint32_t at1 = lane * stretch;
+    const uint32_t v1 = at1 < S ? unit_start[at1] : 0xffffffffu;
+    uint32_t k = (uint32_t)__popcll(__ballot(v1 <= u)) - 1;             // unit_start[0] = 0: at least lane 0
+    if (stretch > 1) {
+        const uint32_t at2 = k * stretch + lane;
+        const uint32_t v2 = lane < stretch && at2 < S ? unit_start[at2] : 0xffffffffu;
+        k = k * stretch + (uint32_t)__popcll(__ballot(v2 <= u)) - 1;
     }
-    const uint32_t k = lo;
     const uint32_t *start = tab_start(tables, S);
     const uint32_t first = start[k] + (u - unit_start[k]) * unit;
     const uint32_t stop = first + unit < start[k + 1] ? first + unit : start[k + 1];
@@ -1330,14 +1335,17 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
         if ((rc1 = sentry::lthash_roots(dev_records, dev_offsets, 0, n, static_cast<uint64_t *>(h0), s))) return rc1;
         return sentry::lthash_expand_and_fold(static_cast<const uint64_t *>(h0), n, dev_source_ids, acc_lanes, true, s);
     }
-    // records per unit (one wave expands one unit): few enough that the launch has about four waves
-    // for every SIMD, whatever the sources' shares (with 32 and more, 50,000 records made 1563 waves
-    // for 1024 SIMDs, half of which then carried two waves and half one), and few enough units to
-    // keep the partial rows small
-    // (a small batch gets units of two records, one pass of a wave: with eight, 128 records made 16
-    // waves of four compressions per lane each, 19 us where 5 us do)
-    uint32_t unit = 2;
-    while (ceil_div(n, unit) > (uint64_t)cu_count() * 16) unit *= 2;
+    // Records per unit (one wave expands one unit, two records per pass).  A SIMD works off whole
+    // units and every unit costs its wave some 3 us of loads one behind the other before the first
+    // pass, so there is a best size, found by timing units of 2 to 128 records on 9000 to 500,000
+    // records: four records up to 65,536 (50,000 records: 0.235 ms for the call with units of 16,
+    // 3125 units on 1024 SIMDs of which some then had four and the others waited; 0.225 ms with
+    // units of 4; 0.230 ms with units of 2, which make 51 MB of partial rows), eight up to 131,072
+    // and so on: at most 64 units per compute unit.  Up to two records per SIMD a unit is one pass:
+    // with units of eight, 128 records made 16 waves of four compressions per lane each, 19 us
+    // where 5 us do.
+    uint32_t unit = n <= (uint64_t)cu_count() * 8 ? 2 : 4;
+    while (ceil_div(n, unit) > (uint64_t)cu_count() * 64) unit *= 2;
     const uint64_t max_units = ceil_div(n, unit) + S;          // every source may end in a short unit
     void *h0, *part, *tables, *perm;
     int rc;
