@@ -893,7 +893,7 @@ __device__ __forceinline__ void src_sort_one_wave(const SourceSort &j, uint32_t 
 {
     uint32_t *hist = lds, *cur = lds + RIDER_MAX_SOURCES;
     const uint32_t lane = threadIdx.x, S = j.S;
-    constexpr int AHEAD = 8;                                        // ids in flight per lane
+    constexpr int AHEAD = 32;                                       // ids in flight per lane: 8192 records are four trips in all
     for (uint32_t k = lane; k < S; k += 64) hist[k] = 0;
     __syncthreads();
     for (uint32_t i0 = lane; i0 < j.n; i0 += 64 * AHEAD) {
