@@ -699,17 +699,24 @@ def main():
             roots_s = torch.zeros(32 * len(ls), dtype=torch.uint8, device=dev)
             lanes_s = torch.zeros(32, dtype=torch.int16, device=dev)
             for scheme, call, mix in (
-                    ("coalesced_alg1", lambda: sentry.sentry_merkle_coalesced(ps, ls, 8192, 0, 0, root7.data_ptr(), stream),
+                    ("coalesced_alg1", lambda st: sentry.sentry_merkle_coalesced(ps, ls, 8192, 0, 0, root7.data_ptr(), st),
                      sha_tree_mix([-(-nb // 8192) * 8192], 8192, flat=True)),
-                    ("per_layer_alg2", lambda: sentry.sentry_merkle_segments(ps, ls, 8192, roots_s.data_ptr(), root7.data_ptr(), stream),
+                    ("per_layer_alg2", lambda st: sentry.sentry_merkle_segments(ps, ls, 8192, roots_s.data_ptr(), root7.data_ptr(), st),
                      sha_tree_mix(ls, 8192)),
-                    ("in_place_alg3", lambda: sentry.sentry_merkle_inplace(ps, ls, 8192, root7.data_ptr(), stream),
+                    ("in_place_alg3", lambda st: sentry.sentry_merkle_inplace(ps, ls, 8192, root7.data_ptr(), st),
                      sha_tree_mix(ls, 8192, flat=True)),
-                    ("lattice_alg4", lambda: sentry.sentry_lthash_model(ps, ls, 8192, 0, lanes_s.data_ptr(), stream),
+                    ("lattice_alg4", lambda st: sentry.sentry_lthash_model(ps, ls, 8192, 0, lanes_s.data_ptr(), st),
                      model_lthash_mix(ls, 8192))):
-                ms = timed_call(call, 20)
+                ms = timed_call(lambda: call(stream), 20)
+                # the scheme's extra GPU memory (section 5.2, memory usage): what the library holds for a stream
+                # that has made this one call
+                own = torch.cuda.Stream()
+                call(own.cuda_stream)
+                own.synchronize()
+                extra = sentry.sentry_scratch_bytes(own.cuda_stream)[0]
                 per_config["E1_%s_%s_8KiB" % (shape, scheme)] = rated(
-                    {"GB/s": nb / ms / 1e6, "ms": ms, "bytes": nb, "tensors": len(ls)}, mix)
+                    {"GB/s": nb / ms / 1e6, "ms": ms, "bytes": nb, "tensors": len(ls), "extra_device_bytes": extra,
+                     "extra_per_model_byte": extra / nb}, mix)
             del ts, roots_s
         # the three leaf functions of section 4.2.1 on the first 16 GiB of the 70B stream, 8 KiB leaves
         f4_bytes = min(bytes70, 16 << 30)

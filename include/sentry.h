@@ -520,6 +520,22 @@ SENTRY_API const char *sentry_last_error(void);
 SENTRY_API int sentry_reserve_scratch(size_t merkle_max_len, size_t merkle_leaf_bytes,
                                       size_t lthash_max_records, void *stream);
 
+/*
+ * The memory the library holds for calls on `stream` of the current device: the
+ * extra GPU memory of a hashing scheme (section 5.2, "Memory Usage Evaluation";
+ * Table 1 reports it per scheme and model).  *out_device_bytes = bytes of the
+ * stream's scratch regions (digests of the tree levels, tables, partial sums,
+ * staging buffers of the host-streaming calls, gathered blocks of the coalesced
+ * scheme), *out_pinned_bytes = pinned host memory of its table staging; either
+ * may be NULL.  Both are grow-only until sentry_release_scratch: after a call
+ * they are what the largest call so far on that stream needed.  Not counted:
+ * the state a sentry_*_stream_begin call holds until its final or abort, and
+ * the 2 MiB array of sentry_merkle_root_noalloc.  Host-side bookkeeping only:
+ * no wait, no GPU work.
+ * Errors: SENTRY_ERR_INVALID_ARG if both outputs are NULL; SENTRY_ERR_HIP.
+ */
+SENTRY_API int sentry_scratch_bytes(void *stream, size_t *out_device_bytes, size_t *out_pinned_bytes);
+
 /* Free all cached scratch memory of the current device (synchronises it). */
 SENTRY_API int sentry_release_scratch(void);
 

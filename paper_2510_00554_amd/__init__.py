@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     sentry_merkle_stream_abort, sentry_merkle_root_h2d, sentry_verify,
     sentry_lthash, sentry_lthash_digests, sentry_lthash_sum, sentry_lthash_sources, sentry_lthash_model, sentry_lthash_model_from, sentry_lthash_combine, sentry_lthash_remove, sentry_lthash32, sentry_lthash_fixed, sentry_lthash32_fixed, sentry_lthash32_sources, sentry_lthash32_combine, sentry_lthash32_remove, sentry_lthash_h2d,
     sentry_lthash_stream_begin, sentry_lthash32_stream_begin, sentry_lthash_stream_update_h2d, sentry_lthash_stream_final, sentry_lthash_stream_abort,
-    sentry_last_error, sentry_reserve_scratch, sentry_release_scratch,
+    sentry_last_error, sentry_reserve_scratch, sentry_scratch_bytes, sentry_release_scratch,
 )

@@ -70,6 +70,7 @@ PROTOTYPES = {
     "sentry_lthash_stream_abort": (_int, [_vp]),
     "sentry_last_error": (ctypes.c_char_p, []),
     "sentry_reserve_scratch": (_int, [_sz, _sz, _sz, _vp]),
+    "sentry_scratch_bytes": (_int, [_vp, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
     "sentry_release_scratch": (_int, []),
 }
 
@@ -108,6 +109,13 @@ def sentry_last_error():
 
 def sentry_reserve_scratch(merkle_max_len, merkle_leaf_bytes, lthash_max_records, stream=0):
     return _check(load().sentry_reserve_scratch(merkle_max_len, merkle_leaf_bytes, lthash_max_records, stream))
+
+
+def sentry_scratch_bytes(stream=0):
+    """(device bytes, pinned host bytes) the library holds for `stream`."""
+    d, h = _sz(0), _sz(0)
+    _check(load().sentry_scratch_bytes(stream, ctypes.byref(d), ctypes.byref(h)))
+    return d.value, h.value
 
 
 def sentry_release_scratch():

@@ -206,6 +206,23 @@ int sweep_retired()
     return sweep_retired_locked();
 }
 
+// Bytes the library holds for (current device, stream): scratch regions, and pinned table staging.
+int scratch_bytes(hipStream_t stream, size_t *device_bytes, size_t *pinned_bytes)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    int dev = 0;
+    SENTRY_HIP_CHECK(hipGetDevice(&dev));
+    size_t d = 0, h = 0;
+    auto it = g_ctx.find(std::make_pair(dev, stream));
+    if (it != g_ctx.end()) {
+        for (int r = 0; r < R_COUNT; r++) d += it->second.cap[r];
+        for (int t = 0; t < TABLE_SLOTS; t++) h += it->second.tab_cap[t];
+    }
+    *device_bytes = d;
+    *pinned_bytes = h;
+    return SENTRY_OK;
+}
+
 int release_all_scratch()
 {
     std::lock_guard<std::mutex> lock(g_mu);
@@ -245,6 +262,18 @@ int release_all_scratch()
 extern "C" {
 
 const char *sentry_last_error(void) { return sentry::g_err; }
+
+int sentry_scratch_bytes(void *stream, size_t *out_device_bytes, size_t *out_pinned_bytes)
+{
+    sentry::clear_error();
+    SENTRY_REQUIRE(out_device_bytes != nullptr || out_pinned_bytes != nullptr, "sentry_scratch_bytes: NULL outputs");
+    size_t d = 0, h = 0;
+    const int rc = sentry::scratch_bytes(static_cast<hipStream_t>(stream), &d, &h);
+    if (rc) return rc;
+    if (out_device_bytes) *out_device_bytes = d;
+    if (out_pinned_bytes) *out_pinned_bytes = h;
+    return SENTRY_OK;
+}
 
 int sentry_release_scratch(void)
 {

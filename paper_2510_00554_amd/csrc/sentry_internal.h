@@ -107,5 +107,7 @@ int retire_device_memory(void *dev_ptr, hipStream_t stream);
 int sweep_retired();
 
 int release_all_scratch();
+// Bytes held for (current device, stream): scratch regions, and pinned table staging.
+int scratch_bytes(hipStream_t stream, size_t *device_bytes, size_t *pinned_bytes);
 
 }  // namespace sentry

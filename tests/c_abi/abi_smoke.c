@@ -45,6 +45,7 @@ int main(void)
     EXPECT(sentry_lthash_fixed(NULL, 100, 5, lanes, NULL) == SENTRY_ERR_INVALID_ARG);
     EXPECT(sentry_merkle_coalesced(ptrs, lens, 1, 100, NULL, 0, a, NULL) == SENTRY_ERR_INVALID_ARG);
     EXPECT(sentry_reserve_scratch(1000, 100, 0, NULL) == SENTRY_ERR_INVALID_ARG);
+    EXPECT(sentry_scratch_bytes(NULL, NULL, NULL) == SENTRY_ERR_INVALID_ARG);
     {   /* a host-only call with a result: one 64-byte tensor in 128-byte blocks is one gathered block */
         size_t gathered = 1, copied = 1, runs = 0;
         EXPECT(sentry_merkle_coalesced_plan(ptrs, lens, 1, 128, &gathered, &copied, &runs) == SENTRY_OK);

@@ -111,6 +111,7 @@ def test_verify_is_host_only():
     lambda: sentry.sentry_lthash32_combine(0x2000, 0),
     lambda: sentry.sentry_lthash32_remove(0x2000, 0x2003),
     lambda: sentry.sentry_lthash_h2d(0x1000, 0x3000, 5, 0, 0x2000),      # batch_bytes == 0
+    lambda: binding._check(binding.load().sentry_scratch_bytes(None, None, None)),    # nowhere to write to
 ])
 def test_bad_arguments_are_rejected_on_the_host(call):
     with pytest.raises(sentry.SentryError) as e:

@@ -115,6 +115,45 @@ def test_release_scratch_then_reuse():
         sentry.sentry_release_scratch()
 
 
+def test_scratch_bytes_is_the_extra_memory_of_a_scheme():
+    # section 5.2 (memory usage): what the library holds for a stream after hashing a model of 40
+    # tensors (26 MB) in 8 KiB blocks.  Per layer and in place it is the digests of the workgroups'
+    # subtrees and the tables: a few pages, where one digest per block would take 1/256 of the
+    # model; coalesced without a buffer it is the gathered blocks on top (at most one per tensor
+    # and the padded last one).  Grow-only, the same after a second call, zero after a release.
+    lens = [8192 * (5 + 7 * i % 150) + (48 * i) % 8192 for i in range(40)]      # tails of whole 16-byte words
+    tensors = [to_dev(wl.uniform_bytes(970 + i, 0, n)) for i, n in enumerate(lens)]
+    ptrs = [t.data_ptr() for t in tensors]
+    host = [t.cpu().numpy() for t in tensors]
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    roots = torch.zeros(32 * len(lens), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    total = sum(lens)
+    seen = {}
+    for name, call in (
+            ("per layer", lambda st: sentry.sentry_merkle_segments(ptrs, lens, 8192, roots.data_ptr(), out.data_ptr(), st)),
+            ("in place", lambda st: sentry.sentry_merkle_inplace(ptrs, lens, 8192, out.data_ptr(), st)),
+            ("coalesced", lambda st: sentry.sentry_merkle_coalesced(ptrs, lens, 8192, 0, 0, out.data_ptr(), st))):
+        s = torch.cuda.Stream()
+        assert sentry.sentry_scratch_bytes(s.cuda_stream) == (0, 0)
+        call(s.cuda_stream)
+        s.synchronize()
+        dev, pinned = sentry.sentry_scratch_bytes(s.cuda_stream)
+        call(s.cuda_stream)
+        s.synchronize()
+        assert sentry.sentry_scratch_bytes(s.cuda_stream) == (dev, pinned)
+        assert 0 < dev and 0 < pinned <= 64 * 1024
+        seen[name] = dev
+    assert bytes(out.cpu().numpy()) == oracle.merkle_coalesced_h(sentry.HASH_SHA256, host, 8192)
+    # (every region is a whole number of 4 KiB pages: that is what shows on a model this small)
+    assert seen["per layer"] < 40 * 4096 + total // 2048 and seen["in place"] < 40 * 4096 + total // 2048
+    gathered, _, _ = sentry.sentry_merkle_coalesced_plan(ptrs, lens, 8192)
+    assert gathered <= 8192 * (len(lens) + 1)
+    assert seen["coalesced"] <= seen["in place"] + gathered + 3 * 4096 + 64 * 1024
+    sentry.sentry_release_scratch()
+    assert sentry.sentry_scratch_bytes(0) == (0, 0)
+
+
 def test_error_text_names_the_argument_and_later_calls_still_work():
     buf = wl.uniform_bytes(960, 0, 4096)
     d = to_dev(buf)
