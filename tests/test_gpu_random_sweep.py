@@ -177,3 +177,37 @@ def test_32_partition_hash_over_random_record_mixes(seed):
     assert (acc.cpu().numpy().view(np.uint16).reshape(n_src, 32) == want).all(), (n, n_src, sh)
     o2 = np.arange(m + 1, dtype=np.uint64) * np.uint64(rb)
     assert (fixed.cpu().numpy().view(np.uint16) == oracle.lthash32(data[:rb * m], o2)).all(), (rb, m, sh)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_per_source_sums_over_random_batches(seed):
+    # batch sizes on both sides of what the root-hash launch sorts by itself (8192 records, 256
+    # sources), numbers of sources on both sides of one 64-entry stretch of the unit table, sources
+    # without records, one source that owns everything, ids outside the table; twice into one sum
+    rng = np.random.default_rng(7900 + seed)
+    n = int(rng.choice([1, 64, 65, 2048, 2049, 8191, 8192, 8193, 12_000, int(rng.integers(1, 9000))]))
+    n_src = int(rng.choice([1, 2, 16, 64, 65, 255, 256, 257, 1000, 4096]))
+    lens = rng.integers(0, int(rng.choice([2, 40, 300])), size=n).astype(np.uint64)
+    if seed % 3 == 0:
+        lens[int(rng.integers(0, n))] = int(rng.integers(1000, 50_000))
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(7950 + seed, 0, int(off[-1]))
+    mode = seed % 4
+    if mode == 0:
+        src = rng.integers(0, n_src, size=n)
+    elif mode == 1:
+        src = rng.integers(0, n_src + 1, size=n)
+    elif mode == 2:
+        src = np.full(n, int(rng.integers(0, n_src)))
+    else:
+        src = (rng.integers(0, n_src, size=n) // 7) * 7 % n_src
+    src = src.astype(np.uint32)
+    acc0 = rng.integers(0, 65536, size=(n_src, 1024)).astype(np.uint16)
+    acc = to_dev(acc0.reshape(-1))
+    dd, do, ds = to_dev(data), to_dev(off), to_dev(src.view(np.int32))
+    want = acc0
+    for _ in range(2):
+        sentry.sentry_lthash_sources(dd.data_ptr(), do.data_ptr(), ds.data_ptr(), n, n_src, acc.data_ptr())
+        torch.cuda.synchronize()
+        want = oracle.lthash_sources(data, off, src, n_src, acc=want)
+        assert (acc.cpu().numpy().view(np.uint16).reshape(n_src, 1024) == want).all(), (seed, n, n_src, mode)
