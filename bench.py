@@ -743,9 +743,10 @@ def main():
         ms = timed_call(lambda: sentry.sentry_lthash_model(t7_ptrs, t7_lens, 8192, 0, mlanes.data_ptr(), stream), 5)
         per_config["F2_lthash_model_7b_8KiB"] = rated({"GB/s": bytes7 / ms / 1e6, "ms": ms, "bytes": bytes7},
                                                       model_lthash_mix(t7_lens, 8192))
-        # mixed-source batches (section 4.3): the same 50,000 samples spread over 1, 16 and 128 sources
+        # mixed-source batches (section 4.3): the same 50,000 samples from 1, 16 and 128 sources whose shares
+        # are drawn from a Dirichlet distribution with concentration 1, as in the paper's run over the number of sources
         for n_src in (1, 16, 128):
-            ids = torch.from_numpy((wl._words_np(wl.SEED_C2 + 7, 0, 50_000) % np.uint64(n_src)).astype(np.int32)).to(dev)
+            ids = torch.from_numpy(wl.dirichlet_source_ids(50_000, n_src, wl.SEED_C2 + 7).view(np.int32)).to(dev)
             acc = torch.zeros(n_src * 1024, dtype=torch.int16, device=dev)
             ms = timed_call(lambda: sentry.sentry_lthash_sources(img.data_ptr(), d_ioff.data_ptr(), ids.data_ptr(),
                                                                  50_000, n_src, acc.data_ptr(), stream), 30)
@@ -791,7 +792,7 @@ def main():
         # the 50,000 images as a data pipeline hands them over (batches of 128 samples from 16 sources, as in the
         # paper's pipeline runs): one per-source call per batch into running sums, 391 calls back to back on one
         # stream, and dealt over four streams (each with running sums of its own, which add up); host time included
-        ids16 = torch.from_numpy((wl._words_np(wl.SEED_C2 + 9, 0, 50_000) % np.uint64(16)).astype(np.int32)).to(dev)
+        ids16 = torch.from_numpy(wl.dirichlet_source_ids(50_000, 16, wl.SEED_C2 + 9).view(np.int32)).to(dev)
         for n_streams in (1, 4):
             pipe_streams = [torch.cuda.Stream() for _ in range(n_streams)]
             for name, call, lanes_per in (("lthash", sentry.sentry_lthash_sources, 1024), ("lthash32", sentry.sentry_lthash32_sources, 32)):

@@ -306,6 +306,20 @@ def lognormal_record_lengths(n, seed=SEED_C4_LEN, median=110_000, sigma=0.5, lo=
     return np.clip(ln, lo, hi).astype(np.uint64)
 
 
+def dirichlet_source_ids(n, n_sources, seed, alpha_one=True):
+    """Source id per sample for a dataset put together from n_sources providers whose shares
+    are drawn from a Dirichlet distribution with concentration 1 (section 5.2, the run over 1 to
+    128 sources): shares = normalised Exp(1) draws, every sample then picks its source by those
+    shares.  Host, float64, from the counter generator; returns uint32[n]."""
+    assert alpha_one
+    w = _words_np(seed, 0, n_sources + n)
+    u = ((w >> np.uint64(11)).astype(np.float64) + 1.0) / 9007199254740992.0          # (0, 1]
+    e = -np.log(u[:n_sources])
+    cdf = np.cumsum(e / e.sum())
+    ids = np.searchsorted(cdf, u[n_sources:], side="left")
+    return np.minimum(ids, n_sources - 1).astype(np.uint32)
+
+
 def offsets_from_lengths(lengths):
     off = np.zeros(len(lengths) + 1, np.uint64)
     np.cumsum(lengths, out=off[1:])

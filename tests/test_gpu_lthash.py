@@ -360,6 +360,17 @@ def test_per_source_small_batches_sorted_inside_the_root_hash_launch(n, n_source
     assert (as_u16(acc, n_sources) == want).all()
 
 
+@pytest.mark.parametrize("n,n_sources", [(6000, 16), (20_000, 128)])
+def test_per_source_with_shares_of_a_dirichlet_draw(n, n_sources):
+    # the source mix of the paper's run over the number of sources (section 5.2): uneven shares
+    lens = np.full(n, 96, dtype=np.uint64)
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(7400 + n, 0, int(off[-1]))
+    src = wl.dirichlet_source_ids(n, n_sources, 7401)
+    want = oracle.lthash_sources(data, off, src, n_sources)
+    assert (as_u16(gpu_sources(data, off, src, n_sources), n_sources) == want).all()
+
+
 def test_per_source_skewed_and_single_source_equals_plain_hash():
     n = 3000
     rng = np.random.default_rng(81)

@@ -68,3 +68,16 @@ def test_checkpoint_stream_ranges():
     flat = np.concatenate(wl.checkpoint_bytes_np(lay))
     for start, n in ((0, 1000), (511, 4097), (flat.size - 777, 777), (2 * lay[0][1] - 3, 10)):
         assert (wl.checkpoint_stream_np(lay, start, n) == flat[start:start + n]).all(), (start, n)
+
+
+def test_dirichlet_source_ids():
+    for n_src in (1, 16, 128):
+        ids = wl.dirichlet_source_ids(50_000, n_src, 99)
+        assert ids.dtype == np.uint32 and ids.shape == (50_000,) and int(ids.max()) < n_src
+        assert (ids == wl.dirichlet_source_ids(50_000, n_src, 99)).all()          # a function of the seed
+        counts = np.bincount(ids, minlength=n_src)
+        assert counts.sum() == 50_000
+        if n_src > 1:
+            assert (ids != wl.dirichlet_source_ids(50_000, n_src, 100)).any()
+            # shares of concentration 1 are far from even: the largest is a multiple of the mean
+            assert counts.max() > 2 * 50_000 / n_src and counts.min() < 0.5 * 50_000 / n_src
