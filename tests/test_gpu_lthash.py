@@ -303,7 +303,7 @@ def as_u16(acc, n_sources):
     return acc.cpu().numpy().view(np.uint16).reshape(n_sources, 1024)
 
 
-@pytest.mark.parametrize("n,n_sources", [(1, 1), (60, 5), (1000, 16), (5000, 128), (333, 4096)])
+@pytest.mark.parametrize("n,n_sources", [(1, 1), (60, 5), (1000, 16), (5000, 128), (333, 4096), (9000, 2), (9000, 9)])
 def test_per_source_running_sums(n, n_sources):
     rng = np.random.default_rng(71 + n)
     lens = rng.integers(0, 600, n).astype(np.uint64)
