@@ -130,6 +130,7 @@ def test_scratch_bytes_is_the_extra_memory_of_a_scheme():
     torch.cuda.synchronize()
     total = sum(lens)
     seen = {}
+    sentry.sentry_release_scratch()      # torch hands out streams from a pool: one may have served an earlier test
     for name, call in (
             ("per layer", lambda st: sentry.sentry_merkle_segments(ptrs, lens, 8192, roots.data_ptr(), out.data_ptr(), st)),
             ("in place", lambda st: sentry.sentry_merkle_inplace(ptrs, lens, 8192, out.data_ptr(), st)),
