@@ -711,12 +711,13 @@ def main():
                 # the scheme's extra GPU memory (section 5.2, memory usage): what the library holds for a stream
                 # that has made this one call
                 own = torch.cuda.Stream()
+                unused = sentry.sentry_scratch_bytes(own.cuda_stream) == (0, 0)    # torch hands out streams from a pool
                 call(own.cuda_stream)
                 own.synchronize()
-                extra = sentry.sentry_scratch_bytes(own.cuda_stream)[0]
+                extra = sentry.sentry_scratch_bytes(own.cuda_stream)[0] if unused else None
                 per_config["E1_%s_%s_8KiB" % (shape, scheme)] = rated(
                     {"GB/s": nb / ms / 1e6, "ms": ms, "bytes": nb, "tensors": len(ls), "extra_device_bytes": extra,
-                     "extra_per_model_byte": extra / nb}, mix)
+                     "extra_per_model_byte": extra / nb if unused else None}, mix)
             del ts, roots_s
         # the three leaf functions of section 4.2.1 on the first 16 GiB of the 70B stream, 8 KiB leaves
         f4_bytes = min(bytes70, 16 << 30)
