@@ -814,15 +814,14 @@ __device__ __forceinline__ void src_plan(uint32_t S, uint32_t unit, uint32_t *ta
 }
 
 // Counts per source; the workgroup that finishes last (a ticket counter, as in the one-launch Merkle
-// tree) turns them into the plan, so that no launch of its own is needed for that.
-__global__ void __launch_bounds__(SRC_WG)
-src_count_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t unit, uint32_t *tables)
+// tree) turns them into the plan, so that no launch of its own is needed for that.  The work of
+// workgroup `block` of `n_blocks` (SRC_WG lanes each); hist: LDS, max(S, 2 * SRC_WG) words.
+__device__ __forceinline__ void src_count_block(const uint32_t *src, uint64_t n, uint32_t S, uint32_t unit, uint32_t *tables,
+                                                uint32_t block, uint32_t n_blocks, uint32_t *hist, uint32_t *last)
 {
-    __shared__ uint32_t hist[SRC_MAX_SOURCES];
-    __shared__ uint32_t last;
     for (uint32_t k = threadIdx.x; k < S; k += SRC_WG) hist[k] = 0;
     __syncthreads();
-    const uint64_t tile = (uint64_t)blockIdx.x * SRC_TILE;
+    const uint64_t tile = (uint64_t)block * SRC_TILE;
 #pragma unroll
     for (int q = 0; q < SRC_ITEMS; q++) {
         const uint64_t i = tile + (uint64_t)q * SRC_WG + threadIdx.x;
@@ -836,25 +835,35 @@ src_count_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t unit, uin
         if (hist[k]) atomicAdd(&tab_count(tables, S)[k], hist[k]);
     __threadfence();          // this workgroup's counts are visible to the device before its ticket
     __syncthreads();
-    if (threadIdx.x == 0) last = atomicAdd(tab_ticket(tables), 1u) == gridDim.x - 1;
+    if (threadIdx.x == 0) *last = atomicAdd(tab_ticket(tables), 1u) == n_blocks - 1;
     __syncthreads();
-    if (!last) return;
+    if (!*last) return;
     __threadfence();          // the counts of all other workgroups are read from memory, not from a stale line
     src_plan(S, unit, tables, hist, hist + SRC_WG);
     if (threadIdx.x == 0) *tab_ticket(tables) = 0;
 }
 
 __global__ void __launch_bounds__(SRC_WG)
-src_scatter_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t *tables, uint32_t *perm)
+src_count_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t unit, uint32_t *tables)
 {
-    __shared__ uint32_t cnt[SRC_MAX_SOURCES];     // records of source k in this tile, then the tile's base
-    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG) cnt[k] = 0;
+    __shared__ uint32_t hist[SRC_MAX_SOURCES];
+    __shared__ uint32_t last;
+    src_count_block(src, n, S, unit, tables, blockIdx.x, gridDim.x, hist, &last);
+}
+
+// Places of the records of tile `block` (WG * SRC_ITEMS records) in the order by source; WG lanes;
+// cnt: LDS, S words (records of source k in this tile, then the tile's base).
+template <int WG>
+__device__ __forceinline__ void src_scatter_block(const uint32_t *src, uint64_t n, uint32_t S, uint32_t *tables, uint32_t *perm,
+                                                  uint32_t block, uint32_t *cnt)
+{
+    for (uint32_t k = threadIdx.x; k < S; k += WG) cnt[k] = 0;
     __syncthreads();
-    const uint64_t tile = (uint64_t)blockIdx.x * SRC_TILE;
+    const uint64_t tile = (uint64_t)block * (WG * SRC_ITEMS);
     uint32_t key[SRC_ITEMS], rank[SRC_ITEMS];
 #pragma unroll
     for (int q = 0; q < SRC_ITEMS; q++) {
-        const uint64_t i = tile + (uint64_t)q * SRC_WG + threadIdx.x;
+        const uint64_t i = tile + (uint64_t)q * WG + threadIdx.x;
         key[q] = 0xffffffffu;
         rank[q] = 0;
         if (i < n) {
@@ -863,14 +872,21 @@ src_scatter_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t *tables
         }
     }
     __syncthreads();
-    for (uint32_t k = threadIdx.x; k < S; k += SRC_WG)
+    for (uint32_t k = threadIdx.x; k < S; k += WG)
         if (cnt[k]) cnt[k] = tab_start(tables, S)[k] + atomicAdd(&tab_cursor(tables, S)[k], cnt[k]);
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < SRC_ITEMS; q++) {
-        const uint64_t i = tile + (uint64_t)q * SRC_WG + threadIdx.x;
+        const uint64_t i = tile + (uint64_t)q * WG + threadIdx.x;
         if (key[q] != 0xffffffffu) perm[cnt[key[q]] + rank[q]] = (uint32_t)i;
     }
+}
+
+__global__ void __launch_bounds__(SRC_WG)
+src_scatter_kernel(const uint32_t *src, uint64_t n, uint32_t S, uint32_t *tables, uint32_t *perm)
+{
+    __shared__ uint32_t cnt[SRC_MAX_SOURCES];
+    src_scatter_block<SRC_WG>(src, n, S, tables, perm, blockIdx.x, cnt);
 }
 
 // A small batch over few sources: the whole sort is the work of one wave, and it does not depend
@@ -961,6 +977,43 @@ lthash_root4_rider_kernel(const uint8_t *records, const uint64_t *offsets, uint6
         return;
     }
     root_four_lanes(records, offsets, offset_base, n, nullptr, h0_out, (uint64_t)blockIdx.x * ROOT4_RECORDS, stage, p0, p1);
+}
+
+// Larger batches over few sources, for which both root kernels are launched: the count by source
+// rides at the front of the one-lane launch and the scatter at the front of the four-lane launch,
+// which follows it on the stream.  Whichever of the two kernels hashes the batch, one of the
+// steps hides behind it and neither needs a launch of its own (50,000 samples of 3 KiB over 16
+// sources: two launches of 11 and 4 us less).
+static_assert(ROOT1_WG == SRC_WG, "the count rides in workgroups of the one-lane root kernel");
+static_assert(RIDER_MAX_SOURCES <= 2 * SRC_WG, "the count's LDS table doubles as the plan's two scan arrays");
+
+__global__ void __launch_bounds__(ROOT1_WG)
+lthash_root1_count_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n, uint64_t *h0_out,
+                          uint64_t p0, uint64_t p1, SourceSort sort, uint32_t n_count)
+{
+    __shared__ uint32_t hist[2 * SRC_WG];
+    __shared__ uint32_t last;
+    if (blockIdx.x < n_count) {
+        src_count_block(sort.src, sort.n, sort.S, sort.unit, sort.tables, blockIdx.x, n_count, hist, &last);
+        return;
+    }
+    if (offsets && four_lane_mode(offsets, n)) return;
+    root_one_lane(records, offsets, offset_base, n, h0_out, (uint64_t)(blockIdx.x - n_count) * ROOT1_WG + threadIdx.x, p0, p1);
+}
+
+__global__ void __launch_bounds__(ROOT4_WG)
+lthash_root4_scatter_kernel(const uint8_t *records, const uint64_t *offsets, uint64_t offset_base, uint64_t n,
+                            const uint32_t *order, uint64_t *h0_out, uint64_t p0, uint64_t p1, SourceSort sort, uint32_t n_scatter)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char stage[ROOT4_RECORDS * 128];
+    static_assert(RIDER_MAX_SOURCES * 4 <= ROOT4_RECORDS * 128, "the scatter's table lies in the root kernel's LDS");
+    if (blockIdx.x < n_scatter) {
+        src_scatter_block<ROOT4_WG>(sort.src, sort.n, sort.S, sort.tables, sort.perm, blockIdx.x, reinterpret_cast<uint32_t *>(stage));
+        return;
+    }
+    if (offsets && !four_lane_mode(offsets, n)) return;
+    root_four_lanes(records, offsets, offset_base, n, offsets && ordered_mode(offsets, n) ? order : nullptr, h0_out,
+                    (uint64_t)(blockIdx.x - n_scatter) * ROOT4_RECORDS, stage, p0, p1);
 }
 
 // One wave per unit.  Lane l owns output block l & 31 and takes every second record of the
@@ -1148,6 +1201,40 @@ int lthash_sum_rows(const uint16_t *rows, uint32_t n_rows, uint16_t *out, hipStr
     return fold_rows(reinterpret_cast<const uint32_t *>(rows), n_rows, nullptr, out, s);
 }
 
+// The three launches that put the records in length order for the four-lane path (see above).
+static int launch_ordering(const uint64_t *dev_offsets, uint64_t n, hipStream_t s, void **order)
+{
+    void *counts;
+    int rc;
+    if ((rc = scratch_get(s, R_LT_ORDER, 4 * n, order))) return rc;
+    uint32_t groups = (uint32_t)ceil_div(n, SORT_MIN_RUN);
+    if (groups > SORT_MAX_GROUPS) groups = SORT_MAX_GROUPS;
+    if ((rc = scratch_get(s, R_LT_COUNTS, 4 * (size_t)SORT_MAX_GROUPS * SORT_BINS, &counts))) return rc;
+    hipLaunchKernelGGL(lthash_order_count_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts));
+    hipLaunchKernelGGL(lthash_order_scan_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts), groups);
+    hipLaunchKernelGGL(lthash_order_place_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n,
+                       static_cast<const uint32_t *>(counts), static_cast<uint32_t *>(*order));
+    return SENTRY_OK;
+}
+
+// The root hashes of more than FEW_RECORDS records as lthash_roots launches them, with the sort
+// by source riding in the two root launches (see lthash_root1_count_kernel).
+static int lthash_roots_sorting(const void *dev_records, const uint64_t *dev_offsets, uint64_t n, uint64_t *h0, hipStream_t s,
+                                const SourceSort &sort)
+{
+    void *order = nullptr;
+    int rc = launch_ordering(dev_offsets, n, s, &order);
+    if (rc) return rc;
+    const uint32_t n_count = (uint32_t)ceil_div(n, SRC_TILE), n_scatter = (uint32_t)ceil_div(n, ROOT4_WG * SRC_ITEMS);
+    hipLaunchKernelGGL(lthash_root1_count_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG) + n_count), dim3(ROOT1_WG), 0, s,
+                       static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, n, h0, LT_ROOT_P0, LT_ROOT_P1, sort, n_count);
+    hipLaunchKernelGGL(lthash_root4_scatter_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS) + n_scatter), dim3(ROOT4_WG), 0, s,
+                       static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, n, static_cast<const uint32_t *>(order),
+                       h0, LT_ROOT_P0, LT_ROOT_P1, sort, n_scatter);
+    SENTRY_HIP_CHECK(hipGetLastError());
+    return SENTRY_OK;
+}
+
 // Root hashes (64 bytes each) of n records at dev_records (offsets relative to offset_base).
 int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t offset_base, uint64_t n,
                  uint64_t *h0, hipStream_t s, uint64_t p0, uint64_t p1)
@@ -1157,21 +1244,12 @@ int lthash_roots(const void *dev_records, const uint64_t *dev_offsets, uint64_t 
     // four-lane path is kept for any number of long records: in length order it sustains
     // 1.7 TB/s, while one lane per record, which issues fewer instructions, has chains three
     // times as long and reaches that rate only with millions of records.
-    void *order = nullptr, *counts;
+    void *order = nullptr;
     int rc;
     // Up to one wave per SIMD (16 records a wave) every wave has a SIMD to itself and the launch lasts as
     // long as its longest record whatever the order: no ordering then, which takes three launches
     // out of the way of a small batch.
-    if (n > ORDER_MIN_RECORDS) {
-        if ((rc = scratch_get(s, R_LT_ORDER, 4 * n, &order))) return rc;
-        uint32_t groups = (uint32_t)ceil_div(n, SORT_MIN_RUN);
-        if (groups > SORT_MAX_GROUPS) groups = SORT_MAX_GROUPS;
-        if ((rc = scratch_get(s, R_LT_COUNTS, 4 * (size_t)SORT_MAX_GROUPS * SORT_BINS, &counts))) return rc;
-        hipLaunchKernelGGL(lthash_order_count_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts));
-        hipLaunchKernelGGL(lthash_order_scan_kernel, dim3(1), dim3(SORT_WG), 0, s, dev_offsets, n, static_cast<uint32_t *>(counts), groups);
-        hipLaunchKernelGGL(lthash_order_place_kernel, dim3(groups), dim3(SORT_WG), 0, s, dev_offsets, n,
-                           static_cast<const uint32_t *>(counts), static_cast<uint32_t *>(order));
-    }
+    if (n > ORDER_MIN_RECORDS && (rc = launch_ordering(dev_offsets, n, s, &order))) return rc;
     if (n > FEW_RECORDS)   // up to there the device always takes the four-lane path: nothing for this kernel to do
         hipLaunchKernelGGL(lthash_root1_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG)), dim3(ROOT1_WG), 0, s,
                            static_cast<const uint8_t *>(dev_records), dev_offsets, offset_base, n, h0, p0, p1);
@@ -1373,6 +1451,9 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
                            static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
                            static_cast<uint64_t *>(h0), sentry::LT_ROOT_P0, sentry::LT_ROOT_P1, sort);
         rc = SENTRY_OK;
+    } else if (n > FEW_RECORDS && S <= RIDER_MAX_SOURCES) {
+        const SourceSort sort{src, (uint32_t)n, S, unit, tab, static_cast<uint32_t *>(perm)};
+        rc = sentry::lthash_roots_sorting(dev_records, dev_offsets, n, static_cast<uint64_t *>(h0), s, sort);
     } else {
         hipLaunchKernelGGL(src_count_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, unit, tab);
         hipLaunchKernelGGL(src_scatter_kernel, dim3(scan_grid), dim3(SRC_WG), 0, s, src, (uint64_t)n, S, tab,

@@ -371,6 +371,31 @@ def test_per_source_with_shares_of_a_dirichlet_draw(n, n_sources):
     assert (as_u16(gpu_sources(data, off, src, n_sources), n_sources) == want).all()
 
 
+@pytest.mark.parametrize("n,n_sources,long_record", [(32_769, 16, False), (33_000, 256, True), (40_000, 3, False),
+                                                    (33_000, 257, True), (70_000, 200, True)])
+def test_per_source_large_batches_sorted_inside_the_two_root_hash_launches(n, n_sources, long_record):
+    # more than 32,768 records over up to 256 sources: the count by source rides in the one-lane
+    # root-hash launch and the scatter in the four-lane launch; whichever of the two the device picks
+    # to hash the batch (short equal records: one lane; one record far longer than the rest among
+    # those the device samples: four lanes), both steps must have run.  257 sources: the two sort
+    # launches.  Twice into one set of sums.
+    rng = np.random.default_rng(7700 + n + n_sources)
+    lens = rng.integers(0, 48, n).astype(np.uint64)
+    if long_record:
+        lens[(5 * n) >> 8] = 60_000
+    off = wl.offsets_from_lengths(lens)
+    data = wl.uniform_bytes(7800 + n, 0, int(off[-1]))
+    src = wl.dirichlet_source_ids(n, n_sources, 7801 + n)
+    src[11] = n_sources
+    src[n - 1] = 0xFFFFFFFF
+    want = oracle.lthash_sources(data, off, src, n_sources)
+    acc = gpu_sources(data, off, src, n_sources)
+    assert (as_u16(acc, n_sources) == want).all()
+    want = oracle.lthash_sources(data, off, src, n_sources, acc=want)
+    acc = gpu_sources(data, off, src, n_sources, acc=acc)
+    assert (as_u16(acc, n_sources) == want).all()
+
+
 def test_per_source_skewed_and_single_source_equals_plain_hash():
     n = 3000
     rng = np.random.default_rng(81)
