@@ -18,7 +18,9 @@
 //                         lane sum over digests that are in memory;
 //   src_count/scatter_kernel, lthash_expand_units_kernel, lthash_fold_sources_kernel   one
 //                         running sum per data source (section 4.3); lthash_root4_rider_kernel
-//                         for small batches: root hashes and the sort by source in one launch.
+//                         for small batches: root hashes and the sort by source in one launch;
+//                         lthash_root1_count_kernel, lthash_root4_scatter_kernel for large ones:
+//                         the two steps of the sort at the front of the two root-hash launches.
 // The root kernels take the first two words of the parameter block as arguments: with those of
 // the plain BLAKE2b-512 they also serve the 32-partition hash of blake2_lthash32.hip.
 #include "blake2b_device.h"
