@@ -1219,16 +1219,18 @@ static int launch_ordering(const uint64_t *dev_offsets, uint64_t n, hipStream_t 
     return SENTRY_OK;
 }
 
-// The root hashes of more than FEW_RECORDS records as lthash_roots launches them, with the sort
-// by source riding in the two root launches (see lthash_root1_count_kernel).
+// The root hashes as lthash_roots launches them, with the sort by source riding in the two root
+// launches (see lthash_root1_count_kernel).  Up to FEW_RECORDS records the one-lane kernel has
+// nothing to hash: its launch is then the count alone, and the scatter still rides.
 static int lthash_roots_sorting(const void *dev_records, const uint64_t *dev_offsets, uint64_t n, uint64_t *h0, hipStream_t s,
                                 const SourceSort &sort)
 {
     void *order = nullptr;
-    int rc = launch_ordering(dev_offsets, n, s, &order);
-    if (rc) return rc;
+    int rc;
+    if (n > ORDER_MIN_RECORDS && (rc = launch_ordering(dev_offsets, n, s, &order))) return rc;
     const uint32_t n_count = (uint32_t)ceil_div(n, SRC_TILE), n_scatter = (uint32_t)ceil_div(n, ROOT4_WG * SRC_ITEMS);
-    hipLaunchKernelGGL(lthash_root1_count_kernel, dim3((uint32_t)ceil_div(n, ROOT1_WG) + n_count), dim3(ROOT1_WG), 0, s,
+    const uint32_t root1_blocks = n > FEW_RECORDS ? (uint32_t)ceil_div(n, ROOT1_WG) : 0;
+    hipLaunchKernelGGL(lthash_root1_count_kernel, dim3(root1_blocks + n_count), dim3(ROOT1_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, n, h0, LT_ROOT_P0, LT_ROOT_P1, sort, n_count);
     hipLaunchKernelGGL(lthash_root4_scatter_kernel, dim3((uint32_t)ceil_div(n, ROOT4_RECORDS) + n_scatter), dim3(ROOT4_WG), 0, s,
                        static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, n, static_cast<const uint32_t *>(order),
@@ -1453,7 +1455,7 @@ int sentry_lthash_sources(const void *dev_records, const uint64_t *dev_offsets, 
                            static_cast<const uint8_t *>(dev_records), dev_offsets, (uint64_t)0, (uint64_t)n,
                            static_cast<uint64_t *>(h0), sentry::LT_ROOT_P0, sentry::LT_ROOT_P1, sort);
         rc = SENTRY_OK;
-    } else if (n > FEW_RECORDS && S <= RIDER_MAX_SOURCES) {
+    } else if (S <= RIDER_MAX_SOURCES) {
         const SourceSort sort{src, (uint32_t)n, S, unit, tab, static_cast<uint32_t *>(perm)};
         rc = sentry::lthash_roots_sorting(dev_records, dev_offsets, n, static_cast<uint64_t *>(h0), s, sort);
     } else {
