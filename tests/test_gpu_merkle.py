@@ -183,6 +183,36 @@ def test_segments_tiny_checkpoint_layout():
     assert bytes(one.cpu().numpy()) == oracle.merkle_root(tensors[0], 4096)
 
 
+def test_changed_tensors_update_the_model_root_through_their_roots():
+    # the per-layer granularity of section 4.1 (fine-tuning changes some layers, the rest is frozen):
+    # with the tensor roots kept, a changed tensor costs its own tree (sentry_merkle_root into its
+    # place among the roots) and the tree over the roots (sentry_merkle_reduce), and the result is
+    # the model root that hashing everything again gives
+    lay = wl.layout_tiny()
+    tensors = [t.copy() for t in wl.checkpoint_bytes_np(lay)]
+    devs = [to_dev(t) for t in tensors]
+    n = len(tensors)
+    ptrs, lens = [d.data_ptr() for d in devs], [t.size for t in tensors]
+    roots = torch.zeros(32 * n, dtype=torch.uint8, device="cuda")
+    top = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_segments(ptrs, lens, 4096, roots.data_ptr(), top.data_ptr())
+    torch.cuda.synchronize()
+    before = bytes(top.cpu().numpy())
+    for i in (0, n // 2, n - 1):
+        tensors[i][tensors[i].size // 3] ^= 0x40
+        devs[i].copy_(torch.from_numpy(tensors[i]))
+        sentry.sentry_merkle_root(ptrs[i], lens[i], 4096, roots.data_ptr() + 32 * i)
+    sentry.sentry_merkle_reduce(roots.data_ptr(), n, top.data_ptr())
+    torch.cuda.synchronize()
+    want_seg, want_top = oracle.merkle_segments(tensors, 4096)
+    assert [bytes(r) for r in roots.cpu().numpy().reshape(n, 32)] == want_seg
+    assert bytes(top.cpu().numpy()) == want_top != before
+    again = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    sentry.sentry_merkle_segments(ptrs, lens, 4096, 0, again.data_ptr())
+    torch.cuda.synchronize()
+    assert bytes(again.cpu().numpy()) == want_top
+
+
 @pytest.mark.parametrize("leaf,n_leaves,tail", [
     (512, 64 * 300 + 5, 0), (512, 64 * 257 + 1, 57), (1024, 64 * 256, 0), (1024, 64 * 256 + 1, 3),
     (512, 64 * 511 + 63, 511), (512, 64 * 512, 0), (512, 64 * 513, 9), (576, 129, 0), (4096, 65, 56),
