@@ -68,6 +68,10 @@ def test_host_threads_with_a_stream_each():
     staged = [(to_dev(b), to_dev(d), to_dev(o)) for b, d, o in work]
     roots = torch.zeros(n_threads, 32, dtype=torch.uint8, device="cuda")
     lanes = torch.zeros(n_threads, 1024, dtype=torch.int16, device="cuda")
+    # per-source sums too: every stream has tables, counters and tickets of its own
+    srcs = [wl.dirichlet_source_ids(len(w[2]) - 1, 5 + t, 945 + t) for t, w in enumerate(work)]
+    d_srcs = [to_dev(x.view(np.int32)) for x in srcs]
+    sums = [torch.zeros((5 + t) * 1024, dtype=torch.int16, device="cuda") for t in range(n_threads)]
     streams = [torch.cuda.Stream() for _ in range(n_threads)]
     torch.cuda.synchronize()
     errors = []
@@ -79,6 +83,8 @@ def test_host_threads_with_a_stream_each():
             for _ in range(3):
                 sentry.sentry_merkle_root(db.data_ptr(), work[t][0].size, 1024, roots[t].data_ptr(), st)
                 sentry.sentry_lthash(dd.data_ptr(), do.data_ptr(), len(work[t][2]) - 1, lanes[t].data_ptr(), st)
+                sentry.sentry_lthash_sources(dd.data_ptr(), do.data_ptr(), d_srcs[t].data_ptr(), len(work[t][2]) - 1, 5 + t,
+                                             sums[t].data_ptr(), st)
             streams[t].synchronize()
         except Exception as e:   # reported in the main thread
             errors.append((t, repr(e)))
@@ -94,6 +100,8 @@ def test_host_threads_with_a_stream_each():
     for t, (buf, data, off) in enumerate(work):
         assert bytes(r[t]) == oracle.merkle_root(buf, 1024), t
         assert (l[t] == oracle.lthash(data, off)).all(), t
+        one = oracle.lthash_sources(data, off, srcs[t], 5 + t).astype(np.uint32)
+        assert (sums[t].cpu().numpy().view(np.uint16).reshape(5 + t, 1024) == ((3 * one) & 0xFFFF)).all(), t
 
 
 def test_release_scratch_then_reuse():
