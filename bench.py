@@ -818,6 +818,41 @@ def main():
                     {"GB/s": img.numel() / ms / 1e6, "ms": ms, "bytes": img.numel(), "samples/s": 50_000 / (ms * 1e-3), "calls": 391,
                      "us_per_call": ms * 1e3 / 391, "clock": "host wall time around all calls and the final synchronisation"},
                     (lthash_mix if name == "lthash" else lthash32_mix)([3072] * 50_000))
+        # the same for a text data set in the shape of the paper's second one (section 5: 40,000 samples of varying
+        # length, padded to one length inside a batch, which is then the block size of the dataset kernel; batches of
+        # 128 from 16 sources): lengths log-normal around 600 bytes, every batch padded to its longest sample
+        t_lens = wl.lognormal_record_lengths(40_000, seed=wl.SEED_C2 + 21, median=600, sigma=0.4, lo=64, hi=4096)
+        t_pad = [(int(t_lens[a:a + 128].max()) + 15) // 16 * 16 for a in range(0, 40_000, 128)]
+        t_cnt = [min(128, 40_000 - a) for a in range(0, 40_000, 128)]
+        t_base = np.concatenate([[0], np.cumsum([p * c for p, c in zip(t_pad, t_cnt)])]).astype(np.int64)
+        text = wl.uniform_bytes(wl.SEED_C2 + 22, 0, int(t_base[-1]), device=dev)
+        t_off = torch.from_numpy(np.concatenate([np.arange(129, dtype=np.int64) * p for p in t_pad])).to(dev)
+        t_ids = torch.from_numpy(wl.dirichlet_source_ids(40_000, 16, wl.SEED_C2 + 23).view(np.int32)).to(dev)
+        t_mix_lens = [p for p, c in zip(t_pad, t_cnt) for _ in range(c)]
+        text_stream = torch.cuda.Stream()
+        for name, call, lanes_per in (("lthash", sentry.sentry_lthash_sources, 1024), ("lthash32", sentry.sentry_lthash32_sources, 32)):
+            acc_t = torch.zeros(16 * lanes_per, dtype=torch.int16, device=dev)
+            torch.cuda.synchronize()
+
+            def whole_text_set():
+                for k in range(len(t_pad)):
+                    call(text.data_ptr() + int(t_base[k]), t_off.data_ptr() + 8 * 129 * k, t_ids.data_ptr() + 4 * 128 * k,
+                         t_cnt[k], 16, acc_t.data_ptr(), text_stream.cuda_stream)
+                torch.cuda.synchronize()
+
+            whole_text_set()
+            ts = []
+            for _ in range(3):
+                t0 = time.perf_counter()
+                whole_text_set()
+                ts.append((time.perf_counter() - t0) * 1e3)
+            ms = statistics.median(ts)
+            per_config["E4_%s_40k_text_samples_batches_of_128_16_sources_1_stream" % name] = rated(
+                {"GB/s": int(t_base[-1]) / ms / 1e6, "ms": ms, "bytes": int(t_base[-1]), "samples/s": 40_000 / (ms * 1e-3),
+                 "calls": len(t_pad), "us_per_call": ms * 1e3 / len(t_pad), "mean_padded_bytes": int(t_base[-1]) // 40_000,
+                 "clock": "host wall time around all calls and the final synchronisation"},
+                (lthash_mix if name == "lthash" else lthash32_mix)(t_mix_lens))
+        del text, t_off, t_ids
         # what a HIP graph buys such a pipeline: the per-source call on a batch buffer (a pipeline hands every batch
         # over in the same buffer) captured once and replayed 391 times, against the same 391 calls issued one by one;
         # both running sums must come out equal
